@@ -1,0 +1,200 @@
+"""Throughput of the gossip step on one MI355X.
+
+Metric: replica-steps/s (= k x gossip steps per second) of gsgd_step_gossip at
+ResNet-50-sized vectors (d = 25,557,032 fp32) with k = 32 replicas, a fresh
+seeded peer permutation per step, x / v / g resident in HBM.  One JSON line on
+stdout; progress on stderr.
+
+Also reported in the same line: the roofline of the dominant kernel (the fused
+SGD+momentum+mix kernel, HBM-bound, 20 algorithmic bytes per replica-element),
+the cost of the synthetic-gradient generator and of the full simulated
+iteration, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
+BYTES_PER_REPLICA_ELEMENT = {   # algorithmic traffic of each kernel, fp32
+    "gossip": 20.0,             # read x, v, g; write x, v
+    "allreduce": 20.0,
+    "easgd": 20.0,              # + 8/k for the centre, added below
+}
+# HBM bytes per launch of the gossip kernel at the benchmark shape, from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of known
+# size (see profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="gossip_r50")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle baseline (0 = skip)")
+    ap.add_argument("--no-extras", action="store_true", help="time only the metric kernel")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU (k replicas live in one GPU's HBM); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_1611_04581_amd import gsgd, workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the library has no CPU fallback")
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[args.config]
+    k, d = cfg.k, cfg.d
+    ld = W.round_up(d, 1024)
+    seg = {}
+    if cfg.layout:
+        off, sc, _ = W.resnet_layout(cfg.layout)
+        seg = dict(seg_offsets=off, seg_lr_scale=sc)
+    K, Wm = args.steps, args.warmup
+    log("config %s: rule=%s k=%d d=%d ld=%d steps=%d warmup=%d" % (cfg.name, cfg.rule, k, d, ld, K, Wm))
+
+    ctx = gsgd.Context(k, d, ld, lr=cfg.lr, momentum=cfg.momentum, sigma=cfg.sigma, seed=cfg.seed,
+                       noise_kind=gsgd.NOISE_GAUSSIAN, **seg)
+    x = torch.empty((k, ld), dtype=torch.float32, device="cuda")
+    v = torch.empty_like(x)
+    g = torch.empty_like(x)
+    h = torch.empty(ld, dtype=torch.float32, device="cuda")
+    xstar = torch.empty_like(h)
+    x0 = torch.empty_like(h)
+    center = torch.empty_like(h)
+    ctx.fill(h, gsgd.FILL_H)
+    ctx.fill(xstar, gsgd.FILL_XSTAR)
+    ctx.fill(x0, gsgd.FILL_X0)
+    ctx.init_replicas(x, v, center, x0, gsgd.INIT_BROADCAST)
+    ctx.gen_grad(x, h, xstar, g, 0)
+    torch.cuda.synchronize()
+    stats0 = ctx.stats(x, xstar)
+
+    def one_step(t):
+        if cfg.rule == "gossip":
+            ctx.step_gossip(x, v, g, gsgd.make_perm(cfg.seed, t, k), cfg.beta)
+        elif cfg.rule == "allreduce":
+            ctx.step_allreduce(x, v, g)
+        else:
+            ctx.step_easgd(x, v, g, center, cfg.alpha_e)
+
+    def timed(fn, n, t_start):
+        """n calls of fn(t) bracketed by synchronize; returns (wall seconds, HIP-event seconds)."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        w0 = time.perf_counter()
+        e0.record()
+        for t in range(t_start, t_start + n):
+            fn(t)
+        e1.record()
+        torch.cuda.synchronize()
+        w1 = time.perf_counter()
+        return w1 - w0, e0.elapsed_time(e1) * 1e-3
+
+    # ---- the metric: K step calls on resident x, v, g -----------------------------------
+    for t in range(Wm):
+        one_step(t)
+    wall, ev = timed(one_step, K, Wm)
+    ms_per_step = wall / K * 1e3
+    value = k * K / wall
+    bpe = BYTES_PER_REPLICA_ELEMENT[cfg.rule] + (8.0 / k if cfg.rule == "easgd" else 0.0)
+    alg_bytes = bpe * k * d
+    kern_s = ev / K                                  # one kernel per step in the timed region
+    achieved = alg_bytes / kern_s / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(cfg.name)
+    log("step: %.3f ms wall, %.3f ms by HIP events -> %.0f replica-steps/s, %.0f GB/s algorithmic (%.1f%% of peak)"
+        % (ms_per_step, kern_s * 1e3, value, achieved, 100 * achieved / HBM_PEAK_GBS))
+
+    out = {
+        "metric": "replica-steps/sec, gossip step, ResNet-50-size d, k=32" if cfg.name == "gossip_r50"
+                  else "replica-steps/sec, %s step" % cfg.rule,
+        "value": value, "unit": "replica-steps/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: k=%d replicas, d=%d fp32 (row stride %d), rule=%s, fresh Philox peer permutation "
+                               "per step, x/v/g resident in HBM" % (cfg.name, k, d, ld, cfg.rule),
+                   "k": k, "d": d, "ld": ld, "rule": cfg.rule, "lr": cfg.lr, "momentum": cfg.momentum,
+                   "beta": cfg.beta, "sigma": cfg.sigma, "layout": cfg.layout or "flat"},
+        "roofline": {"bound": "hbm", "kernel": "%s_step_kernel" % cfg.rule, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kern_s * 1e3},
+    }
+
+    # ---- context: generator and full simulated iteration --------------------------------
+    if not args.no_extras:
+        n2 = max(10, K // 4)
+        t_next = Wm + K
+        w_gen, e_gen = timed(lambda t: ctx.gen_grad(x, h, xstar, g, t), n2, t_next)
+
+        def full(t):
+            ctx.gen_grad(x, h, xstar, g, t)
+            one_step(t)
+        w_full, e_full = timed(full, n2, t_next + n2)
+        extras = {
+            "gen_grad_ms": e_gen / n2 * 1e3,
+            "gen_grad_GBps_algorithmic": (8.0 + 8.0 / k) * k * d / (e_gen / n2) / 1e9,
+            "full_iteration_ms": w_full / n2 * 1e3,
+            "full_iteration_replica_steps_per_s": k * n2 / w_full,
+        }
+        if cfg.rule == "gossip":
+            def fused(t):
+                ctx.step_gossip_fused(x, v, h, xstar, gsgd.make_perm(cfg.seed, t, k), t, cfg.beta)
+            for t in range(3):
+                fused(t_next + 2 * n2 + t)
+            w_fu, e_fu = timed(fused, n2, t_next + 2 * n2 + 3)
+            extras["fused_iteration_ms"] = w_fu / n2 * 1e3
+            extras["fused_iteration_replica_steps_per_s"] = k * n2 / w_fu
+            extras["fused_iteration_GBps_algorithmic"] = (16.0 + 8.0 / k) * k * d / (e_fu / n2) / 1e9
+        st = ctx.stats(x, xstar)
+        extras["stats_start"] = [float(s) for s in stats0]
+        extras["stats_end"] = [float(s) for s in st]
+        out["extras"] = extras
+        log("extras:", json.dumps(extras))
+
+    # ---- CPU baseline: the oracle, as it stands, on a bounded sample ---------------------
+    if args.cpu_seconds > 0:
+        from oracle import oracle
+        ds = min(d, 1 << 20)                       # first 2^20 columns of every replica row
+        inp = W.make_inputs(k, ds, seed=5)
+        perm0 = oracle.make_perm(cfg.seed, 0, k)
+        lrc = np.full(ds, np.float32(cfg.lr), np.float32)
+
+        def ostep(t):
+            if cfg.rule == "gossip":
+                oracle.step_gossip(inp.x, inp.v, inp.g, lrc, cfg.momentum, cfg.beta, oracle.make_perm(cfg.seed, t, k))
+            elif cfg.rule == "allreduce":
+                oracle.step_allreduce(inp.x, inp.v, inp.g, lrc, cfg.momentum)
+            else:
+                oracle.step_easgd(inp.x, inp.v, inp.g, inp.center, lrc, cfg.momentum, cfg.alpha_e)
+        ostep(0)
+        n_cpu, t0 = 0, time.perf_counter()
+        while time.perf_counter() - t0 < args.cpu_seconds:
+            ostep(n_cpu + 1)
+            n_cpu += 1
+        cpu_wall = time.perf_counter() - t0
+        cpu_value = k * n_cpu / cpu_wall * (ds / d)      # scaled to full-length rows
+        out["cpu_baseline"] = {
+            "value": cpu_value, "unit": "replica-steps/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d %s steps of the C oracle on the first %d of %d columns of all %d replicas (%.1f s); "
+                      "rate scaled by %d/%d to full-length rows" % (n_cpu, cfg.rule, ds, d, k, cpu_wall, ds, d),
+        }
+        log("cpu oracle: %.2f replica-steps/s on %d threads" % (cpu_value, oracle.num_threads()))
+
+    ctx.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

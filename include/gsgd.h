@@ -1,0 +1,175 @@
+/*
+ * gsgd.h -- C ABI of libgsgd, the MI355X (gfx950) library for the per-step
+ * parameter-aggregation update of "How to scale distributed deep learning?"
+ * (Jin, Yuan, Iandola, Keutzer; arXiv 1611.04581): a local momentum-SGD step
+ * fused with gossip pairwise averaging (the paper's Section 3), and the two
+ * rules it is compared with, synchronous all-reduce averaging (Algorithm 1)
+ * and elastic averaging (Algorithm 2).
+ *
+ * The k "nodes" of the paper are k replica rows that all live in one GPU's
+ * memory.  Notation follows the paper's Section 2: theta -> x (parameters),
+ * Delta-theta -> v (momentum / update buffer), grad f_i -> g, theta-tilde ->
+ * center, alpha -> lr, mu -> momentum, p -> k.  The gossip mixing weight is
+ * beta (Section 3.1; the authors' runs use 1/2).  The elastic-averaging
+ * "moving rate", which Algorithm 2 also calls beta, is alpha_e here.
+ *
+ * Memory model
+ *   - x, v, g are row-major fp32 matrices of k rows with a row stride of ld
+ *     elements (ld >= d, ld % 4 == 0); element (i, j) is at base[i*ld + j].
+ *     Only columns 0..d-1 are read or written.  center, h, xstar, x0 are fp32
+ *     vectors of at least d elements.
+ *   - Every pointer named "device" is GPU memory owned by the caller, 16-byte
+ *     aligned, valid until the stream has run the call.  The library never
+ *     frees or reallocates caller memory.  x, v, g, center must not overlap.
+ *   - Pointers named "host" are ordinary host memory, read (or written, for
+ *     outputs) before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Step calls only enqueue work; they do not synchronise.  gsgd_stats is
+ *     the one call that waits for the stream.
+ *
+ * Errors: every function returns GSGD_OK (0) or a negative code; nothing
+ * throws, aborts or prints.  A gsgd_ctx is not thread-safe; distinct contexts
+ * are independent.
+ */
+#ifndef GSGD_H
+#define GSGD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GSGD_MAX_K 512              /* most replicas one context can hold */
+
+enum {
+    GSGD_OK               =  0,
+    GSGD_ERR_INVALID_ARG  = -1,    /* null pointer, k/d/ld out of range, misaligned pointer, bad enum */
+    GSGD_ERR_BAD_PERM     = -2,    /* peer_perm is not a bijection on 0..k-1 */
+    GSGD_ERR_BAD_SEGMENTS = -3,    /* segment table not ascending from 0 to d */
+    GSGD_ERR_HIP          = -4,    /* a HIP runtime call failed; see gsgd_last_hip_error */
+    GSGD_ERR_UNSUPPORTED  = -5,
+    GSGD_ERR_NO_MEMORY    = -6
+};
+
+enum { GSGD_NOISE_GAUSSIAN = 0, GSGD_NOISE_UNIFORM = 1 };
+enum { GSGD_INIT_BROADCAST = 0, GSGD_INIT_PER_REPLICA = 1 };
+enum { GSGD_FILL_XSTAR = 2, GSGD_FILL_H = 3, GSGD_FILL_X0 = 4 };
+
+typedef struct gsgd_ctx gsgd_ctx;   /* opaque; owns the segment tables and a small scratch for gsgd_stats */
+
+typedef struct gsgd_config {
+    int32_t  k;                     /* replicas, 1..GSGD_MAX_K (the paper's p) */
+    int64_t  d;                     /* parameters per replica, >= 1 */
+    int64_t  ld;                    /* row stride in elements, >= d, multiple of 4 */
+    float    lr;                    /* step size alpha (Section 2) */
+    float    momentum;              /* mu (Section 2) */
+    float    sigma;                 /* std-dev of the additive gradient noise (Theorem 1's xi) */
+    uint64_t seed;                  /* Philox key */
+    int32_t  noise_kind;            /* GSGD_NOISE_*: both are zero-mean unit-variance (Theorem 1's assumption) */
+    int32_t  n_seg;                 /* 0 = flat vector; else number of per-layer tensors laid back to back */
+    const int64_t* seg_offsets;     /* host, n_seg+1 entries, [0] = 0, strictly ascending, [n_seg] = d; copied */
+    const float*   seg_lr_scale;    /* host, n_seg entries; segment s steps with lr * seg_lr_scale[s]; copied */
+} gsgd_config;
+
+/* Create / destroy a context.  gsgd_create validates the configuration, copies
+ * the segment tables to the current device and allocates the scratch that
+ * gsgd_stats reduces into.  The current HIP device at creation is the device
+ * every later call must run on. */
+int gsgd_create(const gsgd_config* cfg, gsgd_ctx** out);
+int gsgd_destroy(gsgd_ctx* ctx);
+
+/* Change the base step size (the paper anneals alpha, Section 4.2).  Host only. */
+int gsgd_set_lr(gsgd_ctx* ctx, float lr);
+
+/* Initialisation: first line of Algorithms 1-4 (every node starts at the same
+ * theta_0; the elastic-averaging server's centre starts there too).
+ *   mode GSGD_INIT_BROADCAST   : x_i <- x0 for all i; center <- x0
+ *   mode GSGD_INIT_PER_REPLICA : x_i <- N(0,1) drawn per replica from the
+ *        context's Philox stream 1 (lets a run start from non-zero consensus
+ *        distance); center <- mean_i x_i;  x0 is ignored and may be NULL
+ * v <- 0 in both modes.  x, v: device k x ld.  center: device d, may be NULL.
+ * x0: device d. */
+int gsgd_init_replicas(gsgd_ctx* ctx, float* x, float* v, float* center, const float* x0, int mode, void* stream);
+
+/* Fill a device vector of d elements with one of the shared synthetic vectors
+ * of the noisy quadratic f(x) = 1/2 sum_j h_j (x_j - xstar_j)^2, which is
+ * m-strongly convex with L-Lipschitz gradient for m = min h, L = max h
+ * (the function class of Theorem 1):
+ *   GSGD_FILL_XSTAR ~ N(0,1), GSGD_FILL_H ~ U(0.1, 1), GSGD_FILL_X0 ~ N(0,1). */
+int gsgd_fill(gsgd_ctx* ctx, float* dst, int which, void* stream);
+
+/* Synthetic stochastic gradient, the sampling model of Theorem 1
+ * (g = grad f + xi, E xi = 0, bounded variance):
+ *   g_i = h (.) (x_i - xstar) + sigma xi_i,   xi from Philox stream 0 at
+ *   counter (column/4, replica i, step, 0).  step < 2^32.
+ * x: device k x ld (read).  h, xstar: device d.  g: device k x ld (written). */
+int gsgd_gen_grad(gsgd_ctx* ctx, const float* x, const float* h, const float* xstar, float* g,
+                  uint64_t step, void* stream);
+
+/* Synchronous all-reduce step, Algorithm 1:
+ *   u_i = momentum * v_i - lr_s * g_i;  ubar = (1/k) sum_i u_i;
+ *   v_i <- ubar;  x_i <- x_i + ubar          for every replica i.
+ * The k-way sum runs in fp64 in ascending i and is rounded once to fp32.
+ * x, v: device k x ld, updated in place.  g: device k x ld, read. */
+int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const float* g, void* stream);
+
+/* Gossip step: local momentum step (the two lines shared by Algorithms 2-4)
+ * followed by the pairwise mix of Section 3.1 / 6.2.2 ("fresh parameters"):
+ *   v_i <- momentum * v_i - lr_s * g_i;   x'_i = x_i + v_i;
+ *   x_i <- x'_i - beta * (x'_i - x'_{peer_perm[i]}).
+ * peer_perm: host, k entries, a bijection on 0..k-1 (each node is pulled from
+ * exactly once, so pull- and push-gossip coincide); peer_perm[i] == i mixes a
+ * replica with itself, i.e. leaves x'_i.  The array is consumed before the
+ * call returns.  Everything happens in place in one pass over x, v and g. */
+int gsgd_step_gossip(gsgd_ctx* ctx, float* x, float* v, const float* g,
+                     const int32_t* peer_perm, float beta, void* stream);
+
+/* Elastic-averaging step, Algorithm 2 with communication period 1, all k
+ * clients exchanging with the same centre value in one synchronous round:
+ *   v_i <- momentum * v_i - lr_s * g_i;   x'_i = x_i + v_i;
+ *   e_i = alpha_e * (x'_i - center);  x_i <- x'_i - e_i;  center <- center + sum_i e_i.
+ * The sum runs in fp64 in ascending i.  center: device d, updated in place. */
+int gsgd_step_easgd(gsgd_ctx* ctx, float* x, float* v, const float* g,
+                    float* center, float alpha_e, void* stream);
+
+/* Gossip step with the synthetic gradient generated on the fly (g never
+ * touches memory): equivalent to gsgd_gen_grad followed by gsgd_step_gossip. */
+int gsgd_step_gossip_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
+                           const int32_t* peer_perm, float beta, uint64_t step, void* stream);
+
+/* Raw Philox4x32-10 output for counters (q, c1, c2, c3), q = 0..n_blocks-1,
+ * under the context's key: out[4q .. 4q+3] are the four words of block q.
+ * The generator is the one of Salmon, Moraes, Dror and Shaw (SC'11); this
+ * entry point exists so that the device stream can be compared word for word.
+ * out: device, 4 * n_blocks uint32. */
+int gsgd_philox_raw(gsgd_ctx* ctx, uint32_t c1, uint32_t c2, uint32_t c3, int64_t n_blocks, uint32_t* out,
+                    void* stream);
+
+/* Uniformly random peer permutation for one step ("choose a target j",
+ * Algorithms 3-4, with every j used once): Fisher-Yates from the top, driven
+ * by Philox stream 5 at counter (i, 0, step, 5), index floor(r (i+1) / 2^32).
+ * Pure host code, deterministic.  out: host, k entries. */
+int gsgd_make_perm(uint64_t seed, uint64_t step, int32_t k, int32_t* out);
+
+/* Order in which the gossip kernel visits replicas: the cycles of peer_perm,
+ * each walked i, perm[i], perm[perm[i]], ...  walk[t] holds the replica index
+ * in its low 12 bits, bit 14 set on the first member of a cycle and bit 15 on
+ * the last.  Pure host code (exported for tests).  walk: host, k entries.
+ * Returns GSGD_ERR_BAD_PERM when peer_perm is not a bijection. */
+int gsgd_perm_walk(const int32_t* peer_perm, int32_t k, uint16_t* walk);
+
+/* The two quantities the analysis bounds (Section 6.1) and the mean's own
+ * distance, over columns 0..d-1, accumulated in fp64:
+ *   out[0] = sum_i ||x_i - xbar||^2, out[1] = sum_i ||x_i - xstar||^2,
+ *   out[2] = ||xbar - xstar||^2,     out[3] = ||xbar||^2.
+ * Waits for the stream.  out: host. */
+int gsgd_stats(gsgd_ctx* ctx, const float* x, const float* xstar, double out[4], void* stream);
+
+const char* gsgd_strerror(int code);
+int gsgd_last_hip_error(const gsgd_ctx* ctx);   /* raw hipError_t of the last GSGD_ERR_HIP */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSGD_H */

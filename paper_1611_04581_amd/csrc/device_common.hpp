@@ -1,0 +1,201 @@
+// Device-side building blocks shared by the kernels: 128-bit streaming
+// accesses, the Philox4x32-10 block function, the u32 -> noise transforms and
+// the per-layer step-size lookup.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gsgd_internal.hpp"
+
+namespace gsgd {
+
+typedef float  f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+constexpr int BLOCK = 256;            // threads per workgroup: 4 wavefronts of 64
+
+// One thread owns one "quad": four adjacent columns, one 128-bit lane of every
+// row.  A wavefront therefore streams 1 KiB contiguous per row access.
+// `valid` is 4 for a full quad and 1..3 for the ragged last quad of a row
+// whose length is not a multiple of 4.
+__device__ __forceinline__ f32x4 load_quad(const float* p, int valid)
+{
+    if (valid == 4) return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    f32x4 r = {0.f, 0.f, 0.f, 0.f};
+    if (valid > 0) r.x = p[0];
+    if (valid > 1) r.y = p[1];
+    if (valid > 2) r.z = p[2];
+    return r;
+}
+
+__device__ __forceinline__ void store_quad(float* p, f32x4 r, int valid)
+{
+    if (valid == 4) { __builtin_nontemporal_store(r, reinterpret_cast<f32x4*>(p)); return; }
+    if (valid > 0) p[0] = r.x;
+    if (valid > 1) p[1] = r.y;
+    if (valid > 2) p[2] = r.z;
+}
+
+// Shared vectors (h, xstar, center) are read once per column and reused for
+// every replica row: ordinary cached loads.
+__device__ __forceinline__ f32x4 load_quad_cached(const float* p, int valid)
+{
+    if (valid == 4) return *reinterpret_cast<const f32x4*>(p);
+    f32x4 r = {0.f, 0.f, 0.f, 0.f};
+    if (valid > 0) r.x = p[0];
+    if (valid > 1) r.y = p[1];
+    if (valid > 2) r.z = p[2];
+    return r;
+}
+
+// Element-wise helpers with the rounding points spelled out (the library is
+// compiled with FP contraction off; the only fused operations are these).
+__device__ __forceinline__ f32x4 fma4(float a, f32x4 b, f32x4 c)
+{
+    return f32x4{__fmaf_rn(a, b.x, c.x), __fmaf_rn(a, b.y, c.y), __fmaf_rn(a, b.z, c.z), __fmaf_rn(a, b.w, c.w)};
+}
+__device__ __forceinline__ f32x4 fma4(f32x4 a, f32x4 b, f32x4 c)
+{
+    return f32x4{__fmaf_rn(a.x, b.x, c.x), __fmaf_rn(a.y, b.y, c.y), __fmaf_rn(a.z, b.z, c.z), __fmaf_rn(a.w, b.w, c.w)};
+}
+
+// Local momentum step shared by Algorithms 2-4 of the paper:
+//   v' = mu v - lr g  (as fma(-lr, g, mu v)),  x' = x + v'
+__device__ __forceinline__ f32x4 momentum_update(f32x4 v, f32x4 g, f32x4 neg_lr, float mu)
+{
+    const f32x4 t3 = mu * v;
+    return fma4(neg_lr, g, t3);
+}
+
+// Gossip mix of Section 3.1: x' - beta (x' - x'_peer)
+__device__ __forceinline__ f32x4 gossip_mix(f32x4 mine, f32x4 theirs, float neg_beta)
+{
+    const f32x4 diff = mine - theirs;
+    return fma4(neg_beta, diff, mine);
+}
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).  Stream ids select what
+// the numbers are used for; they are the fourth counter word.
+enum : uint32_t { STREAM_GRAD = 0, STREAM_INIT = 1, STREAM_XSTAR = 2, STREAM_H = 3, STREAM_X0 = 4, STREAM_PERM = 5 };
+
+struct u32x4 { uint32_t w[4]; };
+
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1)
+{
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += W0;
+        k1 += W1;
+    }
+    return u32x4{{c0, c1, c2, c3}};
+}
+
+// Top 23 bits b -> (2b+1) / 2^24: exact in fp32, strictly inside (0,1).
+__device__ __forceinline__ float u01(uint32_t r)
+{
+    return __fmaf_rn(static_cast<float>(r >> 9), 0x1.0p-23f, 0x1.0p-24f);   // exact: no rounding occurs
+}
+
+// Four zero-mean unit-variance values (the noise model of Theorem 1).
+//   uniform : sqrt(3) (2u - 1), bit-reproducible on any IEEE machine
+//   gaussian: Box-Muller, words (0,1) -> lanes (0,1), words (2,3) -> lanes (2,3);
+//             even lane carries the cosine
+template <int NOISE>
+__device__ __forceinline__ f32x4 noise4(const u32x4& r)
+{
+    if constexpr (NOISE == GSGD_NOISE_UNIFORM) {
+        constexpr float sqrt3 = 1.7320508075688772f;
+        f32x4 z;
+        z.x = sqrt3 * __fmaf_rn(2.0f, u01(r.w[0]), -1.0f);
+        z.y = sqrt3 * __fmaf_rn(2.0f, u01(r.w[1]), -1.0f);
+        z.z = sqrt3 * __fmaf_rn(2.0f, u01(r.w[2]), -1.0f);
+        z.w = sqrt3 * __fmaf_rn(2.0f, u01(r.w[3]), -1.0f);
+        return z;
+    } else {
+        const float rho0 = sqrtf(-2.0f * logf(u01(r.w[0])));
+        const float rho1 = sqrtf(-2.0f * logf(u01(r.w[2])));
+        float s0, c0, s1, c1;
+        sincospif(2.0f * u01(r.w[1]), &s0, &c0);
+        sincospif(2.0f * u01(r.w[3]), &s1, &c1);
+        return f32x4{rho0 * c0, rho0 * s0, rho1 * c1, rho1 * s1};
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Per-layer step size.  Column j belongs to segment s when
+// offsets[s] <= j < offsets[s+1]; its step size is lr * scales[s].
+// The block stages the table in LDS when it fits and binary-searches there;
+// larger tables are searched in global memory.
+constexpr int SEG_LDS_MAX = 1024;     // segments held in LDS (12 KiB)
+
+struct SegLds {
+    int64_t offsets[SEG_LDS_MAX + 1];
+    float   scales[SEG_LDS_MAX];
+};
+
+// All threads of the block must call this (it contains a barrier).
+__device__ __forceinline__ void stage_segments(const SegTable& seg, SegLds& lds)
+{
+    if (seg.n_seg > 0 && seg.n_seg <= SEG_LDS_MAX) {
+        for (int t = threadIdx.x; t <= seg.n_seg; t += blockDim.x) lds.offsets[t] = seg.offsets[t];
+        for (int t = threadIdx.x; t < seg.n_seg; t += blockDim.x) lds.scales[t] = seg.scales[t];
+        __syncthreads();
+    }
+}
+
+template <typename OffT, typename ScT>
+__device__ __forceinline__ f32x4 seg_lookup(const OffT* off, const ScT* sc, int n_seg, int64_t col, int valid, float lr)
+{
+    // largest s with off[s] <= col
+    int lo = 0, hi = n_seg - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (off[mid] <= col) lo = mid; else hi = mid - 1;
+    }
+    f32x4 out;
+    int s = lo;
+    out.x = lr * sc[s];
+    if (valid > 1) { while (col + 1 >= off[s + 1]) ++s; } out.y = lr * sc[s];
+    if (valid > 2) { while (col + 2 >= off[s + 1]) ++s; } out.z = lr * sc[s];
+    if (valid > 3) { while (col + 3 >= off[s + 1]) ++s; } out.w = lr * sc[s];
+    return out;
+}
+
+// Step sizes of the four columns of a quad starting at column `col`.
+__device__ __forceinline__ f32x4 quad_lr(const SegTable& seg, const SegLds& lds, int64_t col, int valid, float lr)
+{
+    if (seg.n_seg == 0) return f32x4{lr, lr, lr, lr};
+    if (seg.n_seg <= SEG_LDS_MAX) return seg_lookup(lds.offsets, lds.scales, seg.n_seg, col, valid, lr);
+    return seg_lookup(seg.offsets, seg.scales, seg.n_seg, col, valid, lr);
+}
+
+// Quad geometry of a thread.
+struct Quad {
+    int64_t col;     // first column
+    int     valid;   // 0 (no work), 1..3 (ragged tail) or 4
+};
+
+__device__ __forceinline__ Quad my_quad(int64_t d)
+{
+    const int64_t q = static_cast<int64_t>(blockIdx.x) * BLOCK + threadIdx.x;
+    const int64_t col = q * 4;
+    const int64_t left = d - col;
+    Quad out;
+    out.col = col;
+    out.valid = left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0);
+    return out;
+}
+
+inline int64_t num_quads(int64_t d) { return (d + 3) / 4; }
+inline unsigned grid_for(int64_t d) { return static_cast<unsigned>((num_quads(d) + BLOCK - 1) / BLOCK); }
+
+}  // namespace gsgd

@@ -1,0 +1,237 @@
+// C ABI of libgsgd: argument checking, context ownership, and dispatch to the
+// kernel launchers.  No computation of the method happens here.
+#include <new>
+#include <string.h>
+
+#include "gsgd_internal.hpp"
+
+using namespace gsgd;
+
+struct gsgd_ctx {
+    gsgd_config cfg;          // host pointers inside are cleared after copying
+    int         device;
+    int64_t*    d_offsets;    // device copy of the segment table
+    float*      d_scales;
+    double*     d_partials;   // stats scratch: stats_num_blocks(d) * 4 doubles
+    double*     d_result;     // 4 doubles
+    double*     h_result;     // pinned host, 4 doubles
+    int         last_hip;
+};
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int hip_fail(gsgd_ctx* ctx, hipError_t e)
+{
+    if (ctx) ctx->last_hip = static_cast<int>(e);
+    return GSGD_ERR_HIP;
+}
+
+inline Geom geom_of(const gsgd_ctx* c) { return Geom{c->cfg.k, c->cfg.d, c->cfg.ld}; }
+inline Hyper hyper_of(const gsgd_ctx* c) { return Hyper{c->cfg.lr, c->cfg.momentum}; }
+inline SegTable seg_of(const gsgd_ctx* c) { return SegTable{c->d_offsets, c->d_scales, c->cfg.n_seg}; }
+inline RngKey key_of(const gsgd_ctx* c)
+{
+    return RngKey{static_cast<uint32_t>(c->cfg.seed), static_cast<uint32_t>(c->cfg.seed >> 32)};
+}
+
+// Row matrices must be non-null and 16-byte aligned (rows then are, since ld % 4 == 0).
+inline bool ok_matrix(const void* p) { return p && aligned16(p); }
+
+int check_state(const gsgd_ctx* ctx, const float* x, const float* v, const float* g)
+{
+    if (!ctx) return GSGD_ERR_INVALID_ARG;
+    if (!ok_matrix(x) || !ok_matrix(v) || !ok_matrix(g)) return GSGD_ERR_INVALID_ARG;
+    if (x == v || x == g || v == g) return GSGD_ERR_INVALID_ARG;
+    return GSGD_OK;
+}
+
+void release(gsgd_ctx* c)
+{
+    if (c->d_offsets) (void)hipFree(c->d_offsets);
+    if (c->d_scales) (void)hipFree(c->d_scales);
+    if (c->d_partials) (void)hipFree(c->d_partials);
+    if (c->d_result) (void)hipFree(c->d_result);
+    if (c->h_result) (void)hipHostFree(c->h_result);
+    delete c;
+}
+
+}  // namespace
+
+extern "C" int gsgd_create(const gsgd_config* cfg, gsgd_ctx** out)
+{
+    if (!cfg || !out) return GSGD_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (cfg->k < 1 || cfg->k > GSGD_MAX_K || cfg->d < 1 || cfg->ld < cfg->d || (cfg->ld & 3) != 0)
+        return GSGD_ERR_INVALID_ARG;
+    if (cfg->d > (static_cast<int64_t>(1) << 34)) return GSGD_ERR_INVALID_ARG;   // quad index is a 32-bit counter word
+    if (cfg->noise_kind != GSGD_NOISE_GAUSSIAN && cfg->noise_kind != GSGD_NOISE_UNIFORM) return GSGD_ERR_INVALID_ARG;
+    if (!(cfg->sigma >= 0.0f) || !(cfg->lr == cfg->lr) || !(cfg->momentum == cfg->momentum)) return GSGD_ERR_INVALID_ARG;
+    if (cfg->n_seg < 0) return GSGD_ERR_INVALID_ARG;
+    if (cfg->n_seg > 0) {
+        if (!cfg->seg_offsets || !cfg->seg_lr_scale) return GSGD_ERR_INVALID_ARG;
+        if (cfg->seg_offsets[0] != 0 || cfg->seg_offsets[cfg->n_seg] != cfg->d) return GSGD_ERR_BAD_SEGMENTS;
+        for (int32_t s = 0; s < cfg->n_seg; ++s)
+            if (cfg->seg_offsets[s + 1] <= cfg->seg_offsets[s]) return GSGD_ERR_BAD_SEGMENTS;
+    }
+
+    gsgd_ctx* c = new (std::nothrow) gsgd_ctx;
+    if (!c) return GSGD_ERR_NO_MEMORY;
+    memset(c, 0, sizeof(*c));
+    c->cfg = *cfg;
+    c->cfg.seg_offsets = nullptr;
+    c->cfg.seg_lr_scale = nullptr;
+
+    hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess && cfg->n_seg > 0) {
+        const size_t nb_off = sizeof(int64_t) * static_cast<size_t>(cfg->n_seg + 1);
+        const size_t nb_sc = sizeof(float) * static_cast<size_t>(cfg->n_seg);
+        e = hipMalloc(reinterpret_cast<void**>(&c->d_offsets), nb_off);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_scales), nb_sc);
+        if (e == hipSuccess) e = hipMemcpy(c->d_offsets, cfg->seg_offsets, nb_off, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(c->d_scales, cfg->seg_lr_scale, nb_sc, hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess)
+        e = hipMalloc(reinterpret_cast<void**>(&c->d_partials), sizeof(double) * 4 * static_cast<size_t>(stats_num_blocks(cfg->d)));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_result), sizeof(double) * 4);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_result), sizeof(double) * 4, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        release(c);
+        return e == hipErrorOutOfMemory ? GSGD_ERR_NO_MEMORY : GSGD_ERR_HIP;
+    }
+    *out = c;
+    return GSGD_OK;
+}
+
+extern "C" int gsgd_destroy(gsgd_ctx* ctx)
+{
+    if (!ctx) return GSGD_ERR_INVALID_ARG;
+    release(ctx);
+    return GSGD_OK;
+}
+
+extern "C" int gsgd_set_lr(gsgd_ctx* ctx, float lr)
+{
+    if (!ctx || !(lr == lr)) return GSGD_ERR_INVALID_ARG;
+    ctx->cfg.lr = lr;
+    return GSGD_OK;
+}
+
+extern "C" int gsgd_init_replicas(gsgd_ctx* ctx, float* x, float* v, float* center, const float* x0, int mode,
+                                  void* stream)
+{
+    if (!ctx || !ok_matrix(x) || !ok_matrix(v) || x == v) return GSGD_ERR_INVALID_ARG;
+    if (mode != GSGD_INIT_BROADCAST && mode != GSGD_INIT_PER_REPLICA) return GSGD_ERR_INVALID_ARG;
+    if (mode == GSGD_INIT_BROADCAST && !ok_matrix(x0)) return GSGD_ERR_INVALID_ARG;
+    if (center && !aligned16(center)) return GSGD_ERR_INVALID_ARG;
+    const hipError_t e = launch_init_replicas(geom_of(ctx), x, v, center, x0, mode, key_of(ctx),
+                                              static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_fill(gsgd_ctx* ctx, float* dst, int which, void* stream)
+{
+    if (!ctx || !ok_matrix(dst)) return GSGD_ERR_INVALID_ARG;
+    if (which != GSGD_FILL_XSTAR && which != GSGD_FILL_H && which != GSGD_FILL_X0) return GSGD_ERR_INVALID_ARG;
+    const hipError_t e = launch_fill(ctx->cfg.d, dst, which, key_of(ctx), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_gen_grad(gsgd_ctx* ctx, const float* x, const float* h, const float* xstar, float* g,
+                             uint64_t step, void* stream)
+{
+    if (!ctx || !ok_matrix(x) || !ok_matrix(g) || !ok_matrix(h) || !ok_matrix(xstar) || x == g)
+        return GSGD_ERR_INVALID_ARG;
+    if (step > 0xFFFFFFFFull) return GSGD_ERR_INVALID_ARG;
+    const hipError_t e = launch_gen_grad(geom_of(ctx), x, h, xstar, g, ctx->cfg.sigma, key_of(ctx),
+                                         static_cast<uint32_t>(step), ctx->cfg.noise_kind,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_philox_raw(gsgd_ctx* ctx, uint32_t c1, uint32_t c2, uint32_t c3, int64_t n_blocks, uint32_t* out,
+                               void* stream)
+{
+    if (!ctx || !out || n_blocks < 1 || n_blocks > (static_cast<int64_t>(1) << 32)) return GSGD_ERR_INVALID_ARG;
+    const hipError_t e = launch_philox_raw(key_of(ctx), c1, c2, c3, n_blocks, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const float* g, void* stream)
+{
+    const int rc = check_state(ctx, x, v, g);
+    if (rc != GSGD_OK) return rc;
+    const hipError_t e = launch_step_allreduce(geom_of(ctx), hyper_of(ctx), seg_of(ctx), x, v, g,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_step_gossip(gsgd_ctx* ctx, float* x, float* v, const float* g,
+                                const int32_t* peer_perm, float beta, void* stream)
+{
+    int rc = check_state(ctx, x, v, g);
+    if (rc != GSGD_OK) return rc;
+    if (!peer_perm || !(beta == beta)) return GSGD_ERR_INVALID_ARG;
+    Walk walk;
+    rc = build_walk(peer_perm, ctx->cfg.k, &walk);
+    if (rc != GSGD_OK) return rc;
+    const hipError_t e = launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, x, v, g,
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_step_gossip_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
+                                      const int32_t* peer_perm, float beta, uint64_t step, void* stream)
+{
+    if (!ctx || !ok_matrix(x) || !ok_matrix(v) || !ok_matrix(h) || !ok_matrix(xstar) || x == v)
+        return GSGD_ERR_INVALID_ARG;
+    if (!peer_perm || !(beta == beta) || step > 0xFFFFFFFFull) return GSGD_ERR_INVALID_ARG;
+    Walk walk;
+    const int rc = build_walk(peer_perm, ctx->cfg.k, &walk);
+    if (rc != GSGD_OK) return rc;
+    const hipError_t e = launch_step_gossip_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, x, v, h, xstar,
+                                                  ctx->cfg.sigma, key_of(ctx), static_cast<uint32_t>(step),
+                                                  ctx->cfg.noise_kind, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_step_easgd(gsgd_ctx* ctx, float* x, float* v, const float* g,
+                               float* center, float alpha_e, void* stream)
+{
+    const int rc = check_state(ctx, x, v, g);
+    if (rc != GSGD_OK) return rc;
+    if (!ok_matrix(center) || center == x || center == v || center == g || !(alpha_e == alpha_e))
+        return GSGD_ERR_INVALID_ARG;
+    const hipError_t e = launch_step_easgd(geom_of(ctx), hyper_of(ctx), seg_of(ctx), alpha_e, x, v, g, center,
+                                           static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_stats(gsgd_ctx* ctx, const float* x, const float* xstar, double out[4], void* stream)
+{
+    if (!ctx || !ok_matrix(x) || !ok_matrix(xstar) || !out) return GSGD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_stats(geom_of(ctx), x, xstar, ctx->d_partials, ctx->d_result, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(ctx->h_result, ctx->d_result, sizeof(double) * 4, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    for (int m = 0; m < 4; ++m) out[m] = ctx->h_result[m];
+    return GSGD_OK;
+}
+
+extern "C" const char* gsgd_strerror(int code)
+{
+    switch (code) {
+        case GSGD_OK: return "ok";
+        case GSGD_ERR_INVALID_ARG: return "invalid argument";
+        case GSGD_ERR_BAD_PERM: return "peer_perm is not a permutation of 0..k-1";
+        case GSGD_ERR_BAD_SEGMENTS: return "segment table must ascend strictly from 0 to d";
+        case GSGD_ERR_HIP: return "HIP runtime error";
+        case GSGD_ERR_UNSUPPORTED: return "unsupported";
+        case GSGD_ERR_NO_MEMORY: return "out of memory";
+        default: return "unknown error";
+    }
+}
+
+extern "C" int gsgd_last_hip_error(const gsgd_ctx* ctx) { return ctx ? ctx->last_hip : 0; }

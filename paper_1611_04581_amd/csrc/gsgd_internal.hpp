@@ -1,0 +1,68 @@
+// Host-side declarations shared by the translation units of libgsgd.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gsgd.h"
+
+namespace gsgd {
+
+// Replica visiting order of the gossip kernel, carried in the kernel-argument
+// block (uniform for the whole grid, so it lives in scalar registers).
+constexpr uint16_t WALK_ROW_MASK = 0x0FFF;
+constexpr uint16_t WALK_FIRST    = 0x4000;   // first member of a cycle
+constexpr uint16_t WALK_LAST     = 0x8000;   // last member of a cycle
+struct Walk {
+    uint16_t seq[GSGD_MAX_K];
+};
+
+// Per-layer tensor table on the device (n_seg == 0: flat, pointers unused).
+struct SegTable {
+    const int64_t* offsets;   // n_seg + 1
+    const float*   scales;    // n_seg
+    int32_t        n_seg;
+};
+
+// Problem geometry common to every kernel.
+struct Geom {
+    int32_t k;
+    int64_t d;
+    int64_t ld;
+};
+
+struct Hyper {
+    float lr, mu;
+};
+
+// Philox key and the per-call counter words.
+struct RngKey {
+    uint32_t k0, k1;
+};
+
+// ---- launchers (defined next to their kernels) ---------------------------
+hipError_t launch_step_gossip(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&,
+                              float* x, float* v, const float* g, hipStream_t);
+hipError_t launch_step_gossip_fused(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&,
+                                    float* x, float* v, const float* h, const float* xstar,
+                                    float sigma, RngKey key, uint32_t step, int noise_kind, hipStream_t);
+hipError_t launch_step_allreduce(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
+                                 hipStream_t);
+hipError_t launch_step_easgd(const Geom&, const Hyper&, const SegTable&, float alpha_e,
+                             float* x, float* v, const float* g, float* center, hipStream_t);
+hipError_t launch_gen_grad(const Geom&, const float* x, const float* h, const float* xstar, float* g,
+                           float sigma, RngKey key, uint32_t step, int noise_kind, hipStream_t);
+hipError_t launch_fill(int64_t d, float* dst, int which, RngKey key, hipStream_t);
+hipError_t launch_init_replicas(const Geom&, float* x, float* v, float* center, const float* x0, int mode,
+                                RngKey key, hipStream_t);
+hipError_t launch_philox_raw(RngKey key, uint32_t c1, uint32_t c2, uint32_t c3, int64_t n_blocks, uint32_t* out,
+                             hipStream_t);
+// stats: partials holds stats_num_blocks(d) * 4 doubles; result 4 doubles (device)
+int64_t    stats_num_blocks(int64_t d);
+hipError_t launch_stats(const Geom&, const float* x, const float* xstar, double* partials, double* result,
+                        hipStream_t);
+
+// ---- host-only helpers -----------------------------------------------------
+void host_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+int  build_walk(const int32_t* perm, int32_t k, Walk* out);   // GSGD_OK or GSGD_ERR_BAD_PERM
+
+}  // namespace gsgd

@@ -1,0 +1,157 @@
+// Generators: the shared vectors of the noisy quadratic, replica
+// initialisation, and the synthetic stochastic gradient
+//   g_i = h (.) (x_i - xstar) + sigma xi_i
+// that stands in for back-propagation (the gradient-sampling model of the
+// paper's Theorem 1).  All randomness is Philox4x32-10 keyed by the seed, with
+// counter (column / 4, replica, step, stream): one block of four words feeds
+// the four columns of a thread's quad.
+#include "device_common.hpp"
+
+namespace gsgd {
+
+constexpr int GEN_ROWS_IN_FLIGHT = 4;
+
+template <int NOISE>
+__global__ __launch_bounds__(BLOCK)
+void gen_grad_kernel(Geom geo, const float* __restrict__ x, const float* __restrict__ h,
+                     const float* __restrict__ xstar, float* __restrict__ g,
+                     float sigma, RngKey key, uint32_t step)
+{
+    const Quad qd = my_quad(geo.d);
+    if (qd.valid == 0) return;
+    const int valid = qd.valid;
+    const f32x4 h4 = load_quad_cached(h + qd.col, valid);
+    const f32x4 xs4 = load_quad_cached(xstar + qd.col, valid);
+    const float* xq = x + qd.col;
+    float* gq = g + qd.col;
+    const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
+    const int k = geo.k;
+    for (int i0 = 0; i0 < k; i0 += GEN_ROWS_IN_FLIGHT) {
+        f32x4 X[GEN_ROWS_IN_FLIGHT];
+#pragma unroll
+        for (int u = 0; u < GEN_ROWS_IN_FLIGHT; ++u)
+            if (i0 + u < k) X[u] = load_quad(xq + static_cast<int64_t>(i0 + u) * geo.ld, valid);
+#pragma unroll
+        for (int u = 0; u < GEN_ROWS_IN_FLIGHT; ++u) {
+            if (i0 + u < k) {
+                const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, static_cast<uint32_t>(i0 + u), step,
+                                                             STREAM_GRAD, key.k0, key.k1));
+                const f32x4 t1 = X[u] - xs4;
+                const f32x4 t2 = sigma * xi;
+                store_quad(gq + static_cast<int64_t>(i0 + u) * geo.ld, fma4(h4, t1, t2), valid);
+            }
+        }
+    }
+}
+
+// xstar ~ N(0,1), x0 ~ N(0,1), h = fma(0.9, u, 0.1) ~ U(0.1, 1); replica and
+// step counter words are zero for these shared vectors.
+__global__ __launch_bounds__(BLOCK)
+void fill_kernel(int64_t d, float* __restrict__ dst, uint32_t which, RngKey key)
+{
+    const Quad qd = my_quad(d);
+    if (qd.valid == 0) return;
+    const u32x4 r = philox4x32_10(static_cast<uint32_t>(qd.col >> 2), 0u, 0u, which, key.k0, key.k1);
+    f32x4 out;
+    if (which == STREAM_H) {
+        out = f32x4{__fmaf_rn(0.9f, u01(r.w[0]), 0.1f), __fmaf_rn(0.9f, u01(r.w[1]), 0.1f),
+                    __fmaf_rn(0.9f, u01(r.w[2]), 0.1f), __fmaf_rn(0.9f, u01(r.w[3]), 0.1f)};
+    } else {
+        out = noise4<GSGD_NOISE_GAUSSIAN>(r);
+    }
+    store_quad(dst + qd.col, out, qd.valid);
+}
+
+// Start of Algorithms 1-4: all replicas (and the elastic-averaging centre)
+// at one theta_0, momentum buffers at zero.  PER_REPLICA instead draws every
+// row from N(0,1) and puts the centre at the rows' mean (fp64 sum, ascending).
+template <bool PER_REPLICA>
+__global__ __launch_bounds__(BLOCK)
+void init_replicas_kernel(Geom geo, float* __restrict__ x, float* __restrict__ v, float* __restrict__ center,
+                          const float* __restrict__ x0, RngKey key)
+{
+    const Quad qd = my_quad(geo.d);
+    if (qd.valid == 0) return;
+    const int valid = qd.valid;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    float* xq = x + qd.col;
+    float* vq = v + qd.col;
+    if constexpr (PER_REPLICA) {
+        const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
+        f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+        for (int i = 0; i < geo.k; ++i) {
+            const f32x4 xi = noise4<GSGD_NOISE_GAUSSIAN>(
+                philox4x32_10(quad_index, static_cast<uint32_t>(i), 0u, STREAM_INIT, key.k0, key.k1));
+            const int64_t off = static_cast<int64_t>(i) * geo.ld;
+            store_quad(xq + off, xi, valid);
+            store_quad(vq + off, zero, valid);
+            acc.x += static_cast<double>(xi.x);
+            acc.y += static_cast<double>(xi.y);
+            acc.z += static_cast<double>(xi.z);
+            acc.w += static_cast<double>(xi.w);
+        }
+        if (center) {
+            const double kd = static_cast<double>(geo.k);
+            const f32x4 c = {static_cast<float>(acc.x / kd), static_cast<float>(acc.y / kd),
+                             static_cast<float>(acc.z / kd), static_cast<float>(acc.w / kd)};
+            store_quad(center + qd.col, c, valid);
+        }
+    } else {
+        const f32x4 x04 = load_quad_cached(x0 + qd.col, valid);
+        for (int i = 0; i < geo.k; ++i) {
+            const int64_t off = static_cast<int64_t>(i) * geo.ld;
+            store_quad(xq + off, x04, valid);
+            store_quad(vq + off, zero, valid);
+        }
+        if (center) store_quad(center + qd.col, x04, valid);
+    }
+}
+
+__global__ __launch_bounds__(BLOCK)
+void philox_raw_kernel(RngKey key, uint32_t c1, uint32_t c2, uint32_t c3, int64_t n_blocks, uint32_t* __restrict__ out)
+{
+    const int64_t q = static_cast<int64_t>(blockIdx.x) * BLOCK + threadIdx.x;
+    if (q >= n_blocks) return;
+    const u32x4 r = philox4x32_10(static_cast<uint32_t>(q), c1, c2, c3, key.k0, key.k1);
+    for (int m = 0; m < 4; ++m) out[q * 4 + m] = r.w[m];
+}
+
+hipError_t launch_philox_raw(RngKey key, uint32_t c1, uint32_t c2, uint32_t c3, int64_t n_blocks, uint32_t* out,
+                             hipStream_t stream)
+{
+    hipLaunchKernelGGL(philox_raw_kernel, dim3(static_cast<unsigned>((n_blocks + BLOCK - 1) / BLOCK)), dim3(BLOCK), 0,
+                       stream, key, c1, c2, c3, n_blocks, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_gen_grad(const Geom& geo, const float* x, const float* h, const float* xstar, float* g,
+                           float sigma, RngKey key, uint32_t step, int noise_kind, hipStream_t stream)
+{
+    if (noise_kind == GSGD_NOISE_UNIFORM)
+        hipLaunchKernelGGL(gen_grad_kernel<GSGD_NOISE_UNIFORM>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
+                           geo, x, h, xstar, g, sigma, key, step);
+    else
+        hipLaunchKernelGGL(gen_grad_kernel<GSGD_NOISE_GAUSSIAN>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
+                           geo, x, h, xstar, g, sigma, key, step);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill(int64_t d, float* dst, int which, RngKey key, hipStream_t stream)
+{
+    hipLaunchKernelGGL(fill_kernel, dim3(grid_for(d)), dim3(BLOCK), 0, stream, d, dst, static_cast<uint32_t>(which), key);
+    return hipGetLastError();
+}
+
+hipError_t launch_init_replicas(const Geom& geo, float* x, float* v, float* center, const float* x0, int mode,
+                                RngKey key, hipStream_t stream)
+{
+    if (mode == GSGD_INIT_PER_REPLICA)
+        hipLaunchKernelGGL(init_replicas_kernel<true>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
+                           geo, x, v, center, x0, key);
+    else
+        hipLaunchKernelGGL(init_replicas_kernel<false>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
+                           geo, x, v, center, x0, key);
+    return hipGetLastError();
+}
+
+}  // namespace gsgd

@@ -1,0 +1,130 @@
+// Diagnostics the paper's analysis is stated in (Section 6.1): the replicas'
+// distance to their mean ("agent consensus"), their distance to the optimum,
+// and the mean's own distance.  Not part of the timed step.
+//
+// Per column the replica mean and the squared deviations are taken in fp64 in
+// two passes over the rows (second pass re-reads x).  Across columns the
+// reduction is wavefront-wide by DPP lane exchanges, block-wide through LDS,
+// and grid-wide through a partials buffer summed by a second one-block kernel
+// in a fixed order, so the result is reproducible run to run.
+#include "device_common.hpp"
+
+namespace gsgd {
+
+// Lane exchange through the data-parallel-primitive path (no LDS traffic).
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double val)
+{
+    const long long bits = __double_as_longlong(val);
+    const int lo = __builtin_amdgcn_update_dpp(0, static_cast<int>(bits & 0xFFFFFFFFll), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, static_cast<int>(bits >> 32), CTRL, 0xF, 0xF, false);
+    return __longlong_as_double((static_cast<long long>(hi) << 32) | static_cast<unsigned int>(lo));
+}
+
+// Butterfly sum over the 64 lanes; every lane ends with the total.
+__device__ __forceinline__ double wave_sum(double val)
+{
+    val += dpp_move<0xB1>(val);     // quad_perm [1,0,3,2]: lane ^ 1
+    val += dpp_move<0x4E>(val);     // quad_perm [2,3,0,1]: lane ^ 2
+    val += dpp_move<0x141>(val);    // row_half_mirror: other quad of the half-row
+    val += dpp_move<0x140>(val);    // row_mirror: other half of the 16-lane row
+    val += __shfl_xor(val, 16, 64);
+    val += __shfl_xor(val, 32, 64);
+    return val;
+}
+
+// Sum of `val[0..3]` over the block; valid in thread 0.
+__device__ __forceinline__ void block_sum4(double val[4], double (*lds)[4])
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) val[m] = wave_sum(val[m]);
+    if (lane == 0)
+        for (int m = 0; m < 4; ++m) lds[wave][m] = val[m];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int m = 0; m < 4; ++m) {
+            double s = lds[0][m];
+            for (int wv = 1; wv < BLOCK / 64; ++wv) s += lds[wv][m];
+            val[m] = s;
+        }
+    }
+}
+
+__global__ __launch_bounds__(BLOCK)
+void stats_partial_kernel(Geom geo, const float* __restrict__ x, const float* __restrict__ xstar,
+                          double* __restrict__ partials)
+{
+    __shared__ double lds[BLOCK / 64][4];
+    const Quad qd = my_quad(geo.d);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};     // consensus, distance, mean distance, mean norm
+    if (qd.valid > 0) {
+        const int valid = qd.valid;
+        const float* xq = x + qd.col;
+        const f32x4 xs4 = load_quad_cached(xstar + qd.col, valid);
+        double sum[4] = {0.0, 0.0, 0.0, 0.0};
+        for (int i = 0; i < geo.k; ++i) {
+            const f32x4 xi = load_quad_cached(xq + static_cast<int64_t>(i) * geo.ld, valid);
+            sum[0] += static_cast<double>(xi.x);
+            sum[1] += static_cast<double>(xi.y);
+            sum[2] += static_cast<double>(xi.z);
+            sum[3] += static_cast<double>(xi.w);
+        }
+        const double kd = static_cast<double>(geo.k);
+        const double xbar[4] = {sum[0] / kd, sum[1] / kd, sum[2] / kd, sum[3] / kd};
+        const double xs[4] = {static_cast<double>(xs4.x), static_cast<double>(xs4.y),
+                              static_cast<double>(xs4.z), static_cast<double>(xs4.w)};
+        for (int i = 0; i < geo.k; ++i) {
+            const f32x4 xi = load_quad_cached(xq + static_cast<int64_t>(i) * geo.ld, valid);
+            const double xv[4] = {static_cast<double>(xi.x), static_cast<double>(xi.y),
+                                  static_cast<double>(xi.z), static_cast<double>(xi.w)};
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                if (m < valid) {
+                    const double a = xv[m] - xbar[m];
+                    const double b = xv[m] - xs[m];
+                    acc[0] += a * a;
+                    acc[1] += b * b;
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            if (m < valid) {
+                const double c = xbar[m] - xs[m];
+                acc[2] += c * c;
+                acc[3] += xbar[m] * xbar[m];
+            }
+        }
+    }
+    block_sum4(acc, lds);
+    if (threadIdx.x == 0)
+        for (int m = 0; m < 4; ++m) partials[static_cast<int64_t>(blockIdx.x) * 4 + m] = acc[m];
+}
+
+__global__ __launch_bounds__(BLOCK)
+void stats_final_kernel(int64_t n_partials, const double* __restrict__ partials, double* __restrict__ result)
+{
+    __shared__ double lds[BLOCK / 64][4];
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int64_t b = threadIdx.x; b < n_partials; b += BLOCK)
+        for (int m = 0; m < 4; ++m) acc[m] += partials[b * 4 + m];
+    block_sum4(acc, lds);
+    if (threadIdx.x == 0)
+        for (int m = 0; m < 4; ++m) result[m] = acc[m];
+}
+
+int64_t stats_num_blocks(int64_t d) { return static_cast<int64_t>(grid_for(d)); }
+
+hipError_t launch_stats(const Geom& geo, const float* x, const float* xstar, double* partials, double* result,
+                        hipStream_t stream)
+{
+    const unsigned nb = grid_for(geo.d);
+    hipLaunchKernelGGL(stats_partial_kernel, dim3(nb), dim3(BLOCK), 0, stream, geo, x, xstar, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(stats_final_kernel, dim3(1), dim3(BLOCK), 0, stream, static_cast<int64_t>(nb), partials, result);
+    return hipGetLastError();
+}
+
+}  // namespace gsgd

@@ -1,0 +1,201 @@
+"""Thin ctypes binding over libgsgd.so: argument marshalling only.
+
+Every step of the method runs in the library's HIP kernels.  PyTorch is used
+for device memory (tensors are passed as raw pointers) and for the current HIP
+stream.  There is no CPU fallback: if the library is missing or a call fails,
+an exception is raised.
+
+Names mirror include/gsgd.h without the gsgd_ prefix.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgsgd.so")
+
+MAX_K = 512
+OK, ERR_INVALID_ARG, ERR_BAD_PERM, ERR_BAD_SEGMENTS, ERR_HIP, ERR_UNSUPPORTED, ERR_NO_MEMORY = 0, -1, -2, -3, -4, -5, -6
+NOISE_GAUSSIAN, NOISE_UNIFORM = 0, 1
+INIT_BROADCAST, INIT_PER_REPLICA = 0, 1
+FILL_XSTAR, FILL_H, FILL_X0 = 2, 3, 4
+
+WALK_ROW_MASK, WALK_FIRST, WALK_LAST = 0x0FFF, 0x4000, 0x8000
+
+
+class GsgdError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (where, strerror(code), code))
+
+
+class _Config(C.Structure):
+    _fields_ = [("k", C.c_int32), ("d", C.c_int64), ("ld", C.c_int64),
+                ("lr", C.c_float), ("momentum", C.c_float), ("sigma", C.c_float),
+                ("seed", C.c_uint64), ("noise_kind", C.c_int32), ("n_seg", C.c_int32),
+                ("seg_offsets", C.POINTER(C.c_int64)), ("seg_lr_scale", C.POINTER(C.c_float))]
+
+
+_lib = None
+_vp = C.c_void_p
+
+# name -> (restype, argtypes); also the list of symbols include/gsgd.h declares
+SIGNATURES = {
+    "gsgd_create": (C.c_int, [C.POINTER(_Config), C.POINTER(_vp)]),
+    "gsgd_destroy": (C.c_int, [_vp]),
+    "gsgd_set_lr": (C.c_int, [_vp, C.c_float]),
+    "gsgd_init_replicas": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int, _vp]),
+    "gsgd_fill": (C.c_int, [_vp, _vp, C.c_int, _vp]),
+    "gsgd_gen_grad": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_uint64, _vp]),
+    "gsgd_step_allreduce": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
+    "gsgd_step_gossip": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, _vp]),
+    "gsgd_step_easgd": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_float, _vp]),
+    "gsgd_step_gossip_fused": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, C.c_uint64, _vp]),
+    "gsgd_philox_raw": (C.c_int, [_vp, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int64, _vp, _vp]),
+    "gsgd_make_perm": (C.c_int, [C.c_uint64, C.c_uint64, C.c_int32, C.POINTER(C.c_int32)]),
+    "gsgd_perm_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint16)]),
+    "gsgd_stats": (C.c_int, [_vp, _vp, _vp, C.POINTER(C.c_double), _vp]),
+    "gsgd_strerror": (C.c_char_p, [C.c_int]),
+    "gsgd_last_hip_error": (C.c_int, [_vp]),
+}
+
+
+def lib():
+    """Load libgsgd.so (after torch, so that both share one HIP runtime)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libgsgd.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                               "(there is no CPU fallback)")
+        import torch  # noqa: F401  -- loads the HIP runtime the library binds to
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def strerror(code):
+    return lib().gsgd_strerror(int(code)).decode()
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise GsgdError(rc, where)
+
+
+def _ptr(t):
+    """Raw device pointer of a torch tensor (or None)."""
+    if t is None:
+        return None
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is not None:
+        return C.c_void_p(int(stream))
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _perm_arg(peer_perm):
+    p = np.ascontiguousarray(peer_perm, dtype=np.int32)
+    return p, p.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+class Context:
+    """Owns a gsgd_ctx.  Tensors passed to the methods must be fp32 CUDA
+    tensors laid out as the header describes (k x ld rows, or d-vectors)."""
+
+    def __init__(self, k, d, ld=None, lr=0.05, momentum=0.9, sigma=0.1, seed=0x161104581,
+                 noise_kind=NOISE_GAUSSIAN, seg_offsets=None, seg_lr_scale=None):
+        ld = d if ld is None else ld
+        cfg = _Config()
+        cfg.k, cfg.d, cfg.ld = int(k), int(d), int(ld)
+        cfg.lr, cfg.momentum, cfg.sigma = float(lr), float(momentum), float(sigma)
+        cfg.seed, cfg.noise_kind = int(seed), int(noise_kind)
+        self._keep = None
+        if seg_offsets is not None:
+            off = np.ascontiguousarray(seg_offsets, dtype=np.int64)
+            sc = np.ascontiguousarray(seg_lr_scale, dtype=np.float32)
+            if off.shape[0] != sc.shape[0] + 1:
+                raise ValueError("seg_offsets must have one more entry than seg_lr_scale")
+            cfg.n_seg = int(sc.shape[0])
+            cfg.seg_offsets = off.ctypes.data_as(C.POINTER(C.c_int64))
+            cfg.seg_lr_scale = sc.ctypes.data_as(C.POINTER(C.c_float))
+            self._keep = (off, sc)
+        else:
+            cfg.n_seg = 0
+        self.k, self.d, self.ld = cfg.k, cfg.d, cfg.ld
+        self._h = _vp()
+        _check(lib().gsgd_create(C.byref(cfg), C.byref(self._h)), "gsgd_create")
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib().gsgd_destroy(self._h)
+            self._h = _vp()
+
+    __del__ = close
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def set_lr(self, lr):
+        _check(lib().gsgd_set_lr(self._h, float(lr)), "gsgd_set_lr")
+
+    def init_replicas(self, x, v, center, x0, mode=INIT_BROADCAST, stream=None):
+        _check(lib().gsgd_init_replicas(self._h, _ptr(x), _ptr(v), _ptr(center), _ptr(x0), int(mode), _stream(stream)),
+               "gsgd_init_replicas")
+
+    def fill(self, dst, which, stream=None):
+        _check(lib().gsgd_fill(self._h, _ptr(dst), int(which), _stream(stream)), "gsgd_fill")
+
+    def gen_grad(self, x, h, xstar, g, step, stream=None):
+        _check(lib().gsgd_gen_grad(self._h, _ptr(x), _ptr(h), _ptr(xstar), _ptr(g), int(step), _stream(stream)),
+               "gsgd_gen_grad")
+
+    def step_allreduce(self, x, v, g, stream=None):
+        _check(lib().gsgd_step_allreduce(self._h, _ptr(x), _ptr(v), _ptr(g), _stream(stream)), "gsgd_step_allreduce")
+
+    def step_gossip(self, x, v, g, peer_perm, beta=0.5, stream=None):
+        keep, p = _perm_arg(peer_perm)
+        _check(lib().gsgd_step_gossip(self._h, _ptr(x), _ptr(v), _ptr(g), p, float(beta), _stream(stream)),
+               "gsgd_step_gossip")
+
+    def step_easgd(self, x, v, g, center, alpha_e, stream=None):
+        _check(lib().gsgd_step_easgd(self._h, _ptr(x), _ptr(v), _ptr(g), _ptr(center), float(alpha_e),
+                                     _stream(stream)), "gsgd_step_easgd")
+
+    def step_gossip_fused(self, x, v, h, xstar, peer_perm, step, beta=0.5, stream=None):
+        keep, p = _perm_arg(peer_perm)
+        _check(lib().gsgd_step_gossip_fused(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), p, float(beta),
+                                            int(step), _stream(stream)), "gsgd_step_gossip_fused")
+
+    def philox_raw(self, c1, c2, c3, n_blocks, out, stream=None):
+        _check(lib().gsgd_philox_raw(self._h, int(c1), int(c2), int(c3), int(n_blocks), _ptr(out), _stream(stream)),
+               "gsgd_philox_raw")
+
+    def stats(self, x, xstar, stream=None):
+        out = (C.c_double * 4)()
+        _check(lib().gsgd_stats(self._h, _ptr(x), _ptr(xstar), out, _stream(stream)), "gsgd_stats")
+        return np.array(list(out), dtype=np.float64)
+
+
+def make_perm(seed, step, k):
+    out = np.empty(int(k), np.int32)
+    _check(lib().gsgd_make_perm(int(seed), int(step), int(k), out.ctypes.data_as(C.POINTER(C.c_int32))),
+           "gsgd_make_perm")
+    return out
+
+
+def perm_walk(peer_perm):
+    keep, p = _perm_arg(peer_perm)
+    out = np.empty(keep.shape[0], np.uint16)
+    _check(lib().gsgd_perm_walk(p, int(keep.shape[0]), out.ctypes.data_as(C.POINTER(C.c_uint16))), "gsgd_perm_walk")
+    return out

@@ -1,0 +1,381 @@
+"""GPU parity: every entry point of libgsgd, called through the C ABI, against
+the CPU oracle on the same seeded inputs.
+
+Bar: bit-exact for the Philox words, the permutation and everything whose
+arithmetic is fixed-order fp32/fp64 (uniform-noise gradients, the three step
+rules); the tolerance of parity_util for what involves the Gaussian transform
+(device logf/sincospif against the oracle's fp64 Box-Muller).
+"""
+import numpy as np
+import pytest
+
+from paper_1611_04581_amd import workloads as W
+from parity_util import assert_bitwise, assert_rows_close, mean_preserved
+
+pytestmark = pytest.mark.gpu
+
+SEED = 0x161104581
+# several 1024-column workgroup tiles plus a ragged tail, and the degenerate sizes
+SHAPES = [(4, 5 * 1024 + 7, None), (3, 1, 4), (1, 4, None), (7, 1023, 1024), (32, 2 * 1024 + 2, 4096), (5, 2, 8)]
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    from paper_1611_04581_amd import gsgd
+    assert torch.cuda.is_available()
+    gsgd.lib()
+    return gsgd
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def perms_for(k, oracle):
+    out = [list(range(k)), [(i + 1) % k for i in range(k)], [int(t) for t in oracle.make_perm(SEED, 3, k)]]
+    if k >= 2:
+        inv = list(range(k))
+        for a in range(0, k - 1, 2):
+            inv[a], inv[a + 1] = a + 1, a
+        out.append(inv)
+    if k >= 6:
+        # a 3-cycle, a fixed point and one long cycle over the rest
+        out.append([1, 2, 0, 3] + list(range(5, k)) + [4])
+    for p in out:
+        assert sorted(p) == list(range(k))
+    return out
+
+
+# ----------------------------------------------------------------------------
+def test_philox_words_bit_exact(G, oracle):
+    import torch
+    n = 3000
+    with G.Context(4, 64, seed=SEED) as ctx:
+        for (c1, c2, c3) in [(0, 0, 0), (3, 41, 0), (31, 199, 5), (0xFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF)]:
+            out = torch.zeros(4 * n, dtype=torch.int32, device="cuda")
+            ctx.philox_raw(c1, c2, c3, n, out)
+            got = host(out).view(np.uint32).reshape(n, 4)
+            for q in list(range(0, 40)) + list(range(n - 40, n)) + list(range(1000, 1016)):
+                want = oracle.philox4x32_10((q, c1, c2, c3), (SEED & 0xFFFFFFFF, SEED >> 32))
+                assert tuple(int(w) for w in got[q]) == want, (q, c1, c2, c3)
+
+
+def test_fill_and_init(G, oracle):
+    import torch
+    k, d, ld = 5, 3 * 1024 + 5, 3 * 1024 + 8
+    with G.Context(k, d, ld, seed=SEED) as ctx:
+        bufs = {}
+        for which in (G.FILL_XSTAR, G.FILL_H, G.FILL_X0):
+            t = torch.full((ld,), 777.0, device="cuda")
+            ctx.fill(t, which)
+            bufs[which] = host(t)
+            assert (bufs[which][d:] == 777.0).all()
+        assert_bitwise(bufs[G.FILL_H][:d], oracle.fill(d, SEED, oracle.STREAM_H), "h")
+        assert_rows_close(bufs[G.FILL_XSTAR][:d], oracle.fill(d, SEED, oracle.STREAM_XSTAR), "xstar", rtol=2e-6)
+        assert_rows_close(bufs[G.FILL_X0][:d], oracle.fill(d, SEED, oracle.STREAM_X0), "x0", rtol=2e-6)
+
+        inp = W.make_inputs(k, d, ld, seed=1)
+        x, v, c = dev(inp.x), dev(inp.v), dev(inp.center)
+        ctx.init_replicas(x, v, c, dev(inp.x0), G.INIT_BROADCAST)
+        xo, vo, co = inp.x.copy(), inp.v.copy(), inp.center.copy()
+        oracle.init_replicas(xo, vo, co, inp.x0, SEED, 0, n=d)
+        assert_bitwise(host(x), xo, "x")
+        assert_bitwise(host(v), vo, "v")
+        assert_bitwise(host(c), co, "center")
+
+        ctx.init_replicas(x, v, c, None, G.INIT_PER_REPLICA)
+        oracle.init_replicas(xo, vo, co, None, SEED, 1, n=d)
+        assert_rows_close(host(x)[:, :d], xo[:, :d], "x", rtol=2e-6)
+        assert_bitwise(host(v), vo, "v")
+        assert_rows_close(host(c)[:d], co[:d], "center", rtol=2e-6)
+        assert (host(x)[:, d:] == 777.0).all() and (host(c)[d:] == 777.0).all()
+        ctx.init_replicas(x, v, None, None, G.INIT_PER_REPLICA)     # centre is optional
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES)
+def test_gen_grad(G, oracle, k, d, ld):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=2)
+    for kind, step in ((G.NOISE_UNIFORM, 0), (G.NOISE_UNIFORM, 123456), (G.NOISE_GAUSSIAN, 7)):
+        with G.Context(k, d, ld, sigma=0.3, seed=SEED, noise_kind=kind) as ctx:
+            g = dev(inp.g)
+            ctx.gen_grad(dev(inp.x), dev(inp.h), dev(inp.xstar), g, step)
+            go = inp.g.copy()
+            oracle.gen_grad(inp.x, inp.h, inp.xstar, go, 0.3, SEED, step, kind, n=d)
+            if kind == G.NOISE_UNIFORM:
+                assert_bitwise(host(g), go, "g")
+            else:
+                assert_rows_close(host(g)[:, :d], go[:, :d], "g")
+                assert_bitwise(host(g)[:, d:], go[:, d:], "g padding")
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES)
+def test_step_gossip_bit_exact(G, oracle, k, d, ld):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=3)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9) as ctx:
+        for beta in (0.5, 0.3):
+            for perm in perms_for(k, oracle):
+                x, v = dev(inp.x), dev(inp.v)
+                ctx.step_gossip(x, v, dev(inp.g), perm, beta)
+                xo, vo = inp.x.copy(), inp.v.copy()
+                oracle.step_gossip(xo, vo, inp.g, 0.05, 0.9, beta, perm, n=d)
+                assert_bitwise(host(x), xo, "x perm=%s" % perm)
+                assert_bitwise(host(v), vo, "v")
+                # same call again from the same inputs: the in-place walk has no race
+                x2, v2 = dev(inp.x), dev(inp.v)
+                ctx.step_gossip(x2, v2, dev(inp.g), perm, beta)
+                assert_bitwise(host(x2), host(x), "x repeat")
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES)
+def test_step_allreduce_bit_exact(G, oracle, k, d, ld):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=4)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9) as ctx:
+        x, v = dev(inp.x), dev(inp.v)
+        ctx.step_allreduce(x, v, dev(inp.g))
+        xo, vo = inp.x.copy(), inp.v.copy()
+        oracle.step_allreduce(xo, vo, inp.g, 0.05, 0.9, n=d)
+        assert_bitwise(host(x), xo, "x")
+        assert_bitwise(host(v), vo, "v")
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES)
+def test_step_easgd_bit_exact(G, oracle, k, d, ld):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=5)
+    alpha_e = 0.9 / k
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9) as ctx:
+        x, v, c = dev(inp.x), dev(inp.v), dev(inp.center)
+        ctx.step_easgd(x, v, dev(inp.g), c, alpha_e)
+        xo, vo, co = inp.x.copy(), inp.v.copy(), inp.center.copy()
+        oracle.step_easgd(xo, vo, inp.g, co, 0.05, 0.9, alpha_e, n=d)
+        assert_bitwise(host(x), xo, "x")
+        assert_bitwise(host(v), vo, "v")
+        assert_bitwise(host(c), co, "center")
+
+
+@pytest.mark.parametrize("n_seg,align", [(1, 1), (37, 1), (37, 4), (100, 64), (1500, 1)])
+def test_segmented_steps_bit_exact(G, oracle, n_seg, align):
+    """Per-layer step sizes: table staged in LDS (<= 1024 segments) or searched
+    in global memory (1500), boundaries aligned to quads or not."""
+    k, d = 6, 7 * 1024 + 3
+    ld = W.round_up(d, 4)
+    off, sc = W.random_segments(d, n_seg, seed=n_seg, align=align)
+    inp = W.make_inputs(k, d, ld, seed=6)
+    lrc = oracle.expand_lr(0.05, d, off, sc)
+    perm = [int(t) for t in oracle.make_perm(SEED, 1, k)]
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, seg_offsets=off, seg_lr_scale=sc) as ctx:
+        x, v = dev(inp.x), dev(inp.v)
+        ctx.step_gossip(x, v, dev(inp.g), perm, 0.5)
+        xo, vo = inp.x.copy(), inp.v.copy()
+        oracle.step_gossip(xo, vo, inp.g, lrc, 0.9, 0.5, perm, n=d)
+        assert_bitwise(host(x), xo, "gossip x")
+        assert_bitwise(host(v), vo, "gossip v")
+
+        x, v = dev(inp.x), dev(inp.v)
+        ctx.step_allreduce(x, v, dev(inp.g))
+        xo, vo = inp.x.copy(), inp.v.copy()
+        oracle.step_allreduce(xo, vo, inp.g, lrc, 0.9, n=d)
+        assert_bitwise(host(x), xo, "allreduce x")
+        assert_bitwise(host(v), vo, "allreduce v")
+
+        x, v, c = dev(inp.x), dev(inp.v), dev(inp.center)
+        ctx.step_easgd(x, v, dev(inp.g), c, 0.1)
+        xo, vo, co = inp.x.copy(), inp.v.copy(), inp.center.copy()
+        oracle.step_easgd(xo, vo, inp.g, co, lrc, 0.9, 0.1, n=d)
+        assert_bitwise(host(x), xo, "easgd x")
+        assert_bitwise(host(c), co, "easgd center")
+
+
+def test_max_replicas(G, oracle):
+    k, d = G.MAX_K, 1024 + 4
+    inp = W.make_inputs(k, d, seed=7)
+    perm = [int(t) for t in oracle.make_perm(SEED, 9, k)]
+    with G.Context(k, d) as ctx:
+        x, v = dev(inp.x), dev(inp.v)
+        ctx.step_gossip(x, v, dev(inp.g), perm, 0.5)
+        xo, vo = inp.x.copy(), inp.v.copy()
+        oracle.step_gossip(xo, vo, inp.g, 0.05, 0.9, 0.5, perm)
+        assert_bitwise(host(x), xo, "x")
+        x, v = dev(inp.x), dev(inp.v)
+        ctx.step_allreduce(x, v, dev(inp.g))
+        xo, vo = inp.x.copy(), inp.v.copy()
+        oracle.step_allreduce(xo, vo, inp.g, 0.05, 0.9)
+        assert_bitwise(host(x), xo, "x")
+
+
+@pytest.mark.parametrize("kind", [1, 0])
+def test_fused_generator_gossip(G, oracle, kind):
+    k, d = 8, 3 * 1024 + 6
+    ld = W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=8)
+    perm = [int(t) for t in oracle.make_perm(SEED, 2, k)]
+    with G.Context(k, d, ld, sigma=0.2, seed=SEED, noise_kind=kind) as ctx:
+        h, xs = dev(inp.h), dev(inp.xstar)
+        xa, va, g = dev(inp.x), dev(inp.v), dev(inp.g)
+        ctx.gen_grad(xa, h, xs, g, 17)
+        ctx.step_gossip(xa, va, g, perm, 0.5)
+        xb, vb = dev(inp.x), dev(inp.v)
+        ctx.step_gossip_fused(xb, vb, h, xs, perm, 17, 0.5)
+        assert_bitwise(host(xb), host(xa), "fused vs two-kernel x")
+        assert_bitwise(host(vb), host(va), "fused vs two-kernel v")
+        xo, vo, go = inp.x.copy(), inp.v.copy(), inp.g.copy()
+        oracle.gen_grad(xo, inp.h, inp.xstar, go, 0.2, SEED, 17, kind, n=d)
+        oracle.step_gossip(xo, vo, go, 0.05, 0.9, 0.5, perm, n=d)
+        if kind == 1:
+            assert_bitwise(host(xb), xo, "x")
+        else:
+            assert_rows_close(host(xb)[:, :d], xo[:, :d], "x")
+
+
+def test_stats(G, oracle):
+    k, d, ld = 9, 4 * 1024 + 3, 4 * 1024 + 8
+    inp = W.make_inputs(k, d, ld, seed=9)
+    with G.Context(k, d, ld) as ctx:
+        got = ctx.stats(dev(inp.x), dev(inp.xstar))
+    want = oracle.stats(inp.x, inp.xstar, n=d)
+    assert np.allclose(got, want, rtol=1e-11, atol=0)
+    # identical rows: consensus distance exactly zero
+    inp2 = W.make_inputs(4, 1000, seed=10, identical_rows=True)
+    with G.Context(4, 1000) as ctx:
+        assert ctx.stats(dev(inp2.x), dev(inp2.xstar))[0] == 0.0
+
+
+def test_bad_arguments_leave_state_untouched(G):
+    import torch
+    k, d = 4, 1024
+    inp = W.make_inputs(k, d, seed=11)
+    with G.Context(k, d) as ctx:
+        x, v, g = dev(inp.x), dev(inp.v), dev(inp.g)
+        for bad in ([0, 1, 2, 2], [0, 1, 2, 4], [-1, 0, 1, 2]):
+            with pytest.raises(G.GsgdError) as e:
+                ctx.step_gossip(x, v, g, bad, 0.5)
+            assert e.value.code == G.ERR_BAD_PERM
+        with pytest.raises(G.GsgdError) as e:
+            ctx.step_gossip(x, v, x, [0, 1, 2, 3], 0.5)               # aliasing
+        assert e.value.code == G.ERR_INVALID_ARG
+        with pytest.raises(G.GsgdError) as e:
+            ctx.step_allreduce(x.view(-1)[1:], v, g)                   # misaligned
+        assert e.value.code == G.ERR_INVALID_ARG
+        with pytest.raises(G.GsgdError):
+            ctx.gen_grad(x, dev(inp.h), dev(inp.xstar), g, 2**32)
+        torch.cuda.synchronize()
+        assert_bitwise(host(x), inp.x, "x")
+        assert_bitwise(host(v), inp.v, "v")
+
+
+# ----------------------------------------------------------------------------
+# whole trajectories
+
+def _run_both(G, oracle, cfg, d, steps, kind, layout=None, mode=0, sigma=None):
+    """cfg-shaped run on both sides, inputs from the seeded numpy generator."""
+    k = cfg.k
+    ld = W.round_up(d, 1024)
+    sigma = cfg.sigma if sigma is None else sigma
+    inp = W.make_inputs(k, d, ld, seed=12)
+    seg = {}
+    lrc = cfg.lr
+    if layout is not None:
+        off, sc = layout
+        seg = dict(seg_offsets=off, seg_lr_scale=sc)
+        lrc = oracle.expand_lr(cfg.lr, d, off, sc)
+    xo, vo, go, co = inp.x.copy(), inp.v.copy(), inp.g.copy(), inp.center.copy()
+    oracle.init_replicas(xo, vo, co, inp.x0, cfg.seed, mode, n=d)
+    means = []
+    with G.Context(k, d, ld, lr=cfg.lr, momentum=cfg.momentum, sigma=sigma, seed=cfg.seed, noise_kind=kind, **seg) as ctx:
+        x, v, g, c = dev(inp.x), dev(inp.v), dev(inp.g), dev(inp.center)
+        h, xs = dev(inp.h), dev(inp.xstar)
+        ctx.init_replicas(x, v, c, dev(inp.x0), mode)
+        if mode == 1:                     # Gaussian init differs in the last place: start both sides from the oracle's
+            x.copy_(dev(xo)); c.copy_(dev(co))
+        for t in range(steps):
+            ctx.gen_grad(x, h, xs, g, t)
+            oracle.gen_grad(xo, inp.h, inp.xstar, go, sigma, cfg.seed, t, kind, n=d)
+            if cfg.rule == "gossip":
+                perm = G.make_perm(cfg.seed, t, k)
+                assert np.array_equal(perm, oracle.make_perm(cfg.seed, t, k))
+                ctx.step_gossip(x, v, g, perm, cfg.beta)
+                oracle.step_gossip(xo, vo, go, lrc, cfg.momentum, cfg.beta, perm, n=d)
+            elif cfg.rule == "allreduce":
+                ctx.step_allreduce(x, v, g)
+                oracle.step_allreduce(xo, vo, go, lrc, cfg.momentum, n=d)
+            else:
+                ctx.step_easgd(x, v, g, c, cfg.alpha_e)
+                oracle.step_easgd(xo, vo, go, co, lrc, cfg.momentum, cfg.alpha_e, n=d)
+        st = ctx.stats(x, xs)
+        return host(x), host(v), host(c), xo, vo, co, st, inp
+
+
+def test_tiny_config_full_trajectory(G, oracle):
+    """BASELINE config 'tiny': k=4, d=65,536, sigma=0.01, 100 gossip steps."""
+    cfg = W.CONFIGS["tiny"]
+    x, v, c, xo, vo, co, st, inp = _run_both(G, oracle, cfg, cfg.d, cfg.steps, G.NOISE_UNIFORM)
+    assert_bitwise(x, xo, "x (uniform noise: whole trajectory bit-exact)")
+    assert_bitwise(v, vo, "v")
+    x, v, c, xo, vo, co, st, inp = _run_both(G, oracle, cfg, cfg.d, cfg.steps, G.NOISE_GAUSSIAN)
+    assert_rows_close(x[:, :cfg.d], xo[:, :cfg.d], "x")
+    assert_rows_close(v[:, :cfg.d], vo[:, :cfg.d], "v", rtol=1e-5)
+    assert np.allclose(st, oracle.stats(xo, inp.xstar, n=cfg.d), rtol=1e-4)
+    # converged towards x*: distance shrank by orders of magnitude from the start
+    d0 = ((inp.x0[:cfg.d].astype(np.float64) - inp.xstar[:cfg.d]) ** 2).sum() * cfg.k
+    assert st[1] < 0.05 * d0
+
+
+@pytest.mark.parametrize("rule", ["allreduce", "easgd", "gossip_seg", "gossip_spread"])
+def test_small_trajectories_all_rules(G, oracle, rule):
+    d, steps = 9 * 1024 + 5, 40
+    if rule == "allreduce":
+        cfg = W.Config("t", "allreduce", 8, d, steps)
+        x, v, c, xo, vo, co, st, inp = _run_both(G, oracle, cfg, d, steps, G.NOISE_UNIFORM)
+        assert_bitwise(x, xo, "x"); assert_bitwise(v, vo, "v")
+        assert all(np.array_equal(x[0], x[i]) for i in range(1, cfg.k))      # identical start stays identical
+    elif rule == "easgd":
+        cfg = W.Config("t", "easgd", 16, d, steps, alpha_e=0.9 / 16)
+        x, v, c, xo, vo, co, st, inp = _run_both(G, oracle, cfg, d, steps, G.NOISE_UNIFORM)
+        assert_bitwise(x, xo, "x"); assert_bitwise(c, co, "center")
+        x, v, c, xo, vo, co, st, inp = _run_both(G, oracle, cfg, d, steps, G.NOISE_GAUSSIAN)
+        assert_rows_close(x[:, :d], xo[:, :d], "x"); assert_rows_close(c[:d], co[:d], "center")
+    elif rule == "gossip_seg":
+        cfg = W.Config("t", "gossip", 12, d, steps)
+        layout = W.random_segments(d, 50, seed=1, align=4)
+        x, v, c, xo, vo, co, st, inp = _run_both(G, oracle, cfg, d, steps, G.NOISE_UNIFORM, layout=layout)
+        assert_bitwise(x, xo, "x"); assert_bitwise(v, vo, "v")
+    else:
+        cfg = W.Config("t", "gossip", 32, d, steps)
+        x, v, c, xo, vo, co, st, inp = _run_both(G, oracle, cfg, d, steps, G.NOISE_GAUSSIAN, mode=1)
+        assert_rows_close(x[:, :d], xo[:, :d], "x")
+        so = oracle.stats(xo, inp.xstar, n=d)
+        assert np.allclose(st, so, rtol=1e-4)
+
+
+def test_gossip_preserves_replica_mean_and_shrinks_consensus(G, oracle):
+    """One call = local step then mix; the mix must not move the replica mean.
+    Compare against the same call with beta = 0 (local step only)."""
+    k, d = 32, 16 * 1024
+    inp = W.make_inputs(k, d, seed=13)
+    with G.Context(k, d) as ctx:
+        g = dev(inp.g)
+        cons = []
+        x, v = dev(inp.x), dev(inp.v)
+        xs = dev(inp.xstar)
+        cons.append(ctx.stats(x, xs)[0])
+        for t in range(6):
+            perm = G.make_perm(SEED, t, k)
+            xl, vl = x.clone(), v.clone()
+            ctx.step_gossip(xl, vl, g, perm, 0.0)          # local step only
+            ctx.step_gossip(x, v, g, perm, 0.5)
+            mean_preserved(host(xl), host(x))
+            g.zero_()                                      # pure gossip rounds after the first
+            v.zero_()
+            cons.append(ctx.stats(x, xs)[0])
+        # expected halving per round (E[M^T M] = (I + 11^T/k)/2): six rounds shrink it ~64x
+        assert cons[-1] < cons[1] / 16
+        assert all(b < a for a, b in zip(cons[1:], cons[2:]))
