@@ -18,9 +18,10 @@ constexpr int BLOCK = 256;            // threads per workgroup: 4 wavefronts of 
 // row.  A wavefront therefore streams 1 KiB contiguous per row access.
 // `valid` is 4 for a full quad and 1..3 for the ragged last quad of a row
 // whose length is not a multiple of 4.
+template <bool FULL = false>
 __device__ __forceinline__ f32x4 load_quad(const float* p, int valid)
 {
-    if (valid == 4) return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    if (FULL || valid == 4) return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
     f32x4 r = {0.f, 0.f, 0.f, 0.f};
     if (valid > 0) r.x = p[0];
     if (valid > 1) r.y = p[1];
@@ -28,9 +29,10 @@ __device__ __forceinline__ f32x4 load_quad(const float* p, int valid)
     return r;
 }
 
+template <bool FULL = false>
 __device__ __forceinline__ void store_quad(float* p, f32x4 r, int valid)
 {
-    if (valid == 4) { __builtin_nontemporal_store(r, reinterpret_cast<f32x4*>(p)); return; }
+    if (FULL || valid == 4) { __builtin_nontemporal_store(r, reinterpret_cast<f32x4*>(p)); return; }
     if (valid > 0) p[0] = r.x;
     if (valid > 1) p[1] = r.y;
     if (valid > 2) p[2] = r.z;
@@ -38,9 +40,10 @@ __device__ __forceinline__ void store_quad(float* p, f32x4 r, int valid)
 
 // Shared vectors (h, xstar, center) are read once per column and reused for
 // every replica row: ordinary cached loads.
+template <bool FULL = false>
 __device__ __forceinline__ f32x4 load_quad_cached(const float* p, int valid)
 {
-    if (valid == 4) return *reinterpret_cast<const f32x4*>(p);
+    if (FULL || valid == 4) return *reinterpret_cast<const f32x4*>(p);
     f32x4 r = {0.f, 0.f, 0.f, 0.f};
     if (valid > 0) r.x = p[0];
     if (valid > 1) r.y = p[1];
@@ -178,21 +181,34 @@ __device__ __forceinline__ f32x4 quad_lr(const SegTable& seg, const SegLds& lds,
     return seg_lookup(seg.offsets, seg.scales, seg.n_seg, col, valid, lr);
 }
 
-// Quad geometry of a thread.
+// Quad geometry of a thread.  Addresses are formed as
+//   (array + row * ld + tile_col)  +  lane_col
+// with the first part uniform over the workgroup (scalar registers, scalar
+// arithmetic) and only the small lane offset per thread, so that row accesses
+// compile to scalar-base + 32-bit-offset global loads and stores.
 struct Quad {
-    int64_t col;     // first column
-    int     valid;   // 0 (no work), 1..3 (ragged tail) or 4
+    int64_t  tile_col;   // first column of the workgroup's tile (uniform)
+    uint32_t lane_col;   // this thread's first column inside the tile
+    int64_t  col;        // tile_col + lane_col
+    int      valid;      // 0 (no work), 1..3 (ragged tail) or 4
 };
 
 __device__ __forceinline__ Quad my_quad(int64_t d)
 {
-    const int64_t q = static_cast<int64_t>(blockIdx.x) * BLOCK + threadIdx.x;
-    const int64_t col = q * 4;
-    const int64_t left = d - col;
     Quad out;
-    out.col = col;
+    out.tile_col = static_cast<int64_t>(blockIdx.x) * (BLOCK * 4);
+    out.lane_col = threadIdx.x * 4u;
+    out.col = out.tile_col + out.lane_col;
+    const int64_t left = d - out.col;
     out.valid = left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0);
     return out;
+}
+
+// True when every thread of the workgroup owns a full quad (uniform test), so
+// the body can be compiled without any per-lane tail handling.
+__device__ __forceinline__ bool tile_is_full(const Quad& qd, int64_t d)
+{
+    return qd.tile_col + static_cast<int64_t>(BLOCK) * 4 <= d;
 }
 
 inline int64_t num_quads(int64_t d) { return (d + 3) / 4; }

@@ -9,11 +9,14 @@ namespace gsgd {
 
 // Replica visiting order of the gossip kernel, carried in the kernel-argument
 // block (uniform for the whole grid, so it lives in scalar registers).
-constexpr uint16_t WALK_ROW_MASK = 0x0FFF;
-constexpr uint16_t WALK_FIRST    = 0x4000;   // first member of a cycle
-constexpr uint16_t WALK_LAST     = 0x8000;   // last member of a cycle
+// Entries are whole dwords so that the kernel fetches them with scalar loads
+// (a sub-dword element would be fetched per lane through the vector memory
+// path and its wait would drain every row load still in flight).
+constexpr uint32_t WALK_ROW_MASK = 0x0FFF;
+constexpr uint32_t WALK_FIRST    = 0x4000;   // first member of a cycle
+constexpr uint32_t WALK_LAST     = 0x8000;   // last member of a cycle
 struct Walk {
-    uint16_t seq[GSGD_MAX_K];
+    uint32_t seq[GSGD_MAX_K];
 };
 
 // Per-layer tensor table on the device (n_seg == 0: flat, pointers unused).

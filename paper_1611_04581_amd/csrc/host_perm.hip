@@ -46,7 +46,7 @@ int build_walk(const int32_t* perm, int32_t k, Walk* out)
         int32_t i = start;
         do {
             seen[i] = true;
-            out->seq[t++] = static_cast<uint16_t>(i);
+            out->seq[t++] = static_cast<uint32_t>(i);
             i = perm[i];
         } while (i != start);
         out->seq[head] |= WALK_FIRST;
@@ -81,6 +81,6 @@ extern "C" int gsgd_perm_walk(const int32_t* peer_perm, int32_t k, uint16_t* wal
     gsgd::Walk w;
     const int rc = gsgd::build_walk(peer_perm, k, &w);
     if (rc != GSGD_OK) return rc;
-    memcpy(walk, w.seq, sizeof(uint16_t) * static_cast<size_t>(k));
+    for (int32_t t = 0; t < k; ++t) walk[t] = static_cast<uint16_t>(w.seq[t]);
     return GSGD_OK;
 }

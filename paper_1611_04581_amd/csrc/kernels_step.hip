@@ -5,13 +5,32 @@
 // adjacent columns (one 128-bit lane) of all k replica rows and walks the rows.
 // A wavefront reads or writes 1 KiB contiguous per access; x, v and g are each
 // read once and x, v written once: 20 bytes per replica-element, the minimum.
+//
+// Rows are fetched in batches of U: all loads of a batch are issued before the
+// first dependent instruction, the batch loop has no conditionals around the
+// loads (the k % U leftover rows run through a batch of one), and the row
+// order comes from scalar registers, so nothing waits on the vector-memory
+// counter except the uses of the loaded rows themselves.
+#include <type_traits>
+
 #include "device_common.hpp"
 
 namespace gsgd {
 
-// Rows fetched together before any of them is processed: 3*U independent
-// 16-byte loads per lane are in flight ahead of the first dependent use.
-constexpr int ROWS_IN_FLIGHT = 4;
+#ifndef GSGD_ROWS_IN_FLIGHT
+#define GSGD_ROWS_IN_FLIGHT 4
+#endif
+
+template <int N> using Count = std::integral_constant<int, N>;
+
+// Runs body(Count<U>, t) for full batches and body(Count<1>, t) for the rest.
+template <int U, typename Body>
+__device__ __forceinline__ void for_row_batches(int k, Body&& body)
+{
+    int t = 0;
+    for (; t + U <= k; t += U) body(Count<U>{}, t);
+    for (; t < k; ++t) body(Count<1>{}, t);
+}
 
 // ---------------------------------------------------------------------------
 // Gossip.  x_new[i] needs the post-step parameters of replica i and of its
@@ -20,7 +39,62 @@ constexpr int ROWS_IN_FLIGHT = 4;
 // is the row visited now: keeping `first`, `prev` and the current x' in
 // registers is enough to finish every row in place, in one pass, without a
 // second buffer and without two replicas ever racing on a row.
-template <bool FUSED_GEN, int NOISE>
+template <bool FULL, int U, bool FUSED_GEN, int NOISE>
+__device__ __forceinline__
+void gossip_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
+                      float neg_beta, const Walk& walk,
+                      float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                      const float* __restrict__ h, const float* __restrict__ xstar,
+                      float sigma, RngKey key, uint32_t step)
+{
+    const int valid = FULL ? 4 : qd.valid;
+    const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
+    f32x4 h4 = {0.f, 0.f, 0.f, 0.f}, xs4 = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (FUSED_GEN) {
+        h4 = load_quad_cached<FULL>(h + qd.col, valid);
+        xs4 = load_quad_cached<FULL>(xstar + qd.col, valid);
+    }
+    const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
+    const float mu = hp.mu;
+
+    f32x4 first = {0.f, 0.f, 0.f, 0.f}, prev = {0.f, 0.f, 0.f, 0.f};
+    int64_t prev_off = 0;                      // uniform: row offset of the previously visited replica
+
+    for_row_batches<U>(geo.k, [&](auto n, int t0) {
+        constexpr int N = decltype(n)::value;
+        f32x4 X[N], V[N], G[N];
+        uint32_t w[N];
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            w[u] = walk.seq[t0 + u];
+            const int64_t off = static_cast<int64_t>(w[u] & WALK_ROW_MASK) * geo.ld + qd.tile_col;
+            X[u] = load_quad<FULL>(x + off + qd.lane_col, valid);
+            V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
+            if constexpr (!FUSED_GEN) G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
+        }
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const uint32_t row = w[u] & WALK_ROW_MASK;
+            const int64_t off = static_cast<int64_t>(row) * geo.ld + qd.tile_col;
+            if constexpr (FUSED_GEN) {
+                const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, row, step, STREAM_GRAD, key.k0, key.k1));
+                const f32x4 t1 = X[u] - xs4;
+                const f32x4 t2 = sigma * xi;
+                G[u] = fma4(h4, t1, t2);
+            }
+            const f32x4 vn = momentum_update(V[u], G[u], neg_lr, mu);
+            const f32x4 xp = X[u] + vn;
+            store_quad<FULL>(v + off + qd.lane_col, vn, valid);
+            if (w[u] & WALK_FIRST) first = xp;
+            else store_quad<FULL>(x + prev_off + qd.lane_col, gossip_mix(prev, xp, neg_beta), valid);
+            if (w[u] & WALK_LAST) store_quad<FULL>(x + off + qd.lane_col, gossip_mix(xp, first, neg_beta), valid);
+            prev = xp;
+            prev_off = off;
+        }
+    });
+}
+
+template <int U, bool FUSED_GEN, int NOISE>
 __global__ __launch_bounds__(BLOCK)
 void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk walk,
                         float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
@@ -30,63 +104,66 @@ void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk w
     __shared__ SegLds lds;
     stage_segments(seg, lds);
     const Quad qd = my_quad(geo.d);
-    if (qd.valid == 0) return;
-    const int valid = qd.valid;
-    const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
-    float* xq = x + qd.col;
-    float* vq = v + qd.col;
-    const float* gq = FUSED_GEN ? nullptr : g + qd.col;
-    f32x4 h4 = {0.f, 0.f, 0.f, 0.f}, xs4 = {0.f, 0.f, 0.f, 0.f};
-    if constexpr (FUSED_GEN) {
-        h4 = load_quad_cached(h + qd.col, valid);
-        xs4 = load_quad_cached(xstar + qd.col, valid);
-    }
-    const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
-
-    f32x4 first = {0.f, 0.f, 0.f, 0.f}, prev = {0.f, 0.f, 0.f, 0.f};
-    int64_t prev_off = 0;
-    const int k = geo.k;
-    for (int t0 = 0; t0 < k; t0 += ROWS_IN_FLIGHT) {
-        f32x4 X[ROWS_IN_FLIGHT], V[ROWS_IN_FLIGHT], G[ROWS_IN_FLIGHT];
-        uint32_t w[ROWS_IN_FLIGHT];
-#pragma unroll
-        for (int u = 0; u < ROWS_IN_FLIGHT; ++u) {
-            if (t0 + u < k) {
-                w[u] = walk.seq[t0 + u];
-                const int64_t off = static_cast<int64_t>(w[u] & WALK_ROW_MASK) * geo.ld;
-                X[u] = load_quad(xq + off, valid);
-                V[u] = load_quad(vq + off, valid);
-                if constexpr (!FUSED_GEN) G[u] = load_quad(gq + off, valid);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < ROWS_IN_FLIGHT; ++u) {
-            if (t0 + u < k) {
-                const uint32_t row = w[u] & WALK_ROW_MASK;
-                const int64_t off = static_cast<int64_t>(row) * geo.ld;
-                if constexpr (FUSED_GEN) {
-                    const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, row, step, STREAM_GRAD, key.k0, key.k1));
-                    const f32x4 t1 = X[u] - xs4;
-                    const f32x4 t2 = sigma * xi;
-                    G[u] = fma4(h4, t1, t2);
-                }
-                const f32x4 vn = momentum_update(V[u], G[u], neg_lr, hp.mu);
-                const f32x4 xp = X[u] + vn;
-                store_quad(vq + off, vn, valid);
-                if (w[u] & WALK_FIRST) first = xp;
-                else store_quad(xq + prev_off, gossip_mix(prev, xp, neg_beta), valid);
-                if (w[u] & WALK_LAST) store_quad(xq + off, gossip_mix(xp, first, neg_beta), valid);
-                prev = xp;
-                prev_off = off;
-            }
-        }
-    }
+    if (tile_is_full(qd, geo.d))
+        gossip_step_body<true, U, FUSED_GEN, NOISE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h, xstar,
+                                                    sigma, key, step);
+    else if (qd.valid > 0)
+        gossip_step_body<false, U, FUSED_GEN, NOISE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h, xstar,
+                                                     sigma, key, step);
 }
 
 // ---------------------------------------------------------------------------
 // All-reduce average (Algorithm 1).  Pass 1 reads v and g of every row and
 // accumulates u_i = mu v_i - lr g_i in fp64 in ascending i; pass 2 adds the
 // rounded mean to every row of x and leaves it in every row of v.
+template <bool FULL, int U>
+__device__ __forceinline__
+void allreduce_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
+                         float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g)
+{
+    const int valid = FULL ? 4 : qd.valid;
+    const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
+    const float mu = hp.mu;
+    const int k = geo.k;
+
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+    for_row_batches<2 * U>(k, [&](auto n, int i0) {
+        constexpr int N = decltype(n)::value;
+        f32x4 V[N], G[N];
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
+            V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
+            G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
+        }
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const f32x4 un = momentum_update(V[u], G[u], neg_lr, mu);
+            acc.x += static_cast<double>(un.x);
+            acc.y += static_cast<double>(un.y);
+            acc.z += static_cast<double>(un.z);
+            acc.w += static_cast<double>(un.w);
+        }
+    });
+    const double kd = static_cast<double>(k);
+    const f32x4 ubar = {static_cast<float>(acc.x / kd), static_cast<float>(acc.y / kd),
+                        static_cast<float>(acc.z / kd), static_cast<float>(acc.w / kd)};
+    for_row_batches<2 * U>(k, [&](auto n, int i0) {
+        constexpr int N = decltype(n)::value;
+        f32x4 X[N];
+#pragma unroll
+        for (int u = 0; u < N; ++u)
+            X[u] = load_quad<FULL>(x + static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col + qd.lane_col, valid);
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
+            store_quad<FULL>(v + off + qd.lane_col, ubar, valid);
+            store_quad<FULL>(x + off + qd.lane_col, X[u] + ubar, valid);
+        }
+    });
+}
+
+template <int U>
 __global__ __launch_bounds__(BLOCK)
 void allreduce_step_kernel(Geom geo, Hyper hp, SegTable seg,
                            float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g)
@@ -94,59 +171,58 @@ void allreduce_step_kernel(Geom geo, Hyper hp, SegTable seg,
     __shared__ SegLds lds;
     stage_segments(seg, lds);
     const Quad qd = my_quad(geo.d);
-    if (qd.valid == 0) return;
-    const int valid = qd.valid;
-    const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
-    float* xq = x + qd.col;
-    float* vq = v + qd.col;
-    const float* gq = g + qd.col;
-    const int k = geo.k;
-
-    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-    for (int i0 = 0; i0 < k; i0 += ROWS_IN_FLIGHT) {
-        f32x4 V[ROWS_IN_FLIGHT], G[ROWS_IN_FLIGHT];
-#pragma unroll
-        for (int u = 0; u < ROWS_IN_FLIGHT; ++u) {
-            if (i0 + u < k) {
-                const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld;
-                V[u] = load_quad(vq + off, valid);
-                G[u] = load_quad(gq + off, valid);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < ROWS_IN_FLIGHT; ++u) {
-            if (i0 + u < k) {
-                const f32x4 un = momentum_update(V[u], G[u], neg_lr, hp.mu);
-                acc.x += static_cast<double>(un.x);
-                acc.y += static_cast<double>(un.y);
-                acc.z += static_cast<double>(un.z);
-                acc.w += static_cast<double>(un.w);
-            }
-        }
-    }
-    const double kd = static_cast<double>(k);
-    const f32x4 ubar = {static_cast<float>(acc.x / kd), static_cast<float>(acc.y / kd),
-                        static_cast<float>(acc.z / kd), static_cast<float>(acc.w / kd)};
-    for (int i0 = 0; i0 < k; i0 += ROWS_IN_FLIGHT) {
-        f32x4 X[ROWS_IN_FLIGHT];
-#pragma unroll
-        for (int u = 0; u < ROWS_IN_FLIGHT; ++u)
-            if (i0 + u < k) X[u] = load_quad(xq + static_cast<int64_t>(i0 + u) * geo.ld, valid);
-#pragma unroll
-        for (int u = 0; u < ROWS_IN_FLIGHT; ++u) {
-            if (i0 + u < k) {
-                const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld;
-                store_quad(vq + off, ubar, valid);
-                store_quad(xq + off, X[u] + ubar, valid);
-            }
-        }
-    }
+    if (tile_is_full(qd, geo.d)) allreduce_step_body<true, U>(geo, hp, seg, lds, qd, x, v, g);
+    else if (qd.valid > 0) allreduce_step_body<false, U>(geo, hp, seg, lds, qd, x, v, g);
 }
 
 // ---------------------------------------------------------------------------
 // Elastic averaging (Algorithm 2, period 1, one synchronous round):
 // every client moves towards the same centre value, the centre moves by the
 // sum of what the clients gave up.
+template <bool FULL, int U>
+__device__ __forceinline__
+void easgd_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
+                     float alpha_e, float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                     float* __restrict__ center)
+{
+    const int valid = FULL ? 4 : qd.valid;
+    const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
+    const f32x4 c4 = load_quad_cached<FULL>(center + qd.col, valid);
+    const float mu = hp.mu;
+
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+    for_row_batches<U>(geo.k, [&](auto n, int i0) {
+        constexpr int N = decltype(n)::value;
+        f32x4 X[N], V[N], G[N];
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
+            X[u] = load_quad<FULL>(x + off + qd.lane_col, valid);
+            V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
+            G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
+        }
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
+            const f32x4 vn = momentum_update(V[u], G[u], neg_lr, mu);
+            const f32x4 xp = X[u] + vn;
+            const f32x4 e = alpha_e * (xp - c4);
+            store_quad<FULL>(v + off + qd.lane_col, vn, valid);
+            store_quad<FULL>(x + off + qd.lane_col, xp - e, valid);
+            acc.x += static_cast<double>(e.x);
+            acc.y += static_cast<double>(e.y);
+            acc.z += static_cast<double>(e.z);
+            acc.w += static_cast<double>(e.w);
+        }
+    });
+    const f32x4 cn = {static_cast<float>(static_cast<double>(c4.x) + acc.x),
+                      static_cast<float>(static_cast<double>(c4.y) + acc.y),
+                      static_cast<float>(static_cast<double>(c4.z) + acc.z),
+                      static_cast<float>(static_cast<double>(c4.w) + acc.w)};
+    store_quad<FULL>(center + qd.col, cn, valid);
+}
+
+template <int U>
 __global__ __launch_bounds__(BLOCK)
 void easgd_step_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e,
                        float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
@@ -155,55 +231,18 @@ void easgd_step_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e,
     __shared__ SegLds lds;
     stage_segments(seg, lds);
     const Quad qd = my_quad(geo.d);
-    if (qd.valid == 0) return;
-    const int valid = qd.valid;
-    const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
-    float* xq = x + qd.col;
-    float* vq = v + qd.col;
-    const float* gq = g + qd.col;
-    const f32x4 c4 = load_quad_cached(center + qd.col, valid);
-    const int k = geo.k;
-
-    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-    for (int i0 = 0; i0 < k; i0 += ROWS_IN_FLIGHT) {
-        f32x4 X[ROWS_IN_FLIGHT], V[ROWS_IN_FLIGHT], G[ROWS_IN_FLIGHT];
-#pragma unroll
-        for (int u = 0; u < ROWS_IN_FLIGHT; ++u) {
-            if (i0 + u < k) {
-                const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld;
-                X[u] = load_quad(xq + off, valid);
-                V[u] = load_quad(vq + off, valid);
-                G[u] = load_quad(gq + off, valid);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < ROWS_IN_FLIGHT; ++u) {
-            if (i0 + u < k) {
-                const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld;
-                const f32x4 vn = momentum_update(V[u], G[u], neg_lr, hp.mu);
-                const f32x4 xp = X[u] + vn;
-                const f32x4 e = alpha_e * (xp - c4);
-                store_quad(vq + off, vn, valid);
-                store_quad(xq + off, xp - e, valid);
-                acc.x += static_cast<double>(e.x);
-                acc.y += static_cast<double>(e.y);
-                acc.z += static_cast<double>(e.z);
-                acc.w += static_cast<double>(e.w);
-            }
-        }
-    }
-    const f32x4 cn = {static_cast<float>(static_cast<double>(c4.x) + acc.x),
-                      static_cast<float>(static_cast<double>(c4.y) + acc.y),
-                      static_cast<float>(static_cast<double>(c4.z) + acc.z),
-                      static_cast<float>(static_cast<double>(c4.w) + acc.w)};
-    store_quad(center + qd.col, cn, valid);
+    if (tile_is_full(qd, geo.d)) easgd_step_body<true, U>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
+    else if (qd.valid > 0) easgd_step_body<false, U>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
 }
 
 // ---------------------------------------------------------------------------
+#ifndef GSGD_NO_LAUNCHERS
+constexpr int RIF = GSGD_ROWS_IN_FLIGHT;
+
 hipError_t launch_step_gossip(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta, const Walk& walk,
                               float* x, float* v, const float* g, hipStream_t stream)
 {
-    hipLaunchKernelGGL((gossip_step_kernel<false, 0>), dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
+    hipLaunchKernelGGL((gossip_step_kernel<RIF, false, 0>), dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
                        geo, hp, seg, -beta, walk, x, v, g, nullptr, nullptr, 0.0f, RngKey{0u, 0u}, 0u);
     return hipGetLastError();
 }
@@ -213,10 +252,10 @@ hipError_t launch_step_gossip_fused(const Geom& geo, const Hyper& hp, const SegT
                                     float sigma, RngKey key, uint32_t step, int noise_kind, hipStream_t stream)
 {
     if (noise_kind == GSGD_NOISE_UNIFORM)
-        hipLaunchKernelGGL((gossip_step_kernel<true, GSGD_NOISE_UNIFORM>), dim3(grid_for(geo.d)), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((gossip_step_kernel<RIF, true, GSGD_NOISE_UNIFORM>), dim3(grid_for(geo.d)), dim3(BLOCK), 0,
                            stream, geo, hp, seg, -beta, walk, x, v, nullptr, h, xstar, sigma, key, step);
     else
-        hipLaunchKernelGGL((gossip_step_kernel<true, GSGD_NOISE_GAUSSIAN>), dim3(grid_for(geo.d)), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((gossip_step_kernel<RIF, true, GSGD_NOISE_GAUSSIAN>), dim3(grid_for(geo.d)), dim3(BLOCK), 0,
                            stream, geo, hp, seg, -beta, walk, x, v, nullptr, h, xstar, sigma, key, step);
     return hipGetLastError();
 }
@@ -224,16 +263,18 @@ hipError_t launch_step_gossip_fused(const Geom& geo, const Hyper& hp, const SegT
 hipError_t launch_step_allreduce(const Geom& geo, const Hyper& hp, const SegTable& seg,
                                  float* x, float* v, const float* g, hipStream_t stream)
 {
-    hipLaunchKernelGGL(allreduce_step_kernel, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream, geo, hp, seg, x, v, g);
+    hipLaunchKernelGGL(allreduce_step_kernel<RIF>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
+                       geo, hp, seg, x, v, g);
     return hipGetLastError();
 }
 
 hipError_t launch_step_easgd(const Geom& geo, const Hyper& hp, const SegTable& seg, float alpha_e,
                              float* x, float* v, const float* g, float* center, hipStream_t stream)
 {
-    hipLaunchKernelGGL(easgd_step_kernel, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
+    hipLaunchKernelGGL(easgd_step_kernel<RIF>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
                        geo, hp, seg, alpha_e, x, v, g, center);
     return hipGetLastError();
 }
+#endif  // GSGD_NO_LAUNCHERS
 
 }  // namespace gsgd
