@@ -29,7 +29,10 @@ BYTES_PER_REPLICA_ELEMENT = {   # algorithmic traffic of each kernel, fp32
 # HBM bytes per launch of the gossip kernel at the benchmark shape, from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of known
 # size (see profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/gossip_step_kernel_gossip_r50.md: FETCH_SIZE 4,791,990.5 x 2.000 KiB + WRITE_SIZE 6,389,272.9 KiB
+    "gossip_r50": (4791990.5 * 2.0 + 6389272.9) * 1024.0,
+}
 
 
 def log(*a):
@@ -44,6 +47,9 @@ def main():
     ap.add_argument("--config", default="gossip_r50")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle baseline (0 = skip)")
     ap.add_argument("--no-extras", action="store_true", help="time only the metric kernel")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain elementwise copy of a k x ld fp32 matrix (known size), so that a "
+                         "rocprofv3 --pmc run has a reference dispatch to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (k replicas live in one GPU's HBM); run with --gpus 1")
@@ -80,6 +86,13 @@ def main():
     ctx.init_replicas(x, v, center, x0, gsgd.INIT_BROADCAST)
     ctx.gen_grad(x, h, xstar, g, 0)
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        # reads k*ld*4 bytes and writes k*ld*4 bytes; g is regenerated right after
+        torch.mul(x, 1.0, out=g)
+        torch.cuda.synchronize()
+        log("calibration copy: %d bytes read, %d bytes written" % (k * ld * 4, k * ld * 4))
+        ctx.gen_grad(x, h, xstar, g, 0)
+        torch.cuda.synchronize()
     stats0 = ctx.stats(x, xstar)
 
     def one_step(t):
