@@ -55,6 +55,9 @@ enum {
 enum { GSGD_NOISE_GAUSSIAN = 0, GSGD_NOISE_UNIFORM = 1 };
 enum { GSGD_INIT_BROADCAST = 0, GSGD_INIT_PER_REPLICA = 1 };
 enum { GSGD_FILL_XSTAR = 2, GSGD_FILL_H = 3, GSGD_FILL_X0 = 4 };
+/* the streaming kernels, for gsgd_set_launch_width */
+enum { GSGD_KERNEL_GOSSIP = 0, GSGD_KERNEL_ALLREDUCE = 1, GSGD_KERNEL_EASGD = 2, GSGD_KERNEL_GEN_GRAD = 3,
+       GSGD_KERNEL_GOSSIP_FUSED = 4, GSGD_KERNEL_COUNT = 5 };
 
 typedef struct gsgd_ctx gsgd_ctx;   /* opaque; owns the segment tables and a small scratch for gsgd_stats */
 
@@ -81,6 +84,14 @@ int gsgd_destroy(gsgd_ctx* ctx);
 
 /* Change the base step size (the paper anneals alpha, Section 4.2).  Host only. */
 int gsgd_set_lr(gsgd_ctx* ctx, float lr);
+
+/* Tuning knob.  The streaming kernels run as a fixed number of persistent
+ * workgroups that pull 1024-column tiles from a ticket counter owned by the
+ * context; `workgroups` sets that number for one GSGD_KERNEL_*, 0 restores the
+ * default (a small multiple of the device's compute-unit count).  Results do
+ * not depend on it.  Because the ticket counter belongs to the context, a
+ * context must not have calls in flight on two streams at once.  Host only. */
+int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups);
 
 /* Initialisation: first line of Algorithms 1-4 (every node starts at the same
  * theta_0; the elastic-averaging server's centre starts there too).

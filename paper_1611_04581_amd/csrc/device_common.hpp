@@ -12,7 +12,10 @@ namespace gsgd {
 typedef float  f32x4 __attribute__((ext_vector_type(4)));
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BLOCK = 256;            // threads per workgroup: 4 wavefronts of 64
+#ifndef GSGD_BLOCK
+#define GSGD_BLOCK 256
+#endif
+constexpr int BLOCK = GSGD_BLOCK;     // threads per workgroup: 4 wavefronts of 64
 
 // One thread owns one "quad": four adjacent columns, one 128-bit lane of every
 // row.  A wavefront therefore streams 1 KiB contiguous per row access.
@@ -193,15 +196,51 @@ struct Quad {
     int      valid;      // 0 (no work), 1..3 (ragged tail) or 4
 };
 
-__device__ __forceinline__ Quad my_quad(int64_t d)
+__device__ __forceinline__ Quad quad_of_tile(int64_t tile, int64_t d)
 {
     Quad out;
-    out.tile_col = static_cast<int64_t>(blockIdx.x) * (BLOCK * 4);
+    out.tile_col = tile * (BLOCK * 4);
     out.lane_col = threadIdx.x * 4u;
     out.col = out.tile_col + out.lane_col;
     const int64_t left = d - out.col;
     out.valid = left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0);
     return out;
+}
+
+// One tile per workgroup, tile = workgroup index (the cold kernels).
+__device__ __forceinline__ Quad my_quad(int64_t d) { return quad_of_tile(static_cast<int64_t>(blockIdx.x), d); }
+
+// Persistent workgroups for the streaming kernels.  A launch has far fewer
+// workgroups than tiles (about one per compute unit); each pulls the next
+// 1024-column tile from a device-wide ticket counter until none are left.
+// Two reasons, both measured: (i) tiles are handed out in address order to
+// whichever compute unit is free, so the chip finishes together (a static
+// tile-to-workgroup map left half the XCDs idle for the last 8 % of the
+// kernel); (ii) with k rows per tile, few concurrent tiles keep the set of
+// DRAM pages in use small, which the HBM controller rewards.
+//   tickets[0] = next tile, tickets[1] = workgroups that have finished.
+// The last workgroup out zeroes both, so a launch leaves them as it found them.
+// Every workgroup leaves the loop after exactly one failed fetch, so the grid
+// always drains.  `body(tile)` must not return early for part of a workgroup.
+template <typename Body>
+__device__ __forceinline__ void for_each_tile(uint32_t* __restrict__ tickets, uint32_t n_tiles, Body&& body)
+{
+    __shared__ uint32_t s_tile;
+    for (;;) {
+        if (threadIdx.x == 0) s_tile = atomicAdd(&tickets[0], 1u);
+        __syncthreads();
+        const uint32_t tile = s_tile;
+        __syncthreads();
+        if (tile >= n_tiles) break;
+        body(tile);
+    }
+    if (threadIdx.x == 0) {
+        const uint32_t finished = atomicAdd(&tickets[1], 1u);
+        if (finished == gridDim.x - 1) {
+            atomicExch(&tickets[0], 0u);
+            atomicExch(&tickets[1], 0u);
+        }
+    }
 }
 
 // True when every thread of the workgroup owns a full quad (uniform test), so

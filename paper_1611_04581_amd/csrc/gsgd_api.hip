@@ -15,10 +15,17 @@ struct gsgd_ctx {
     double*     d_partials;   // stats scratch: stats_num_blocks(d) * 4 doubles
     double*     d_result;     // 4 doubles
     double*     h_result;     // pinned host, 4 doubles
+    uint32_t*   d_tickets;    // tile tickets of the persistent kernels (2 words, zero between launches)
+    int         cu_count;     // compute units of the device
+    unsigned    width[GSGD_KERNEL_COUNT];   // persistent workgroups per streaming kernel
     int         last_hip;
 };
 
 namespace {
+
+// Persistent workgroups per compute unit for each streaming kernel
+// (GSGD_KERNEL_* order).  Measured on MI355X at the benchmark shapes.
+constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 4u, 2u};
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -31,6 +38,7 @@ inline int hip_fail(gsgd_ctx* ctx, hipError_t e)
 inline Geom geom_of(const gsgd_ctx* c) { return Geom{c->cfg.k, c->cfg.d, c->cfg.ld}; }
 inline Hyper hyper_of(const gsgd_ctx* c) { return Hyper{c->cfg.lr, c->cfg.momentum}; }
 inline SegTable seg_of(const gsgd_ctx* c) { return SegTable{c->d_offsets, c->d_scales, c->cfg.n_seg}; }
+inline Persist persist_of(const gsgd_ctx* c, int kernel) { return Persist{c->d_tickets, c->width[kernel]}; }
 inline RngKey key_of(const gsgd_ctx* c)
 {
     return RngKey{static_cast<uint32_t>(c->cfg.seed), static_cast<uint32_t>(c->cfg.seed >> 32)};
@@ -54,6 +62,7 @@ void release(gsgd_ctx* c)
     if (c->d_partials) (void)hipFree(c->d_partials);
     if (c->d_result) (void)hipFree(c->d_result);
     if (c->h_result) (void)hipHostFree(c->h_result);
+    if (c->d_tickets) (void)hipFree(c->d_tickets);
     delete c;
 }
 
@@ -96,6 +105,14 @@ extern "C" int gsgd_create(const gsgd_config* cfg, gsgd_ctx** out)
         e = hipMalloc(reinterpret_cast<void**>(&c->d_partials), sizeof(double) * 4 * static_cast<size_t>(stats_num_blocks(cfg->d)));
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_result), sizeof(double) * 4);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_result), sizeof(double) * 4, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_tickets), 256);
+    if (e == hipSuccess) e = hipMemset(c->d_tickets, 0, 256);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&c->cu_count, hipDeviceAttributeMultiprocessorCount, c->device);
+    if (e == hipSuccess) {
+        if (c->cu_count < 1) c->cu_count = 1;
+        for (int kn = 0; kn < GSGD_KERNEL_COUNT; ++kn)
+            c->width[kn] = static_cast<unsigned>(c->cu_count) * DEFAULT_WORKGROUPS_PER_CU[kn];
+    }
     if (e != hipSuccess) {
         release(c);
         return e == hipErrorOutOfMemory ? GSGD_ERR_NO_MEMORY : GSGD_ERR_HIP;
@@ -115,6 +132,15 @@ extern "C" int gsgd_set_lr(gsgd_ctx* ctx, float lr)
 {
     if (!ctx || !(lr == lr)) return GSGD_ERR_INVALID_ARG;
     ctx->cfg.lr = lr;
+    return GSGD_OK;
+}
+
+extern "C" int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups)
+{
+    if (!ctx || kernel < 0 || kernel >= GSGD_KERNEL_COUNT || workgroups < 0 || workgroups > (1 << 20))
+        return GSGD_ERR_INVALID_ARG;
+    ctx->width[kernel] = workgroups > 0 ? static_cast<unsigned>(workgroups)
+                                        : static_cast<unsigned>(ctx->cu_count) * DEFAULT_WORKGROUPS_PER_CU[kernel];
     return GSGD_OK;
 }
 
@@ -146,7 +172,7 @@ extern "C" int gsgd_gen_grad(gsgd_ctx* ctx, const float* x, const float* h, cons
     if (step > 0xFFFFFFFFull) return GSGD_ERR_INVALID_ARG;
     const hipError_t e = launch_gen_grad(geom_of(ctx), x, h, xstar, g, ctx->cfg.sigma, key_of(ctx),
                                          static_cast<uint32_t>(step), ctx->cfg.noise_kind,
-                                         static_cast<hipStream_t>(stream));
+                                         persist_of(ctx, GSGD_KERNEL_GEN_GRAD), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -163,7 +189,7 @@ extern "C" int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const floa
     const int rc = check_state(ctx, x, v, g);
     if (rc != GSGD_OK) return rc;
     const hipError_t e = launch_step_allreduce(geom_of(ctx), hyper_of(ctx), seg_of(ctx), x, v, g,
-                                               static_cast<hipStream_t>(stream));
+                                               persist_of(ctx, GSGD_KERNEL_ALLREDUCE), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -177,7 +203,7 @@ extern "C" int gsgd_step_gossip(gsgd_ctx* ctx, float* x, float* v, const float* 
     rc = build_walk(peer_perm, ctx->cfg.k, &walk);
     if (rc != GSGD_OK) return rc;
     const hipError_t e = launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, x, v, g,
-                                            static_cast<hipStream_t>(stream));
+                                            persist_of(ctx, GSGD_KERNEL_GOSSIP), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -192,7 +218,8 @@ extern "C" int gsgd_step_gossip_fused(gsgd_ctx* ctx, float* x, float* v, const f
     if (rc != GSGD_OK) return rc;
     const hipError_t e = launch_step_gossip_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, x, v, h, xstar,
                                                   ctx->cfg.sigma, key_of(ctx), static_cast<uint32_t>(step),
-                                                  ctx->cfg.noise_kind, static_cast<hipStream_t>(stream));
+                                                  ctx->cfg.noise_kind, persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED),
+                                                  static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -204,7 +231,7 @@ extern "C" int gsgd_step_easgd(gsgd_ctx* ctx, float* x, float* v, const float* g
     if (!ok_matrix(center) || center == x || center == v || center == g || !(alpha_e == alpha_e))
         return GSGD_ERR_INVALID_ARG;
     const hipError_t e = launch_step_easgd(geom_of(ctx), hyper_of(ctx), seg_of(ctx), alpha_e, x, v, g, center,
-                                           static_cast<hipStream_t>(stream));
+                                           persist_of(ctx, GSGD_KERNEL_EASGD), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 

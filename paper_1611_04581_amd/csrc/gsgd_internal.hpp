@@ -42,18 +42,26 @@ struct RngKey {
     uint32_t k0, k1;
 };
 
+// How a streaming kernel is launched: `workgroups` persistent workgroups that
+// pull tiles through the two ticket words at `tickets` (device memory, both
+// zero between launches).
+struct Persist {
+    uint32_t* tickets;
+    unsigned  workgroups;
+};
+
 // ---- launchers (defined next to their kernels) ---------------------------
 hipError_t launch_step_gossip(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&,
-                              float* x, float* v, const float* g, hipStream_t);
+                              float* x, float* v, const float* g, Persist, hipStream_t);
 hipError_t launch_step_gossip_fused(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&,
                                     float* x, float* v, const float* h, const float* xstar,
-                                    float sigma, RngKey key, uint32_t step, int noise_kind, hipStream_t);
+                                    float sigma, RngKey key, uint32_t step, int noise_kind, Persist, hipStream_t);
 hipError_t launch_step_allreduce(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
-                                 hipStream_t);
+                                 Persist, hipStream_t);
 hipError_t launch_step_easgd(const Geom&, const Hyper&, const SegTable&, float alpha_e,
-                             float* x, float* v, const float* g, float* center, hipStream_t);
+                             float* x, float* v, const float* g, float* center, Persist, hipStream_t);
 hipError_t launch_gen_grad(const Geom&, const float* x, const float* h, const float* xstar, float* g,
-                           float sigma, RngKey key, uint32_t step, int noise_kind, hipStream_t);
+                           float sigma, RngKey key, uint32_t step, int noise_kind, Persist, hipStream_t);
 hipError_t launch_fill(int64_t d, float* dst, int which, RngKey key, hipStream_t);
 hipError_t launch_init_replicas(const Geom&, float* x, float* v, float* center, const float* x0, int mode,
                                 RngKey key, hipStream_t);

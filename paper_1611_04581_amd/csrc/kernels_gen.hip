@@ -15,10 +15,11 @@ template <int NOISE>
 __global__ __launch_bounds__(BLOCK)
 void gen_grad_kernel(Geom geo, const float* __restrict__ x, const float* __restrict__ h,
                      const float* __restrict__ xstar, float* __restrict__ g,
-                     float sigma, RngKey key, uint32_t step)
+                     float sigma, RngKey key, uint32_t step, uint32_t* __restrict__ tickets, uint32_t n_tiles)
 {
-    const Quad qd = my_quad(geo.d);
-    if (qd.valid == 0) return;
+  for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
+    const Quad qd = quad_of_tile(tile, geo.d);
+    if (qd.valid == 0) return;            // leaves the lambda only; the tile loop goes on for the whole workgroup
     const int valid = qd.valid;
     const f32x4 h4 = load_quad_cached(h + qd.col, valid);
     const f32x4 xs4 = load_quad_cached(xstar + qd.col, valid);
@@ -42,6 +43,7 @@ void gen_grad_kernel(Geom geo, const float* __restrict__ x, const float* __restr
             }
         }
     }
+  });
 }
 
 // xstar ~ N(0,1), x0 ~ N(0,1), h = fma(0.9, u, 0.1) ~ U(0.1, 1); replica and
@@ -125,14 +127,16 @@ hipError_t launch_philox_raw(RngKey key, uint32_t c1, uint32_t c2, uint32_t c3, 
 }
 
 hipError_t launch_gen_grad(const Geom& geo, const float* x, const float* h, const float* xstar, float* g,
-                           float sigma, RngKey key, uint32_t step, int noise_kind, hipStream_t stream)
+                           float sigma, RngKey key, uint32_t step, int noise_kind, Persist p, hipStream_t stream)
 {
+    const unsigned tiles = grid_for(geo.d);
+    const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
     if (noise_kind == GSGD_NOISE_UNIFORM)
-        hipLaunchKernelGGL(gen_grad_kernel<GSGD_NOISE_UNIFORM>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
-                           geo, x, h, xstar, g, sigma, key, step);
+        hipLaunchKernelGGL(gen_grad_kernel<GSGD_NOISE_UNIFORM>, dim3(width), dim3(BLOCK), 0, stream,
+                           geo, x, h, xstar, g, sigma, key, step, p.tickets, tiles);
     else
-        hipLaunchKernelGGL(gen_grad_kernel<GSGD_NOISE_GAUSSIAN>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
-                           geo, x, h, xstar, g, sigma, key, step);
+        hipLaunchKernelGGL(gen_grad_kernel<GSGD_NOISE_GAUSSIAN>, dim3(width), dim3(BLOCK), 0, stream,
+                           geo, x, h, xstar, g, sigma, key, step, p.tickets, tiles);
     return hipGetLastError();
 }
 

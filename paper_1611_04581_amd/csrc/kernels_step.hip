@@ -99,17 +99,19 @@ __global__ __launch_bounds__(BLOCK)
 void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk walk,
                         float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
                         const float* __restrict__ h, const float* __restrict__ xstar,
-                        float sigma, RngKey key, uint32_t step)
+                        float sigma, RngKey key, uint32_t step, uint32_t* __restrict__ tickets, uint32_t n_tiles)
 {
     __shared__ SegLds lds;
     stage_segments(seg, lds);
-    const Quad qd = my_quad(geo.d);
-    if (tile_is_full(qd, geo.d))
-        gossip_step_body<true, U, FUSED_GEN, NOISE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h, xstar,
-                                                    sigma, key, step);
-    else if (qd.valid > 0)
-        gossip_step_body<false, U, FUSED_GEN, NOISE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h, xstar,
-                                                     sigma, key, step);
+    for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
+        const Quad qd = quad_of_tile(tile, geo.d);
+        if (tile_is_full(qd, geo.d))
+            gossip_step_body<true, U, FUSED_GEN, NOISE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h, xstar,
+                                                        sigma, key, step);
+        else if (qd.valid > 0)
+            gossip_step_body<false, U, FUSED_GEN, NOISE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h, xstar,
+                                                         sigma, key, step);
+    });
 }
 
 // ---------------------------------------------------------------------------
@@ -166,13 +168,16 @@ void allreduce_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, 
 template <int U>
 __global__ __launch_bounds__(BLOCK)
 void allreduce_step_kernel(Geom geo, Hyper hp, SegTable seg,
-                           float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g)
+                           float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                           uint32_t* __restrict__ tickets, uint32_t n_tiles)
 {
     __shared__ SegLds lds;
     stage_segments(seg, lds);
-    const Quad qd = my_quad(geo.d);
-    if (tile_is_full(qd, geo.d)) allreduce_step_body<true, U>(geo, hp, seg, lds, qd, x, v, g);
-    else if (qd.valid > 0) allreduce_step_body<false, U>(geo, hp, seg, lds, qd, x, v, g);
+    for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
+        const Quad qd = quad_of_tile(tile, geo.d);
+        if (tile_is_full(qd, geo.d)) allreduce_step_body<true, U>(geo, hp, seg, lds, qd, x, v, g);
+        else if (qd.valid > 0) allreduce_step_body<false, U>(geo, hp, seg, lds, qd, x, v, g);
+    });
 }
 
 // ---------------------------------------------------------------------------
@@ -226,53 +231,66 @@ template <int U>
 __global__ __launch_bounds__(BLOCK)
 void easgd_step_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e,
                        float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
-                       float* __restrict__ center)
+                       float* __restrict__ center, uint32_t* __restrict__ tickets, uint32_t n_tiles)
 {
     __shared__ SegLds lds;
     stage_segments(seg, lds);
-    const Quad qd = my_quad(geo.d);
-    if (tile_is_full(qd, geo.d)) easgd_step_body<true, U>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
-    else if (qd.valid > 0) easgd_step_body<false, U>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
+    for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
+        const Quad qd = quad_of_tile(tile, geo.d);
+        if (tile_is_full(qd, geo.d)) easgd_step_body<true, U>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
+        else if (qd.valid > 0) easgd_step_body<false, U>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
+    });
 }
 
 // ---------------------------------------------------------------------------
 #ifndef GSGD_NO_LAUNCHERS
 constexpr int RIF = GSGD_ROWS_IN_FLIGHT;
 
-hipError_t launch_step_gossip(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta, const Walk& walk,
-                              float* x, float* v, const float* g, hipStream_t stream)
+// Persistent launch: never more workgroups than tiles.
+static inline unsigned width_for(const Geom& geo, const Persist& p)
 {
-    hipLaunchKernelGGL((gossip_step_kernel<RIF, false, 0>), dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
-                       geo, hp, seg, -beta, walk, x, v, g, nullptr, nullptr, 0.0f, RngKey{0u, 0u}, 0u);
+    const unsigned tiles = grid_for(geo.d);
+    return p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
+}
+
+hipError_t launch_step_gossip(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta, const Walk& walk,
+                              float* x, float* v, const float* g, Persist p, hipStream_t stream)
+{
+    hipLaunchKernelGGL((gossip_step_kernel<RIF, false, 0>), dim3(width_for(geo, p)), dim3(BLOCK), 0, stream,
+                       geo, hp, seg, -beta, walk, x, v, g, nullptr, nullptr, 0.0f, RngKey{0u, 0u}, 0u,
+                       p.tickets, grid_for(geo.d));
     return hipGetLastError();
 }
 
 hipError_t launch_step_gossip_fused(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta,
                                     const Walk& walk, float* x, float* v, const float* h, const float* xstar,
-                                    float sigma, RngKey key, uint32_t step, int noise_kind, hipStream_t stream)
+                                    float sigma, RngKey key, uint32_t step, int noise_kind, Persist p,
+                                    hipStream_t stream)
 {
     if (noise_kind == GSGD_NOISE_UNIFORM)
-        hipLaunchKernelGGL((gossip_step_kernel<RIF, true, GSGD_NOISE_UNIFORM>), dim3(grid_for(geo.d)), dim3(BLOCK), 0,
-                           stream, geo, hp, seg, -beta, walk, x, v, nullptr, h, xstar, sigma, key, step);
+        hipLaunchKernelGGL((gossip_step_kernel<RIF, true, GSGD_NOISE_UNIFORM>), dim3(width_for(geo, p)), dim3(BLOCK), 0,
+                           stream, geo, hp, seg, -beta, walk, x, v, nullptr, h, xstar, sigma, key, step,
+                           p.tickets, grid_for(geo.d));
     else
-        hipLaunchKernelGGL((gossip_step_kernel<RIF, true, GSGD_NOISE_GAUSSIAN>), dim3(grid_for(geo.d)), dim3(BLOCK), 0,
-                           stream, geo, hp, seg, -beta, walk, x, v, nullptr, h, xstar, sigma, key, step);
+        hipLaunchKernelGGL((gossip_step_kernel<RIF, true, GSGD_NOISE_GAUSSIAN>), dim3(width_for(geo, p)), dim3(BLOCK), 0,
+                           stream, geo, hp, seg, -beta, walk, x, v, nullptr, h, xstar, sigma, key, step,
+                           p.tickets, grid_for(geo.d));
     return hipGetLastError();
 }
 
 hipError_t launch_step_allreduce(const Geom& geo, const Hyper& hp, const SegTable& seg,
-                                 float* x, float* v, const float* g, hipStream_t stream)
+                                 float* x, float* v, const float* g, Persist p, hipStream_t stream)
 {
-    hipLaunchKernelGGL(allreduce_step_kernel<RIF>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
-                       geo, hp, seg, x, v, g);
+    hipLaunchKernelGGL(allreduce_step_kernel<RIF>, dim3(width_for(geo, p)), dim3(BLOCK), 0, stream,
+                       geo, hp, seg, x, v, g, p.tickets, grid_for(geo.d));
     return hipGetLastError();
 }
 
 hipError_t launch_step_easgd(const Geom& geo, const Hyper& hp, const SegTable& seg, float alpha_e,
-                             float* x, float* v, const float* g, float* center, hipStream_t stream)
+                             float* x, float* v, const float* g, float* center, Persist p, hipStream_t stream)
 {
-    hipLaunchKernelGGL(easgd_step_kernel<RIF>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
-                       geo, hp, seg, alpha_e, x, v, g, center);
+    hipLaunchKernelGGL(easgd_step_kernel<RIF>, dim3(width_for(geo, p)), dim3(BLOCK), 0, stream,
+                       geo, hp, seg, alpha_e, x, v, g, center, p.tickets, grid_for(geo.d));
     return hipGetLastError();
 }
 #endif  // GSGD_NO_LAUNCHERS

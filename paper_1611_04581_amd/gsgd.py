@@ -21,6 +21,7 @@ NOISE_GAUSSIAN, NOISE_UNIFORM = 0, 1
 INIT_BROADCAST, INIT_PER_REPLICA = 0, 1
 FILL_XSTAR, FILL_H, FILL_X0 = 2, 3, 4
 
+KERNEL_GOSSIP, KERNEL_ALLREDUCE, KERNEL_EASGD, KERNEL_GEN_GRAD, KERNEL_GOSSIP_FUSED = range(5)
 WALK_ROW_MASK, WALK_FIRST, WALK_LAST = 0x0FFF, 0x4000, 0x8000
 
 
@@ -45,6 +46,7 @@ SIGNATURES = {
     "gsgd_create": (C.c_int, [C.POINTER(_Config), C.POINTER(_vp)]),
     "gsgd_destroy": (C.c_int, [_vp]),
     "gsgd_set_lr": (C.c_int, [_vp, C.c_float]),
+    "gsgd_set_launch_width": (C.c_int, [_vp, C.c_int, C.c_int]),
     "gsgd_init_replicas": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int, _vp]),
     "gsgd_fill": (C.c_int, [_vp, _vp, C.c_int, _vp]),
     "gsgd_gen_grad": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_uint64, _vp]),
@@ -148,6 +150,9 @@ class Context:
 
     def set_lr(self, lr):
         _check(lib().gsgd_set_lr(self._h, float(lr)), "gsgd_set_lr")
+
+    def set_launch_width(self, kernel, workgroups):
+        _check(lib().gsgd_set_launch_width(self._h, int(kernel), int(workgroups)), "gsgd_set_launch_width")
 
     def init_replicas(self, x, v, center, x0, mode=INIT_BROADCAST, stream=None):
         _check(lib().gsgd_init_replicas(self._h, _ptr(x), _ptr(v), _ptr(center), _ptr(x0), int(mode), _stream(stream)),

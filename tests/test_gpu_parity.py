@@ -379,3 +379,40 @@ def test_gossip_preserves_replica_mean_and_shrinks_consensus(G, oracle):
         # expected halving per round (E[M^T M] = (I + 11^T/k)/2): six rounds shrink it ~64x
         assert cons[-1] < cons[1] / 16
         assert all(b < a for a, b in zip(cons[1:], cons[2:]))
+
+
+@pytest.mark.parametrize("width", [1, 3, 255, 100000])
+def test_results_do_not_depend_on_launch_width(G, oracle, width):
+    """The streaming kernels run as `width` persistent workgroups pulling tiles
+    from a ticket counter; any width (fewer or more workgroups than tiles) must
+    give the oracle's bits, call after call (the counter resets itself)."""
+    k, d = 6, 9 * 1024 + 5
+    ld = W.round_up(d, 4)
+    off, sc = W.random_segments(d, 23, seed=5, align=1)
+    lrc = oracle.expand_lr(0.05, d, off, sc)
+    inp = W.make_inputs(k, d, ld, seed=14)
+    perm = [int(t) for t in oracle.make_perm(SEED, 4, k)]
+    with G.Context(k, d, ld, sigma=0.2, seed=SEED, noise_kind=G.NOISE_UNIFORM, seg_offsets=off, seg_lr_scale=sc) as ctx:
+        for kern in (G.KERNEL_GOSSIP, G.KERNEL_ALLREDUCE, G.KERNEL_EASGD, G.KERNEL_GEN_GRAD, G.KERNEL_GOSSIP_FUSED):
+            ctx.set_launch_width(kern, width)
+        h, xs = dev(inp.h), dev(inp.xstar)
+        x, v, g, c = dev(inp.x), dev(inp.v), dev(inp.g), dev(inp.center)
+        xo, vo, go, co = inp.x.copy(), inp.v.copy(), inp.g.copy(), inp.center.copy()
+        for t in range(3):
+            ctx.gen_grad(x, h, xs, g, t)
+            ctx.step_gossip(x, v, g, perm, 0.5)
+            ctx.step_allreduce(x, v, g)
+            ctx.step_easgd(x, v, g, c, 0.1)
+            ctx.step_gossip_fused(x, v, h, xs, perm, 100 + t, 0.5)
+            oracle.gen_grad(xo, inp.h, inp.xstar, go, 0.2, SEED, t, 1, n=d)
+            oracle.step_gossip(xo, vo, go, lrc, 0.9, 0.5, perm, n=d)
+            oracle.step_allreduce(xo, vo, go, lrc, 0.9, n=d)
+            oracle.step_easgd(xo, vo, go, co, lrc, 0.9, 0.1, n=d)
+            oracle.gen_grad(xo, inp.h, inp.xstar, go, 0.2, SEED, 100 + t, 1, n=d)
+            oracle.step_gossip(xo, vo, go, lrc, 0.9, 0.5, perm, n=d)
+        assert_bitwise(host(x), xo, "x")
+        assert_bitwise(host(v), vo, "v")
+        assert_bitwise(host(c), co, "center")
+        with pytest.raises(G.GsgdError):
+            ctx.set_launch_width(9, 1)
+        ctx.set_launch_width(G.KERNEL_GOSSIP, 0)          # back to the default
