@@ -314,6 +314,125 @@ int oracle_step_easgd(float* x, float* v, const float* g, float* center, int32_t
 }
 
 /* ------------------------------------------------------------------------ */
+/* Variants the paper's experiments and appendix use beyond the algorithm boxes
+ * (Section 4.2: Nesterov momentum 0.9 and weight decay 1e-4; Section 6.2.1:
+ * gossip with stale parameters).  The functions above are the special case
+ * wd = 0, nesterov = 0, stale = 0 of the ones below (a test checks bit equality).
+ *
+ * Local step with weight decay and optional Nesterov momentum, in the usual
+ * "momentum buffer" form:
+ *   gt = g + wd x;   v' = mu v - lr gt;
+ *   heavy ball: x' = x + v'        Nesterov: x' = (x - lr gt) + mu v'           */
+static inline void local_step_ext(float x, float v, float g, float lr, float mu, float wd, int nesterov,
+                                  float* v_new, float* x_post)
+{
+    const float gt = fmaf(wd, x, g);
+    const float t3 = mu * v;
+    const float vn = fmaf(-lr, gt, t3);
+    *v_new = vn;
+    if (nesterov) {
+        const float t4 = fmaf(-lr, gt, x);
+        *x_post = fmaf(mu, vn, t4);
+    } else {
+        *x_post = x + vn;
+    }
+}
+
+/* Gossip with fresh (stale = 0, Section 6.2.2) or stale (stale = 1, Section
+ * 6.2.1) parameters.  Stale: the mixing term uses the parameters from before
+ * the local step, theta_{t+1,i} = theta'_i - beta (theta_{t,i} - theta_{t,peer}). */
+int oracle_step_gossip_ext(float* x, float* v, const float* g, int32_t k, int64_t n, int64_t ld,
+                           const float* lr_col, float mu, float wd, int nesterov, float beta,
+                           const int32_t* peer, int stale)
+{
+    for (int32_t i = 0; i < k; ++i) if (peer[i] < 0 || peer[i] >= k) return -1;
+    float* xp = (float*)malloc(sizeof(float) * (size_t)k * (size_t)n);
+    float* xo = (float*)malloc(sizeof(float) * (size_t)k * (size_t)n);
+    if (!xp || !xo) { free(xp); free(xo); return -2; }
+    for (int32_t i = 0; i < k; ++i) {
+        #pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < n; ++j) {
+            float vn, xpost;
+            local_step_ext(x[i * ld + j], v[i * ld + j], g[i * ld + j], lr_col[j], mu, wd, nesterov, &vn, &xpost);
+            xo[(int64_t)i * n + j] = x[i * ld + j];
+            v[i * ld + j] = vn;
+            xp[(int64_t)i * n + j] = xpost;
+        }
+    }
+    const float* mixed = stale ? xo : xp;
+    for (int32_t i = 0; i < k; ++i) {
+        const int32_t p = peer[i];
+        #pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < n; ++j) {
+            const float diff = mixed[(int64_t)i * n + j] - mixed[(int64_t)p * n + j];
+            x[i * ld + j] = fmaf(-beta, diff, xp[(int64_t)i * n + j]);
+        }
+    }
+    free(xp); free(xo);
+    return 0;
+}
+
+/* All-reduce (Algorithm 1) with the extended local step: every node's momentum
+ * buffer and the update it applies to theta are both averaged over the nodes.
+ *   heavy ball: applied update d_i = v'_i;  Nesterov: d_i = mu v'_i - lr gt_i
+ *   v_i <- mean_i v'_i;  theta_i <- theta_i + mean_i d_i                          */
+int oracle_step_allreduce_ext(float* x, float* v, const float* g, int32_t k, int64_t n, int64_t ld,
+                              const float* lr_col, float mu, float wd, int nesterov)
+{
+    double* acc_v = (double*)calloc((size_t)n, sizeof(double));
+    double* acc_d = (double*)calloc((size_t)n, sizeof(double));
+    if (!acc_v || !acc_d) { free(acc_v); free(acc_d); return -2; }
+    for (int32_t i = 0; i < k; ++i) {
+        #pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < n; ++j) {
+            const float xi = x[i * ld + j];
+            const float gt = fmaf(wd, xi, g[i * ld + j]);
+            const float t3 = mu * v[i * ld + j];
+            const float vn = fmaf(-lr_col[j], gt, t3);
+            float di = vn;
+            if (nesterov) { const float t5 = mu * vn; di = fmaf(-lr_col[j], gt, t5); }
+            acc_v[j] += (double)vn;
+            acc_d[j] += (double)di;
+        }
+    }
+    for (int32_t i = 0; i < k; ++i) {
+        #pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < n; ++j) {
+            const float vbar = (float)(acc_v[j] / (double)k);
+            const float dbar = (float)(acc_d[j] / (double)k);
+            v[i * ld + j] = vbar;
+            x[i * ld + j] = x[i * ld + j] + dbar;
+        }
+    }
+    free(acc_v); free(acc_d);
+    return 0;
+}
+
+/* Elastic averaging (Algorithm 2) with the extended local step. */
+int oracle_step_easgd_ext(float* x, float* v, const float* g, float* center, int32_t k, int64_t n, int64_t ld,
+                          const float* lr_col, float mu, float wd, int nesterov, float alpha_e)
+{
+    double* acc = (double*)calloc((size_t)n, sizeof(double));
+    if (!acc) return -2;
+    for (int32_t i = 0; i < k; ++i) {
+        #pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < n; ++j) {
+            float vn, xp;
+            local_step_ext(x[i * ld + j], v[i * ld + j], g[i * ld + j], lr_col[j], mu, wd, nesterov, &vn, &xp);
+            const float e = alpha_e * (xp - center[j]);
+            v[i * ld + j] = vn;
+            x[i * ld + j] = xp - e;
+            acc[j] += (double)e;
+        }
+    }
+    #pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n; ++j)
+        center[j] = (float)((double)center[j] + acc[j]);
+    free(acc);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
 /* Peer permutation for one step: Fisher-Yates driven by Philox stream PERM.
  * For i = k-1 .. 1: r = word 0 of Philox(counter (i, 0, step, PERM), seed);
  * j = floor(r (i+1) / 2^32); swap p[i], p[j].  Integer only.                 */

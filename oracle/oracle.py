@@ -55,6 +55,15 @@ def lib():
         L.oracle_step_easgd.argtypes = [_f32p, _f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f32p,
                                         C.c_float, C.c_float]
         L.oracle_step_easgd.restype = C.c_int
+        L.oracle_step_gossip_ext.argtypes = [_f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f32p,
+                                             C.c_float, C.c_float, C.c_int, C.c_float, _i32p, C.c_int]
+        L.oracle_step_gossip_ext.restype = C.c_int
+        L.oracle_step_allreduce_ext.argtypes = [_f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f32p,
+                                                C.c_float, C.c_float, C.c_int]
+        L.oracle_step_allreduce_ext.restype = C.c_int
+        L.oracle_step_easgd_ext.argtypes = [_f32p, _f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f32p,
+                                            C.c_float, C.c_float, C.c_int, C.c_float]
+        L.oracle_step_easgd_ext.restype = C.c_int
         L.oracle_make_perm.argtypes = [C.c_uint64, C.c_uint32, C.c_int32, _i32p]
         L.oracle_make_perm.restype = C.c_int
         L.oracle_stats.argtypes = [_f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f64p]
@@ -170,6 +179,38 @@ def step_easgd(x, v, g, center, lr, mu, alpha_e, n=None):
                                  float(mu), float(alpha_e))
     if rc:
         raise ValueError("oracle_step_easgd failed (%d)" % rc)
+
+
+def step_gossip_ext(x, v, g, lr, mu, beta, peer, wd=0.0, nesterov=False, stale=False, n=None):
+    k, ld = _rows(x)
+    n = ld if n is None else int(n)
+    lrc = _lr_col(lr, n)
+    p = np.ascontiguousarray(peer, dtype=np.int32)
+    assert p.shape[0] == k
+    rc = lib().oracle_step_gossip_ext(_f32(x), _f32(v), _f32(g), k, n, ld, _f32(lrc), float(mu), float(wd),
+                                      int(bool(nesterov)), float(beta), p.ctypes.data_as(_i32p), int(bool(stale)))
+    if rc:
+        raise ValueError("oracle_step_gossip_ext failed (%d)" % rc)
+
+
+def step_allreduce_ext(x, v, g, lr, mu, wd=0.0, nesterov=False, n=None):
+    k, ld = _rows(x)
+    n = ld if n is None else int(n)
+    lrc = _lr_col(lr, n)
+    rc = lib().oracle_step_allreduce_ext(_f32(x), _f32(v), _f32(g), k, n, ld, _f32(lrc), float(mu), float(wd),
+                                         int(bool(nesterov)))
+    if rc:
+        raise ValueError("oracle_step_allreduce_ext failed (%d)" % rc)
+
+
+def step_easgd_ext(x, v, g, center, lr, mu, alpha_e, wd=0.0, nesterov=False, n=None):
+    k, ld = _rows(x)
+    n = ld if n is None else int(n)
+    lrc = _lr_col(lr, n)
+    rc = lib().oracle_step_easgd_ext(_f32(x), _f32(v), _f32(g), _f32(center), k, n, ld, _f32(lrc), float(mu),
+                                     float(wd), int(bool(nesterov)), float(alpha_e))
+    if rc:
+        raise ValueError("oracle_step_easgd_ext failed (%d)" % rc)
 
 
 def make_perm(seed, step, k):

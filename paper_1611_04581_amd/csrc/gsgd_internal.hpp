@@ -15,6 +15,13 @@ namespace gsgd {
 constexpr uint32_t WALK_ROW_MASK = 0x0FFF;
 constexpr uint32_t WALK_FIRST    = 0x4000;   // first member of a cycle
 constexpr uint32_t WALK_LAST     = 0x8000;   // last member of a cycle
+// General pull maps (several replicas may pull from the same one) add tree
+// nodes hanging off the cycles: a tree node's peer is its parent, whose x' is
+// the cycle node's register (depth 1) or an LDS stack slot (depth >= 2).
+constexpr uint32_t WALK_TREE        = 0x2000;   // not on a cycle; finished as soon as it is loaded
+constexpr uint32_t WALK_PUSH        = 0x1000;   // has children: keep its x' at stack level depth-1
+constexpr uint32_t WALK_DEPTH_SHIFT = 16;       // bits 16..27: distance to the cycle (tree nodes)
+constexpr int      WALK_MAX_LEVELS  = 32;       // stack levels a launch can hold in LDS
 struct Walk {
     uint32_t seq[GSGD_MAX_K];
 };
