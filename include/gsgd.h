@@ -57,7 +57,7 @@ enum { GSGD_INIT_BROADCAST = 0, GSGD_INIT_PER_REPLICA = 1 };
 enum { GSGD_FILL_XSTAR = 2, GSGD_FILL_H = 3, GSGD_FILL_X0 = 4 };
 /* the streaming kernels, for gsgd_set_launch_width */
 enum { GSGD_KERNEL_GOSSIP = 0, GSGD_KERNEL_ALLREDUCE = 1, GSGD_KERNEL_EASGD = 2, GSGD_KERNEL_GEN_GRAD = 3,
-       GSGD_KERNEL_GOSSIP_FUSED = 4, GSGD_KERNEL_COUNT = 5 };
+       GSGD_KERNEL_GOSSIP_FUSED = 4, GSGD_KERNEL_LOCAL = 5, GSGD_KERNEL_COUNT = 6 };
 
 typedef struct gsgd_ctx gsgd_ctx;   /* opaque; owns the segment tables and a small scratch for gsgd_stats */
 
@@ -84,6 +84,17 @@ int gsgd_destroy(gsgd_ctx* ctx);
 
 /* Change the base step size (the paper anneals alpha, Section 4.2).  Host only. */
 int gsgd_set_lr(gsgd_ctx* ctx, float lr);
+
+/* The local step the experiments use (Section 4.2: Nesterov momentum 0.9 and
+ * weight decay 1e-4) in place of the plain heavy-ball step of the algorithm
+ * boxes.  With gt = g + weight_decay * x, every step rule below computes
+ *   v_i <- momentum * v_i - lr_s * gt_i;
+ *   x'_i = x_i + v_i                          (nesterov = 0)
+ *   x'_i = (x_i - lr_s * gt_i) + momentum * v_i   (nesterov = 1)
+ * and then communicates as documented.  Under all-reduce the momentum buffers
+ * and the applied updates x'_i - x_i are averaged separately (they differ when
+ * nesterov = 1).  weight_decay >= 0; (0, 0) restores the default.  Host only. */
+int gsgd_set_local_step(gsgd_ctx* ctx, float weight_decay, int nesterov);
 
 /* Tuning knob.  The streaming kernels run as a fixed number of persistent
  * workgroups that pull 1024-column tiles from a ticket counter owned by the
@@ -135,6 +146,26 @@ int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const float* g, void*
  * call returns.  Everything happens in place in one pass over x, v and g. */
 int gsgd_step_gossip(gsgd_ctx* ctx, float* x, float* v, const float* g,
                      const int32_t* peer_perm, float beta, void* stream);
+
+/* Gossip with stale parameters (Section 6.2.1, "gradient step and gossip at
+ * the same time"): as gsgd_step_gossip, but the mixing term is the difference
+ * of the parameters from before the local step,
+ *   x_i <- x'_i - beta * (x_i - x_{peer_perm[i]}). */
+int gsgd_step_gossip_stale(gsgd_ctx* ctx, float* x, float* v, const float* g,
+                           const int32_t* peer_perm, float beta, void* stream);
+
+/* The local step alone (v_i and x_i <- x'_i, no exchange): what every node
+ * does in the iterations between two exchanges when the communication period
+ * tau of Algorithms 2-4 is larger than 1. */
+int gsgd_step_local(gsgd_ctx* ctx, float* x, float* v, const float* g, void* stream);
+
+/* Communication schedule of Algorithms 2-4 ("if t > 0 and t = 0 mod tau",
+ * exchange at the top of iteration t).  The step calls here run the local step
+ * first and the exchange after it, so the exchange of iteration t+1 is the
+ * tail of step call t: returns 1 when step call number `step` (0-based) should
+ * be an exchanging call, 0 when it should be gsgd_step_local, and
+ * GSGD_ERR_INVALID_ARG for tau = 0.  Pure host code. */
+int gsgd_comm_due(uint64_t step, uint32_t tau);
 
 /* Elastic-averaging step, Algorithm 2 with communication period 1, all k
  * clients exchanging with the same centre value in one synchronous round:

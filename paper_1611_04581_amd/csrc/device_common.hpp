@@ -73,11 +73,47 @@ __device__ __forceinline__ f32x4 momentum_update(f32x4 v, f32x4 g, f32x4 neg_lr,
     return fma4(neg_lr, g, t3);
 }
 
+// The local step of every rule.  EXT = false: the two lines the algorithm
+// boxes share.  EXT = true: the form the experiments of Section 4.2 use, with
+// weight decay and optionally Nesterov momentum, on the momentum buffer:
+//   gt = g + wd x;  v' = mu v - lr gt;
+//   heavy ball: x' = x + v'      Nesterov: x' = (x - lr gt) + mu v'
+// `gt` is returned because the all-reduce rule needs it again.
+template <bool EXT>
+__device__ __forceinline__ void local_step(f32x4 x, f32x4 v, f32x4 g, f32x4 neg_lr, const Hyper& hp,
+                                           f32x4& v_new, f32x4& x_post, f32x4* gt_out = nullptr)
+{
+    if constexpr (!EXT) {
+        v_new = momentum_update(v, g, neg_lr, hp.mu);
+        x_post = x + v_new;
+        if (gt_out) *gt_out = g;
+    } else {
+        const f32x4 gt = fma4(hp.wd, x, g);
+        const f32x4 t3 = hp.mu * v;
+        v_new = fma4(neg_lr, gt, t3);
+        if (hp.nesterov) {
+            const f32x4 t4 = fma4(neg_lr, gt, x);
+            x_post = fma4(hp.mu, v_new, t4);
+        } else {
+            x_post = x + v_new;
+        }
+        if (gt_out) *gt_out = gt;
+    }
+}
+
 // Gossip mix of Section 3.1: x' - beta (x' - x'_peer)
 __device__ __forceinline__ f32x4 gossip_mix(f32x4 mine, f32x4 theirs, float neg_beta)
 {
     const f32x4 diff = mine - theirs;
     return fma4(neg_beta, diff, mine);
+}
+
+// Gossip with stale parameters (Section 6.2.1): x' - beta (x - x_peer), the
+// difference taken between the parameters from before the local step.
+__device__ __forceinline__ f32x4 stale_mix(f32x4 post, f32x4 mine_old, f32x4 theirs_old, float neg_beta)
+{
+    const f32x4 diff = mine_old - theirs_old;
+    return fma4(neg_beta, diff, post);
 }
 
 // ---------------------------------------------------------------------------

@@ -18,6 +18,8 @@ struct gsgd_ctx {
     uint32_t*   d_tickets;    // tile tickets of the persistent kernels (2 words, zero between launches)
     int         cu_count;     // compute units of the device
     unsigned    width[GSGD_KERNEL_COUNT];   // persistent workgroups per streaming kernel
+    float       weight_decay;               // extras of the local step (Section 4.2); 0 / 0 = the boxed algorithms
+    int         nesterov;
     int         last_hip;
 };
 
@@ -25,7 +27,7 @@ namespace {
 
 // Persistent workgroups per compute unit for each streaming kernel
 // (GSGD_KERNEL_* order).  Measured on MI355X at the benchmark shapes.
-constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 4u, 2u};
+constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 4u, 2u, 1u};
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -36,7 +38,7 @@ inline int hip_fail(gsgd_ctx* ctx, hipError_t e)
 }
 
 inline Geom geom_of(const gsgd_ctx* c) { return Geom{c->cfg.k, c->cfg.d, c->cfg.ld}; }
-inline Hyper hyper_of(const gsgd_ctx* c) { return Hyper{c->cfg.lr, c->cfg.momentum}; }
+inline Hyper hyper_of(const gsgd_ctx* c) { return Hyper{c->cfg.lr, c->cfg.momentum, c->weight_decay, c->nesterov}; }
 inline SegTable seg_of(const gsgd_ctx* c) { return SegTable{c->d_offsets, c->d_scales, c->cfg.n_seg}; }
 inline Persist persist_of(const gsgd_ctx* c, int kernel) { return Persist{c->d_tickets, c->width[kernel]}; }
 inline RngKey key_of(const gsgd_ctx* c)
@@ -135,6 +137,20 @@ extern "C" int gsgd_set_lr(gsgd_ctx* ctx, float lr)
     return GSGD_OK;
 }
 
+extern "C" int gsgd_set_local_step(gsgd_ctx* ctx, float weight_decay, int nesterov)
+{
+    if (!ctx || !(weight_decay >= 0.0f) || (nesterov != 0 && nesterov != 1)) return GSGD_ERR_INVALID_ARG;
+    ctx->weight_decay = weight_decay;
+    ctx->nesterov = nesterov;
+    return GSGD_OK;
+}
+
+extern "C" int gsgd_comm_due(uint64_t step, uint32_t tau)
+{
+    if (tau == 0) return GSGD_ERR_INVALID_ARG;
+    return (step + 1) % tau == 0 ? 1 : 0;
+}
+
 extern "C" int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups)
 {
     if (!ctx || kernel < 0 || kernel >= GSGD_KERNEL_COUNT || workgroups < 0 || workgroups > (1 << 20))
@@ -193,8 +209,9 @@ extern "C" int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const floa
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
-extern "C" int gsgd_step_gossip(gsgd_ctx* ctx, float* x, float* v, const float* g,
-                                const int32_t* peer_perm, float beta, void* stream)
+namespace {
+int gossip_on_permutation(gsgd_ctx* ctx, float* x, float* v, const float* g, const int32_t* peer_perm, float beta,
+                          bool stale, void* stream)
 {
     int rc = check_state(ctx, x, v, g);
     if (rc != GSGD_OK) return rc;
@@ -202,8 +219,30 @@ extern "C" int gsgd_step_gossip(gsgd_ctx* ctx, float* x, float* v, const float* 
     Walk walk;
     rc = build_walk(peer_perm, ctx->cfg.k, &walk);
     if (rc != GSGD_OK) return rc;
-    const hipError_t e = launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, x, v, g,
+    const hipError_t e = launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale, x, v, g,
                                             persist_of(ctx, GSGD_KERNEL_GOSSIP), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+}  // namespace
+
+extern "C" int gsgd_step_gossip(gsgd_ctx* ctx, float* x, float* v, const float* g,
+                                const int32_t* peer_perm, float beta, void* stream)
+{
+    return gossip_on_permutation(ctx, x, v, g, peer_perm, beta, false, stream);
+}
+
+extern "C" int gsgd_step_gossip_stale(gsgd_ctx* ctx, float* x, float* v, const float* g,
+                                      const int32_t* peer_perm, float beta, void* stream)
+{
+    return gossip_on_permutation(ctx, x, v, g, peer_perm, beta, true, stream);
+}
+
+extern "C" int gsgd_step_local(gsgd_ctx* ctx, float* x, float* v, const float* g, void* stream)
+{
+    const int rc = check_state(ctx, x, v, g);
+    if (rc != GSGD_OK) return rc;
+    const hipError_t e = launch_step_local(geom_of(ctx), hyper_of(ctx), seg_of(ctx), x, v, g,
+                                           persist_of(ctx, GSGD_KERNEL_LOCAL), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 

@@ -40,8 +40,13 @@ struct Geom {
     int64_t ld;
 };
 
+// Step size, momentum, and the two extras of the experiments' local step
+// (Section 4.2): weight decay and the Nesterov flag.  Kernels compiled without
+// the extras ignore wd and nesterov.
 struct Hyper {
-    float lr, mu;
+    float   lr, mu, wd;
+    int32_t nesterov;
+    bool    extended() const { return wd != 0.0f || nesterov != 0; }
 };
 
 // Philox key and the per-call counter words.
@@ -58,8 +63,10 @@ struct Persist {
 };
 
 // ---- launchers (defined next to their kernels) ---------------------------
-hipError_t launch_step_gossip(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&,
+hipError_t launch_step_gossip(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&, bool stale,
                               float* x, float* v, const float* g, Persist, hipStream_t);
+hipError_t launch_step_local(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
+                             Persist, hipStream_t);
 hipError_t launch_step_gossip_fused(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&,
                                     float* x, float* v, const float* h, const float* xstar,
                                     float sigma, RngKey key, uint32_t step, int noise_kind, Persist, hipStream_t);

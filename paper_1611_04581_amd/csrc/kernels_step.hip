@@ -39,7 +39,12 @@ __device__ __forceinline__ void for_row_batches(int k, Body&& body)
 // is the row visited now: keeping `first`, `prev` and the current x' in
 // registers is enough to finish every row in place, in one pass, without a
 // second buffer and without two replicas ever racing on a row.
-template <bool FULL, int U, bool FUSED_GEN, int NOISE>
+//
+// STALE selects the variant of Section 6.2.1 (gradient step and gossip at the
+// same time): the mixing term is taken between the parameters from before the
+// local step, x_i <- x'_i - beta (x_i - x_peer), so the walk also carries the
+// old x of the first and of the previous row.
+template <bool FULL, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE>
 __device__ __forceinline__
 void gossip_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
                       float neg_beta, const Walk& walk,
@@ -55,9 +60,9 @@ void gossip_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, con
         xs4 = load_quad_cached<FULL>(xstar + qd.col, valid);
     }
     const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
-    const float mu = hp.mu;
 
     f32x4 first = {0.f, 0.f, 0.f, 0.f}, prev = {0.f, 0.f, 0.f, 0.f};
+    f32x4 first_old = {0.f, 0.f, 0.f, 0.f}, prev_old = {0.f, 0.f, 0.f, 0.f};   // STALE only
     int64_t prev_off = 0;                      // uniform: row offset of the previously visited replica
 
     for_row_batches<U>(geo.k, [&](auto n, int t0) {
@@ -82,19 +87,27 @@ void gossip_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, con
                 const f32x4 t2 = sigma * xi;
                 G[u] = fma4(h4, t1, t2);
             }
-            const f32x4 vn = momentum_update(V[u], G[u], neg_lr, mu);
-            const f32x4 xp = X[u] + vn;
+            f32x4 vn, xp;
+            local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, xp);
             store_quad<FULL>(v + off + qd.lane_col, vn, valid);
-            if (w[u] & WALK_FIRST) first = xp;
-            else store_quad<FULL>(x + prev_off + qd.lane_col, gossip_mix(prev, xp, neg_beta), valid);
-            if (w[u] & WALK_LAST) store_quad<FULL>(x + off + qd.lane_col, gossip_mix(xp, first, neg_beta), valid);
+            if constexpr (!STALE) {
+                if (w[u] & WALK_FIRST) first = xp;
+                else store_quad<FULL>(x + prev_off + qd.lane_col, gossip_mix(prev, xp, neg_beta), valid);
+                if (w[u] & WALK_LAST) store_quad<FULL>(x + off + qd.lane_col, gossip_mix(xp, first, neg_beta), valid);
+            } else {
+                if (w[u] & WALK_FIRST) first_old = X[u];
+                else store_quad<FULL>(x + prev_off + qd.lane_col, stale_mix(prev, prev_old, X[u], neg_beta), valid);
+                if (w[u] & WALK_LAST)
+                    store_quad<FULL>(x + off + qd.lane_col, stale_mix(xp, X[u], first_old, neg_beta), valid);
+                prev_old = X[u];
+            }
             prev = xp;
             prev_off = off;
         }
     });
 }
 
-template <int U, bool FUSED_GEN, int NOISE>
+template <int U, bool FUSED_GEN, int NOISE, bool EXT = false, bool STALE = false>
 __global__ __launch_bounds__(BLOCK)
 void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk walk,
                         float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
@@ -106,11 +119,11 @@ void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk w
     for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
         const Quad qd = quad_of_tile(tile, geo.d);
         if (tile_is_full(qd, geo.d))
-            gossip_step_body<true, U, FUSED_GEN, NOISE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h, xstar,
-                                                        sigma, key, step);
+            gossip_step_body<true, U, FUSED_GEN, NOISE, EXT, STALE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h,
+                                                                    xstar, sigma, key, step);
         else if (qd.valid > 0)
-            gossip_step_body<false, U, FUSED_GEN, NOISE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h, xstar,
-                                                         sigma, key, step);
+            gossip_step_body<false, U, FUSED_GEN, NOISE, EXT, STALE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h,
+                                                                     xstar, sigma, key, step);
     });
 }
 
@@ -118,38 +131,61 @@ void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk w
 // All-reduce average (Algorithm 1).  Pass 1 reads v and g of every row and
 // accumulates u_i = mu v_i - lr g_i in fp64 in ascending i; pass 2 adds the
 // rounded mean to every row of x and leaves it in every row of v.
-template <bool FULL, int U>
+// EXT (weight decay / Nesterov, Section 4.2): the momentum buffers and the
+// applied updates are averaged separately (they differ under Nesterov), and
+// pass 1 also reads x when the weight decay is non-zero.
+template <bool FULL, int U, bool EXT>
 __device__ __forceinline__
 void allreduce_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
                          float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g)
 {
     const int valid = FULL ? 4 : qd.valid;
     const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
-    const float mu = hp.mu;
     const int k = geo.k;
+    const bool need_x = EXT && hp.wd != 0.0f;       // uniform
+    const bool nesterov = EXT && hp.nesterov != 0;   // uniform
 
-    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+    f64x4 acc_v = {0.0, 0.0, 0.0, 0.0}, acc_d = {0.0, 0.0, 0.0, 0.0};
     for_row_batches<2 * U>(k, [&](auto n, int i0) {
         constexpr int N = decltype(n)::value;
-        f32x4 V[N], G[N];
+        f32x4 X[N], V[N], G[N];
 #pragma unroll
         for (int u = 0; u < N; ++u) {
             const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
             V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
             G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
+            X[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if constexpr (EXT) { if (need_x) X[u] = load_quad_cached<FULL>(x + off + qd.lane_col, valid); }
         }
 #pragma unroll
         for (int u = 0; u < N; ++u) {
-            const f32x4 un = momentum_update(V[u], G[u], neg_lr, mu);
-            acc.x += static_cast<double>(un.x);
-            acc.y += static_cast<double>(un.y);
-            acc.z += static_cast<double>(un.z);
-            acc.w += static_cast<double>(un.w);
+            f32x4 un, xp_unused, gt;
+            local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, un, xp_unused, &gt);
+            acc_v.x += static_cast<double>(un.x);
+            acc_v.y += static_cast<double>(un.y);
+            acc_v.z += static_cast<double>(un.z);
+            acc_v.w += static_cast<double>(un.w);
+            if constexpr (EXT) {
+                if (nesterov) {
+                    const f32x4 t5 = hp.mu * un;
+                    const f32x4 di = fma4(neg_lr, gt, t5);
+                    acc_d.x += static_cast<double>(di.x);
+                    acc_d.y += static_cast<double>(di.y);
+                    acc_d.z += static_cast<double>(di.z);
+                    acc_d.w += static_cast<double>(di.w);
+                }
+            }
         }
     });
     const double kd = static_cast<double>(k);
-    const f32x4 ubar = {static_cast<float>(acc.x / kd), static_cast<float>(acc.y / kd),
-                        static_cast<float>(acc.z / kd), static_cast<float>(acc.w / kd)};
+    const f32x4 ubar = {static_cast<float>(acc_v.x / kd), static_cast<float>(acc_v.y / kd),
+                        static_cast<float>(acc_v.z / kd), static_cast<float>(acc_v.w / kd)};
+    f32x4 dbar = ubar;
+    if constexpr (EXT) {
+        if (nesterov)
+            dbar = f32x4{static_cast<float>(acc_d.x / kd), static_cast<float>(acc_d.y / kd),
+                         static_cast<float>(acc_d.z / kd), static_cast<float>(acc_d.w / kd)};
+    }
     for_row_batches<2 * U>(k, [&](auto n, int i0) {
         constexpr int N = decltype(n)::value;
         f32x4 X[N];
@@ -160,12 +196,12 @@ void allreduce_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, 
         for (int u = 0; u < N; ++u) {
             const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
             store_quad<FULL>(v + off + qd.lane_col, ubar, valid);
-            store_quad<FULL>(x + off + qd.lane_col, X[u] + ubar, valid);
+            store_quad<FULL>(x + off + qd.lane_col, X[u] + dbar, valid);
         }
     });
 }
 
-template <int U>
+template <int U, bool EXT = false>
 __global__ __launch_bounds__(BLOCK)
 void allreduce_step_kernel(Geom geo, Hyper hp, SegTable seg,
                            float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
@@ -175,8 +211,8 @@ void allreduce_step_kernel(Geom geo, Hyper hp, SegTable seg,
     stage_segments(seg, lds);
     for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
         const Quad qd = quad_of_tile(tile, geo.d);
-        if (tile_is_full(qd, geo.d)) allreduce_step_body<true, U>(geo, hp, seg, lds, qd, x, v, g);
-        else if (qd.valid > 0) allreduce_step_body<false, U>(geo, hp, seg, lds, qd, x, v, g);
+        if (tile_is_full(qd, geo.d)) allreduce_step_body<true, U, EXT>(geo, hp, seg, lds, qd, x, v, g);
+        else if (qd.valid > 0) allreduce_step_body<false, U, EXT>(geo, hp, seg, lds, qd, x, v, g);
     });
 }
 
@@ -184,7 +220,7 @@ void allreduce_step_kernel(Geom geo, Hyper hp, SegTable seg,
 // Elastic averaging (Algorithm 2, period 1, one synchronous round):
 // every client moves towards the same centre value, the centre moves by the
 // sum of what the clients gave up.
-template <bool FULL, int U>
+template <bool FULL, int U, bool EXT>
 __device__ __forceinline__
 void easgd_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
                      float alpha_e, float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
@@ -193,7 +229,6 @@ void easgd_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, cons
     const int valid = FULL ? 4 : qd.valid;
     const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
     const f32x4 c4 = load_quad_cached<FULL>(center + qd.col, valid);
-    const float mu = hp.mu;
 
     f64x4 acc = {0.0, 0.0, 0.0, 0.0};
     for_row_batches<U>(geo.k, [&](auto n, int i0) {
@@ -209,8 +244,8 @@ void easgd_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, cons
 #pragma unroll
         for (int u = 0; u < N; ++u) {
             const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
-            const f32x4 vn = momentum_update(V[u], G[u], neg_lr, mu);
-            const f32x4 xp = X[u] + vn;
+            f32x4 vn, xp;
+            local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, xp);
             const f32x4 e = alpha_e * (xp - c4);
             store_quad<FULL>(v + off + qd.lane_col, vn, valid);
             store_quad<FULL>(x + off + qd.lane_col, xp - e, valid);
@@ -227,7 +262,7 @@ void easgd_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, cons
     store_quad<FULL>(center + qd.col, cn, valid);
 }
 
-template <int U>
+template <int U, bool EXT = false>
 __global__ __launch_bounds__(BLOCK)
 void easgd_step_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e,
                        float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
@@ -237,8 +272,54 @@ void easgd_step_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e,
     stage_segments(seg, lds);
     for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
         const Quad qd = quad_of_tile(tile, geo.d);
-        if (tile_is_full(qd, geo.d)) easgd_step_body<true, U>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
-        else if (qd.valid > 0) easgd_step_body<false, U>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
+        if (tile_is_full(qd, geo.d)) easgd_step_body<true, U, EXT>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
+        else if (qd.valid > 0) easgd_step_body<false, U, EXT>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
+    });
+}
+
+// ---------------------------------------------------------------------------
+// Local step alone: what a node does in the iterations between two exchanges
+// when the communication period tau of Algorithms 2-4 is larger than 1.
+template <bool FULL, int U, bool EXT>
+__device__ __forceinline__
+void local_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
+                     float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g)
+{
+    const int valid = FULL ? 4 : qd.valid;
+    const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
+    for_row_batches<U>(geo.k, [&](auto n, int i0) {
+        constexpr int N = decltype(n)::value;
+        f32x4 X[N], V[N], G[N];
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
+            X[u] = load_quad<FULL>(x + off + qd.lane_col, valid);
+            V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
+            G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
+        }
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
+            f32x4 vn, xp;
+            local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, xp);
+            store_quad<FULL>(v + off + qd.lane_col, vn, valid);
+            store_quad<FULL>(x + off + qd.lane_col, xp, valid);
+        }
+    });
+}
+
+template <int U, bool EXT>
+__global__ __launch_bounds__(BLOCK)
+void local_step_kernel(Geom geo, Hyper hp, SegTable seg,
+                       float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                       uint32_t* __restrict__ tickets, uint32_t n_tiles)
+{
+    __shared__ SegLds lds;
+    stage_segments(seg, lds);
+    for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
+        const Quad qd = quad_of_tile(tile, geo.d);
+        if (tile_is_full(qd, geo.d)) local_step_body<true, U, EXT>(geo, hp, seg, lds, qd, x, v, g);
+        else if (qd.valid > 0) local_step_body<false, U, EXT>(geo, hp, seg, lds, qd, x, v, g);
     });
 }
 
@@ -253,12 +334,36 @@ static inline unsigned width_for(const Geom& geo, const Persist& p)
     return p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
 }
 
+// The kernels without the extras of Section 4.2 are the ones the benchmark
+// times; the extended ones are picked only when weight decay or Nesterov
+// momentum is switched on (or, for gossip, the stale variant is asked for).
+#define GSGD_LAUNCH(KERNEL, ...) \
+    hipLaunchKernelGGL(KERNEL, dim3(width_for(geo, p)), dim3(BLOCK), 0, stream, __VA_ARGS__)
+
 hipError_t launch_step_gossip(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta, const Walk& walk,
-                              float* x, float* v, const float* g, Persist p, hipStream_t stream)
+                              bool stale, float* x, float* v, const float* g, Persist p, hipStream_t stream)
 {
-    hipLaunchKernelGGL((gossip_step_kernel<RIF, false, 0>), dim3(width_for(geo, p)), dim3(BLOCK), 0, stream,
-                       geo, hp, seg, -beta, walk, x, v, g, nullptr, nullptr, 0.0f, RngKey{0u, 0u}, 0u,
-                       p.tickets, grid_for(geo.d));
+    const RngKey no_key{0u, 0u};
+    const uint32_t tiles = grid_for(geo.d);
+    if (stale)
+        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0, true, true>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
+                    nullptr, 0.0f, no_key, 0u, p.tickets, tiles);
+    else if (hp.extended())
+        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0, true, false>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
+                    nullptr, 0.0f, no_key, 0u, p.tickets, tiles);
+    else
+        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0>), geo, hp, seg, -beta, walk, x, v, g, nullptr, nullptr,
+                    0.0f, no_key, 0u, p.tickets, tiles);
+    return hipGetLastError();
+}
+
+hipError_t launch_step_local(const Geom& geo, const Hyper& hp, const SegTable& seg,
+                             float* x, float* v, const float* g, Persist p, hipStream_t stream)
+{
+    if (hp.extended())
+        GSGD_LAUNCH((local_step_kernel<RIF, true>), geo, hp, seg, x, v, g, p.tickets, grid_for(geo.d));
+    else
+        GSGD_LAUNCH((local_step_kernel<RIF, false>), geo, hp, seg, x, v, g, p.tickets, grid_for(geo.d));
     return hipGetLastError();
 }
 
@@ -267,32 +372,47 @@ hipError_t launch_step_gossip_fused(const Geom& geo, const Hyper& hp, const SegT
                                     float sigma, RngKey key, uint32_t step, int noise_kind, Persist p,
                                     hipStream_t stream)
 {
-    if (noise_kind == GSGD_NOISE_UNIFORM)
-        hipLaunchKernelGGL((gossip_step_kernel<RIF, true, GSGD_NOISE_UNIFORM>), dim3(width_for(geo, p)), dim3(BLOCK), 0,
-                           stream, geo, hp, seg, -beta, walk, x, v, nullptr, h, xstar, sigma, key, step,
-                           p.tickets, grid_for(geo.d));
-    else
-        hipLaunchKernelGGL((gossip_step_kernel<RIF, true, GSGD_NOISE_GAUSSIAN>), dim3(width_for(geo, p)), dim3(BLOCK), 0,
-                           stream, geo, hp, seg, -beta, walk, x, v, nullptr, h, xstar, sigma, key, step,
-                           p.tickets, grid_for(geo.d));
+    const uint32_t tiles = grid_for(geo.d);
+    const bool uniform = noise_kind == GSGD_NOISE_UNIFORM;
+    if (hp.extended()) {
+        if (uniform)
+            GSGD_LAUNCH((gossip_step_kernel<RIF, true, GSGD_NOISE_UNIFORM, true>), geo, hp, seg, -beta, walk, x, v,
+                        nullptr, h, xstar, sigma, key, step, p.tickets, tiles);
+        else
+            GSGD_LAUNCH((gossip_step_kernel<RIF, true, GSGD_NOISE_GAUSSIAN, true>), geo, hp, seg, -beta, walk, x, v,
+                        nullptr, h, xstar, sigma, key, step, p.tickets, tiles);
+    } else {
+        if (uniform)
+            GSGD_LAUNCH((gossip_step_kernel<RIF, true, GSGD_NOISE_UNIFORM>), geo, hp, seg, -beta, walk, x, v,
+                        nullptr, h, xstar, sigma, key, step, p.tickets, tiles);
+        else
+            GSGD_LAUNCH((gossip_step_kernel<RIF, true, GSGD_NOISE_GAUSSIAN>), geo, hp, seg, -beta, walk, x, v,
+                        nullptr, h, xstar, sigma, key, step, p.tickets, tiles);
+    }
     return hipGetLastError();
 }
 
 hipError_t launch_step_allreduce(const Geom& geo, const Hyper& hp, const SegTable& seg,
                                  float* x, float* v, const float* g, Persist p, hipStream_t stream)
 {
-    hipLaunchKernelGGL(allreduce_step_kernel<RIF>, dim3(width_for(geo, p)), dim3(BLOCK), 0, stream,
-                       geo, hp, seg, x, v, g, p.tickets, grid_for(geo.d));
+    if (hp.extended())
+        GSGD_LAUNCH((allreduce_step_kernel<RIF, true>), geo, hp, seg, x, v, g, p.tickets, grid_for(geo.d));
+    else
+        GSGD_LAUNCH((allreduce_step_kernel<RIF>), geo, hp, seg, x, v, g, p.tickets, grid_for(geo.d));
     return hipGetLastError();
 }
 
 hipError_t launch_step_easgd(const Geom& geo, const Hyper& hp, const SegTable& seg, float alpha_e,
                              float* x, float* v, const float* g, float* center, Persist p, hipStream_t stream)
 {
-    hipLaunchKernelGGL(easgd_step_kernel<RIF>, dim3(width_for(geo, p)), dim3(BLOCK), 0, stream,
-                       geo, hp, seg, alpha_e, x, v, g, center, p.tickets, grid_for(geo.d));
+    if (hp.extended())
+        GSGD_LAUNCH((easgd_step_kernel<RIF, true>), geo, hp, seg, alpha_e, x, v, g, center, p.tickets,
+                    grid_for(geo.d));
+    else
+        GSGD_LAUNCH((easgd_step_kernel<RIF>), geo, hp, seg, alpha_e, x, v, g, center, p.tickets, grid_for(geo.d));
     return hipGetLastError();
 }
+#undef GSGD_LAUNCH
 #endif  // GSGD_NO_LAUNCHERS
 
 }  // namespace gsgd

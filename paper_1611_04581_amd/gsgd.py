@@ -21,7 +21,8 @@ NOISE_GAUSSIAN, NOISE_UNIFORM = 0, 1
 INIT_BROADCAST, INIT_PER_REPLICA = 0, 1
 FILL_XSTAR, FILL_H, FILL_X0 = 2, 3, 4
 
-KERNEL_GOSSIP, KERNEL_ALLREDUCE, KERNEL_EASGD, KERNEL_GEN_GRAD, KERNEL_GOSSIP_FUSED = range(5)
+KERNEL_GOSSIP, KERNEL_ALLREDUCE, KERNEL_EASGD, KERNEL_GEN_GRAD, KERNEL_GOSSIP_FUSED, KERNEL_LOCAL = range(6)
+KERNEL_COUNT = 6
 WALK_ROW_MASK, WALK_FIRST, WALK_LAST = 0x0FFF, 0x4000, 0x8000
 
 
@@ -47,6 +48,10 @@ SIGNATURES = {
     "gsgd_destroy": (C.c_int, [_vp]),
     "gsgd_set_lr": (C.c_int, [_vp, C.c_float]),
     "gsgd_set_launch_width": (C.c_int, [_vp, C.c_int, C.c_int]),
+    "gsgd_set_local_step": (C.c_int, [_vp, C.c_float, C.c_int]),
+    "gsgd_comm_due": (C.c_int, [C.c_uint64, C.c_uint32]),
+    "gsgd_step_gossip_stale": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, _vp]),
+    "gsgd_step_local": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
     "gsgd_init_replicas": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int, _vp]),
     "gsgd_fill": (C.c_int, [_vp, _vp, C.c_int, _vp]),
     "gsgd_gen_grad": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_uint64, _vp]),
@@ -151,6 +156,9 @@ class Context:
     def set_lr(self, lr):
         _check(lib().gsgd_set_lr(self._h, float(lr)), "gsgd_set_lr")
 
+    def set_local_step(self, weight_decay=0.0, nesterov=False):
+        _check(lib().gsgd_set_local_step(self._h, float(weight_decay), int(bool(nesterov))), "gsgd_set_local_step")
+
     def set_launch_width(self, kernel, workgroups):
         _check(lib().gsgd_set_launch_width(self._h, int(kernel), int(workgroups)), "gsgd_set_launch_width")
 
@@ -173,6 +181,14 @@ class Context:
         _check(lib().gsgd_step_gossip(self._h, _ptr(x), _ptr(v), _ptr(g), p, float(beta), _stream(stream)),
                "gsgd_step_gossip")
 
+    def step_gossip_stale(self, x, v, g, peer_perm, beta=0.5, stream=None):
+        keep, p = _perm_arg(peer_perm)
+        _check(lib().gsgd_step_gossip_stale(self._h, _ptr(x), _ptr(v), _ptr(g), p, float(beta), _stream(stream)),
+               "gsgd_step_gossip_stale")
+
+    def step_local(self, x, v, g, stream=None):
+        _check(lib().gsgd_step_local(self._h, _ptr(x), _ptr(v), _ptr(g), _stream(stream)), "gsgd_step_local")
+
     def step_easgd(self, x, v, g, center, alpha_e, stream=None):
         _check(lib().gsgd_step_easgd(self._h, _ptr(x), _ptr(v), _ptr(g), _ptr(center), float(alpha_e),
                                      _stream(stream)), "gsgd_step_easgd")
@@ -190,6 +206,13 @@ class Context:
         out = (C.c_double * 4)()
         _check(lib().gsgd_stats(self._h, _ptr(x), _ptr(xstar), out, _stream(stream)), "gsgd_stats")
         return np.array(list(out), dtype=np.float64)
+
+
+def comm_due(step, tau):
+    rc = lib().gsgd_comm_due(int(step), int(tau))
+    if rc < 0:
+        raise GsgdError(rc, "gsgd_comm_due")
+    return bool(rc)
 
 
 def make_perm(seed, step, k):

@@ -134,3 +134,17 @@ def test_null_context_and_error_strings():
     texts = {gsgd.strerror(c) for c in range(0, -7, -1)}
     assert len(texts) == 7 and "unknown error" not in texts
     assert gsgd.strerror(-99) == "unknown error"
+
+
+def test_comm_due_follows_the_algorithm_boxes():
+    """Algorithms 2-4 exchange at the top of iteration t when t > 0 and
+    t = 0 mod tau; with the exchange fused to the end of the previous step
+    call, call s exchanges iff s + 1 is such a t."""
+    for tau in (1, 2, 3, 10):
+        T = 50
+        box = [t > 0 and t % tau == 0 for t in range(T + 1)]          # exchange at the top of iteration t
+        for s in range(T):
+            assert gsgd.comm_due(s, tau) == box[s + 1], (s, tau)
+    assert all(gsgd.comm_due(s, 1) for s in range(20))
+    with pytest.raises(gsgd.GsgdError):
+        gsgd.comm_due(3, 0)

@@ -1,0 +1,197 @@
+"""GPU parity for the variants beyond the algorithm boxes: the local step with
+weight decay and Nesterov momentum (the paper's training setup, Section 4.2),
+gossip with stale parameters (Section 6.2.1), and the local-only step used
+between exchanges when the communication period is larger than 1.
+
+All of these are fixed-order fp32 / fp64 arithmetic, so the bar is bit
+equality with the CPU oracle on the same seeded inputs.
+"""
+import numpy as np
+import pytest
+
+from paper_1611_04581_amd import workloads as W
+from parity_util import assert_bitwise, assert_rows_close
+
+pytestmark = pytest.mark.gpu
+
+SEED = 0x161104581
+SHAPES = [(4, 5 * 1024 + 7, None), (3, 1, 4), (7, 1023, 1024), (32, 2 * 1024 + 2, 4096)]
+LOCAL_STEPS = [(1e-4, False), (0.0, True), (1e-4, True), (0.03, True)]
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    from paper_1611_04581_amd import gsgd
+    assert torch.cuda.is_available()
+    gsgd.lib()
+    return gsgd
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def some_perms(k, oracle):
+    out = [[(i + 1) % k for i in range(k)], [int(t) for t in oracle.make_perm(SEED, 5, k)]]
+    if k >= 6:
+        out.append([1, 2, 0, 3] + list(range(5, k)) + [4])
+    return out
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES)
+@pytest.mark.parametrize("wd,nesterov", LOCAL_STEPS)
+def test_gossip_with_weight_decay_and_nesterov(G, oracle, k, d, ld, wd, nesterov):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=21)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9) as ctx:
+        ctx.set_local_step(wd, nesterov)
+        for perm in some_perms(k, oracle):
+            for stale in (False, True):
+                x, v = dev(inp.x), dev(inp.v)
+                (ctx.step_gossip_stale if stale else ctx.step_gossip)(x, v, dev(inp.g), perm, 0.5)
+                xo, vo = inp.x.copy(), inp.v.copy()
+                oracle.step_gossip_ext(xo, vo, inp.g, 0.05, 0.9, 0.5, perm, wd=wd, nesterov=nesterov, stale=stale,
+                                       n=d)
+                assert_bitwise(host(x), xo, "x perm=%s stale=%s" % (perm, stale))
+                assert_bitwise(host(v), vo, "v")
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES)
+def test_stale_gossip_plain_local_step(G, oracle, k, d, ld):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=22)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9) as ctx:
+        for beta in (0.5, 0.25):
+            for perm in some_perms(k, oracle) + [list(range(k))]:
+                x, v = dev(inp.x), dev(inp.v)
+                ctx.step_gossip_stale(x, v, dev(inp.g), perm, beta)
+                xo, vo = inp.x.copy(), inp.v.copy()
+                oracle.step_gossip_ext(xo, vo, inp.g, 0.05, 0.9, beta, perm, stale=True, n=d)
+                assert_bitwise(host(x), xo, "x perm=%s" % perm)
+                assert_bitwise(host(v), vo, "v")
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES)
+@pytest.mark.parametrize("wd,nesterov", LOCAL_STEPS)
+def test_allreduce_and_easgd_with_weight_decay_and_nesterov(G, oracle, k, d, ld, wd, nesterov):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=23)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9) as ctx:
+        ctx.set_local_step(wd, nesterov)
+        x, v = dev(inp.x), dev(inp.v)
+        ctx.step_allreduce(x, v, dev(inp.g))
+        xo, vo = inp.x.copy(), inp.v.copy()
+        oracle.step_allreduce_ext(xo, vo, inp.g, 0.05, 0.9, wd=wd, nesterov=nesterov, n=d)
+        assert_bitwise(host(x), xo, "allreduce x")
+        assert_bitwise(host(v), vo, "allreduce v")
+
+        x, v, c = dev(inp.x), dev(inp.v), dev(inp.center)
+        ctx.step_easgd(x, v, dev(inp.g), c, 0.9 / k)
+        xo, vo, co = inp.x.copy(), inp.v.copy(), inp.center.copy()
+        oracle.step_easgd_ext(xo, vo, inp.g, co, 0.05, 0.9, 0.9 / k, wd=wd, nesterov=nesterov, n=d)
+        assert_bitwise(host(x), xo, "easgd x")
+        assert_bitwise(host(v), vo, "easgd v")
+        assert_bitwise(host(c), co, "easgd center")
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES)
+@pytest.mark.parametrize("wd,nesterov", [(0.0, False)] + LOCAL_STEPS)
+def test_local_step_alone(G, oracle, k, d, ld, wd, nesterov):
+    """The local step is the gossip step against oneself (the mix term is zero)."""
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=24)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9) as ctx:
+        ctx.set_local_step(wd, nesterov)
+        x, v = dev(inp.x), dev(inp.v)
+        ctx.step_local(x, v, dev(inp.g))
+        xo, vo = inp.x.copy(), inp.v.copy()
+        oracle.step_gossip_ext(xo, vo, inp.g, 0.05, 0.9, 0.5, list(range(k)), wd=wd, nesterov=nesterov, n=d)
+        assert_bitwise(host(x), xo, "x")
+        assert_bitwise(host(v), vo, "v")
+
+
+def test_segmented_layout_with_the_extended_local_step(G, oracle):
+    k, d = 6, 7 * 1024 + 3
+    ld = W.round_up(d, 4)
+    off, sc = W.random_segments(d, 37, seed=3, align=1)
+    lrc = oracle.expand_lr(0.05, d, off, sc)
+    inp = W.make_inputs(k, d, ld, seed=25)
+    perm = [int(t) for t in oracle.make_perm(SEED, 1, k)]
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, seg_offsets=off, seg_lr_scale=sc) as ctx:
+        ctx.set_local_step(1e-4, True)
+        x, v = dev(inp.x), dev(inp.v)
+        ctx.step_gossip_stale(x, v, dev(inp.g), perm, 0.5)
+        xo, vo = inp.x.copy(), inp.v.copy()
+        oracle.step_gossip_ext(xo, vo, inp.g, lrc, 0.9, 0.5, perm, wd=1e-4, nesterov=True, stale=True, n=d)
+        assert_bitwise(host(x), xo, "stale gossip x")
+        x, v = dev(inp.x), dev(inp.v)
+        ctx.step_allreduce(x, v, dev(inp.g))
+        xo, vo = inp.x.copy(), inp.v.copy()
+        oracle.step_allreduce_ext(xo, vo, inp.g, lrc, 0.9, wd=1e-4, nesterov=True, n=d)
+        assert_bitwise(host(x), xo, "allreduce x")
+        assert_bitwise(host(v), vo, "allreduce v")
+        x, v = dev(inp.x), dev(inp.v)
+        ctx.step_local(x, v, dev(inp.g))
+        xo, vo = inp.x.copy(), inp.v.copy()
+        oracle.step_gossip_ext(xo, vo, inp.g, lrc, 0.9, 0.0, list(range(k)), wd=1e-4, nesterov=True, n=d)
+        assert_bitwise(host(x), xo, "local x")
+
+
+@pytest.mark.parametrize("kind", [1, 0])
+def test_fused_generator_with_the_extended_local_step(G, oracle, kind):
+    k, d = 8, 3 * 1024 + 6
+    ld = W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=26)
+    perm = [int(t) for t in oracle.make_perm(SEED, 2, k)]
+    with G.Context(k, d, ld, sigma=0.2, seed=SEED, noise_kind=kind) as ctx:
+        ctx.set_local_step(1e-4, True)
+        xb, vb = dev(inp.x), dev(inp.v)
+        ctx.step_gossip_fused(xb, vb, dev(inp.h), dev(inp.xstar), perm, 17, 0.5)
+        xo, vo, go = inp.x.copy(), inp.v.copy(), inp.g.copy()
+        oracle.gen_grad(xo, inp.h, inp.xstar, go, 0.2, SEED, 17, kind, n=d)
+        oracle.step_gossip_ext(xo, vo, go, 0.05, 0.9, 0.5, perm, wd=1e-4, nesterov=True, n=d)
+        if kind == 1:
+            assert_bitwise(host(xb), xo, "x")
+            assert_bitwise(host(vb), vo, "v")
+        else:
+            assert_rows_close(host(xb)[:, :d], xo[:, :d], "x")
+
+
+def test_training_setup_trajectory_with_period_and_annealing(G, oracle):
+    """The paper's schedule in miniature: Nesterov 0.9, weight decay 1e-4,
+    exchange every tau = 10 iterations, step size annealed by 0.1 twice."""
+    k, d, steps, tau = 8, 5 * 1024 + 3, 60, 10
+    ld = W.round_up(d, 1024)
+    inp = W.make_inputs(k, d, ld, seed=27)
+    lr = 0.1
+    xo, vo, go = inp.x.copy(), inp.v.copy(), inp.g.copy()
+    oracle.init_replicas(xo, vo, None, inp.x0, SEED, 0, n=d)
+    exchanges = 0
+    with G.Context(k, d, ld, lr=lr, momentum=0.9, sigma=0.05, seed=SEED, noise_kind=G.NOISE_UNIFORM) as ctx:
+        ctx.set_local_step(1e-4, True)
+        x, v, g = dev(inp.x), dev(inp.v), dev(inp.g)
+        h, xs = dev(inp.h), dev(inp.xstar)
+        ctx.init_replicas(x, v, None, dev(inp.x0), G.INIT_BROADCAST)
+        for t in range(steps):
+            if t in (20, 40):
+                lr *= 0.1
+                ctx.set_lr(lr)
+            ctx.gen_grad(x, h, xs, g, t)
+            oracle.gen_grad(xo, inp.h, inp.xstar, go, 0.05, SEED, t, 1, n=d)
+            if G.comm_due(t, tau):
+                exchanges += 1
+                perm = G.make_perm(SEED, t, k)
+                ctx.step_gossip(x, v, g, perm, 0.5)
+            else:
+                perm = list(range(k))
+                ctx.step_local(x, v, g)
+            oracle.step_gossip_ext(xo, vo, go, np.float32(lr), 0.9, 0.5, perm, wd=1e-4, nesterov=True, n=d)
+        assert exchanges == steps // tau
+        assert_bitwise(host(x), xo, "x")
+        assert_bitwise(host(v), vo, "v")
