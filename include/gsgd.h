@@ -45,7 +45,7 @@ extern "C" {
 enum {
     GSGD_OK               =  0,
     GSGD_ERR_INVALID_ARG  = -1,    /* null pointer, k/d/ld out of range, misaligned pointer, bad enum */
-    GSGD_ERR_BAD_PERM     = -2,    /* peer_perm is not a bijection on 0..k-1 */
+    GSGD_ERR_BAD_PERM     = -2,    /* peer entry outside 0..k-1, or peer_perm not a bijection where one is required */
     GSGD_ERR_BAD_SEGMENTS = -3,    /* segment table not ascending from 0 to d */
     GSGD_ERR_HIP          = -4,    /* a HIP runtime call failed; see gsgd_last_hip_error */
     GSGD_ERR_UNSUPPORTED  = -5,
@@ -154,6 +154,18 @@ int gsgd_step_gossip(gsgd_ctx* ctx, float* x, float* v, const float* g,
 int gsgd_step_gossip_stale(gsgd_ctx* ctx, float* x, float* v, const float* g,
                            const int32_t* peer_perm, float beta, void* stream);
 
+/* Pull-gossip with arbitrary targets (Algorithm 3; Section 3.1: every node
+ * pulls from one node chosen uniformly at random, so several may pull from the
+ * same node and a node may pull from itself).  The update is that of
+ * gsgd_step_gossip (stale = 0) or of gsgd_step_gossip_stale (stale = 1), but
+ * peer may be any map into 0..k-1.  The mixing matrix is then only
+ * row-stochastic (Section 6.1.1): the replica mean is preserved in
+ * expectation, not exactly.  Still one in-place pass over x, v and g.
+ * peer: host, k entries, consumed before the call returns; GSGD_ERR_BAD_PERM
+ * for an entry outside 0..k-1. */
+int gsgd_step_gossip_pull(gsgd_ctx* ctx, float* x, float* v, const float* g,
+                          const int32_t* peer, float beta, int stale, void* stream);
+
 /* The local step alone (v_i and x_i <- x'_i, no exchange): what every node
  * does in the iterations between two exchanges when the communication period
  * tau of Algorithms 2-4 is larger than 1. */
@@ -193,6 +205,28 @@ int gsgd_philox_raw(gsgd_ctx* ctx, uint32_t c1, uint32_t c2, uint32_t c3, int64_
  * by Philox stream 5 at counter (i, 0, step, 5), index floor(r (i+1) / 2^32).
  * Pure host code, deterministic.  out: host, k entries. */
 int gsgd_make_perm(uint64_t seed, uint64_t step, int32_t k, int32_t* out);
+
+/* Independent uniform targets for one step (Section 3.1, j ~ Uniform over the
+ * nodes): node i takes word 0 of Philox stream 5 at counter (i, 1, step, 5).
+ *   exclude_self = 0: target floor(r k / 2^32), the node itself included
+ *                     (pull-gossip; a self-target is a no-op mix);
+ *   exclude_self = 1: a uniform draw among the k-1 other nodes (push-gossip's
+ *                     "one other random node"), floor(r (k-1) / 2^32) stepped
+ *                     over i; needs k >= 2.
+ * Pure host code, deterministic.  out: host, k entries. */
+int gsgd_make_targets(uint64_t seed, uint64_t step, int32_t k, int exclude_self, int32_t* out);
+
+/* Visiting order of the pull-gossip kernel for an arbitrary peer map, exported
+ * for tests.  walk[t] holds the replica index in its low 12 bits.  Replicas on
+ * a cycle of the map carry bit 14 (first of its cycle) / bit 15 (last), as in
+ * gsgd_perm_walk.  The others (bit 13 set) follow the cycle replica they hang
+ * off, parents before children, and say how the kernel's parent register is
+ * kept: bits 16..17 = 1 reload it from the last cycle replica, = 2 reload it
+ * from stack slot bits 20..23; bit 12 = this replica becomes the parent of what
+ * follows; bit 18 = the old parent is first saved to stack slot bits 20..23.
+ * *slots_used = stack slots the walk needs (at most 8 for k <= GSGD_MAX_K).
+ * Pure host code.  walk: host, k entries. */
+int gsgd_pull_walk(const int32_t* peer, int32_t k, uint32_t* walk, int32_t* slots_used);
 
 /* Order in which the gossip kernel visits replicas: the cycles of peer_perm,
  * each walked i, perm[i], perm[perm[i]], ...  walk[t] holds the replica index

@@ -449,6 +449,65 @@ int oracle_make_perm(uint64_t seed, uint32_t step, int32_t k, int32_t* out)
     return 0;
 }
 
+/* Independent uniform targets for one step (Section 3.1: every node draws
+ * j ~ Uniform over the nodes): node i uses word 0 of Philox(counter
+ * (i, 1, step, PERM), seed).  exclude_self = 0: j = floor(r k / 2^32), the node
+ * itself included (pull-gossip).  exclude_self = 1: a uniform draw among the
+ * k-1 other nodes, j = floor(r (k-1) / 2^32), stepped over i ("one other random
+ * node", push-gossip); needs k >= 2.                                          */
+int oracle_make_targets(uint64_t seed, uint32_t step, int32_t k, int exclude_self, int32_t* out)
+{
+    if (k < 1 || (exclude_self && k < 2)) return -1;
+    for (int32_t i = 0; i < k; ++i) {
+        uint32_t r[4];
+        philox_at(seed, (uint32_t)i, 1u, step, STREAM_PERM, r);
+        if (!exclude_self) {
+            out[i] = (int32_t)(((uint64_t)r[0] * (uint64_t)k) >> 32);
+        } else {
+            const int32_t j = (int32_t)(((uint64_t)r[0] * (uint64_t)(k - 1)) >> 32);
+            out[i] = j >= i ? j + 1 : j;
+        }
+    }
+    return 0;
+}
+
+/* Push-gossip step (Algorithm 4): after the local step every node sends its
+ * parameters to itself and to its target; a node's new parameters are the
+ * average of what it received,
+ *   theta_r <- ( theta'_r + sum over { i != r : target[i] = r } of theta'_i ) / (1 + number of such i).
+ * A node whose target is itself sends nothing beyond its own copy.  The sum
+ * runs in fp64 (own value first, then senders in ascending index) and the
+ * average is rounded once to fp32.                                            */
+int oracle_step_gossip_push(float* x, float* v, const float* g, int32_t k, int64_t n, int64_t ld,
+                            const float* lr_col, float mu, float wd, int nesterov, const int32_t* target)
+{
+    for (int32_t i = 0; i < k; ++i) if (target[i] < 0 || target[i] >= k) return -1;
+    float* xp = (float*)malloc(sizeof(float) * (size_t)k * (size_t)n);
+    if (!xp) return -2;
+    for (int32_t i = 0; i < k; ++i) {
+        #pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < n; ++j) {
+            float vn, xpost;
+            local_step_ext(x[i * ld + j], v[i * ld + j], g[i * ld + j], lr_col[j], mu, wd, nesterov, &vn, &xpost);
+            v[i * ld + j] = vn;
+            xp[(int64_t)i * n + j] = xpost;
+        }
+    }
+    for (int32_t r = 0; r < k; ++r) {
+        int32_t received = 1;
+        for (int32_t i = 0; i < k; ++i) if (i != r && target[i] == r) ++received;
+        #pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < n; ++j) {
+            double s = (double)xp[(int64_t)r * n + j];
+            for (int32_t i = 0; i < k; ++i)
+                if (i != r && target[i] == r) s += (double)xp[(int64_t)i * n + j];
+            x[r * ld + j] = (float)(s / (double)received);
+        }
+    }
+    free(xp);
+    return 0;
+}
+
 /* The two quantities the analysis bounds (Section 6.1) plus the mean's own
  * distance, all over the slice, in fp64:
  *   out[0] = sum_i ||x_i - xbar||^2   (agent consensus)

@@ -64,6 +64,11 @@ def lib():
         L.oracle_step_easgd_ext.argtypes = [_f32p, _f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f32p,
                                             C.c_float, C.c_float, C.c_int, C.c_float]
         L.oracle_step_easgd_ext.restype = C.c_int
+        L.oracle_make_targets.argtypes = [C.c_uint64, C.c_uint32, C.c_int32, C.c_int, _i32p]
+        L.oracle_make_targets.restype = C.c_int
+        L.oracle_step_gossip_push.argtypes = [_f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f32p,
+                                              C.c_float, C.c_float, C.c_int, _i32p]
+        L.oracle_step_gossip_push.restype = C.c_int
         L.oracle_make_perm.argtypes = [C.c_uint64, C.c_uint32, C.c_int32, _i32p]
         L.oracle_make_perm.restype = C.c_int
         L.oracle_stats.argtypes = [_f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f64p]
@@ -211,6 +216,26 @@ def step_easgd_ext(x, v, g, center, lr, mu, alpha_e, wd=0.0, nesterov=False, n=N
                                      float(wd), int(bool(nesterov)), float(alpha_e))
     if rc:
         raise ValueError("oracle_step_easgd_ext failed (%d)" % rc)
+
+
+def step_gossip_push(x, v, g, lr, mu, target, wd=0.0, nesterov=False, n=None):
+    k, ld = _rows(x)
+    n = ld if n is None else int(n)
+    lrc = _lr_col(lr, n)
+    t = np.ascontiguousarray(target, dtype=np.int32)
+    assert t.shape[0] == k
+    rc = lib().oracle_step_gossip_push(_f32(x), _f32(v), _f32(g), k, n, ld, _f32(lrc), float(mu), float(wd),
+                                       int(bool(nesterov)), t.ctypes.data_as(_i32p))
+    if rc:
+        raise ValueError("oracle_step_gossip_push failed (%d)" % rc)
+
+
+def make_targets(seed, step, k, exclude_self=False):
+    out = np.empty(int(k), np.int32)
+    rc = lib().oracle_make_targets(int(seed), int(step), int(k), int(bool(exclude_self)), out.ctypes.data_as(_i32p))
+    if rc:
+        raise ValueError("oracle_make_targets: k too small")
+    return out
 
 
 def make_perm(seed, step, k):

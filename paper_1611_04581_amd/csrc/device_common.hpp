@@ -101,18 +101,13 @@ __device__ __forceinline__ void local_step(f32x4 x, f32x4 v, f32x4 g, f32x4 neg_
     }
 }
 
-// Gossip mix of Section 3.1: x' - beta (x' - x'_peer)
-__device__ __forceinline__ f32x4 gossip_mix(f32x4 mine, f32x4 theirs, float neg_beta)
+// Gossip mix: post - beta (mine - theirs).  With fresh parameters (Section
+// 3.1 / 6.2.2) `mine` is the node's own post-step x' and `theirs` its peer's;
+// with stale parameters (Section 6.2.1) they are the two nodes' x from before
+// the local step.
+__device__ __forceinline__ f32x4 mix_keys(f32x4 post, f32x4 mine, f32x4 theirs, float neg_beta)
 {
     const f32x4 diff = mine - theirs;
-    return fma4(neg_beta, diff, mine);
-}
-
-// Gossip with stale parameters (Section 6.2.1): x' - beta (x - x_peer), the
-// difference taken between the parameters from before the local step.
-__device__ __forceinline__ f32x4 stale_mix(f32x4 post, f32x4 mine_old, f32x4 theirs_old, float neg_beta)
-{
-    const f32x4 diff = mine_old - theirs_old;
     return fma4(neg_beta, diff, post);
 }
 

@@ -219,11 +219,27 @@ int gossip_on_permutation(gsgd_ctx* ctx, float* x, float* v, const float* g, con
     Walk walk;
     rc = build_walk(peer_perm, ctx->cfg.k, &walk);
     if (rc != GSGD_OK) return rc;
-    const hipError_t e = launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale, x, v, g,
+    const hipError_t e = launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale, false, x, v, g,
                                             persist_of(ctx, GSGD_KERNEL_GOSSIP), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 }  // namespace
+
+extern "C" int gsgd_step_gossip_pull(gsgd_ctx* ctx, float* x, float* v, const float* g,
+                                     const int32_t* peer, float beta, int stale, void* stream)
+{
+    int rc = check_state(ctx, x, v, g);
+    if (rc != GSGD_OK) return rc;
+    if (!peer || !(beta == beta) || (stale != 0 && stale != 1)) return GSGD_ERR_INVALID_ARG;
+    Walk walk;
+    int has_trees = 0, slots = 0;
+    rc = build_pull_walk(peer, ctx->cfg.k, &walk, &has_trees, &slots);
+    if (rc != GSGD_OK) return rc;
+    const hipError_t e = launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale != 0,
+                                            has_trees != 0, x, v, g, persist_of(ctx, GSGD_KERNEL_GOSSIP),
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
 
 extern "C" int gsgd_step_gossip(gsgd_ctx* ctx, float* x, float* v, const float* g,
                                 const int32_t* peer_perm, float beta, void* stream)
@@ -291,7 +307,7 @@ extern "C" const char* gsgd_strerror(int code)
     switch (code) {
         case GSGD_OK: return "ok";
         case GSGD_ERR_INVALID_ARG: return "invalid argument";
-        case GSGD_ERR_BAD_PERM: return "peer_perm is not a permutation of 0..k-1";
+        case GSGD_ERR_BAD_PERM: return "peer map has an entry outside 0..k-1 or is not the permutation the call requires";
         case GSGD_ERR_BAD_SEGMENTS: return "segment table must ascend strictly from 0 to d";
         case GSGD_ERR_HIP: return "HIP runtime error";
         case GSGD_ERR_UNSUPPORTED: return "unsupported";

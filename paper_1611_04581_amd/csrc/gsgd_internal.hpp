@@ -16,12 +16,26 @@ constexpr uint32_t WALK_ROW_MASK = 0x0FFF;
 constexpr uint32_t WALK_FIRST    = 0x4000;   // first member of a cycle
 constexpr uint32_t WALK_LAST     = 0x8000;   // last member of a cycle
 // General pull maps (several replicas may pull from the same one) add tree
-// nodes hanging off the cycles: a tree node's peer is its parent, whose x' is
-// the cycle node's register (depth 1) or an LDS stack slot (depth >= 2).
-constexpr uint32_t WALK_TREE        = 0x2000;   // not on a cycle; finished as soon as it is loaded
-constexpr uint32_t WALK_PUSH        = 0x1000;   // has children: keep its x' at stack level depth-1
-constexpr uint32_t WALK_DEPTH_SHIFT = 16;       // bits 16..27: distance to the cycle (tree nodes)
-constexpr int      WALK_MAX_LEVELS  = 32;       // stack levels a launch can hold in LDS
+// nodes hanging off the cycles.  A tree node's peer is its parent, which was
+// visited earlier; the kernel keeps the parent's value in a register `par`
+// and is told per entry how to maintain it:
+//   restore (before use): par <- the last cycle node's value, or <- stack slot
+//   descend (after use) : par <- this node's value (its children follow)
+//   save    (with descend): stack slot <- par first (a sibling subtree follows)
+// The stack lives in LDS, one 16-byte lane per thread and slot.
+constexpr uint32_t WALK_TREE          = 0x2000;    // not on a cycle: finished as soon as it is loaded
+constexpr uint32_t WALK_DESCEND       = 0x1000;
+constexpr uint32_t WALK_RESTORE_SHIFT = 16;        // bits 16..17: 0 keep par, 1 from the cycle register, 2 from a slot
+constexpr uint32_t WALK_RESTORE_PREV  = 1u << WALK_RESTORE_SHIFT;
+constexpr uint32_t WALK_RESTORE_SLOT  = 2u << WALK_RESTORE_SHIFT;
+constexpr uint32_t WALK_RESTORE_MASK  = 3u << WALK_RESTORE_SHIFT;
+constexpr uint32_t WALK_SAVE          = 0x40000;   // bit 18
+constexpr uint32_t WALK_SLOT_SHIFT    = 20;        // bits 20..23: the slot restored from or saved to
+constexpr uint32_t WALK_SLOT_MASK     = 0xFu << WALK_SLOT_SHIFT;
+// Children are visited so that the subtree needing most slots comes last and
+// reuses its parent's slot; a subtree that needs s slots then has at least
+// 3 * 2^s - 1 nodes, so 8 slots cover every map on up to GSGD_MAX_K replicas.
+constexpr int      WALK_SLOTS         = 8;
 struct Walk {
     uint32_t seq[GSGD_MAX_K];
 };
@@ -64,7 +78,7 @@ struct Persist {
 
 // ---- launchers (defined next to their kernels) ---------------------------
 hipError_t launch_step_gossip(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&, bool stale,
-                              float* x, float* v, const float* g, Persist, hipStream_t);
+                              bool has_trees, float* x, float* v, const float* g, Persist, hipStream_t);
 hipError_t launch_step_local(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
                              Persist, hipStream_t);
 hipError_t launch_step_gossip_fused(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&,
@@ -89,5 +103,7 @@ hipError_t launch_stats(const Geom&, const float* x, const float* xstar, double*
 // ---- host-only helpers -----------------------------------------------------
 void host_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 int  build_walk(const int32_t* perm, int32_t k, Walk* out);   // GSGD_OK or GSGD_ERR_BAD_PERM
+// any map into 0..k-1; *has_trees = 0 when the map is a permutation
+int  build_pull_walk(const int32_t* peer, int32_t k, Walk* out, int* has_trees, int* slots_used);
 
 }  // namespace gsgd

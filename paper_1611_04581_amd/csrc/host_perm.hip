@@ -57,74 +57,158 @@ int build_walk(const int32_t* perm, int32_t k, Walk* out)
 }
 
 // Visiting order for an arbitrary pull map ("each node pulls from one uniformly
-// chosen node", Section 3.1): the map is a functional graph, i.e. cycles with
-// trees hanging off them.  Cycles are walked as for a permutation; right after
-// a cycle node is loaded, every node that pulls from it is visited depth-first
-// (children in ascending index).  A tree node's peer is its parent, which was
-// loaded earlier and whose x' is still held (the cycle register at depth 1,
-// stack level depth-2 otherwise), so tree nodes are finished the moment they
-// are loaded.  *levels is the number of stack levels the kernel needs.
-int build_pull_walk(const int32_t* peer, int32_t k, Walk* out, int* levels)
+// chosen node", Section 3.1).  The map is a functional graph: cycles with trees
+// hanging off them.  Cycles are walked as for a permutation; right after a
+// cycle node, the trees of nodes that pull (directly or through others) from
+// it are visited depth-first, parents before children, so that a tree node's
+// peer has always been loaded already and the node is finished on the spot.
+//
+// Order of the children of a node: childless ones first, then the others by
+// the number of stack slots their subtree needs, the neediest last.  Only a
+// subtree that is not the last one forces its parent's value to be saved, so
+// slots(n) = max(slots(last child), 1 + slots(any other child with children)),
+// which grows like log2 of the subtree size instead of its height.
+namespace {
+
+struct PullWalkBuilder {
+    Walk*          out;
+    int32_t        t;
+    int            max_slot;
+    int32_t        head[GSGD_MAX_K], next[GSGD_MAX_K];   // children lists (tree nodes only), ascending index
+    int32_t        need[GSGD_MAX_K];                     // slots the subtree below a tree node needs
+    int32_t        pool[GSGD_MAX_K];                     // ordered children of the nodes on the current path
+    int32_t        pool_top;
+
+    bool inner(int32_t n) const { return head[n] >= 0; }
+
+    // Writes the children of n in visiting order to kids; *first_inner is the
+    // position of the first child that has children itself.
+    int32_t ordered_children(int32_t n, int32_t* kids, int32_t* first_inner) const
+    {
+        int32_t m = 0;
+        for (int32_t c = head[n]; c >= 0; c = next[c]) if (!inner(c)) kids[m++] = c;
+        *first_inner = m;
+        for (int32_t c = head[n]; c >= 0; c = next[c]) if (inner(c)) kids[m++] = c;
+        for (int32_t a = *first_inner + 1; a < m; ++a) {          // stable insertion sort by need
+            const int32_t c = kids[a];
+            int32_t b = a;
+            while (b > *first_inner && need[kids[b - 1]] > need[c]) { kids[b] = kids[b - 1]; --b; }
+            kids[b] = c;
+        }
+        return m;
+    }
+
+    // Emits the subtree below n (n itself is already out).  On entry the
+    // kernel's `par` holds n's value unless n is a cycle node, in which case
+    // every child fetches it from the cycle register.  Slots below `base` are
+    // in use by ancestors.
+    void emit_children(int32_t n, int base, bool n_on_cycle)
+    {
+        int32_t* kids = pool + pool_top;
+        int32_t first_inner = 0;
+        const int32_t m = ordered_children(n, kids, &first_inner);
+        pool_top += m;
+        for (int32_t a = 0; a < m; ++a) {
+            const int32_t c = kids[a];
+            uint32_t word = static_cast<uint32_t>(c) | WALK_TREE;
+            const bool c_inner = a >= first_inner;
+            const bool last = a == m - 1;
+            int child_base = base;
+            if (n_on_cycle) {
+                word |= WALK_RESTORE_PREV;
+            } else if (c_inner && a > first_inner) {
+                word |= WALK_RESTORE_SLOT | (static_cast<uint32_t>(base) << WALK_SLOT_SHIFT);
+            }
+            if (c_inner) {
+                word |= WALK_DESCEND;
+                if (!n_on_cycle && !last) {
+                    // n's value is needed again after c's subtree: it sits in slot `base` meanwhile
+                    if (a == first_inner) word |= WALK_SAVE | (static_cast<uint32_t>(base) << WALK_SLOT_SHIFT);
+                    if (base > max_slot) max_slot = base;
+                    child_base = base + 1;
+                }
+            }
+            out->seq[t++] = word;
+            if (c_inner) emit_children(c, child_base, false);
+        }
+        pool_top -= m;
+    }
+};
+
+}  // namespace
+
+int build_pull_walk(const int32_t* peer, int32_t k, Walk* out, int* has_trees, int* slots_used)
 {
-    if (!peer || !out || !levels || k < 1 || k > GSGD_MAX_K) return GSGD_ERR_INVALID_ARG;
+    if (!peer || !out || !has_trees || !slots_used || k < 1 || k > GSGD_MAX_K) return GSGD_ERR_INVALID_ARG;
     for (int32_t i = 0; i < k; ++i)
         if (peer[i] < 0 || peer[i] >= k) return GSGD_ERR_BAD_PERM;
-    // which nodes lie on a cycle: follow the map k steps from everywhere (lands on a cycle), then mark that cycle
+    // which nodes lie on a cycle: follow the map from every unvisited node, tagging the path; a path that runs
+    // into its own tag has closed a new cycle, one that runs into an older tag has joined a known component
     bool on_cycle[GSGD_MAX_K];
+    int32_t tag[GSGD_MAX_K];
     memset(on_cycle, 0, sizeof(on_cycle));
+    memset(tag, 0, sizeof(tag));
     for (int32_t s = 0; s < k; ++s) {
         int32_t i = s;
-        for (int32_t step = 0; step < k; ++step) i = peer[i];
-        while (!on_cycle[i]) { on_cycle[i] = true; i = peer[i]; }
+        while (tag[i] == 0) { tag[i] = s + 1; i = peer[i]; }
+        if (tag[i] != s + 1) continue;
+        for (int32_t j = i; !on_cycle[j]; j = peer[j]) on_cycle[j] = true;
     }
-    // children lists (nodes pulling from j, cycle predecessors excluded), ascending by construction
-    int32_t head[GSGD_MAX_K], next[GSGD_MAX_K], tail[GSGD_MAX_K];
-    for (int32_t i = 0; i < k; ++i) head[i] = tail[i] = next[i] = -1;
+    PullWalkBuilder b;
+    b.out = out;
+    b.t = 0;
+    b.max_slot = -1;
+    b.pool_top = 0;
+    int32_t tail[GSGD_MAX_K];
+    for (int32_t i = 0; i < k; ++i) { b.head[i] = tail[i] = b.next[i] = -1; b.need[i] = 0; }
+    int32_t n_tree = 0;
     for (int32_t i = 0; i < k; ++i) {
         if (on_cycle[i]) continue;
+        ++n_tree;
         const int32_t j = peer[i];
-        if (head[j] < 0) head[j] = i; else next[tail[j]] = i;
+        if (b.head[j] < 0) b.head[j] = i; else b.next[tail[j]] = i;
         tail[j] = i;
+    }
+    // slots needed below every tree node, children before parents (reverse breadth-first order)
+    int32_t order[GSGD_MAX_K];
+    int32_t n_order = 0;
+    for (int32_t i = 0; i < k; ++i)
+        if (on_cycle[i]) for (int32_t c = b.head[i]; c >= 0; c = b.next[c]) order[n_order++] = c;
+    for (int32_t q = 0; q < n_order; ++q)
+        for (int32_t c = b.head[order[q]]; c >= 0; c = b.next[c]) order[n_order++] = c;
+    if (n_order != n_tree) return GSGD_ERR_BAD_PERM;        // cannot happen for a valid map
+    for (int32_t q = n_order - 1; q >= 0; --q) {
+        const int32_t n = order[q];
+        int32_t largest = -1, second = -1;
+        for (int32_t c = b.head[n]; c >= 0; c = b.next[c]) {
+            if (!b.inner(c)) continue;
+            if (b.need[c] > largest) { second = largest; largest = b.need[c]; }
+            else if (b.need[c] > second) second = b.need[c];
+        }
+        b.need[n] = largest < 0 ? 0 : (second < 0 ? largest : (largest > second + 1 ? largest : second + 1));
     }
     bool seen[GSGD_MAX_K];
     memset(seen, 0, sizeof(seen));
-    int32_t t = 0, max_level = 0;
-    int32_t stack_node[GSGD_MAX_K], stack_child[GSGD_MAX_K];
     for (int32_t start = 0; start < k; ++start) {
         if (!on_cycle[start] || seen[start]) continue;
-        const int32_t first_slot = t;
-        int32_t last_cycle_slot = t;
+        const int32_t first_slot = b.t;
+        int32_t last_cycle_slot = b.t;
         int32_t c = start;
         do {
             seen[c] = true;
-            last_cycle_slot = t;
-            out->seq[t++] = static_cast<uint32_t>(c);
-            // depth-first over the tree below cycle node c
-            int32_t sp = 0;
-            stack_node[0] = c;
-            stack_child[0] = head[c];
-            while (sp >= 0) {
-                const int32_t child = stack_child[sp];
-                if (child < 0) { --sp; continue; }
-                stack_child[sp] = next[child];
-                const int32_t depth = sp + 1;                 // distance of `child` to the cycle
-                uint32_t word = static_cast<uint32_t>(child) | WALK_TREE | (static_cast<uint32_t>(depth) << WALK_DEPTH_SHIFT);
-                if (head[child] >= 0) {
-                    word |= WALK_PUSH;
-                    if (depth > max_level) max_level = depth;  // uses stack level depth-1
-                }
-                seen[child] = true;
-                out->seq[t++] = word;
-                if (head[child] >= 0) { ++sp; stack_node[sp] = child; stack_child[sp] = head[child]; }
-            }
+            last_cycle_slot = b.t;
+            out->seq[b.t++] = static_cast<uint32_t>(c);
+            b.emit_children(c, 0, true);
             c = peer[c];
         } while (c != start);
         out->seq[first_slot] |= WALK_FIRST;
         out->seq[last_cycle_slot] |= WALK_LAST;
     }
-    for (int32_t r = t; r < GSGD_MAX_K; ++r) out->seq[r] = 0;
-    *levels = max_level;
-    return t == k ? GSGD_OK : GSGD_ERR_BAD_PERM;
+    for (int32_t r = b.t; r < GSGD_MAX_K; ++r) out->seq[r] = 0;
+    if (b.t != k) return GSGD_ERR_BAD_PERM;
+    *has_trees = n_tree > 0 ? 1 : 0;
+    *slots_used = b.max_slot + 1;
+    return *slots_used <= WALK_SLOTS ? GSGD_OK : GSGD_ERR_UNSUPPORTED;
 }
 
 }  // namespace gsgd
@@ -143,6 +227,37 @@ extern "C" int gsgd_make_perm(uint64_t seed, uint64_t step, int32_t k, int32_t* 
         out[i] = out[j];
         out[j] = tmp;
     }
+    return GSGD_OK;
+}
+
+// Independent uniform targets, one draw per node (Section 3.1: j ~ Uniform over
+// the nodes): node i takes word 0 of Philox(counter (i, 1, step, 5)).
+extern "C" int gsgd_make_targets(uint64_t seed, uint64_t step, int32_t k, int exclude_self, int32_t* out)
+{
+    if (!out || k < 1 || step > 0xFFFFFFFFull || (exclude_self != 0 && exclude_self != 1)) return GSGD_ERR_INVALID_ARG;
+    if (exclude_self && k < 2) return GSGD_ERR_INVALID_ARG;
+    const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+    const uint64_t range = static_cast<uint64_t>(exclude_self ? k - 1 : k);
+    for (int32_t i = 0; i < k; ++i) {
+        const uint32_t ctr[4] = {static_cast<uint32_t>(i), 1u, static_cast<uint32_t>(step), 5u};
+        uint32_t r[4];
+        gsgd::host_philox4x32_10(ctr, key, r);
+        int32_t j = static_cast<int32_t>((static_cast<uint64_t>(r[0]) * range) >> 32);
+        if (exclude_self && j >= i) ++j;          // skip over the node itself
+        out[i] = j;
+    }
+    return GSGD_OK;
+}
+
+extern "C" int gsgd_pull_walk(const int32_t* peer, int32_t k, uint32_t* walk, int32_t* slots_used)
+{
+    if (!walk || !slots_used) return GSGD_ERR_INVALID_ARG;
+    gsgd::Walk w;
+    int has_trees = 0, slots = 0;
+    const int rc = gsgd::build_pull_walk(peer, k, &w, &has_trees, &slots);
+    if (rc != GSGD_OK) return rc;
+    for (int32_t t = 0; t < k; ++t) walk[t] = w.seq[t];
+    *slots_used = slots;
     return GSGD_OK;
 }
 

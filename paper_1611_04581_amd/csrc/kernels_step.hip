@@ -34,20 +34,28 @@ __device__ __forceinline__ void for_row_batches(int k, Body&& body)
 
 // ---------------------------------------------------------------------------
 // Gossip.  x_new[i] needs the post-step parameters of replica i and of its
-// peer.  Rows are visited along the cycles of the permutation,
-// i -> perm[i] -> perm[perm[i]] ..., so the peer of the row visited last time
+// peer.  Rows are visited along the cycles of the peer map,
+// i -> peer[i] -> peer[peer[i]] ..., so the peer of the row visited last time
 // is the row visited now: keeping `first`, `prev` and the current x' in
 // registers is enough to finish every row in place, in one pass, without a
 // second buffer and without two replicas ever racing on a row.
 //
-// STALE selects the variant of Section 6.2.1 (gradient step and gossip at the
-// same time): the mixing term is taken between the parameters from before the
-// local step, x_i <- x'_i - beta (x_i - x_peer), so the walk also carries the
-// old x of the first and of the previous row.
-template <bool FULL, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE>
+// What a row contributes to the mix of the row pulling from it is called its
+// "key" below: x' for the fresh-parameter rule of Sections 3.1 / 6.2.2, and
+// the x from before the local step for the stale-parameter rule of Section
+// 6.2.1 (STALE), x_i <- x'_i - beta (x_i - x_peer).
+//
+// TREE: the peer map is not a bijection (iid pull targets).  Rows that are on
+// no cycle follow the cycle row they hang off, parents before children; each
+// is finished as soon as it is loaded, against its parent's key, which the
+// walk keeps in `par` (see the WALK_* flags) with an LDS stack lane per thread
+// for the few keys that must outlive a sibling subtree.
+typedef f32x4 KeyStack[WALK_SLOTS][BLOCK];
+
+template <bool FULL, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE, bool TREE>
 __device__ __forceinline__
 void gossip_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
-                      float neg_beta, const Walk& walk,
+                      float neg_beta, const Walk& walk, KeyStack* stack,
                       float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
                       const float* __restrict__ h, const float* __restrict__ xstar,
                       float sigma, RngKey key, uint32_t step)
@@ -61,9 +69,9 @@ void gossip_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, con
     }
     const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
 
-    f32x4 first = {0.f, 0.f, 0.f, 0.f}, prev = {0.f, 0.f, 0.f, 0.f};
-    f32x4 first_old = {0.f, 0.f, 0.f, 0.f}, prev_old = {0.f, 0.f, 0.f, 0.f};   // STALE only
-    int64_t prev_off = 0;                      // uniform: row offset of the previously visited replica
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4 first_key = zero, prev_key = zero, prev_post = zero, par = zero;
+    int64_t prev_off = 0;                      // uniform: row offset of the cycle row visited last
 
     for_row_batches<U>(geo.k, [&](auto n, int t0) {
         constexpr int N = decltype(n)::value;
@@ -87,27 +95,32 @@ void gossip_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, con
                 const f32x4 t2 = sigma * xi;
                 G[u] = fma4(h4, t1, t2);
             }
-            f32x4 vn, xp;
-            local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, xp);
+            f32x4 vn, post;
+            local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, post);
             store_quad<FULL>(v + off + qd.lane_col, vn, valid);
-            if constexpr (!STALE) {
-                if (w[u] & WALK_FIRST) first = xp;
-                else store_quad<FULL>(x + prev_off + qd.lane_col, gossip_mix(prev, xp, neg_beta), valid);
-                if (w[u] & WALK_LAST) store_quad<FULL>(x + off + qd.lane_col, gossip_mix(xp, first, neg_beta), valid);
+            const f32x4 mine = STALE ? X[u] : post;
+            if (TREE && (w[u] & WALK_TREE)) {
+                const uint32_t slot = (w[u] & WALK_SLOT_MASK) >> WALK_SLOT_SHIFT;
+                const uint32_t restore = w[u] & WALK_RESTORE_MASK;
+                if (restore == WALK_RESTORE_PREV) par = prev_key;
+                else if (restore == WALK_RESTORE_SLOT) par = (*stack)[slot][threadIdx.x];
+                store_quad<FULL>(x + off + qd.lane_col, mix_keys(post, mine, par, neg_beta), valid);
+                if (w[u] & WALK_SAVE) (*stack)[slot][threadIdx.x] = par;
+                if (w[u] & WALK_DESCEND) par = mine;
             } else {
-                if (w[u] & WALK_FIRST) first_old = X[u];
-                else store_quad<FULL>(x + prev_off + qd.lane_col, stale_mix(prev, prev_old, X[u], neg_beta), valid);
+                if (w[u] & WALK_FIRST) first_key = mine;
+                else store_quad<FULL>(x + prev_off + qd.lane_col, mix_keys(prev_post, prev_key, mine, neg_beta), valid);
                 if (w[u] & WALK_LAST)
-                    store_quad<FULL>(x + off + qd.lane_col, stale_mix(xp, X[u], first_old, neg_beta), valid);
-                prev_old = X[u];
+                    store_quad<FULL>(x + off + qd.lane_col, mix_keys(post, mine, first_key, neg_beta), valid);
+                prev_key = mine;
+                prev_post = post;
+                prev_off = off;
             }
-            prev = xp;
-            prev_off = off;
         }
     });
 }
 
-template <int U, bool FUSED_GEN, int NOISE, bool EXT = false, bool STALE = false>
+template <int U, bool FUSED_GEN, int NOISE, bool EXT = false, bool STALE = false, bool TREE = false>
 __global__ __launch_bounds__(BLOCK)
 void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk walk,
                         float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
@@ -115,15 +128,17 @@ void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk w
                         float sigma, RngKey key, uint32_t step, uint32_t* __restrict__ tickets, uint32_t n_tiles)
 {
     __shared__ SegLds lds;
+    __shared__ f32x4 stack_mem[TREE ? WALK_SLOTS : 1][TREE ? BLOCK : 1];
+    KeyStack* stack = reinterpret_cast<KeyStack*>(&stack_mem[0][0]);     // only dereferenced when TREE
     stage_segments(seg, lds);
     for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
         const Quad qd = quad_of_tile(tile, geo.d);
         if (tile_is_full(qd, geo.d))
-            gossip_step_body<true, U, FUSED_GEN, NOISE, EXT, STALE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h,
-                                                                    xstar, sigma, key, step);
+            gossip_step_body<true, U, FUSED_GEN, NOISE, EXT, STALE, TREE>(geo, hp, seg, lds, qd, neg_beta, walk, stack,
+                                                                          x, v, g, h, xstar, sigma, key, step);
         else if (qd.valid > 0)
-            gossip_step_body<false, U, FUSED_GEN, NOISE, EXT, STALE>(geo, hp, seg, lds, qd, neg_beta, walk, x, v, g, h,
-                                                                     xstar, sigma, key, step);
+            gossip_step_body<false, U, FUSED_GEN, NOISE, EXT, STALE, TREE>(geo, hp, seg, lds, qd, neg_beta, walk, stack,
+                                                                           x, v, g, h, xstar, sigma, key, step);
     });
 }
 
@@ -341,11 +356,21 @@ static inline unsigned width_for(const Geom& geo, const Persist& p)
     hipLaunchKernelGGL(KERNEL, dim3(width_for(geo, p)), dim3(BLOCK), 0, stream, __VA_ARGS__)
 
 hipError_t launch_step_gossip(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta, const Walk& walk,
-                              bool stale, float* x, float* v, const float* g, Persist p, hipStream_t stream)
+                              bool stale, bool has_trees, float* x, float* v, const float* g, Persist p,
+                              hipStream_t stream)
 {
     const RngKey no_key{0u, 0u};
     const uint32_t tiles = grid_for(geo.d);
-    if (stale)
+    if (has_trees && stale)
+        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0, true, true, true>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
+                    nullptr, 0.0f, no_key, 0u, p.tickets, tiles);
+    else if (has_trees && hp.extended())
+        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0, true, false, true>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
+                    nullptr, 0.0f, no_key, 0u, p.tickets, tiles);
+    else if (has_trees)
+        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0, false, false, true>), geo, hp, seg, -beta, walk, x, v, g,
+                    nullptr, nullptr, 0.0f, no_key, 0u, p.tickets, tiles);
+    else if (stale)
         GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0, true, true>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
                     nullptr, 0.0f, no_key, 0u, p.tickets, tiles);
     else if (hp.extended())

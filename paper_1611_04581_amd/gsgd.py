@@ -24,6 +24,8 @@ FILL_XSTAR, FILL_H, FILL_X0 = 2, 3, 4
 KERNEL_GOSSIP, KERNEL_ALLREDUCE, KERNEL_EASGD, KERNEL_GEN_GRAD, KERNEL_GOSSIP_FUSED, KERNEL_LOCAL = range(6)
 KERNEL_COUNT = 6
 WALK_ROW_MASK, WALK_FIRST, WALK_LAST = 0x0FFF, 0x4000, 0x8000
+WALK_TREE, WALK_DESCEND, WALK_SAVE = 0x2000, 0x1000, 0x40000
+WALK_RESTORE_SHIFT, WALK_SLOT_SHIFT, WALK_SLOTS = 16, 20, 8
 
 
 class GsgdError(RuntimeError):
@@ -52,6 +54,9 @@ SIGNATURES = {
     "gsgd_comm_due": (C.c_int, [C.c_uint64, C.c_uint32]),
     "gsgd_step_gossip_stale": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, _vp]),
     "gsgd_step_local": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
+    "gsgd_step_gossip_pull": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, C.c_int, _vp]),
+    "gsgd_make_targets": (C.c_int, [C.c_uint64, C.c_uint64, C.c_int32, C.c_int, C.POINTER(C.c_int32)]),
+    "gsgd_pull_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint32), C.POINTER(C.c_int32)]),
     "gsgd_init_replicas": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int, _vp]),
     "gsgd_fill": (C.c_int, [_vp, _vp, C.c_int, _vp]),
     "gsgd_gen_grad": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_uint64, _vp]),
@@ -186,6 +191,11 @@ class Context:
         _check(lib().gsgd_step_gossip_stale(self._h, _ptr(x), _ptr(v), _ptr(g), p, float(beta), _stream(stream)),
                "gsgd_step_gossip_stale")
 
+    def step_gossip_pull(self, x, v, g, peer, beta=0.5, stale=False, stream=None):
+        keep, p = _perm_arg(peer)
+        _check(lib().gsgd_step_gossip_pull(self._h, _ptr(x), _ptr(v), _ptr(g), p, float(beta), int(bool(stale)),
+                                           _stream(stream)), "gsgd_step_gossip_pull")
+
     def step_local(self, x, v, g, stream=None):
         _check(lib().gsgd_step_local(self._h, _ptr(x), _ptr(v), _ptr(g), _stream(stream)), "gsgd_step_local")
 
@@ -220,6 +230,23 @@ def make_perm(seed, step, k):
     _check(lib().gsgd_make_perm(int(seed), int(step), int(k), out.ctypes.data_as(C.POINTER(C.c_int32))),
            "gsgd_make_perm")
     return out
+
+
+def make_targets(seed, step, k, exclude_self=False):
+    out = np.empty(int(k), np.int32)
+    _check(lib().gsgd_make_targets(int(seed), int(step), int(k), int(bool(exclude_self)),
+                                   out.ctypes.data_as(C.POINTER(C.c_int32))), "gsgd_make_targets")
+    return out
+
+
+def pull_walk(peer):
+    """(walk words, stack slots used) for an arbitrary peer map."""
+    keep, p = _perm_arg(peer)
+    out = np.empty(keep.shape[0], np.uint32)
+    slots = C.c_int32(0)
+    _check(lib().gsgd_pull_walk(p, int(keep.shape[0]), out.ctypes.data_as(C.POINTER(C.c_uint32)), C.byref(slots)),
+           "gsgd_pull_walk")
+    return out, int(slots.value)
 
 
 def perm_walk(peer_perm):

@@ -195,3 +195,91 @@ def test_training_setup_trajectory_with_period_and_annealing(G, oracle):
         assert exchanges == steps // tau
         assert_bitwise(host(x), xo, "x")
         assert_bitwise(host(v), vo, "v")
+
+
+# ----------------------------------------------------------------------------
+# pull-gossip on arbitrary maps (iid targets: several replicas may pull from one)
+
+def some_maps(k, oracle):
+    rng = np.random.default_rng(100 + k)
+    maps = [[0] * k, [max(i - 1, 0) for i in range(k)], [i // 2 for i in range(k)],
+            [(i - 1) // 3 if i else 0 for i in range(k)], [(i + 1) % k for i in range(k)]]
+    maps += [[int(t) for t in oracle.make_targets(SEED, s, k)] for s in range(4)]
+    maps += [[int(t) for t in rng.integers(0, k, size=k)] for _ in range(3)]
+    return maps
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES + [(128, 1024 + 12, None)])
+def test_pull_gossip_on_arbitrary_maps(G, oracle, k, d, ld):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=31)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9) as ctx:
+        for peer in some_maps(k, oracle):
+            assert np.array_equal(G.make_targets(SEED, 3, k), oracle.make_targets(SEED, 3, k))
+            for stale in (False, True):
+                x, v = dev(inp.x), dev(inp.v)
+                ctx.step_gossip_pull(x, v, dev(inp.g), peer, 0.5, stale)
+                xo, vo = inp.x.copy(), inp.v.copy()
+                if stale:
+                    oracle.step_gossip_ext(xo, vo, inp.g, 0.05, 0.9, 0.5, peer, stale=True, n=d)
+                else:
+                    oracle.step_gossip(xo, vo, inp.g, 0.05, 0.9, 0.5, peer, n=d)
+                assert_bitwise(host(x), xo, "x peer=%s stale=%s" % (peer, stale))
+                assert_bitwise(host(v), vo, "v")
+        ctx.set_local_step(1e-4, True)
+        for peer in some_maps(k, oracle)[5:8]:
+            x, v = dev(inp.x), dev(inp.v)
+            ctx.step_gossip_pull(x, v, dev(inp.g), peer, 0.3)
+            xo, vo = inp.x.copy(), inp.v.copy()
+            oracle.step_gossip_ext(xo, vo, inp.g, 0.05, 0.9, 0.3, peer, wd=1e-4, nesterov=True, n=d)
+            assert_bitwise(host(x), xo, "x peer=%s nesterov" % peer)
+        with pytest.raises(G.GsgdError) as e:
+            ctx.step_gossip_pull(x, v, dev(inp.g), [k] * k, 0.5)
+        assert e.value.code == G.ERR_BAD_PERM
+
+
+def test_pull_gossip_max_replicas_deep_and_bushy_maps(G, oracle):
+    k, d = G.MAX_K, 1024 + 4
+    inp = W.make_inputs(k, d, seed=32)
+    maps = [[max(i - 1, 0) for i in range(k)],                  # one chain of 512
+            [(i - 1) // 2 if i else 0 for i in range(k)],       # complete binary tree: the most stack slots
+            [int(t) for t in oracle.make_targets(SEED, 11, k)]]
+    with G.Context(k, d) as ctx:
+        for peer in maps:
+            x, v = dev(inp.x), dev(inp.v)
+            ctx.step_gossip_pull(x, v, dev(inp.g), peer, 0.5)
+            xo, vo = inp.x.copy(), inp.v.copy()
+            oracle.step_gossip(xo, vo, inp.g, 0.05, 0.9, 0.5, peer)
+            assert_bitwise(host(x), xo, "x")
+            assert_bitwise(host(v), vo, "v")
+
+
+def test_iid_pull_gossip_trajectory_and_theorem_bound(G, oracle):
+    """Synchronous pull-gossip with iid targets and no momentum, the setting of
+    the paper's first theorem: the trajectory is bit-exact against the oracle
+    and the summed squared distance to the optimum stays under the theorem's
+    bound (m = min h, L = max h) at every checked step."""
+    k, d, steps = 16, 6 * 1024 + 2, 60
+    ld = W.round_up(d, 1024)
+    lr, sigma = 0.5, 0.05
+    inp = W.make_inputs(k, d, ld, seed=33)
+    xo, vo, go = inp.x.copy(), inp.v.copy(), inp.g.copy()
+    oracle.init_replicas(xo, vo, None, inp.x0, SEED, 0, n=d)
+    m, L = float(inp.h[:d].min()), float(inp.h[:d].max())
+    assert lr <= 2.0 / (m + L)
+    rate = 1.0 - 2.0 * lr * m * L / (m + L)
+    floor = k * lr * sigma**2 * (m + L) / (2 * m * L) * d
+    with G.Context(k, d, ld, lr=lr, momentum=0.0, sigma=sigma, seed=SEED, noise_kind=G.NOISE_UNIFORM) as ctx:
+        x, v, g = dev(inp.x), dev(inp.v), dev(inp.g)
+        h, xs = dev(inp.h), dev(inp.xstar)
+        ctx.init_replicas(x, v, None, dev(inp.x0), G.INIT_BROADCAST)
+        d0 = ctx.stats(x, xs)[1]
+        for t in range(steps):
+            peer = G.make_targets(SEED, t, k)
+            ctx.gen_grad(x, h, xs, g, t)
+            ctx.step_gossip_pull(x, v, g, peer, 0.5)
+            oracle.gen_grad(xo, inp.h, inp.xstar, go, sigma, SEED, t, 1, n=d)
+            oracle.step_gossip(xo, vo, go, lr, 0.0, 0.5, peer, n=d)
+            if t % 10 == 9:
+                assert ctx.stats(x, xs)[1] <= rate ** (t + 1) * d0 + floor
+        assert_bitwise(host(x), xo, "x")
