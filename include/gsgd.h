@@ -166,6 +166,18 @@ int gsgd_step_gossip_stale(gsgd_ctx* ctx, float* x, float* v, const float* g,
 int gsgd_step_gossip_pull(gsgd_ctx* ctx, float* x, float* v, const float* g,
                           const int32_t* peer, float beta, int stale, void* stream);
 
+/* Push-gossip step (Algorithm 4): after the local step every node sends its
+ * parameters to itself and to target[i]; a node's new parameters are the
+ * average of what it received,
+ *   x_r <- ( x'_r + sum over { i != r : target[i] = r } of x'_i ) / (1 + number of such i).
+ * target may be any map into 0..k-1 (a node may receive from none or from
+ * many); target[i] == i sends nothing beyond the node's own copy.  The sum is
+ * accumulated in fp64 and the average rounded once.  One in-place pass over x,
+ * v and g.  target: host, k entries, consumed before the call returns;
+ * GSGD_ERR_BAD_PERM for an entry outside 0..k-1. */
+int gsgd_step_gossip_push(gsgd_ctx* ctx, float* x, float* v, const float* g,
+                          const int32_t* target, void* stream);
+
 /* The local step alone (v_i and x_i <- x'_i, no exchange): what every node
  * does in the iterations between two exchanges when the communication period
  * tau of Algorithms 2-4 is larger than 1. */
@@ -227,6 +239,17 @@ int gsgd_make_targets(uint64_t seed, uint64_t step, int32_t k, int exclude_self,
  * *slots_used = stack slots the walk needs (at most 8 for k <= GSGD_MAX_K).
  * Pure host code.  walk: host, k entries. */
 int gsgd_pull_walk(const int32_t* peer, int32_t k, uint32_t* walk, int32_t* slots_used);
+
+/* Visiting order of the push-gossip kernel, exported for tests: senders before
+ * receivers.  walk[t]: replica in the low 12 bits; bits 22..31 = how many
+ * values its average takes (1 + senders); bit 12 = the running sum holds its
+ * senders' values; bit 13 = not on a cycle of the map, and then bits 16..17 say
+ * how its own value joins its receiver's running sum (1 start it, 2 add, 3 add
+ * to what stack slot bits 19..21 holds) and bit 18 that the running sum is
+ * then parked in that slot; cycle replicas carry bits 14 / 15 (first / last of
+ * the cycle, walked in the direction of sending).  *slots_used <= 8.
+ * Pure host code.  walk: host, k entries. */
+int gsgd_push_walk(const int32_t* target, int32_t k, uint32_t* walk, int32_t* slots_used);
 
 /* Order in which the gossip kernel visits replicas: the cycles of peer_perm,
  * each walked i, perm[i], perm[perm[i]], ...  walk[t] holds the replica index

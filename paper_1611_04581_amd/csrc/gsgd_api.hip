@@ -253,6 +253,21 @@ extern "C" int gsgd_step_gossip_stale(gsgd_ctx* ctx, float* x, float* v, const f
     return gossip_on_permutation(ctx, x, v, g, peer_perm, beta, true, stream);
 }
 
+extern "C" int gsgd_step_gossip_push(gsgd_ctx* ctx, float* x, float* v, const float* g,
+                                     const int32_t* target, void* stream)
+{
+    int rc = check_state(ctx, x, v, g);
+    if (rc != GSGD_OK) return rc;
+    if (!target) return GSGD_ERR_INVALID_ARG;
+    Walk walk;
+    int slots = 0;
+    rc = build_push_walk(target, ctx->cfg.k, &walk, &slots);
+    if (rc != GSGD_OK) return rc;
+    const hipError_t e = launch_step_gossip_push(geom_of(ctx), hyper_of(ctx), seg_of(ctx), walk, x, v, g,
+                                                 persist_of(ctx, GSGD_KERNEL_GOSSIP), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
 extern "C" int gsgd_step_local(gsgd_ctx* ctx, float* x, float* v, const float* g, void* stream)
 {
     const int rc = check_state(ctx, x, v, g);

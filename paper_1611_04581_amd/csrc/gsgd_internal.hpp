@@ -36,6 +36,24 @@ constexpr uint32_t WALK_SLOT_MASK     = 0xFu << WALK_SLOT_SHIFT;
 // reuses its parent's slot; a subtree that needs s slots then has at least
 // 3 * 2^s - 1 nodes, so 8 slots cover every map on up to GSGD_MAX_K replicas.
 constexpr int      WALK_SLOTS         = 8;
+// Push-gossip (Algorithm 4) visits children before parents: a node's new value
+// is the average of its own x' and the x' of every node that sent to it.  The
+// kernel keeps the running sum of the node being assembled in `acc`; an entry
+// says how the visited node's x' joins its receiver's sum:
+//   START        acc <- x'                 (first sender visited)
+//   ADD          acc <- acc + x'
+//   RESTORE_ADD  acc <- stack slot + x'    (a subtree in between used acc)
+// and whether acc is then saved to the slot because such a subtree comes next.
+constexpr uint32_t PUSH_HAS_SENDERS  = 0x1000;    // acc holds the sum of this node's (tree) senders
+constexpr uint32_t PUSH_MODE_SHIFT   = 16;
+constexpr uint32_t PUSH_START        = 1u << PUSH_MODE_SHIFT;
+constexpr uint32_t PUSH_ADD          = 2u << PUSH_MODE_SHIFT;
+constexpr uint32_t PUSH_RESTORE_ADD  = 3u << PUSH_MODE_SHIFT;
+constexpr uint32_t PUSH_MODE_MASK    = 3u << PUSH_MODE_SHIFT;
+constexpr uint32_t PUSH_SAVE_AFTER   = 0x40000;   // bit 18
+constexpr uint32_t PUSH_SLOT_SHIFT   = 19;        // bits 19..21
+constexpr uint32_t PUSH_SLOT_MASK    = 7u << PUSH_SLOT_SHIFT;
+constexpr uint32_t PUSH_COUNT_SHIFT  = 22;        // bits 22..31: number of values averaged (1 + senders)
 struct Walk {
     uint32_t seq[GSGD_MAX_K];
 };
@@ -79,6 +97,8 @@ struct Persist {
 // ---- launchers (defined next to their kernels) ---------------------------
 hipError_t launch_step_gossip(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&, bool stale,
                               bool has_trees, float* x, float* v, const float* g, Persist, hipStream_t);
+hipError_t launch_step_gossip_push(const Geom&, const Hyper&, const SegTable&, const Walk&,
+                                   float* x, float* v, const float* g, Persist, hipStream_t);
 hipError_t launch_step_local(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
                              Persist, hipStream_t);
 hipError_t launch_step_gossip_fused(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&,
@@ -105,5 +125,6 @@ void host_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t o
 int  build_walk(const int32_t* perm, int32_t k, Walk* out);   // GSGD_OK or GSGD_ERR_BAD_PERM
 // any map into 0..k-1; *has_trees = 0 when the map is a permutation
 int  build_pull_walk(const int32_t* peer, int32_t k, Walk* out, int* has_trees, int* slots_used);
+int  build_push_walk(const int32_t* target, int32_t k, Walk* out, int* slots_used);
 
 }  // namespace gsgd

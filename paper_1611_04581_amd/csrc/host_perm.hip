@@ -211,6 +211,150 @@ int build_pull_walk(const int32_t* peer, int32_t k, Walk* out, int* has_trees, i
     return *slots_used <= WALK_SLOTS ? GSGD_OK : GSGD_ERR_UNSUPPORTED;
 }
 
+// Visiting order for push-gossip (Algorithm 4): target[i] is where node i sends
+// its parameters (target[i] == i: nowhere).  A node is finished when all its
+// senders have been visited, so trees are walked children first; the cycles of
+// the map are walked in the direction of sending, each cycle node after the
+// trees that send to it, its cycle predecessor's x' riding along in a register.
+//
+// Among the senders of a node, the one whose subtree needs most stack slots
+// goes first (nothing is pending yet), the others follow with the partial sum
+// parked in a slot, childless senders last: the same log2 bound on the number
+// of slots as for the pull walk.
+namespace {
+
+struct PushWalkBuilder {
+    Walk*   out;
+    int32_t t;
+    int     max_slot;
+    int32_t head[GSGD_MAX_K], next[GSGD_MAX_K];   // tree senders of every node, ascending index
+    int32_t n_senders[GSGD_MAX_K];                // tree senders only
+    int32_t need[GSGD_MAX_K];
+    int32_t pool[GSGD_MAX_K];
+    int32_t pool_top;
+
+    bool inner(int32_t n) const { return head[n] >= 0; }
+
+    // senders of n in visiting order: those with senders of their own by descending need, then the rest
+    int32_t ordered_senders(int32_t n, int32_t* kids, int32_t* n_inner) const
+    {
+        int32_t m = 0;
+        for (int32_t c = head[n]; c >= 0; c = next[c]) if (inner(c)) kids[m++] = c;
+        *n_inner = m;
+        for (int32_t a = 1; a < m; ++a) {                       // stable insertion sort, descending need
+            const int32_t c = kids[a];
+            int32_t b = a;
+            while (b > 0 && need[kids[b - 1]] < need[c]) { kids[b] = kids[b - 1]; --b; }
+            kids[b] = c;
+        }
+        for (int32_t c = head[n]; c >= 0; c = next[c]) if (!inner(c)) kids[m++] = c;
+        return m;
+    }
+
+    // Emits everything that sends (directly or not) to n through tree edges.
+    // Afterwards the kernel's acc holds the sum of n's tree senders' x'.
+    void emit_senders(int32_t n, int base)
+    {
+        int32_t* kids = pool + pool_top;
+        int32_t n_inner = 0;
+        const int32_t m = ordered_senders(n, kids, &n_inner);
+        pool_top += m;
+        for (int32_t a = 0; a < m; ++a) {
+            const int32_t c = kids[a];
+            const bool c_inner = a < n_inner;
+            uint32_t word = static_cast<uint32_t>(c) | WALK_TREE
+                          | (static_cast<uint32_t>(1 + n_senders[c]) << PUSH_COUNT_SHIFT);
+            if (c_inner) word |= PUSH_HAS_SENDERS;
+            if (a == 0) word |= PUSH_START;
+            else if (c_inner) word |= PUSH_RESTORE_ADD | (static_cast<uint32_t>(base) << PUSH_SLOT_SHIFT);
+            else word |= PUSH_ADD;
+            if (a + 1 < n_inner) {                              // the next sender's subtree will use acc
+                word |= PUSH_SAVE_AFTER | (static_cast<uint32_t>(base) << PUSH_SLOT_SHIFT);
+                if (base > max_slot) max_slot = base;
+            }
+            if (c_inner) emit_senders(c, a == 0 ? base : base + 1);
+            out->seq[t++] = word;
+        }
+        pool_top -= m;
+    }
+};
+
+}  // namespace
+
+int build_push_walk(const int32_t* target, int32_t k, Walk* out, int* slots_used)
+{
+    if (!target || !out || !slots_used || k < 1 || k > GSGD_MAX_K) return GSGD_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < k; ++i)
+        if (target[i] < 0 || target[i] >= k) return GSGD_ERR_BAD_PERM;
+    bool on_cycle[GSGD_MAX_K];
+    int32_t tag[GSGD_MAX_K];
+    memset(on_cycle, 0, sizeof(on_cycle));
+    memset(tag, 0, sizeof(tag));
+    for (int32_t s = 0; s < k; ++s) {
+        int32_t i = s;
+        while (tag[i] == 0) { tag[i] = s + 1; i = target[i]; }
+        if (tag[i] != s + 1) continue;
+        for (int32_t j = i; !on_cycle[j]; j = target[j]) on_cycle[j] = true;
+    }
+    PushWalkBuilder b;
+    b.out = out;
+    b.t = 0;
+    b.max_slot = -1;
+    b.pool_top = 0;
+    int32_t tail[GSGD_MAX_K];
+    for (int32_t i = 0; i < k; ++i) { b.head[i] = tail[i] = b.next[i] = -1; b.need[i] = 0; b.n_senders[i] = 0; }
+    for (int32_t i = 0; i < k; ++i) {
+        if (on_cycle[i]) continue;
+        const int32_t j = target[i];
+        if (b.head[j] < 0) b.head[j] = i; else b.next[tail[j]] = i;
+        tail[j] = i;
+        ++b.n_senders[j];
+    }
+    // slots needed to assemble every node's sum, senders before receivers (reverse breadth-first order);
+    // cycle nodes last, they are receivers of trees too
+    int32_t order[GSGD_MAX_K];
+    int32_t n_order = 0;
+    for (int32_t i = 0; i < k; ++i) if (on_cycle[i]) order[n_order++] = i;
+    for (int32_t q = 0; q < n_order; ++q)
+        for (int32_t c = b.head[order[q]]; c >= 0; c = b.next[c]) order[n_order++] = c;
+    if (n_order != k) return GSGD_ERR_BAD_PERM;              // cannot happen for a valid map
+    for (int32_t q = n_order - 1; q >= 0; --q) {
+        const int32_t n = order[q];
+        int32_t largest = -1, second = -1;
+        for (int32_t c = b.head[n]; c >= 0; c = b.next[c]) {
+            if (!b.inner(c)) continue;
+            if (b.need[c] > largest) { second = largest; largest = b.need[c]; }
+            else if (b.need[c] > second) second = b.need[c];
+        }
+        b.need[n] = largest < 0 ? 0 : (second < 0 ? largest : (largest > second + 1 ? largest : second + 1));
+    }
+    bool seen[GSGD_MAX_K];
+    memset(seen, 0, sizeof(seen));
+    for (int32_t start = 0; start < k; ++start) {
+        if (!on_cycle[start] || seen[start]) continue;
+        const bool self_loop = target[start] == start;
+        int32_t first_slot = -1, last_slot = -1;
+        int32_t c = start;
+        do {
+            seen[c] = true;
+            b.emit_senders(c, 0);
+            uint32_t word = static_cast<uint32_t>(c)
+                          | (static_cast<uint32_t>(1 + b.n_senders[c] + (self_loop ? 0 : 1)) << PUSH_COUNT_SHIFT);
+            if (b.inner(c)) word |= PUSH_HAS_SENDERS;
+            if (first_slot < 0) first_slot = b.t;
+            last_slot = b.t;
+            out->seq[b.t++] = word;
+            c = target[c];
+        } while (c != start);
+        out->seq[first_slot] |= WALK_FIRST;
+        out->seq[last_slot] |= WALK_LAST;
+    }
+    for (int32_t r = b.t; r < GSGD_MAX_K; ++r) out->seq[r] = 0;
+    if (b.t != k) return GSGD_ERR_BAD_PERM;
+    *slots_used = b.max_slot + 1;
+    return *slots_used <= WALK_SLOTS ? GSGD_OK : GSGD_ERR_UNSUPPORTED;
+}
+
 }  // namespace gsgd
 
 extern "C" int gsgd_make_perm(uint64_t seed, uint64_t step, int32_t k, int32_t* out)
@@ -255,6 +399,18 @@ extern "C" int gsgd_pull_walk(const int32_t* peer, int32_t k, uint32_t* walk, in
     gsgd::Walk w;
     int has_trees = 0, slots = 0;
     const int rc = gsgd::build_pull_walk(peer, k, &w, &has_trees, &slots);
+    if (rc != GSGD_OK) return rc;
+    for (int32_t t = 0; t < k; ++t) walk[t] = w.seq[t];
+    *slots_used = slots;
+    return GSGD_OK;
+}
+
+extern "C" int gsgd_push_walk(const int32_t* target, int32_t k, uint32_t* walk, int32_t* slots_used)
+{
+    if (!walk || !slots_used) return GSGD_ERR_INVALID_ARG;
+    gsgd::Walk w;
+    int slots = 0;
+    const int rc = gsgd::build_push_walk(target, k, &w, &slots);
     if (rc != GSGD_OK) return rc;
     for (int32_t t = 0; t < k; ++t) walk[t] = w.seq[t];
     *slots_used = slots;

@@ -143,6 +143,107 @@ void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk w
 }
 
 // ---------------------------------------------------------------------------
+// Push-gossip (Algorithm 4): every node sends x' to itself and to its target;
+// a node's new parameters are the average of what it received.  Rows are
+// visited senders first (see build_push_walk), so when a row is loaded the
+// fp64 sum of everything sent to it through tree edges is in `acc`; the x' of
+// a cycle row's cycle predecessor rides in `prev`, and the first row of a
+// cycle waits in `first_sum` for the last.  One in-place pass, as for pull.
+typedef f64x4 SumStack[WALK_SLOTS][BLOCK];
+
+__device__ __forceinline__ f64x4 widen(f32x4 a)
+{
+    return f64x4{static_cast<double>(a.x), static_cast<double>(a.y), static_cast<double>(a.z), static_cast<double>(a.w)};
+}
+
+// average of `count` received values whose fp64 sum is `sum`, rounded once
+__device__ __forceinline__ f32x4 average(f64x4 sum, uint32_t count)
+{
+    const double c = static_cast<double>(count);
+    return f32x4{static_cast<float>(sum.x / c), static_cast<float>(sum.y / c),
+                 static_cast<float>(sum.z / c), static_cast<float>(sum.w / c)};
+}
+
+template <bool FULL, int U, bool EXT>
+__device__ __forceinline__
+void push_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
+                    const Walk& walk, SumStack* stack,
+                    float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g)
+{
+    const int valid = FULL ? 4 : qd.valid;
+    const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
+
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0}, first_sum = {0.0, 0.0, 0.0, 0.0};
+    f32x4 prev = {0.f, 0.f, 0.f, 0.f};
+    uint32_t first_count = 1;                  // uniform
+    int64_t first_off = 0;                     // uniform
+
+    for_row_batches<U>(geo.k, [&](auto n, int t0) {
+        constexpr int N = decltype(n)::value;
+        f32x4 X[N], V[N], G[N];
+        uint32_t w[N];
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            w[u] = walk.seq[t0 + u];
+            const int64_t off = static_cast<int64_t>(w[u] & WALK_ROW_MASK) * geo.ld + qd.tile_col;
+            X[u] = load_quad<FULL>(x + off + qd.lane_col, valid);
+            V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
+            G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
+        }
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int64_t off = static_cast<int64_t>(w[u] & WALK_ROW_MASK) * geo.ld + qd.tile_col;
+            const uint32_t count = w[u] >> PUSH_COUNT_SHIFT;
+            const uint32_t slot = (w[u] & PUSH_SLOT_MASK) >> PUSH_SLOT_SHIFT;
+            f32x4 vn, post;
+            local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, post);
+            store_quad<FULL>(v + off + qd.lane_col, vn, valid);
+            const f64x4 post64 = widen(post);
+            f64x4 sum = post64;
+            if (w[u] & PUSH_HAS_SENDERS) sum = acc + post64;
+            if (w[u] & WALK_TREE) {
+                store_quad<FULL>(x + off + qd.lane_col, count == 1 ? post : average(sum, count), valid);
+                const uint32_t mode = w[u] & PUSH_MODE_MASK;
+                if (mode == PUSH_START) acc = post64;
+                else if (mode == PUSH_ADD) acc = acc + post64;
+                else acc = (*stack)[slot][threadIdx.x] + post64;
+                if (w[u] & PUSH_SAVE_AFTER) (*stack)[slot][threadIdx.x] = acc;
+            } else if (w[u] & WALK_FIRST) {
+                if (w[u] & WALK_LAST) {        // a node that sends to nobody but itself
+                    store_quad<FULL>(x + off + qd.lane_col, count == 1 ? post : average(sum, count), valid);
+                } else {
+                    first_sum = sum;
+                    first_count = count;
+                    first_off = off;
+                }
+                prev = post;
+            } else {
+                store_quad<FULL>(x + off + qd.lane_col, average(sum + widen(prev), count), valid);
+                if (w[u] & WALK_LAST)
+                    store_quad<FULL>(x + first_off + qd.lane_col, average(first_sum + post64, first_count), valid);
+                prev = post;
+            }
+        }
+    });
+}
+
+template <int U, bool EXT>
+__global__ __launch_bounds__(BLOCK)
+void push_step_kernel(Geom geo, Hyper hp, SegTable seg, Walk walk,
+                      float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                      uint32_t* __restrict__ tickets, uint32_t n_tiles)
+{
+    __shared__ SegLds lds;
+    __shared__ SumStack stack;
+    stage_segments(seg, lds);
+    for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
+        const Quad qd = quad_of_tile(tile, geo.d);
+        if (tile_is_full(qd, geo.d)) push_step_body<true, U, EXT>(geo, hp, seg, lds, qd, walk, &stack, x, v, g);
+        else if (qd.valid > 0) push_step_body<false, U, EXT>(geo, hp, seg, lds, qd, walk, &stack, x, v, g);
+    });
+}
+
+// ---------------------------------------------------------------------------
 // All-reduce average (Algorithm 1).  Pass 1 reads v and g of every row and
 // accumulates u_i = mu v_i - lr g_i in fp64 in ascending i; pass 2 adds the
 // rounded mean to every row of x and leaves it in every row of v.
@@ -379,6 +480,16 @@ hipError_t launch_step_gossip(const Geom& geo, const Hyper& hp, const SegTable& 
     else
         GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0>), geo, hp, seg, -beta, walk, x, v, g, nullptr, nullptr,
                     0.0f, no_key, 0u, p.tickets, tiles);
+    return hipGetLastError();
+}
+
+hipError_t launch_step_gossip_push(const Geom& geo, const Hyper& hp, const SegTable& seg, const Walk& walk,
+                                   float* x, float* v, const float* g, Persist p, hipStream_t stream)
+{
+    if (hp.extended())
+        GSGD_LAUNCH((push_step_kernel<RIF, true>), geo, hp, seg, walk, x, v, g, p.tickets, grid_for(geo.d));
+    else
+        GSGD_LAUNCH((push_step_kernel<RIF, false>), geo, hp, seg, walk, x, v, g, p.tickets, grid_for(geo.d));
     return hipGetLastError();
 }
 

@@ -26,6 +26,7 @@ KERNEL_COUNT = 6
 WALK_ROW_MASK, WALK_FIRST, WALK_LAST = 0x0FFF, 0x4000, 0x8000
 WALK_TREE, WALK_DESCEND, WALK_SAVE = 0x2000, 0x1000, 0x40000
 WALK_RESTORE_SHIFT, WALK_SLOT_SHIFT, WALK_SLOTS = 16, 20, 8
+PUSH_HAS_SENDERS, PUSH_MODE_SHIFT, PUSH_SAVE_AFTER, PUSH_SLOT_SHIFT, PUSH_COUNT_SHIFT = 0x1000, 16, 0x40000, 19, 22
 
 
 class GsgdError(RuntimeError):
@@ -55,6 +56,8 @@ SIGNATURES = {
     "gsgd_step_gossip_stale": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, _vp]),
     "gsgd_step_local": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
     "gsgd_step_gossip_pull": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, C.c_int, _vp]),
+    "gsgd_step_gossip_push": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), _vp]),
+    "gsgd_push_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint32), C.POINTER(C.c_int32)]),
     "gsgd_make_targets": (C.c_int, [C.c_uint64, C.c_uint64, C.c_int32, C.c_int, C.POINTER(C.c_int32)]),
     "gsgd_pull_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint32), C.POINTER(C.c_int32)]),
     "gsgd_init_replicas": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int, _vp]),
@@ -196,6 +199,11 @@ class Context:
         _check(lib().gsgd_step_gossip_pull(self._h, _ptr(x), _ptr(v), _ptr(g), p, float(beta), int(bool(stale)),
                                            _stream(stream)), "gsgd_step_gossip_pull")
 
+    def step_gossip_push(self, x, v, g, target, stream=None):
+        keep, p = _perm_arg(target)
+        _check(lib().gsgd_step_gossip_push(self._h, _ptr(x), _ptr(v), _ptr(g), p, _stream(stream)),
+               "gsgd_step_gossip_push")
+
     def step_local(self, x, v, g, stream=None):
         _check(lib().gsgd_step_local(self._h, _ptr(x), _ptr(v), _ptr(g), _stream(stream)), "gsgd_step_local")
 
@@ -246,6 +254,16 @@ def pull_walk(peer):
     slots = C.c_int32(0)
     _check(lib().gsgd_pull_walk(p, int(keep.shape[0]), out.ctypes.data_as(C.POINTER(C.c_uint32)), C.byref(slots)),
            "gsgd_pull_walk")
+    return out, int(slots.value)
+
+
+def push_walk(target):
+    """(walk words, stack slots used) of the push-gossip kernel for a target map."""
+    keep, p = _perm_arg(target)
+    out = np.empty(keep.shape[0], np.uint32)
+    slots = C.c_int32(0)
+    _check(lib().gsgd_push_walk(p, int(keep.shape[0]), out.ctypes.data_as(C.POINTER(C.c_uint32)), C.byref(slots)),
+           "gsgd_push_walk")
     return out, int(slots.value)
 
 

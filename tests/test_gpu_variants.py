@@ -283,3 +283,89 @@ def test_iid_pull_gossip_trajectory_and_theorem_bound(G, oracle):
             if t % 10 == 9:
                 assert ctx.stats(x, xs)[1] <= rate ** (t + 1) * d0 + floor
         assert_bitwise(host(x), xo, "x")
+
+
+# ----------------------------------------------------------------------------
+# push-gossip (Algorithm 4): average of a variable number of received messages
+
+def assert_push_close(got, want, what):
+    """The kernel adds the received values in visiting order, the oracle in
+    ascending sender index, both in fp64: the rounded averages agree except
+    where an fp64 sum was itself inexact, so nearly every element is bit-equal
+    and the rest are within the parameter tolerance."""
+    assert_rows_close(got, want, what)
+    same = (np.ascontiguousarray(got).view(np.uint32) == np.ascontiguousarray(want).view(np.uint32)).mean()
+    assert same >= 0.9999, "%s: only %.6f of the elements are bit-equal" % (what, same)
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES + [(128, 1024 + 12, None)])
+def test_push_gossip_on_arbitrary_maps(G, oracle, k, d, ld):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=41)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9) as ctx:
+        maps = some_maps(k, oracle) + [list(range(k))]
+        if k >= 2:
+            maps += [[int(t) for t in oracle.make_targets(SEED, s, k, True)] for s in range(3)]
+            assert np.array_equal(G.make_targets(SEED, 3, k, True), oracle.make_targets(SEED, 3, k, True))
+        for target in maps:
+            x, v = dev(inp.x), dev(inp.v)
+            ctx.step_gossip_push(x, v, dev(inp.g), target)
+            xo, vo = inp.x.copy(), inp.v.copy()
+            oracle.step_gossip_push(xo, vo, inp.g, 0.05, 0.9, target, n=d)
+            assert_push_close(host(x)[:, :d], xo[:, :d], "x target=%s" % target)
+            assert_bitwise(host(x)[:, d:], xo[:, d:], "x padding")
+            assert_bitwise(host(v), vo, "v")
+        ctx.set_local_step(1e-4, True)
+        for target in maps[5:8]:
+            x, v = dev(inp.x), dev(inp.v)
+            ctx.step_gossip_push(x, v, dev(inp.g), target)
+            xo, vo = inp.x.copy(), inp.v.copy()
+            oracle.step_gossip_push(xo, vo, inp.g, 0.05, 0.9, target, wd=1e-4, nesterov=True, n=d)
+            assert_push_close(host(x)[:, :d], xo[:, :d], "x nesterov target=%s" % target)
+            assert_bitwise(host(v), vo, "v")
+        with pytest.raises(G.GsgdError) as e:
+            ctx.step_gossip_push(x, v, dev(inp.g), [-1] * k)
+        assert e.value.code == G.ERR_BAD_PERM
+
+
+def test_push_gossip_max_replicas_and_segments(G, oracle):
+    k, d = G.MAX_K, 1024 + 4
+    inp = W.make_inputs(k, d, seed=42)
+    off, sc = W.random_segments(d, 9, seed=2, align=1)
+    lrc = oracle.expand_lr(0.05, d, off, sc)
+    maps = [[max(i - 1, 0) for i in range(k)], [(i - 1) // 2 if i else 0 for i in range(k)], [0] * k,
+            [int(t) for t in oracle.make_targets(SEED, 11, k, True)]]
+    with G.Context(k, d, seg_offsets=off, seg_lr_scale=sc) as ctx:
+        for target in maps:
+            x, v = dev(inp.x), dev(inp.v)
+            ctx.step_gossip_push(x, v, dev(inp.g), target)
+            xo, vo = inp.x.copy(), inp.v.copy()
+            oracle.step_gossip_push(xo, vo, inp.g, lrc, 0.9, target)
+            assert_push_close(host(x), xo, "x")
+            assert_bitwise(host(v), vo, "v")
+
+
+def test_push_gossip_trajectory(G, oracle):
+    """Push-gossip with fresh uniform targets among the other nodes, Gaussian
+    gradient noise, 40 steps: parameters within tolerance of the oracle's and
+    the replicas pulled together (consensus distance far below a run without
+    any exchange)."""
+    k, d, steps = 16, 6 * 1024 + 2, 40
+    ld = W.round_up(d, 1024)
+    inp = W.make_inputs(k, d, ld, seed=43)
+    xo, vo, go = inp.x.copy(), inp.v.copy(), inp.g.copy()
+    oracle.init_replicas(xo, vo, None, None, SEED, 1, n=d)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, sigma=0.1, seed=SEED) as ctx:
+        x, v, g = dev(xo), dev(vo), dev(inp.g)
+        xi, vi = x.clone(), v.clone()                      # the same run without exchanges
+        h, xs = dev(inp.h), dev(inp.xstar)
+        for t in range(steps):
+            target = G.make_targets(SEED, t, k, True)
+            ctx.gen_grad(x, h, xs, g, t)
+            ctx.step_gossip_push(x, v, g, target)
+            oracle.gen_grad(xo, inp.h, inp.xstar, go, 0.1, SEED, t, 0, n=d)
+            oracle.step_gossip_push(xo, vo, go, 0.05, 0.9, target, n=d)
+            ctx.gen_grad(xi, h, xs, g, t)
+            ctx.step_local(xi, vi, g)
+        assert_rows_close(host(x)[:, :d], xo[:, :d], "x")
+        assert ctx.stats(x, xs)[0] < 0.05 * ctx.stats(xi, xs)[0]

@@ -289,3 +289,68 @@ def test_pull_walk_of_a_permutation_is_the_cycle_walk():
     with pytest.raises(gsgd.GsgdError) as e:
         gsgd.pull_walk([0, 3, 1])
     assert e.value.code == gsgd.ERR_BAD_PERM
+
+
+# ----------------------------------------------------------------------------
+# the push kernel's visiting order, replayed
+
+def _replay_push_walk(walk, post):
+    """Runs the push kernel's register machine on exact rationals."""
+    k = len(post)
+    out = [None] * k
+    stack = [None] * gsgd.WALK_SLOTS
+    acc = first_sum = first_count = first_row = prev = None
+    for wd in walk:
+        wd = int(wd)
+        row = wd & gsgd.WALK_ROW_MASK
+        count = wd >> gsgd.PUSH_COUNT_SHIFT
+        slot = (wd >> gsgd.PUSH_SLOT_SHIFT) & 7
+        total = post[row]
+        if wd & gsgd.PUSH_HAS_SENDERS:
+            assert acc is not None
+            total = acc + post[row]
+        assert out[row] is None
+        if wd & gsgd.WALK_TREE:
+            out[row] = total / count
+            mode = (wd >> gsgd.PUSH_MODE_SHIFT) & 3
+            assert mode in (1, 2, 3)
+            if mode == 1:
+                acc = post[row]
+            elif mode == 2:
+                acc = acc + post[row]
+            else:
+                acc = stack[slot] + post[row]
+            if wd & gsgd.PUSH_SAVE_AFTER:
+                stack[slot] = acc
+        elif wd & gsgd.WALK_FIRST:
+            if wd & gsgd.WALK_LAST:
+                out[row] = total / count
+            else:
+                first_sum, first_count, first_row = total, count, row
+            prev = post[row]
+        else:
+            out[row] = (total + prev) / count
+            if wd & gsgd.WALK_LAST:
+                out[first_row] = (first_sum + post[row]) / first_count
+            prev = post[row]
+    return out
+
+
+@pytest.mark.parametrize("k", [1, 2, 5, 32, 33, 128, 512])
+def test_push_walk_realises_the_definition(k):
+    rng = np.random.default_rng(1000 + k)
+    post = [Fraction(int(a), 16) for a in rng.integers(-1000, 1000, size=k)]
+    for target in _maps_for(k, rng):
+        target = [int(p) for p in target]
+        walk, slots = gsgd.push_walk(target)
+        assert 0 <= slots <= gsgd.WALK_SLOTS
+        assert sorted(int(w) & gsgd.WALK_ROW_MASK for w in walk) == list(range(k))
+        got = _replay_push_walk(walk, post)
+        want = _push_exact([[p] for p in post], target)
+        for r in range(k):
+            assert got[r] == want[r][0], (target, r)
+    if k == 512:
+        assert gsgd.push_walk([max(i - 1, 0) for i in range(k)])[1] == 0
+        assert 1 <= gsgd.push_walk([(i - 1) // 2 if i else 0 for i in range(k)])[1] <= 8
+    with pytest.raises(gsgd.GsgdError):
+        gsgd.push_walk([k] * k)
