@@ -35,6 +35,11 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+KERNEL_OF_RULE = {"gossip": "gossip_step_kernel", "gossip_stale": "gossip_step_kernel (stale)",
+                  "gossip_pull": "gossip_step_kernel (tree walk)", "gossip_push": "push_step_kernel",
+                  "allreduce": "allreduce_step_kernel", "easgd": "easgd_step_kernel"}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -47,6 +52,7 @@ def main():
     ap.add_argument("--config", default="gossip_r50")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle baseline (0 = skip)")
     ap.add_argument("--no-extras", action="store_true", help="time only the metric kernel")
+    ap.add_argument("--no-fused", action="store_true", help="skip the fused-generator extra")
     ap.add_argument("--launch-width", type=int, default=0,
                     help="persistent workgroups per streaming kernel (0 = the library's default)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -76,7 +82,7 @@ def main():
     ctx = gsgd.Context(k, d, ld, lr=cfg.lr, momentum=cfg.momentum, sigma=cfg.sigma, seed=cfg.seed,
                        noise_kind=gsgd.NOISE_GAUSSIAN, **seg)
     if args.launch_width:
-        for kern in range(5):
+        for kern in range(gsgd.KERNEL_COUNT):
             ctx.set_launch_width(kern, args.launch_width)
     x = torch.empty((k, ld), dtype=torch.float32, device="cuda")
     v = torch.empty_like(x)
@@ -99,10 +105,21 @@ def main():
         ctx.gen_grad(x, h, xstar, g, 0)
         torch.cuda.synchronize()
 
+    ctx.set_local_step(cfg.weight_decay, cfg.nesterov)
+
     def one_step(t):
-        if cfg.rule == "gossip":
+        rule = cfg.rule if gsgd.comm_due(t, cfg.tau) else "local"
+        if rule == "gossip":
             ctx.step_gossip(x, v, g, gsgd.make_perm(cfg.seed, t, k), cfg.beta)
-        elif cfg.rule == "allreduce":
+        elif rule == "gossip_stale":
+            ctx.step_gossip_stale(x, v, g, gsgd.make_perm(cfg.seed, t, k), cfg.beta)
+        elif rule == "gossip_pull":
+            ctx.step_gossip_pull(x, v, g, gsgd.make_targets(cfg.seed, t, k), cfg.beta)
+        elif rule == "gossip_push":
+            ctx.step_gossip_push(x, v, g, gsgd.make_targets(cfg.seed, t, k, True))
+        elif rule == "local":
+            ctx.step_local(x, v, g)
+        elif rule == "allreduce":
             ctx.step_allreduce(x, v, g)
         else:
             ctx.step_easgd(x, v, g, center, cfg.alpha_e)
@@ -126,7 +143,7 @@ def main():
     wall, ev = timed(one_step, K, Wm)
     ms_per_step = wall / K * 1e3
     value = k * K / wall
-    bpe = BYTES_PER_REPLICA_ELEMENT[cfg.rule] + (8.0 / k if cfg.rule == "easgd" else 0.0)
+    bpe = BYTES_PER_REPLICA_ELEMENT.get(cfg.rule, 20.0) + (8.0 / k if cfg.rule == "easgd" else 0.0)
     alg_bytes = bpe * k * d
     kern_s = ev / K                                  # one kernel per step in the timed region
     achieved = alg_bytes / kern_s / 1e9
@@ -144,7 +161,7 @@ def main():
                                "per step, x/v/g resident in HBM" % (cfg.name, k, d, ld, cfg.rule),
                    "k": k, "d": d, "ld": ld, "rule": cfg.rule, "lr": cfg.lr, "momentum": cfg.momentum,
                    "beta": cfg.beta, "sigma": cfg.sigma, "layout": cfg.layout or "flat"},
-        "roofline": {"bound": "hbm", "kernel": "%s_step_kernel" % cfg.rule, "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": KERNEL_OF_RULE[cfg.rule], "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kern_s * 1e3},
     }
@@ -165,7 +182,7 @@ def main():
             "full_iteration_ms": w_full / n2 * 1e3,
             "full_iteration_replica_steps_per_s": k * n2 / w_full,
         }
-        if cfg.rule == "gossip":
+        if cfg.rule == "gossip" and not args.no_fused:
             def fused(t):
                 ctx.step_gossip_fused(x, v, h, xstar, gsgd.make_perm(cfg.seed, t, k), t, cfg.beta)
             for t in range(3):
@@ -188,6 +205,13 @@ def main():
         def ostep(t):
             if cfg.rule == "gossip":
                 oracle.step_gossip(inp.x, inp.v, inp.g, lrc, cfg.momentum, cfg.beta, oracle.make_perm(cfg.seed, t, k))
+            elif cfg.rule in ("gossip_stale", "gossip_pull"):
+                peer = oracle.make_perm(cfg.seed, t, k) if cfg.rule == "gossip_stale" else oracle.make_targets(cfg.seed, t, k)
+                oracle.step_gossip_ext(inp.x, inp.v, inp.g, lrc, cfg.momentum, cfg.beta, peer, wd=cfg.weight_decay,
+                                       nesterov=cfg.nesterov, stale=cfg.rule == "gossip_stale")
+            elif cfg.rule == "gossip_push":
+                oracle.step_gossip_push(inp.x, inp.v, inp.g, lrc, cfg.momentum, oracle.make_targets(cfg.seed, t, k, True),
+                                        wd=cfg.weight_decay, nesterov=cfg.nesterov)
             elif cfg.rule == "allreduce":
                 oracle.step_allreduce(inp.x, inp.v, inp.g, lrc, cfg.momentum)
             else:

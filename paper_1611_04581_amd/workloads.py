@@ -86,7 +86,7 @@ RESNET50_D = 25_557_032
 @dataclass
 class Config:
     name: str
-    rule: str                 # "gossip" | "allreduce" | "easgd"
+    rule: str                 # "gossip" | "gossip_stale" | "gossip_pull" | "gossip_push" | "allreduce" | "easgd"
     k: int
     d: int
     steps: int
@@ -97,6 +97,9 @@ class Config:
     alpha_e: Optional[float] = None   # EASGD moving rate
     layout: Optional[str] = None      # segmented layout name, None = flat
     seed: int = DEFAULT_SEED
+    weight_decay: float = 0.0         # extras of the paper's training runs (Section 4.2)
+    nesterov: bool = False
+    tau: int = 1                      # communication period: exchange on every tau-th step, local steps between
 
 
 CONFIGS = {
@@ -106,6 +109,12 @@ CONFIGS = {
     "gossip_r50": Config("gossip_r50", "gossip", 32, RESNET50_D, 200),
     "easgd_r50": Config("easgd_r50", "easgd", 16, RESNET50_D, 200, alpha_e=0.9 / 16),
     "seg_gossip_r50_k128": Config("seg_gossip_r50_k128", "gossip", 128, RESNET50_D, 100, layout="resnet50"),
+    # beyond the five benchmark configurations: the other gossip forms the paper describes, at the metric shape
+    "pull_gossip_r50": Config("pull_gossip_r50", "gossip_pull", 32, RESNET50_D, 100),       # iid targets, Algorithm 3
+    "push_gossip_r50": Config("push_gossip_r50", "gossip_push", 32, RESNET50_D, 100),       # Algorithm 4
+    "stale_gossip_r50": Config("stale_gossip_r50", "gossip_stale", 32, RESNET50_D, 100),    # Section 6.2.1
+    "paper_setup_r18": Config("paper_setup_r18", "gossip_push", 16, RESNET18_D, 100, lr=0.1,  # Section 4.2's recipe
+                              weight_decay=1e-4, nesterov=True, tau=10),
 }
 
 

@@ -61,8 +61,10 @@ def _run(G, oracle, cfg, steps, kind, mode=0, check_identical_rows=False):
         seg = dict(seg_offsets=off, seg_lr_scale=sc)
     xstar, h, x0 = _shared_vectors(d, ld, seed=77)
     slices = _slices(d, layout)
+    wd, nest = cfg.weight_decay, cfg.nesterov
     with G.Context(k, d, ld, lr=cfg.lr, momentum=cfg.momentum, sigma=cfg.sigma, seed=cfg.seed, noise_kind=kind,
                    **seg) as ctx:
+        ctx.set_local_step(wd, nest)
         x = torch.empty((k, ld), dtype=torch.float32, device="cuda")
         v = torch.empty_like(x)
         g = torch.empty_like(x)
@@ -82,20 +84,40 @@ def _run(G, oracle, cfg, steps, kind, mode=0, check_identical_rows=False):
             st.append(dict(c0=c0, n=n, x=xo, v=np.zeros((k, n), np.float32), g=np.zeros((k, n), np.float32), c=co,
                            lr=lrc, xs=xstar[c0:c0 + n].copy(), h=h[c0:c0 + n].copy()))
         cons = [ctx.stats(x, dxs)[0]]
+        identity = list(range(k))
         for t in range(steps):
-            perm = G.make_perm(cfg.seed, t, k) if cfg.rule == "gossip" else None
+            rule = cfg.rule if G.comm_due(t, cfg.tau) else "local"
+            perm = None
+            if rule in ("gossip", "gossip_stale"):
+                perm = G.make_perm(cfg.seed, t, k)
+            elif rule in ("gossip_pull", "gossip_push"):
+                perm = G.make_targets(cfg.seed, t, k, rule == "gossip_push")
             ctx.gen_grad(x, dh, dxs, g, t)
-            if cfg.rule == "gossip":
+            if rule == "gossip":
                 ctx.step_gossip(x, v, g, perm, cfg.beta)
-            elif cfg.rule == "allreduce":
+            elif rule == "gossip_stale":
+                ctx.step_gossip_stale(x, v, g, perm, cfg.beta)
+            elif rule == "gossip_pull":
+                ctx.step_gossip_pull(x, v, g, perm, cfg.beta)
+            elif rule == "gossip_push":
+                ctx.step_gossip_push(x, v, g, perm)
+            elif rule == "local":
+                ctx.step_local(x, v, g)
+            elif rule == "allreduce":
                 ctx.step_allreduce(x, v, g)
             else:
                 ctx.step_easgd(x, v, g, c, cfg.alpha_e)
             for s in st:
                 oracle.gen_grad(s["x"], s["h"], s["xs"], s["g"], cfg.sigma, cfg.seed, t, kind, col0=s["c0"])
-                if cfg.rule == "gossip":
+                if rule == "gossip" and not (wd or nest):
                     oracle.step_gossip(s["x"], s["v"], s["g"], s["lr"], cfg.momentum, cfg.beta, perm)
-                elif cfg.rule == "allreduce":
+                elif rule in ("gossip", "gossip_stale", "gossip_pull", "local"):
+                    oracle.step_gossip_ext(s["x"], s["v"], s["g"], s["lr"], cfg.momentum, cfg.beta,
+                                           identity if rule == "local" else perm, wd=wd, nesterov=nest,
+                                           stale=rule == "gossip_stale")
+                elif rule == "gossip_push":
+                    oracle.step_gossip_push(s["x"], s["v"], s["g"], s["lr"], cfg.momentum, perm, wd=wd, nesterov=nest)
+                elif rule == "allreduce":
                     oracle.step_allreduce(s["x"], s["v"], s["g"], s["lr"], cfg.momentum)
                 else:
                     oracle.step_easgd(s["x"], s["v"], s["g"], s["c"], s["lr"], cfg.momentum, cfg.alpha_e)
@@ -107,10 +129,10 @@ def _run(G, oracle, cfg, steps, kind, mode=0, check_identical_rows=False):
             c0, n = s["c0"], s["n"]
             gx = np.ascontiguousarray(x[:, c0:c0 + n].cpu().numpy())
             gv = np.ascontiguousarray(v[:, c0:c0 + n].cpu().numpy())
-            if kind == G.NOISE_UNIFORM:
+            if kind == G.NOISE_UNIFORM and cfg.rule != "gossip_push":
                 assert_bitwise(gx, s["x"], "x cols %d..%d" % (c0, c0 + n))
                 assert_bitwise(gv, s["v"], "v cols %d..%d" % (c0, c0 + n))
-            else:
+            else:         # Gaussian transform, or push-gossip's fp64 sums taken in a different order
                 assert_rows_close(gx, s["x"], "x cols %d..%d" % (c0, c0 + n))
             if cfg.rule == "easgd":
                 gc = np.ascontiguousarray(c[c0:c0 + n].cpu().numpy())
@@ -170,4 +192,20 @@ def test_easgd_resnet50_200_steps(G, oracle):
 
 def test_segmented_gossip_k128_100_steps(G, oracle):
     cfg = W.CONFIGS["seg_gossip_r50_k128"]
+    _run(G, oracle, cfg, cfg.steps, G.NOISE_UNIFORM)
+
+
+@pytest.mark.parametrize("name", ["pull_gossip_r50", "stale_gossip_r50", "push_gossip_r50"])
+def test_other_gossip_forms_at_the_metric_shape(G, oracle, name):
+    """iid pull targets (Algorithm 3), stale parameters (Section 6.2.1) and
+    push-gossip (Algorithm 4) at k = 32, ResNet-50 size, from a spread start."""
+    cfg = W.CONFIGS[name]
+    cons, final, _ = _run(G, oracle, cfg, 50, G.NOISE_UNIFORM, mode=1)
+    assert cons[-1] < 1e-2 * cons[0]
+
+
+def test_paper_training_recipe_resnet18(G, oracle):
+    """Section 4.2's recipe on the quadratic: push-gossip, 16 nodes, Nesterov
+    0.9, weight decay 1e-4, step size 0.1, exchange every 10th iteration."""
+    cfg = W.CONFIGS["paper_setup_r18"]
     _run(G, oracle, cfg, cfg.steps, G.NOISE_UNIFORM)
