@@ -20,6 +20,9 @@ namespace gsgd {
 #ifndef GSGD_ROWS_IN_FLIGHT
 #define GSGD_ROWS_IN_FLIGHT 4
 #endif
+#ifndef GSGD_WALK_ROWS_IN_FLIGHT
+#define GSGD_WALK_ROWS_IN_FLIGHT 3
+#endif
 
 template <int N> using Count = std::integral_constant<int, N>;
 
@@ -442,6 +445,10 @@ void local_step_kernel(Geom geo, Hyper hp, SegTable seg,
 // ---------------------------------------------------------------------------
 #ifndef GSGD_NO_LAUNCHERS
 constexpr int RIF = GSGD_ROWS_IN_FLIGHT;
+// Rows in flight for the kernels that walk a peer map.  Measured on MI355X at k = 32 and both ResNet sizes with
+// a fresh permutation per launch: 3 rows sustain 71.3-72.0 % of the HBM peak, 2 rows 70.6-71.4 %, 4-6 rows
+// 69.9-70.7 %; at k = 128 all sit within 0.3 % of each other.
+constexpr int WALK_RIF = GSGD_WALK_ROWS_IN_FLIGHT;
 
 // Persistent launch: never more workgroups than tiles.
 static inline unsigned width_for(const Geom& geo, const Persist& p)
@@ -463,22 +470,22 @@ hipError_t launch_step_gossip(const Geom& geo, const Hyper& hp, const SegTable& 
     const RngKey no_key{0u, 0u};
     const uint32_t tiles = grid_for(geo.d);
     if (has_trees && stale)
-        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0, true, true, true>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
+        GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, false, 0, true, true, true>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
                     nullptr, 0.0f, no_key, 0u, p.tickets, tiles);
     else if (has_trees && hp.extended())
-        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0, true, false, true>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
+        GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, false, 0, true, false, true>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
                     nullptr, 0.0f, no_key, 0u, p.tickets, tiles);
     else if (has_trees)
-        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0, false, false, true>), geo, hp, seg, -beta, walk, x, v, g,
+        GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, false, 0, false, false, true>), geo, hp, seg, -beta, walk, x, v, g,
                     nullptr, nullptr, 0.0f, no_key, 0u, p.tickets, tiles);
     else if (stale)
-        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0, true, true>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
+        GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, false, 0, true, true>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
                     nullptr, 0.0f, no_key, 0u, p.tickets, tiles);
     else if (hp.extended())
-        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0, true, false>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
+        GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, false, 0, true, false>), geo, hp, seg, -beta, walk, x, v, g, nullptr,
                     nullptr, 0.0f, no_key, 0u, p.tickets, tiles);
     else
-        GSGD_LAUNCH((gossip_step_kernel<RIF, false, 0>), geo, hp, seg, -beta, walk, x, v, g, nullptr, nullptr,
+        GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, false, 0>), geo, hp, seg, -beta, walk, x, v, g, nullptr, nullptr,
                     0.0f, no_key, 0u, p.tickets, tiles);
     return hipGetLastError();
 }
@@ -487,9 +494,9 @@ hipError_t launch_step_gossip_push(const Geom& geo, const Hyper& hp, const SegTa
                                    float* x, float* v, const float* g, Persist p, hipStream_t stream)
 {
     if (hp.extended())
-        GSGD_LAUNCH((push_step_kernel<RIF, true>), geo, hp, seg, walk, x, v, g, p.tickets, grid_for(geo.d));
+        GSGD_LAUNCH((push_step_kernel<WALK_RIF, true>), geo, hp, seg, walk, x, v, g, p.tickets, grid_for(geo.d));
     else
-        GSGD_LAUNCH((push_step_kernel<RIF, false>), geo, hp, seg, walk, x, v, g, p.tickets, grid_for(geo.d));
+        GSGD_LAUNCH((push_step_kernel<WALK_RIF, false>), geo, hp, seg, walk, x, v, g, p.tickets, grid_for(geo.d));
     return hipGetLastError();
 }
 
@@ -512,17 +519,17 @@ hipError_t launch_step_gossip_fused(const Geom& geo, const Hyper& hp, const SegT
     const bool uniform = noise_kind == GSGD_NOISE_UNIFORM;
     if (hp.extended()) {
         if (uniform)
-            GSGD_LAUNCH((gossip_step_kernel<RIF, true, GSGD_NOISE_UNIFORM, true>), geo, hp, seg, -beta, walk, x, v,
+            GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, true, GSGD_NOISE_UNIFORM, true>), geo, hp, seg, -beta, walk, x, v,
                         nullptr, h, xstar, sigma, key, step, p.tickets, tiles);
         else
-            GSGD_LAUNCH((gossip_step_kernel<RIF, true, GSGD_NOISE_GAUSSIAN, true>), geo, hp, seg, -beta, walk, x, v,
+            GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, true, GSGD_NOISE_GAUSSIAN, true>), geo, hp, seg, -beta, walk, x, v,
                         nullptr, h, xstar, sigma, key, step, p.tickets, tiles);
     } else {
         if (uniform)
-            GSGD_LAUNCH((gossip_step_kernel<RIF, true, GSGD_NOISE_UNIFORM>), geo, hp, seg, -beta, walk, x, v,
+            GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, true, GSGD_NOISE_UNIFORM>), geo, hp, seg, -beta, walk, x, v,
                         nullptr, h, xstar, sigma, key, step, p.tickets, tiles);
         else
-            GSGD_LAUNCH((gossip_step_kernel<RIF, true, GSGD_NOISE_GAUSSIAN>), geo, hp, seg, -beta, walk, x, v,
+            GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, true, GSGD_NOISE_GAUSSIAN>), geo, hp, seg, -beta, walk, x, v,
                         nullptr, h, xstar, sigma, key, step, p.tickets, tiles);
     }
     return hipGetLastError();
