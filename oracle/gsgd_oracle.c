@@ -508,6 +508,56 @@ int oracle_step_gossip_push(float* x, float* v, const float* g, int32_t k, int64
     return 0;
 }
 
+/* ------------------------------------------------------------------------ */
+/* Asynchronous pull-gossip, one tick of the master clock (Section 6.1.2): the
+ * node i whose clock ticked takes its local step and pulls from node j,
+ *   theta_{t+1,i} = (1 - beta)(theta_{t,i} - alpha g_{t,i}) + beta theta_{t,j},   theta_{t+1,m} = theta_{t,m} for m != i,
+ * i.e. theta_{t+1} = D (theta_t - alpha g_t) with D = I + beta e_i (e_j - e_i)^T.  j is read as it stands
+ * (node j takes no step in this tick); j == i leaves theta'_i.  g_row is node i's gradient (n values).
+ * The local step is the same as everywhere else (momentum / weight decay / Nesterov optional); the mix is written
+ * theta' - beta (theta' - theta_j) as in Section 3.1.                                                              */
+int oracle_async_tick(float* x, float* v, const float* g_row, int32_t k, int64_t n, int64_t ld,
+                      const float* lr_col, float mu, float wd, int nesterov, float beta, int32_t i, int32_t j)
+{
+    if (i < 0 || i >= k || j < 0 || j >= k) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < n; ++c) {
+        float vn, xp;
+        local_step_ext(x[i * ld + c], v[i * ld + c], g_row[c], lr_col[c], mu, wd, nesterov, &vn, &xp);
+        const float theirs = (j == i) ? xp : x[j * ld + c];
+        v[i * ld + c] = vn;
+        x[i * ld + c] = fmaf(-beta, xp - theirs, xp);
+    }
+    return 0;
+}
+
+/* Synthetic gradient of one node for one tick: as oracle_gen_grad, for row i only, the noise drawn at counter
+ * (column / 4, i, tick, GRAD).                                                                                    */
+void oracle_gen_grad_row(const float* x, const float* h, const float* xstar, float* g_row,
+                         int32_t i, int64_t col0, int64_t n, int64_t ld,
+                         float sigma, uint64_t seed, uint32_t tick, int noise_kind)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < n; ++c) {
+        const float xi = noise_at(seed, col0 + c, (uint32_t)i, tick, STREAM_GRAD, noise_kind);
+        const float t1 = x[i * ld + c] - xstar[c];
+        const float t2 = sigma * xi;
+        g_row[c] = fmaf(h[c], t1, t2);
+    }
+}
+
+/* Which node ticks and whom it pulls from (Section 6.1.2: the ticking clock is uniform over the nodes, and so is
+ * the node pulled from): words 0 and 1 of Philox(counter (tick, 2, 0, PERM), seed), each mapped by floor(r k / 2^32). */
+int oracle_make_tick(uint64_t seed, uint32_t tick, int32_t k, int32_t* i_out, int32_t* j_out)
+{
+    if (k < 1) return -1;
+    uint32_t r[4];
+    philox_at(seed, tick, 2u, 0u, STREAM_PERM, r);
+    *i_out = (int32_t)(((uint64_t)r[0] * (uint64_t)k) >> 32);
+    *j_out = (int32_t)(((uint64_t)r[1] * (uint64_t)k) >> 32);
+    return 0;
+}
+
 /* The two quantities the analysis bounds (Section 6.1) plus the mean's own
  * distance, all over the slice, in fp64:
  *   out[0] = sum_i ||x_i - xbar||^2   (agent consensus)

@@ -69,6 +69,14 @@ def lib():
         L.oracle_step_gossip_push.argtypes = [_f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f32p,
                                               C.c_float, C.c_float, C.c_int, _i32p]
         L.oracle_step_gossip_push.restype = C.c_int
+        L.oracle_async_tick.argtypes = [_f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f32p,
+                                        C.c_float, C.c_float, C.c_int, C.c_float, C.c_int32, C.c_int32]
+        L.oracle_async_tick.restype = C.c_int
+        L.oracle_gen_grad_row.argtypes = [_f32p, _f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, C.c_int64,
+                                          C.c_float, C.c_uint64, C.c_uint32, C.c_int]
+        L.oracle_gen_grad_row.restype = None
+        L.oracle_make_tick.argtypes = [C.c_uint64, C.c_uint32, C.c_int32, _i32p, _i32p]
+        L.oracle_make_tick.restype = C.c_int
         L.oracle_make_perm.argtypes = [C.c_uint64, C.c_uint32, C.c_int32, _i32p]
         L.oracle_make_perm.restype = C.c_int
         L.oracle_stats.argtypes = [_f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f64p]
@@ -228,6 +236,33 @@ def step_gossip_push(x, v, g, lr, mu, target, wd=0.0, nesterov=False, n=None):
                                        int(bool(nesterov)), t.ctypes.data_as(_i32p))
     if rc:
         raise ValueError("oracle_step_gossip_push failed (%d)" % rc)
+
+
+def async_tick(x, v, g_row, lr, mu, beta, i, j, wd=0.0, nesterov=False, n=None):
+    k, ld = _rows(x)
+    n = ld if n is None else int(n)
+    lrc = _lr_col(lr, n)
+    assert g_row.shape[0] >= n
+    rc = lib().oracle_async_tick(_f32(x), _f32(v), _f32(g_row), k, n, ld, _f32(lrc), float(mu), float(wd),
+                                 int(bool(nesterov)), float(beta), int(i), int(j))
+    if rc:
+        raise ValueError("oracle_async_tick: node index out of range")
+
+
+def gen_grad_row(x, h, xstar, g_row, i, sigma, seed, tick, noise_kind=NOISE_GAUSSIAN, n=None, col0=0):
+    k, ld = _rows(x)
+    n = ld if n is None else int(n)
+    assert 0 <= i < k and g_row.shape[0] >= n and h.shape[0] >= n and xstar.shape[0] >= n
+    lib().oracle_gen_grad_row(_f32(x), _f32(h), _f32(xstar), _f32(g_row), int(i), int(col0), n, ld,
+                              float(sigma), int(seed), int(tick), int(noise_kind))
+
+
+def make_tick(seed, tick, k):
+    i, j = C.c_int32(0), C.c_int32(0)
+    rc = lib().oracle_make_tick(int(seed), int(tick), int(k), C.byref(i), C.byref(j))
+    if rc:
+        raise ValueError("oracle_make_tick: k < 1")
+    return int(i.value), int(j.value)
 
 
 def make_targets(seed, step, k, exclude_self=False):

@@ -1,0 +1,137 @@
+"""Pins for the oracle's asynchronous pull-gossip tick (Section 6.1.2): one
+node, drawn uniformly, takes its gradient step and pulls from a uniformly drawn
+node; everyone else stands still.  CPU only.
+
+Tied to: exact replay on rationals with binary32 rounding; the matrix form
+theta_{t+1} = D (theta_t - alpha g_t), D = I + beta e_i (e_j - e_i)^T, applied
+with numpy; the two second moments the proof computes, E[D^T D] and
+E[D^T 1 1^T D], reproduced exactly by enumerating all (i, j); both bounds of
+the theorem on a long seeded run; big-integer restatement of the tick draw.
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import brute
+from paper_1611_04581_amd import workloads as W
+
+SEED = 0x161104581
+F = lambda a: Fraction(float(a))
+
+
+def test_tick_exact_replay(oracle):
+    k, n = 4, 9
+    lr, mu, beta = np.float32(0.05), np.float32(0.9), np.float32(0.5)
+    for (i, j) in [(0, 3), (2, 2), (3, 1)]:
+        inp = W.make_inputs(k, n, seed=50 + i)
+        x0, v0 = inp.x.copy(), inp.v.copy()
+        g_row = inp.g[1].copy()
+        oracle.async_tick(inp.x, inp.v, g_row, lr, mu, beta, i, j)
+        for c in range(n):
+            vn = brute.f32_fma(-F(lr), F(g_row[c]), brute.f32_mul(F(mu), F(v0[i, c])))
+            xp = brute.f32_add(F(x0[i, c]), vn)
+            theirs = xp if j == i else F(x0[j, c])
+            want = brute.f32_fma(-F(beta), brute.f32_sub(xp, theirs), xp)
+            assert F(inp.x[i, c]) == want and F(inp.v[i, c]) == vn
+        others = [m for m in range(k) if m != i]
+        assert np.array_equal(inp.x[others], x0[others]) and np.array_equal(inp.v[others], v0[others])
+
+
+def test_tick_is_the_matrix_D_applied_after_the_gradient_step(oracle):
+    k, n = 6, 200
+    lr, beta = 0.3, 0.4
+    inp = W.make_inputs(k, n, seed=60)
+    rng = np.random.default_rng(0)
+    for _ in range(10):
+        i, j = (int(a) for a in rng.integers(0, k, 2))
+        x, v = inp.x.copy(), np.zeros_like(inp.x)
+        oracle.async_tick(x, v, inp.g[i].copy(), lr, 0.0, beta, i, j)
+        D = np.eye(k)
+        D[i, j] += beta
+        D[i, i] -= beta
+        stepped = inp.x.astype(np.float64).copy()
+        stepped[i] -= np.float64(np.float32(lr)) * inp.g[i]
+        assert np.allclose(x, D @ stepped, rtol=0, atol=1e-6)
+
+
+@pytest.mark.parametrize("k", [2, 3, 5])
+@pytest.mark.parametrize("beta", [Fraction(1, 2), Fraction(1, 4)])
+def test_second_moments_of_D(oracle, k, beta):
+    """E[D^T D] = (1 - 2b(1-b)/p) I + 2b(1-b)/p^2 11^T and
+    E[D^T 11^T D] = (2b^2/p) I + (1 - 2b^2/p^2) 11^T (Section 6.1.2), over i and
+    j uniform and independent.  lr = 0 makes the tick the mix alone; dyadic
+    inputs make it exact; y^T E[.] y is compared for a random y."""
+    n = 3
+    rng = np.random.default_rng(k)
+    y = (rng.integers(-32, 32, size=(k, n)) / 4.0).astype(np.float32)
+    zeros = np.zeros_like(y)
+    sum_sq = Fraction(0)
+    sum_tot = Fraction(0)
+    for i in range(k):
+        for j in range(k):
+            x, v = y.copy(), zeros.copy()
+            oracle.async_tick(x, v, zeros[0].copy(), 0.0, 0.0, float(beta), i, j)
+            sum_sq += sum(F(a) ** 2 for a in x.ravel())
+            sum_tot += sum(sum(F(x[m, c]) for m in range(k)) ** 2 for c in range(n))
+    yy = [[F(a) for a in row] for row in y]
+    norm2 = sum(a * a for row in yy for a in row)
+    ones2 = sum(sum(yy[m][c] for m in range(k)) ** 2 for c in range(n))
+    b, p = beta, k
+    assert sum_sq / p**2 == (1 - 2 * b * (1 - b) / p) * norm2 + 2 * b * (1 - b) / p**2 * ones2
+    assert sum_tot / p**2 == (2 * b * b / p) * norm2 + (1 - 2 * b * b / Fraction(p * p)) * ones2
+
+
+def test_tick_draw(oracle):
+    key = (SEED & 0xFFFFFFFF, SEED >> 32)
+    for k in (1, 2, 7, 32, 512):
+        for t in (0, 1, 12345, 2**32 - 1):
+            r = brute.philox4((t, 2, 0, 5), key)
+            assert oracle.make_tick(SEED, t, k) == ((r[0] * k) >> 32, (r[1] * k) >> 32)
+    k, T = 6, 36000
+    ij = np.array([oracle.make_tick(SEED, t, k) for t in range(T)])
+    joint = np.bincount(ij[:, 0] * k + ij[:, 1], minlength=k * k)
+    chi2 = ((joint - T / k**2) ** 2 / (T / k**2)).sum()
+    assert chi2 < 75.0                                   # 35 dof
+
+
+def test_async_theorem_bounds_hold(oracle):
+    """Both bounds of the asynchronous theorem on a seeded run: distance to the
+    optimum, and distance to the replica mean with
+    lambda = 1 - 2b(1-b)/p - 2b^2/p.  The columns are independent copies of the
+    univariate problem the proof treats, so the sums over many columns stand in
+    for the expectations (C bounds |grad f| along the run)."""
+    k, n, ticks = 8, 4000, 1200
+    lr, sigma, beta = 0.5, 0.1, 0.5
+    inp = W.make_inputs(k, n, seed=70)
+    m_, L_ = float(inp.h.min()), float(inp.h.max())
+    assert lr <= 2.0 / (m_ + L_)
+    x, v = inp.x.copy(), np.zeros_like(inp.x)
+    g_row = np.zeros(n, np.float32)
+    st0 = oracle.stats(x, inp.xstar)
+    rate = 1.0 - 2.0 * lr / k * m_ * L_ / (m_ + L_)
+    floor = k * lr * (sigma**2 * n) * (m_ + L_) / (2 * m_ * L_)
+    lam = 1.0 - 2 * beta * (1 - beta) / k - 2 * beta**2 / k
+    C2 = float(((inp.h * (np.abs(inp.x - inp.xstar)).max(0)) ** 2).sum())     # sup |grad f|^2 summed over columns
+    crate = lam * (1.0 - lr * m_ / k)
+    cfloor = lam * lr**2 * (C2 + sigma**2 * n) / (1.0 - crate)
+    for t in range(ticks):
+        i, j = oracle.make_tick(SEED, t, k)
+        oracle.gen_grad_row(x, inp.h, inp.xstar, g_row, i, sigma, SEED, t)
+        oracle.async_tick(x, v, g_row, lr, 0.0, beta, i, j)
+        if t % 100 == 99:
+            st = oracle.stats(x, inp.xstar)
+            assert st[1] <= 1.05 * (rate ** (t + 1) * st0[1] + floor), t
+            assert st[0] <= 1.05 * (crate ** (t + 1) * st0[0] + cfloor), t
+    assert st[1] < 0.05 * st0[1] and st[0] < 0.05 * st0[0]
+
+
+def test_gen_grad_row_is_a_row_of_gen_grad(oracle):
+    k, n = 5, 333
+    inp = W.make_inputs(k, n, seed=80)
+    g = np.zeros_like(inp.x)
+    oracle.gen_grad(inp.x, inp.h, inp.xstar, g, 0.3, SEED, 17, 1)
+    row = np.zeros(n, np.float32)
+    for i in range(k):
+        oracle.gen_grad_row(inp.x, inp.h, inp.xstar, row, i, 0.3, SEED, 17, 1)
+        assert np.array_equal(row, g[i])
