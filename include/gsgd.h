@@ -57,7 +57,7 @@ enum { GSGD_INIT_BROADCAST = 0, GSGD_INIT_PER_REPLICA = 1 };
 enum { GSGD_FILL_XSTAR = 2, GSGD_FILL_H = 3, GSGD_FILL_X0 = 4 };
 /* the streaming kernels, for gsgd_set_launch_width */
 enum { GSGD_KERNEL_GOSSIP = 0, GSGD_KERNEL_ALLREDUCE = 1, GSGD_KERNEL_EASGD = 2, GSGD_KERNEL_GEN_GRAD = 3,
-       GSGD_KERNEL_GOSSIP_FUSED = 4, GSGD_KERNEL_LOCAL = 5, GSGD_KERNEL_COUNT = 6 };
+       GSGD_KERNEL_GOSSIP_FUSED = 4, GSGD_KERNEL_LOCAL = 5, GSGD_KERNEL_ASYNC_TICK = 6, GSGD_KERNEL_COUNT = 7 };
 
 typedef struct gsgd_ctx gsgd_ctx;   /* opaque; owns the segment tables and a small scratch for gsgd_stats */
 
@@ -177,6 +177,34 @@ int gsgd_step_gossip_pull(gsgd_ctx* ctx, float* x, float* v, const float* g,
  * GSGD_ERR_BAD_PERM for an entry outside 0..k-1. */
 int gsgd_step_gossip_push(gsgd_ctx* ctx, float* x, float* v, const float* g,
                           const int32_t* target, void* stream);
+
+/* Asynchronous pull-gossip, one tick of the master clock (Section 6.1.2): node
+ * i, whose clock ticked, takes its local step and mixes with node j as j
+ * stands; every other node is left alone:
+ *   v_i <- momentum * v_i - lr_s * g_i;  x'_i = x_i + v_i;  x_i <- x'_i - beta * (x'_i - x_j)
+ * (x_j is j's current value, j takes no step; j == i leaves x'_i).  In the
+ * paper's matrix form x <- D (x - lr g e_i), D = I + beta e_i (e_j - e_i)^T.
+ * Only row i of g is read.  0 <= i, j < k, else GSGD_ERR_INVALID_ARG. */
+int gsgd_step_async_tick(gsgd_ctx* ctx, float* x, float* v, const float* g, int32_t i, int32_t j,
+                         float beta, void* stream);
+
+/* The same tick with node i's synthetic gradient generated on the fly:
+ * g_i = h (.) (x_i - xstar) + sigma xi, xi from Philox stream 0 at counter
+ * (column/4, i, tick, 0).  tick < 2^32. */
+int gsgd_step_async_tick_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
+                               int32_t i, int32_t j, float beta, uint64_t tick, void* stream);
+
+/* Who ticks and whom it pulls from at tick number `tick`: i and j uniform over
+ * the k nodes and independent (the Poisson-clock model of Section 6.1.2),
+ * words 0 and 1 of Philox stream 5 at counter (tick, 2, 0, 5), each mapped by
+ * floor(r k / 2^32).  Pure host code. */
+int gsgd_make_tick(uint64_t seed, uint64_t tick, int32_t k, int32_t* i_out, int32_t* j_out);
+
+/* n_ticks consecutive ticks first_tick, first_tick+1, ... of the asynchronous
+ * model, each drawn with gsgd_make_tick under the context's seed and run with
+ * gsgd_step_async_tick_fused.  Enqueues n_ticks kernels; does not wait. */
+int gsgd_run_async_ticks(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
+                         float beta, uint64_t first_tick, uint64_t n_ticks, void* stream);
 
 /* The local step alone (v_i and x_i <- x'_i, no exchange): what every node
  * does in the iterations between two exchanges when the communication period

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgsgd.so")
-SOURCES = ["gsgd_api.hip", "host_perm.hip", "kernels_step.hip", "kernels_gen.hip", "kernels_stats.hip"]
+SOURCES = ["gsgd_api.hip", "host_perm.hip", "kernels_step.hip", "kernels_async.hip", "kernels_gen.hip", "kernels_stats.hip"]
 
 # FP contraction is off: every fused multiply-add in the kernels is written out,
 # so results do not depend on what the optimiser decides to fuse.  Packed fp32

@@ -27,7 +27,7 @@ namespace {
 
 // Persistent workgroups per compute unit for each streaming kernel
 // (GSGD_KERNEL_* order).  Measured on MI355X at the benchmark shapes.
-constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 4u, 2u, 1u};
+constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 4u, 2u, 1u, 4u};
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -266,6 +266,45 @@ extern "C" int gsgd_step_gossip_push(gsgd_ctx* ctx, float* x, float* v, const fl
     const hipError_t e = launch_step_gossip_push(geom_of(ctx), hyper_of(ctx), seg_of(ctx), walk, x, v, g,
                                                  persist_of(ctx, GSGD_KERNEL_GOSSIP), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_step_async_tick(gsgd_ctx* ctx, float* x, float* v, const float* g, int32_t i, int32_t j,
+                                    float beta, void* stream)
+{
+    const int rc = check_state(ctx, x, v, g);
+    if (rc != GSGD_OK) return rc;
+    if (i < 0 || i >= ctx->cfg.k || j < 0 || j >= ctx->cfg.k || !(beta == beta)) return GSGD_ERR_INVALID_ARG;
+    const hipError_t e = launch_async_tick(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, i, j, x, v, g,
+                                           persist_of(ctx, GSGD_KERNEL_ASYNC_TICK), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_step_async_tick_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
+                                          int32_t i, int32_t j, float beta, uint64_t tick, void* stream)
+{
+    if (!ctx || !ok_matrix(x) || !ok_matrix(v) || !ok_matrix(h) || !ok_matrix(xstar) || x == v)
+        return GSGD_ERR_INVALID_ARG;
+    if (i < 0 || i >= ctx->cfg.k || j < 0 || j >= ctx->cfg.k || !(beta == beta) || tick > 0xFFFFFFFFull)
+        return GSGD_ERR_INVALID_ARG;
+    const hipError_t e = launch_async_tick_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, i, j, x, v, h, xstar,
+                                                 ctx->cfg.sigma, key_of(ctx), static_cast<uint32_t>(tick),
+                                                 ctx->cfg.noise_kind, persist_of(ctx, GSGD_KERNEL_ASYNC_TICK),
+                                                 static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_run_async_ticks(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
+                                    float beta, uint64_t first_tick, uint64_t n_ticks, void* stream)
+{
+    if (!ctx || first_tick > 0xFFFFFFFFull || n_ticks > 0xFFFFFFFFull || first_tick + n_ticks > 0x100000000ull)
+        return GSGD_ERR_INVALID_ARG;
+    for (uint64_t t = first_tick; t < first_tick + n_ticks; ++t) {
+        int32_t i = 0, j = 0;
+        int rc = gsgd_make_tick(ctx->cfg.seed, t, ctx->cfg.k, &i, &j);
+        if (rc == GSGD_OK) rc = gsgd_step_async_tick_fused(ctx, x, v, h, xstar, i, j, beta, t, stream);
+        if (rc != GSGD_OK) return rc;
+    }
+    return GSGD_OK;
 }
 
 extern "C" int gsgd_step_local(gsgd_ctx* ctx, float* x, float* v, const float* g, void* stream)

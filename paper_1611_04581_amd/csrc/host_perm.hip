@@ -393,6 +393,20 @@ extern "C" int gsgd_make_targets(uint64_t seed, uint64_t step, int32_t k, int ex
     return GSGD_OK;
 }
 
+// Which node's clock ticks and whom it pulls from (Section 6.1.2): both uniform
+// over the nodes and independent, words 0 and 1 of Philox(counter (tick, 2, 0, 5)).
+extern "C" int gsgd_make_tick(uint64_t seed, uint64_t tick, int32_t k, int32_t* i_out, int32_t* j_out)
+{
+    if (!i_out || !j_out || k < 1 || tick > 0xFFFFFFFFull) return GSGD_ERR_INVALID_ARG;
+    const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+    const uint32_t ctr[4] = {static_cast<uint32_t>(tick), 2u, 0u, 5u};
+    uint32_t r[4];
+    gsgd::host_philox4x32_10(ctr, key, r);
+    *i_out = static_cast<int32_t>((static_cast<uint64_t>(r[0]) * static_cast<uint64_t>(k)) >> 32);
+    *j_out = static_cast<int32_t>((static_cast<uint64_t>(r[1]) * static_cast<uint64_t>(k)) >> 32);
+    return GSGD_OK;
+}
+
 extern "C" int gsgd_pull_walk(const int32_t* peer, int32_t k, uint32_t* walk, int32_t* slots_used)
 {
     if (!walk || !slots_used) return GSGD_ERR_INVALID_ARG;

@@ -21,8 +21,9 @@ NOISE_GAUSSIAN, NOISE_UNIFORM = 0, 1
 INIT_BROADCAST, INIT_PER_REPLICA = 0, 1
 FILL_XSTAR, FILL_H, FILL_X0 = 2, 3, 4
 
-KERNEL_GOSSIP, KERNEL_ALLREDUCE, KERNEL_EASGD, KERNEL_GEN_GRAD, KERNEL_GOSSIP_FUSED, KERNEL_LOCAL = range(6)
-KERNEL_COUNT = 6
+(KERNEL_GOSSIP, KERNEL_ALLREDUCE, KERNEL_EASGD, KERNEL_GEN_GRAD, KERNEL_GOSSIP_FUSED, KERNEL_LOCAL,
+ KERNEL_ASYNC_TICK) = range(7)
+KERNEL_COUNT = 7
 WALK_ROW_MASK, WALK_FIRST, WALK_LAST = 0x0FFF, 0x4000, 0x8000
 WALK_TREE, WALK_DESCEND, WALK_SAVE = 0x2000, 0x1000, 0x40000
 WALK_RESTORE_SHIFT, WALK_SLOT_SHIFT, WALK_SLOTS = 16, 20, 8
@@ -58,6 +59,11 @@ SIGNATURES = {
     "gsgd_step_gossip_pull": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, C.c_int, _vp]),
     "gsgd_step_gossip_push": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), _vp]),
     "gsgd_push_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint32), C.POINTER(C.c_int32)]),
+    "gsgd_step_async_tick": (C.c_int, [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_float, _vp]),
+    "gsgd_step_async_tick_fused": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_float, C.c_uint64,
+                                             _vp]),
+    "gsgd_run_async_ticks": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_float, C.c_uint64, C.c_uint64, _vp]),
+    "gsgd_make_tick": (C.c_int, [C.c_uint64, C.c_uint64, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "gsgd_make_targets": (C.c_int, [C.c_uint64, C.c_uint64, C.c_int32, C.c_int, C.POINTER(C.c_int32)]),
     "gsgd_pull_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint32), C.POINTER(C.c_int32)]),
     "gsgd_init_replicas": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int, _vp]),
@@ -204,6 +210,19 @@ class Context:
         _check(lib().gsgd_step_gossip_push(self._h, _ptr(x), _ptr(v), _ptr(g), p, _stream(stream)),
                "gsgd_step_gossip_push")
 
+    def step_async_tick(self, x, v, g, i, j, beta=0.5, stream=None):
+        _check(lib().gsgd_step_async_tick(self._h, _ptr(x), _ptr(v), _ptr(g), int(i), int(j), float(beta),
+                                          _stream(stream)), "gsgd_step_async_tick")
+
+    def step_async_tick_fused(self, x, v, h, xstar, i, j, tick, beta=0.5, stream=None):
+        _check(lib().gsgd_step_async_tick_fused(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), int(i), int(j),
+                                                float(beta), int(tick), _stream(stream)),
+               "gsgd_step_async_tick_fused")
+
+    def run_async_ticks(self, x, v, h, xstar, first_tick, n_ticks, beta=0.5, stream=None):
+        _check(lib().gsgd_run_async_ticks(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), float(beta),
+                                          int(first_tick), int(n_ticks), _stream(stream)), "gsgd_run_async_ticks")
+
     def step_local(self, x, v, g, stream=None):
         _check(lib().gsgd_step_local(self._h, _ptr(x), _ptr(v), _ptr(g), _stream(stream)), "gsgd_step_local")
 
@@ -238,6 +257,12 @@ def make_perm(seed, step, k):
     _check(lib().gsgd_make_perm(int(seed), int(step), int(k), out.ctypes.data_as(C.POINTER(C.c_int32))),
            "gsgd_make_perm")
     return out
+
+
+def make_tick(seed, tick, k):
+    i, j = C.c_int32(0), C.c_int32(0)
+    _check(lib().gsgd_make_tick(int(seed), int(tick), int(k), C.byref(i), C.byref(j)), "gsgd_make_tick")
+    return int(i.value), int(j.value)
 
 
 def make_targets(seed, step, k, exclude_self=False):

@@ -148,3 +148,11 @@ def test_comm_due_follows_the_algorithm_boxes():
     assert all(gsgd.comm_due(s, 1) for s in range(20))
     with pytest.raises(gsgd.GsgdError):
         gsgd.comm_due(3, 0)
+
+
+def test_make_tick_bit_exact_with_oracle(oracle):
+    for k in (1, 2, 32, 512):
+        for t in (0, 1, 1000, 2**32 - 1):
+            assert gsgd.make_tick(SEED, t, k) == oracle.make_tick(SEED, t, k)
+    with pytest.raises(gsgd.GsgdError):
+        gsgd.make_tick(SEED, 2**32, 4)

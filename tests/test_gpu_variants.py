@@ -369,3 +369,88 @@ def test_push_gossip_trajectory(G, oracle):
             ctx.step_local(xi, vi, g)
         assert_rows_close(host(x)[:, :d], xo[:, :d], "x")
         assert ctx.stats(x, xs)[0] < 0.05 * ctx.stats(xi, xs)[0]
+
+
+# ----------------------------------------------------------------------------
+# asynchronous pull-gossip, tick by tick (Section 6.1.2)
+
+@pytest.mark.parametrize("k,d,ld", SHAPES)
+def test_async_tick_with_given_gradient(G, oracle, k, d, ld):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=51)
+    pairs = [(0, k - 1), (k - 1, 0), (k // 2, k // 2)] + [G.make_tick(SEED, t, k) for t in range(4)]
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9) as ctx:
+        for wd, nest in ((0.0, False), (1e-4, True)):
+            ctx.set_local_step(wd, nest)
+            x, v, g = dev(inp.x), dev(inp.v), dev(inp.g)
+            xo, vo = inp.x.copy(), inp.v.copy()
+            for (i, j) in pairs:
+                ctx.step_async_tick(x, v, g, i, j, 0.5)
+                oracle.async_tick(xo, vo, inp.g[i].copy(), 0.05, 0.9, 0.5, i, j, wd=wd, nesterov=nest, n=d)
+            assert_bitwise(host(x), xo, "x")
+            assert_bitwise(host(v), vo, "v")
+        for bad in ((-1, 0), (0, k), (k, 0)):
+            with pytest.raises(G.GsgdError) as e:
+                ctx.step_async_tick(x, v, g, bad[0], bad[1], 0.5)
+            assert e.value.code == G.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("kind", [1, 0])
+def test_async_ticks_fused_generator_and_driver(G, oracle, kind):
+    """n ticks through gsgd_run_async_ticks (tick draw, gradient generator and
+    update all in the library) against the oracle taking the same ticks one by
+    one; per-layer step sizes on."""
+    k, d, ticks = 6, 5 * 1024 + 3, 40
+    ld = W.round_up(d, 1024)
+    off, sc = W.random_segments(d, 11, seed=4, align=1)
+    lrc = oracle.expand_lr(0.05, d, off, sc)
+    inp = W.make_inputs(k, d, ld, seed=52)
+    xo, vo = inp.x.copy(), inp.v.copy()
+    g_row = np.zeros(ld, np.float32)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, sigma=0.2, seed=SEED, noise_kind=kind, seg_offsets=off,
+                   seg_lr_scale=sc) as ctx:
+        x, v = dev(inp.x), dev(inp.v)
+        h, xs = dev(inp.h), dev(inp.xstar)
+        ctx.run_async_ticks(x, v, h, xs, 5, ticks, 0.5)
+        for t in range(5, 5 + ticks):
+            i, j = oracle.make_tick(SEED, t, k)
+            assert (i, j) == G.make_tick(SEED, t, k)
+            oracle.gen_grad_row(xo, inp.h, inp.xstar, g_row, i, 0.2, SEED, t, kind, n=d)
+            oracle.async_tick(xo, vo, g_row, lrc, 0.9, 0.5, i, j, n=d)
+        if kind == 1:
+            assert_bitwise(host(x), xo, "x")
+            assert_bitwise(host(v), vo, "v")
+        else:
+            assert_rows_close(host(x)[:, :d], xo[:, :d], "x")
+            assert_bitwise(host(x)[:, d:], xo[:, d:], "x padding")
+        # one explicit tick equals one driven tick
+        x2, v2 = x.clone(), v.clone()
+        i, j = G.make_tick(SEED, 99, k)
+        ctx.step_async_tick_fused(x, v, h, xs, i, j, 99, 0.5)
+        ctx.run_async_ticks(x2, v2, h, xs, 99, 1, 0.5)
+        assert_bitwise(host(x2), host(x), "driver vs explicit")
+
+
+def test_async_theorem_bounds_on_the_gpu(G, oracle):
+    """Both bounds of the asynchronous theorem (distance to the optimum,
+    distance to the replica mean) along 1600 ticks run by the library."""
+    k, d, ticks = 8, 64 * 1024, 1600
+    lr, sigma, beta = 0.5, 0.1, 0.5
+    inp = W.make_inputs(k, d, seed=53)
+    m_, L_ = float(inp.h.min()), float(inp.h.max())
+    rate = 1.0 - 2.0 * lr / k * m_ * L_ / (m_ + L_)
+    floor = k * lr * (sigma**2 * d) * (m_ + L_) / (2 * m_ * L_)
+    lam = 1.0 - 2 * beta * (1 - beta) / k - 2 * beta**2 / k
+    C2 = float(((inp.h * (np.abs(inp.x - inp.xstar)).max(0)) ** 2).sum())
+    crate = lam * (1.0 - lr * m_ / k)
+    cfloor = lam * lr**2 * (C2 + sigma**2 * d) / (1.0 - crate)
+    with G.Context(k, d, lr=lr, momentum=0.0, sigma=sigma, seed=SEED) as ctx:
+        x, v = dev(inp.x), dev(np.zeros_like(inp.v))
+        h, xs = dev(inp.h), dev(inp.xstar)
+        st0 = ctx.stats(x, xs)
+        for t0 in range(0, ticks, 200):
+            ctx.run_async_ticks(x, v, h, xs, t0, 200, beta)
+            st = ctx.stats(x, xs)
+            assert st[1] <= 1.05 * (rate ** (t0 + 200) * st0[1] + floor)
+            assert st[0] <= 1.05 * (crate ** (t0 + 200) * st0[0] + cfloor)
+        assert st[1] < 0.05 * st0[1] and st[0] < 0.05 * st0[0]
