@@ -27,7 +27,7 @@ namespace {
 
 // Persistent workgroups per compute unit for each streaming kernel
 // (GSGD_KERNEL_* order).  Measured on MI355X at the benchmark shapes.
-constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 4u, 2u, 1u, 4u};
+constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 4u, 2u, 1u};
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -275,7 +275,7 @@ extern "C" int gsgd_step_async_tick(gsgd_ctx* ctx, float* x, float* v, const flo
     if (rc != GSGD_OK) return rc;
     if (i < 0 || i >= ctx->cfg.k || j < 0 || j >= ctx->cfg.k || !(beta == beta)) return GSGD_ERR_INVALID_ARG;
     const hipError_t e = launch_async_tick(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, i, j, x, v, g,
-                                           persist_of(ctx, GSGD_KERNEL_ASYNC_TICK), static_cast<hipStream_t>(stream));
+                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -288,8 +288,7 @@ extern "C" int gsgd_step_async_tick_fused(gsgd_ctx* ctx, float* x, float* v, con
         return GSGD_ERR_INVALID_ARG;
     const hipError_t e = launch_async_tick_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, i, j, x, v, h, xstar,
                                                  ctx->cfg.sigma, key_of(ctx), static_cast<uint32_t>(tick),
-                                                 ctx->cfg.noise_kind, persist_of(ctx, GSGD_KERNEL_ASYNC_TICK),
-                                                 static_cast<hipStream_t>(stream));
+                                                 ctx->cfg.noise_kind, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 

@@ -100,10 +100,10 @@ hipError_t launch_step_gossip(const Geom&, const Hyper&, const SegTable&, float 
 hipError_t launch_step_gossip_push(const Geom&, const Hyper&, const SegTable&, const Walk&,
                                    float* x, float* v, const float* g, Persist, hipStream_t);
 hipError_t launch_async_tick(const Geom&, const Hyper&, const SegTable&, float beta, int32_t i, int32_t j,
-                             float* x, float* v, const float* g, Persist, hipStream_t);
+                             float* x, float* v, const float* g, hipStream_t);
 hipError_t launch_async_tick_fused(const Geom&, const Hyper&, const SegTable&, float beta, int32_t i, int32_t j,
                                    float* x, float* v, const float* h, const float* xstar,
-                                   float sigma, RngKey key, uint32_t tick, int noise_kind, Persist, hipStream_t);
+                                   float sigma, RngKey key, uint32_t tick, int noise_kind, hipStream_t);
 hipError_t launch_step_local(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
                              Persist, hipStream_t);
 hipError_t launch_step_gossip_fused(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&,

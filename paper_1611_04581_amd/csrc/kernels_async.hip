@@ -3,7 +3,9 @@
 // node j as node j stands; every other node is untouched,
 //   theta_{t+1} = D (theta_t - alpha g_t),   D = I + beta e_i (e_j - e_i)^T.
 // One tick streams one replica row (plus the peer's row): a flat kernel, every
-// thread owning one quad of the row.
+// thread owning one quad of the row, one workgroup per 1024-column tile.  (The
+// ticket-fed persistent launch of the k-row kernels does not pay here: a tile
+// is a single 20 KB visit, and the ticket round trip per visit would dominate.)
 #include "device_common.hpp"
 
 namespace gsgd {
@@ -46,53 +48,49 @@ __global__ __launch_bounds__(BLOCK)
 void async_tick_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, int32_t i, int32_t j,
                        float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
                        const float* __restrict__ h, const float* __restrict__ xstar,
-                       float sigma, RngKey key, uint32_t tick, uint32_t* __restrict__ tickets, uint32_t n_tiles)
+                       float sigma, RngKey key, uint32_t tick)
 {
     __shared__ SegLds lds;
     stage_segments(seg, lds);
-    for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
-        const Quad qd = quad_of_tile(tile, geo.d);
-        if (tile_is_full(qd, geo.d))
-            async_tick_body<true, FUSED_GEN, NOISE, EXT>(geo, hp, seg, lds, qd, neg_beta, i, j, x, v, g, h, xstar, sigma,
-                                                         key, tick);
-        else if (qd.valid > 0)
-            async_tick_body<false, FUSED_GEN, NOISE, EXT>(geo, hp, seg, lds, qd, neg_beta, i, j, x, v, g, h, xstar, sigma,
-                                                          key, tick);
-    });
+    const Quad qd = my_quad(geo.d);
+    if (tile_is_full(qd, geo.d))
+        async_tick_body<true, FUSED_GEN, NOISE, EXT>(geo, hp, seg, lds, qd, neg_beta, i, j, x, v, g, h, xstar, sigma,
+                                                     key, tick);
+    else if (qd.valid > 0)
+        async_tick_body<false, FUSED_GEN, NOISE, EXT>(geo, hp, seg, lds, qd, neg_beta, i, j, x, v, g, h, xstar, sigma,
+                                                      key, tick);
 }
 
 template <bool FUSED_GEN, int NOISE>
 static void launch_one(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta, int32_t i, int32_t j,
                        float* x, float* v, const float* g, const float* h, const float* xstar,
-                       float sigma, RngKey key, uint32_t tick, Persist p, hipStream_t stream)
+                       float sigma, RngKey key, uint32_t tick, hipStream_t stream)
 {
     const unsigned tiles = grid_for(geo.d);
-    const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
     if (hp.extended())
-        hipLaunchKernelGGL((async_tick_kernel<FUSED_GEN, NOISE, true>), dim3(width), dim3(BLOCK), 0, stream,
-                           geo, hp, seg, -beta, i, j, x, v, g, h, xstar, sigma, key, tick, p.tickets, tiles);
+        hipLaunchKernelGGL((async_tick_kernel<FUSED_GEN, NOISE, true>), dim3(tiles), dim3(BLOCK), 0, stream,
+                           geo, hp, seg, -beta, i, j, x, v, g, h, xstar, sigma, key, tick);
     else
-        hipLaunchKernelGGL((async_tick_kernel<FUSED_GEN, NOISE, false>), dim3(width), dim3(BLOCK), 0, stream,
-                           geo, hp, seg, -beta, i, j, x, v, g, h, xstar, sigma, key, tick, p.tickets, tiles);
+        hipLaunchKernelGGL((async_tick_kernel<FUSED_GEN, NOISE, false>), dim3(tiles), dim3(BLOCK), 0, stream,
+                           geo, hp, seg, -beta, i, j, x, v, g, h, xstar, sigma, key, tick);
 }
 
 hipError_t launch_async_tick(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta, int32_t i, int32_t j,
-                             float* x, float* v, const float* g, Persist p, hipStream_t stream)
+                             float* x, float* v, const float* g, hipStream_t stream)
 {
-    launch_one<false, 0>(geo, hp, seg, beta, i, j, x, v, g, nullptr, nullptr, 0.0f, RngKey{0u, 0u}, 0u, p, stream);
+    launch_one<false, 0>(geo, hp, seg, beta, i, j, x, v, g, nullptr, nullptr, 0.0f, RngKey{0u, 0u}, 0u, stream);
     return hipGetLastError();
 }
 
 hipError_t launch_async_tick_fused(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta, int32_t i,
                                    int32_t j, float* x, float* v, const float* h, const float* xstar,
-                                   float sigma, RngKey key, uint32_t tick, int noise_kind, Persist p,
-                                   hipStream_t stream)
+                                   float sigma, RngKey key, uint32_t tick, int noise_kind, hipStream_t stream)
 {
     if (noise_kind == GSGD_NOISE_UNIFORM)
-        launch_one<true, GSGD_NOISE_UNIFORM>(geo, hp, seg, beta, i, j, x, v, nullptr, h, xstar, sigma, key, tick, p,
+        launch_one<true, GSGD_NOISE_UNIFORM>(geo, hp, seg, beta, i, j, x, v, nullptr, h, xstar, sigma, key, tick,
                                              stream);
     else
-        launch_one<true, GSGD_NOISE_GAUSSIAN>(geo, hp, seg, beta, i, j, x, v, nullptr, h, xstar, sigma, key, tick, p,
+        launch_one<true, GSGD_NOISE_GAUSSIAN>(geo, hp, seg, beta, i, j, x, v, nullptr, h, xstar, sigma, key, tick,
                                               stream);
     return hipGetLastError();
 }

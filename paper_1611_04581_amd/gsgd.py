@@ -21,9 +21,8 @@ NOISE_GAUSSIAN, NOISE_UNIFORM = 0, 1
 INIT_BROADCAST, INIT_PER_REPLICA = 0, 1
 FILL_XSTAR, FILL_H, FILL_X0 = 2, 3, 4
 
-(KERNEL_GOSSIP, KERNEL_ALLREDUCE, KERNEL_EASGD, KERNEL_GEN_GRAD, KERNEL_GOSSIP_FUSED, KERNEL_LOCAL,
- KERNEL_ASYNC_TICK) = range(7)
-KERNEL_COUNT = 7
+KERNEL_GOSSIP, KERNEL_ALLREDUCE, KERNEL_EASGD, KERNEL_GEN_GRAD, KERNEL_GOSSIP_FUSED, KERNEL_LOCAL = range(6)
+KERNEL_COUNT = 6
 WALK_ROW_MASK, WALK_FIRST, WALK_LAST = 0x0FFF, 0x4000, 0x8000
 WALK_TREE, WALK_DESCEND, WALK_SAVE = 0x2000, 0x1000, 0x40000
 WALK_RESTORE_SHIFT, WALK_SLOT_SHIFT, WALK_SLOTS = 16, 20, 8
@@ -155,8 +154,8 @@ class Context:
         _check(lib().gsgd_create(C.byref(cfg), C.byref(self._h)), "gsgd_create")
 
     def close(self):
-        if getattr(self, "_h", None) is not None and self._h.value:
-            lib().gsgd_destroy(self._h)
+        if getattr(self, "_h", None) is not None and self._h.value and _lib is not None:
+            _lib.gsgd_destroy(self._h)
             self._h = _vp()
 
     __del__ = close
