@@ -30,8 +30,8 @@ BYTES_PER_REPLICA_ELEMENT = {   # algorithmic traffic of each kernel, fp32
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of known
 # size (see profiles/); None until measured.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/gossip_step_kernel_gossip_r50.md: FETCH_SIZE 4,792,020.8 x 2.000 KiB + WRITE_SIZE 6,390,064.6 KiB
-    "gossip_r50": (4792020.8 * 2.0 + 6390064.6) * 1024.0,
+    # profiles/gossip_step_kernel_gossip_r50.md: FETCH_SIZE 4,792,017.0 x 2.000 KiB + WRITE_SIZE 6,390,054.1 KiB
+    "gossip_r50": (4792017.0 * 2.0 + 6390054.1) * 1024.0,
 }
 
 
