@@ -531,6 +531,26 @@ int oracle_async_tick(float* x, float* v, const float* g_row, int32_t k, int64_t
     return 0;
 }
 
+/* Elastic averaging as Algorithm 2 states it, one client at a time: client i takes its local step and exchanges
+ * with the server, which applies that one client's update immediately (the asynchronous parameter-server form):
+ *   theta'_i = local step;  e = alpha_e (theta'_i - c);  theta_i <- theta'_i - e;  c <- c + e.
+ * The other clients and their view of the centre are untouched; they meet the moved centre at their own exchange. */
+int oracle_easgd_tick(float* x, float* v, const float* g_row, float* center, int32_t k, int64_t n, int64_t ld,
+                      const float* lr_col, float mu, float wd, int nesterov, float alpha_e, int32_t i)
+{
+    if (i < 0 || i >= k) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < n; ++c) {
+        float vn, xp;
+        local_step_ext(x[i * ld + c], v[i * ld + c], g_row[c], lr_col[c], mu, wd, nesterov, &vn, &xp);
+        const float e = alpha_e * (xp - center[c]);
+        v[i * ld + c] = vn;
+        x[i * ld + c] = xp - e;
+        center[c] = center[c] + e;
+    }
+    return 0;
+}
+
 /* Synthetic gradient of one node for one tick: as oracle_gen_grad, for row i only, the noise drawn at counter
  * (column / 4, i, tick, GRAD).                                                                                    */
 void oracle_gen_grad_row(const float* x, const float* h, const float* xstar, float* g_row,

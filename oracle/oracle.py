@@ -72,6 +72,9 @@ def lib():
         L.oracle_async_tick.argtypes = [_f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f32p,
                                         C.c_float, C.c_float, C.c_int, C.c_float, C.c_int32, C.c_int32]
         L.oracle_async_tick.restype = C.c_int
+        L.oracle_easgd_tick.argtypes = [_f32p, _f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f32p,
+                                        C.c_float, C.c_float, C.c_int, C.c_float, C.c_int32]
+        L.oracle_easgd_tick.restype = C.c_int
         L.oracle_gen_grad_row.argtypes = [_f32p, _f32p, _f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, C.c_int64,
                                           C.c_float, C.c_uint64, C.c_uint32, C.c_int]
         L.oracle_gen_grad_row.restype = None
@@ -247,6 +250,17 @@ def async_tick(x, v, g_row, lr, mu, beta, i, j, wd=0.0, nesterov=False, n=None):
                                  int(bool(nesterov)), float(beta), int(i), int(j))
     if rc:
         raise ValueError("oracle_async_tick: node index out of range")
+
+
+def easgd_tick(x, v, g_row, center, lr, mu, alpha_e, i, wd=0.0, nesterov=False, n=None):
+    k, ld = _rows(x)
+    n = ld if n is None else int(n)
+    lrc = _lr_col(lr, n)
+    assert g_row.shape[0] >= n and center.shape[0] >= n
+    rc = lib().oracle_easgd_tick(_f32(x), _f32(v), _f32(g_row), _f32(center), k, n, ld, _f32(lrc), float(mu),
+                                 float(wd), int(bool(nesterov)), float(alpha_e), int(i))
+    if rc:
+        raise ValueError("oracle_easgd_tick: node index out of range")
 
 
 def gen_grad_row(x, h, xstar, g_row, i, sigma, seed, tick, noise_kind=NOISE_GAUSSIAN, n=None, col0=0):

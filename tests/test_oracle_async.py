@@ -135,3 +135,65 @@ def test_gen_grad_row_is_a_row_of_gen_grad(oracle):
     for i in range(k):
         oracle.gen_grad_row(inp.x, inp.h, inp.xstar, row, i, 0.3, SEED, 17, 1)
         assert np.array_equal(row, g[i])
+
+
+# ----------------------------------------------------------------------------
+# elastic averaging, one client at a time (Algorithm 2 as a client/server exchange)
+
+def test_easgd_tick_is_the_synchronous_rule_with_one_client(oracle):
+    """A single client's exchange is the synchronous round with k = 1: same
+    bits for that client's row and for the centre, nothing else touched."""
+    k, n = 5, 300
+    inp = W.make_inputs(k, n, seed=90)
+    for i in (0, 3, 4):
+        x, v, c = inp.x.copy(), inp.v.copy(), inp.center.copy()
+        oracle.easgd_tick(x, v, inp.g[i].copy(), c, 0.05, 0.9, 0.2, i)
+        x1, v1, c1 = inp.x[i:i + 1].copy(), inp.v[i:i + 1].copy(), inp.center.copy()
+        oracle.step_easgd(x1, v1, inp.g[i:i + 1].copy(), c1, 0.05, 0.9, 0.2)
+        assert np.array_equal(x[i], x1[0]) and np.array_equal(v[i], v1[0]) and np.array_equal(c, c1)
+        others = [m for m in range(k) if m != i]
+        assert np.array_equal(x[others], inp.x[others]) and np.array_equal(v[others], inp.v[others])
+
+
+def test_easgd_tick_exact_replay_and_closed_form(oracle):
+    k, n = 3, 8
+    lr, mu, alpha = np.float32(0.05), np.float32(0.9), np.float32(0.25)
+    inp = W.make_inputs(k, n, seed=91)
+    x0, v0, c0 = inp.x.copy(), inp.v.copy(), inp.center.copy()
+    g_row = inp.g[2].copy()
+    oracle.easgd_tick(inp.x, inp.v, g_row, inp.center, lr, mu, alpha, 1, wd=1e-3, nesterov=True)
+    for c in range(n):
+        gt = brute.f32_fma(F(np.float32(1e-3)), F(x0[1, c]), F(g_row[c]))
+        vn = brute.f32_fma(-F(lr), gt, brute.f32_mul(F(mu), F(v0[1, c])))
+        xp = brute.f32_fma(F(mu), vn, brute.f32_fma(-F(lr), gt, F(x0[1, c])))
+        e = brute.f32_mul(F(alpha), brute.f32_sub(xp, F(c0[c])))
+        assert F(inp.x[1, c]) == brute.f32_sub(xp, e)
+        assert F(inp.center[c]) == brute.f32_add(F(c0[c]), e)
+        assert F(inp.v[1, c]) == vn
+    # closed form of one exchange, and what it conserves
+    inp = W.make_inputs(k, 500, seed=92)
+    xl, vl = inp.x.copy(), inp.v.copy()
+    oracle.step_gossip(xl, vl, inp.g, 0.05, 0.9, 0.5, list(range(k)))               # x' of every node
+    x, v, c = inp.x.copy(), inp.v.copy(), inp.center.copy()
+    oracle.easgd_tick(x, v, inp.g[0].copy(), c, 0.05, 0.9, 0.25, 0)
+    a = float(np.float32(0.25))
+    assert np.allclose(x[0], (1 - a) * xl[0].astype(np.float64) + a * inp.center, rtol=0, atol=1e-6)
+    assert np.allclose(c, (1 - a) * inp.center.astype(np.float64) + a * xl[0], rtol=0, atol=1e-6)
+    assert np.allclose(x[0].astype(np.float64) + c, xl[0].astype(np.float64) + inp.center, rtol=0, atol=1e-6)
+
+
+def test_easgd_ticks_pull_clients_and_centre_together(oracle):
+    """Exchanges alone (no gradient), clients taking turns: every exchange
+    keeps sum_i x_i + c and the spread of the clients around the centre decays
+    geometrically -- the elastic force of the consensus objective (Section 2.3)."""
+    k, n = 8, 1000
+    inp = W.make_inputs(k, n, seed=93)
+    x, v, c = inp.x.copy(), np.zeros_like(inp.x), inp.center.copy()
+    zeros = np.zeros(n, np.float32)
+    total0 = x.astype(np.float64).sum(0) + c
+    spread0 = ((x.astype(np.float64) - c) ** 2).sum()
+    for sweep in range(30):
+        for i in range(k):
+            oracle.easgd_tick(x, v, zeros, c, 0.0, 0.0, 0.1, i)
+    assert np.allclose(x.astype(np.float64).sum(0) + c, total0, rtol=0, atol=1e-4)
+    assert ((x.astype(np.float64) - c) ** 2).sum() < 1e-3 * spread0
