@@ -189,7 +189,16 @@ int gsgd_step_gossip_push(gsgd_ctx* ctx, float* x, float* v, const float* g,
 int gsgd_step_async_tick(gsgd_ctx* ctx, float* x, float* v, const float* g, int32_t i, int32_t j,
                          float beta, void* stream);
 
-/* The same tick with node i's synthetic gradient generated on the fly:
+/* Elastic averaging, one client's exchange with the server (Algorithm 2 as a
+ * client/server protocol: the server applies each client's update as it
+ * arrives).  Client i takes its local step and exchanges; nobody else moves:
+ *   v_i <- momentum * v_i - lr_s * g_i;  x'_i = x_i + v_i;
+ *   e = alpha_e * (x'_i - center);  x_i <- x'_i - e;  center <- center + e.
+ * Only row i of g is read.  center: device d, updated in place. */
+int gsgd_step_easgd_tick(gsgd_ctx* ctx, float* x, float* v, const float* g, float* center, int32_t i,
+                         float alpha_e, void* stream);
+
+/* The asynchronous pull-gossip tick with node i's synthetic gradient generated on the fly:
  * g_i = h (.) (x_i - xstar) + sigma xi, xi from Philox stream 0 at counter
  * (column/4, i, tick, 0).  tick < 2^32. */
 int gsgd_step_async_tick_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,

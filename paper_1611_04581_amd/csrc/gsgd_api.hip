@@ -279,6 +279,19 @@ extern "C" int gsgd_step_async_tick(gsgd_ctx* ctx, float* x, float* v, const flo
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
+extern "C" int gsgd_step_easgd_tick(gsgd_ctx* ctx, float* x, float* v, const float* g, float* center, int32_t i,
+                                    float alpha_e, void* stream)
+{
+    const int rc = check_state(ctx, x, v, g);
+    if (rc != GSGD_OK) return rc;
+    if (!ok_matrix(center) || center == x || center == v || center == g || !(alpha_e == alpha_e))
+        return GSGD_ERR_INVALID_ARG;
+    if (i < 0 || i >= ctx->cfg.k) return GSGD_ERR_INVALID_ARG;
+    const hipError_t e = launch_easgd_tick(geom_of(ctx), hyper_of(ctx), seg_of(ctx), alpha_e, i, x, v, g, center,
+                                           static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
 extern "C" int gsgd_step_async_tick_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
                                           int32_t i, int32_t j, float beta, uint64_t tick, void* stream)
 {

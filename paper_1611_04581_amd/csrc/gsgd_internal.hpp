@@ -104,6 +104,8 @@ hipError_t launch_async_tick(const Geom&, const Hyper&, const SegTable&, float b
 hipError_t launch_async_tick_fused(const Geom&, const Hyper&, const SegTable&, float beta, int32_t i, int32_t j,
                                    float* x, float* v, const float* h, const float* xstar,
                                    float sigma, RngKey key, uint32_t tick, int noise_kind, hipStream_t);
+hipError_t launch_easgd_tick(const Geom&, const Hyper&, const SegTable&, float alpha_e, int32_t i,
+                             float* x, float* v, const float* g, float* center, hipStream_t);
 hipError_t launch_step_local(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
                              Persist, hipStream_t);
 hipError_t launch_step_gossip_fused(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&,

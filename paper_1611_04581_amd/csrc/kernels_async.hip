@@ -61,6 +61,55 @@ void async_tick_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, int32_t
                                                       key, tick);
 }
 
+// Elastic averaging, one client's exchange with the server (Algorithm 2 in its
+// asynchronous client/server form): client i takes its local step, gives up
+// e = alpha_e (x'_i - center) and the centre takes it.
+template <bool FULL, bool EXT>
+__device__ __forceinline__
+void easgd_tick_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
+                     float alpha_e, int32_t i, float* __restrict__ x, float* __restrict__ v,
+                     const float* __restrict__ g, float* __restrict__ center)
+{
+    const int valid = FULL ? 4 : qd.valid;
+    const int64_t mine_off = static_cast<int64_t>(i) * geo.ld + qd.col;
+    const f32x4 X = load_quad<FULL>(x + mine_off, valid);
+    const f32x4 V = load_quad<FULL>(v + mine_off, valid);
+    const f32x4 G = load_quad<FULL>(g + mine_off, valid);
+    const f32x4 C = load_quad<FULL>(center + qd.col, valid);
+    const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
+    f32x4 vn, post;
+    local_step<EXT>(X, V, G, neg_lr, hp, vn, post);
+    const f32x4 e = alpha_e * (post - C);
+    store_quad<FULL>(v + mine_off, vn, valid);
+    store_quad<FULL>(x + mine_off, post - e, valid);
+    store_quad<FULL>(center + qd.col, C + e, valid);
+}
+
+template <bool EXT>
+__global__ __launch_bounds__(BLOCK)
+void easgd_tick_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e, int32_t i,
+                       float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                       float* __restrict__ center)
+{
+    __shared__ SegLds lds;
+    stage_segments(seg, lds);
+    const Quad qd = my_quad(geo.d);
+    if (tile_is_full(qd, geo.d)) easgd_tick_body<true, EXT>(geo, hp, seg, lds, qd, alpha_e, i, x, v, g, center);
+    else if (qd.valid > 0) easgd_tick_body<false, EXT>(geo, hp, seg, lds, qd, alpha_e, i, x, v, g, center);
+}
+
+hipError_t launch_easgd_tick(const Geom& geo, const Hyper& hp, const SegTable& seg, float alpha_e, int32_t i,
+                             float* x, float* v, const float* g, float* center, hipStream_t stream)
+{
+    if (hp.extended())
+        hipLaunchKernelGGL(easgd_tick_kernel<true>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
+                           geo, hp, seg, alpha_e, i, x, v, g, center);
+    else
+        hipLaunchKernelGGL(easgd_tick_kernel<false>, dim3(grid_for(geo.d)), dim3(BLOCK), 0, stream,
+                           geo, hp, seg, alpha_e, i, x, v, g, center);
+    return hipGetLastError();
+}
+
 template <bool FUSED_GEN, int NOISE>
 static void launch_one(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta, int32_t i, int32_t j,
                        float* x, float* v, const float* g, const float* h, const float* xstar,

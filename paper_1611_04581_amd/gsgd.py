@@ -59,6 +59,7 @@ SIGNATURES = {
     "gsgd_step_gossip_push": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), _vp]),
     "gsgd_push_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint32), C.POINTER(C.c_int32)]),
     "gsgd_step_async_tick": (C.c_int, [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_float, _vp]),
+    "gsgd_step_easgd_tick": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int32, C.c_float, _vp]),
     "gsgd_step_async_tick_fused": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_float, C.c_uint64,
                                              _vp]),
     "gsgd_run_async_ticks": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_float, C.c_uint64, C.c_uint64, _vp]),
@@ -212,6 +213,10 @@ class Context:
     def step_async_tick(self, x, v, g, i, j, beta=0.5, stream=None):
         _check(lib().gsgd_step_async_tick(self._h, _ptr(x), _ptr(v), _ptr(g), int(i), int(j), float(beta),
                                           _stream(stream)), "gsgd_step_async_tick")
+
+    def step_easgd_tick(self, x, v, g, center, i, alpha_e, stream=None):
+        _check(lib().gsgd_step_easgd_tick(self._h, _ptr(x), _ptr(v), _ptr(g), _ptr(center), int(i), float(alpha_e),
+                                          _stream(stream)), "gsgd_step_easgd_tick")
 
     def step_async_tick_fused(self, x, v, h, xstar, i, j, tick, beta=0.5, stream=None):
         _check(lib().gsgd_step_async_tick_fused(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), int(i), int(j),

@@ -454,3 +454,25 @@ def test_async_theorem_bounds_on_the_gpu(G, oracle):
             assert st[1] <= 1.05 * (rate ** (t0 + 200) * st0[1] + floor)
             assert st[0] <= 1.05 * (crate ** (t0 + 200) * st0[0] + cfloor)
         assert st[1] < 0.05 * st0[1] and st[0] < 0.05 * st0[0]
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES)
+def test_easgd_one_client_at_a_time(G, oracle, k, d, ld):
+    """Algorithm 2 as a client/server exchange: clients take turns, the centre
+    moves after every one of them."""
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=61)
+    order = [int(i) for i in np.random.default_rng(k).integers(0, k, size=2 * k)]
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9) as ctx:
+        for wd, nest in ((0.0, False), (1e-4, True)):
+            ctx.set_local_step(wd, nest)
+            x, v, g, c = dev(inp.x), dev(inp.v), dev(inp.g), dev(inp.center)
+            xo, vo, co = inp.x.copy(), inp.v.copy(), inp.center.copy()
+            for i in order:
+                ctx.step_easgd_tick(x, v, g, c, i, 0.9 / k)
+                oracle.easgd_tick(xo, vo, inp.g[i].copy(), co, 0.05, 0.9, 0.9 / k, i, wd=wd, nesterov=nest, n=d)
+            assert_bitwise(host(x), xo, "x")
+            assert_bitwise(host(v), vo, "v")
+            assert_bitwise(host(c), co, "center")
+        with pytest.raises(G.GsgdError):
+            ctx.step_easgd_tick(x, v, g, c, k, 0.1)
