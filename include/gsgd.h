@@ -303,6 +303,27 @@ int gsgd_perm_walk(const int32_t* peer_perm, int32_t k, uint16_t* walk);
  * Waits for the stream.  out: host. */
 int gsgd_stats(gsgd_ctx* ctx, const float* x, const float* xstar, double out[4], void* stream);
 
+/* Squared Euclidean norm of every replica row over columns 0..d-1, in fp64:
+ * out[i] = ||x_i||^2.  Waits for the stream.  out: host, k doubles. */
+int gsgd_row_sqnorms(gsgd_ctx* ctx, const float* x, double* out, void* stream);
+
+/* The diffusion potential of Section 3.1.  Under rounds of gossip alone (no
+ * gradient steps) every node's parameters stay a weighted average of the
+ * starting ones, theta_i(r) = sum_j v_ij theta_j(0), and
+ *   Phi = sum_i sum_j || v_ij theta_j(0) - (1/p) sum_j' v_ij' theta_j'(0) ||^2
+ *       = sum_i [ sum_j v_ij^2 ||theta_j(0)||^2 - (1/p) ||theta_i(r)||^2 ].
+ * V is the k x k row-major matrix of the v_ij, the identity before the first
+ * round; gsgd_weights_pull / gsgd_weights_push advance it by one round of
+ * pull-gossip (v_i <- v_i - beta (v_i - v_peer[i])) or push-gossip (v_r <-
+ * average of v_r and the v_i sent to r), the same maps the step calls take.
+ * gsgd_diffusion_potential evaluates the second form from the row norms at the
+ * start (sqnorm_start) and now (sqnorm_now), both from gsgd_row_sqnorms.
+ * All three are pure host code; V, the norms and out are host memory. */
+int gsgd_weights_pull(double* V, int32_t k, const int32_t* peer, double beta);
+int gsgd_weights_push(double* V, int32_t k, const int32_t* target);
+int gsgd_diffusion_potential(const double* V, int32_t k, const double* sqnorm_start, const double* sqnorm_now,
+                             double* out);
+
 const char* gsgd_strerror(int code);
 int gsgd_last_hip_error(const gsgd_ctx* ctx);   /* raw hipError_t of the last GSGD_ERR_HIP */
 

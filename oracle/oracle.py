@@ -305,3 +305,43 @@ def stats(x, xstar, n=None):
 
 def num_threads():
     return int(lib().oracle_num_threads())
+
+
+# ----------------------------------------------------------------------------
+# Diffusion potential (Section 3.1), written out from its definition in fp64.
+# Under gossip rounds alone, theta_i(r) = sum_j v_ij theta_j(0) with V = M_r ... M_1.
+
+def mixing_matrix_pull(peer, beta):
+    """M with theta' = M theta for one pull round: row i is (1 - beta) e_i + beta e_peer[i]."""
+    k = len(peer)
+    M = np.zeros((k, k), np.float64)
+    for i in range(k):
+        M[i, i] += 1.0 - float(beta)
+        M[i, int(peer[i])] += float(beta)
+    return M
+
+
+def mixing_matrix_push(target):
+    """M for one push round: row r averages r itself and every i != r with target[i] == r."""
+    k = len(target)
+    M = np.zeros((k, k), np.float64)
+    for r in range(k):
+        got = [r] + [i for i in range(k) if i != r and int(target[i]) == r]
+        for i in got:
+            M[r, i] = 1.0 / len(got)
+    return M
+
+
+def diffusion_potential(theta0, V):
+    """sum_i sum_j || v_ij theta_j(0) - (1/p) sum_j' v_ij' theta_j'(0) ||^2, term by term."""
+    theta0 = np.asarray(theta0, np.float64)
+    V = np.asarray(V, np.float64)
+    p = theta0.shape[0]
+    total = 0.0
+    for i in range(p):
+        contrib = [V[i, j] * theta0[j] for j in range(p)]
+        centre = sum(contrib) / p
+        for j in range(p):
+            diff = contrib[j] - centre
+            total += float(diff @ diff)
+    return total

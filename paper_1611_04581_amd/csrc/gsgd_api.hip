@@ -13,8 +13,9 @@ struct gsgd_ctx {
     int64_t*    d_offsets;    // device copy of the segment table
     float*      d_scales;
     double*     d_partials;   // stats scratch: stats_num_blocks(d) * 4 doubles
-    double*     d_result;     // 4 doubles
-    double*     h_result;     // pinned host, 4 doubles
+    double*     d_result;     // max(4, k) doubles
+    double*     h_result;     // pinned host, max(4, k) doubles
+    double*     d_norm_partials;   // row-norm scratch: k * NORM_CHUNKS doubles
     uint32_t*   d_tickets;    // tile tickets of the persistent kernels (2 words, zero between launches)
     int         cu_count;     // compute units of the device
     unsigned    width[GSGD_KERNEL_COUNT];   // persistent workgroups per streaming kernel
@@ -65,6 +66,7 @@ void release(gsgd_ctx* c)
     if (c->d_result) (void)hipFree(c->d_result);
     if (c->h_result) (void)hipHostFree(c->h_result);
     if (c->d_tickets) (void)hipFree(c->d_tickets);
+    if (c->d_norm_partials) (void)hipFree(c->d_norm_partials);
     delete c;
 }
 
@@ -105,8 +107,13 @@ extern "C" int gsgd_create(const gsgd_config* cfg, gsgd_ctx** out)
     }
     if (e == hipSuccess)
         e = hipMalloc(reinterpret_cast<void**>(&c->d_partials), sizeof(double) * 4 * static_cast<size_t>(stats_num_blocks(cfg->d)));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_result), sizeof(double) * 4);
-    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_result), sizeof(double) * 4, hipHostMallocDefault);
+    const size_t n_result = static_cast<size_t>(cfg->k > 4 ? cfg->k : 4);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_result), sizeof(double) * n_result);
+    if (e == hipSuccess)
+        e = hipHostMalloc(reinterpret_cast<void**>(&c->h_result), sizeof(double) * n_result, hipHostMallocDefault);
+    if (e == hipSuccess)
+        e = hipMalloc(reinterpret_cast<void**>(&c->d_norm_partials),
+                      sizeof(double) * static_cast<size_t>(cfg->k) * NORM_CHUNKS);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_tickets), 256);
     if (e == hipSuccess) e = hipMemset(c->d_tickets, 0, 256);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->cu_count, hipDeviceAttributeMultiprocessorCount, c->device);
@@ -365,6 +372,74 @@ extern "C" int gsgd_stats(gsgd_ctx* ctx, const float* x, const float* xstar, dou
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return hip_fail(ctx, e);
     for (int m = 0; m < 4; ++m) out[m] = ctx->h_result[m];
+    return GSGD_OK;
+}
+
+extern "C" int gsgd_row_sqnorms(gsgd_ctx* ctx, const float* x, double* out, void* stream)
+{
+    if (!ctx || !ok_matrix(x) || !out) return GSGD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_row_sqnorms(geom_of(ctx), x, ctx->d_norm_partials, ctx->d_result, s);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(ctx->h_result, ctx->d_result, sizeof(double) * static_cast<size_t>(ctx->cfg.k),
+                           hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    for (int32_t i = 0; i < ctx->cfg.k; ++i) out[i] = ctx->h_result[i];
+    return GSGD_OK;
+}
+
+// ---- the weights v_ij of Section 3.1 and the diffusion potential: host arithmetic on k x k matrices -----------
+
+extern "C" int gsgd_weights_pull(double* V, int32_t k, const int32_t* peer, double beta)
+{
+    if (!V || !peer || k < 1 || k > GSGD_MAX_K || !(beta == beta)) return GSGD_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < k; ++i)
+        if (peer[i] < 0 || peer[i] >= k) return GSGD_ERR_BAD_PERM;
+    double* old = new (std::nothrow) double[static_cast<size_t>(k) * k];
+    if (!old) return GSGD_ERR_NO_MEMORY;
+    memcpy(old, V, sizeof(double) * static_cast<size_t>(k) * k);
+    for (int32_t i = 0; i < k; ++i)
+        for (int32_t j = 0; j < k; ++j) {
+            const double mine = old[static_cast<size_t>(i) * k + j], theirs = old[static_cast<size_t>(peer[i]) * k + j];
+            V[static_cast<size_t>(i) * k + j] = mine - beta * (mine - theirs);
+        }
+    delete[] old;
+    return GSGD_OK;
+}
+
+extern "C" int gsgd_weights_push(double* V, int32_t k, const int32_t* target)
+{
+    if (!V || !target || k < 1 || k > GSGD_MAX_K) return GSGD_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < k; ++i)
+        if (target[i] < 0 || target[i] >= k) return GSGD_ERR_BAD_PERM;
+    double* old = new (std::nothrow) double[static_cast<size_t>(k) * k];
+    if (!old) return GSGD_ERR_NO_MEMORY;
+    memcpy(old, V, sizeof(double) * static_cast<size_t>(k) * k);
+    for (int32_t r = 0; r < k; ++r) {
+        int32_t received = 1;
+        for (int32_t i = 0; i < k; ++i)
+            if (i != r && target[i] == r) {
+                ++received;
+                for (int32_t j = 0; j < k; ++j) V[static_cast<size_t>(r) * k + j] += old[static_cast<size_t>(i) * k + j];
+            }
+        for (int32_t j = 0; j < k; ++j) V[static_cast<size_t>(r) * k + j] /= static_cast<double>(received);
+    }
+    delete[] old;
+    return GSGD_OK;
+}
+
+extern "C" int gsgd_diffusion_potential(const double* V, int32_t k, const double* sqnorm_start,
+                                        const double* sqnorm_now, double* out)
+{
+    if (!V || !sqnorm_start || !sqnorm_now || !out || k < 1 || k > GSGD_MAX_K) return GSGD_ERR_INVALID_ARG;
+    double total = 0.0;
+    for (int32_t i = 0; i < k; ++i) {
+        double own = 0.0;
+        for (int32_t j = 0; j < k; ++j) own += V[static_cast<size_t>(i) * k + j] * V[static_cast<size_t>(i) * k + j] * sqnorm_start[j];
+        total += own - sqnorm_now[i] / static_cast<double>(k);
+    }
+    *out = total;
     return GSGD_OK;
 }
 

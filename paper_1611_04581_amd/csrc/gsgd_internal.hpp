@@ -127,6 +127,10 @@ int64_t    stats_num_blocks(int64_t d);
 hipError_t launch_stats(const Geom&, const float* x, const float* xstar, double* partials, double* result,
                         hipStream_t);
 
+// row norms: partials holds k * NORM_CHUNKS doubles, result k doubles (device)
+constexpr int NORM_CHUNKS = 256;
+hipError_t launch_row_sqnorms(const Geom&, const float* x, double* partials, double* result, hipStream_t);
+
 // ---- host-only helpers -----------------------------------------------------
 void host_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 int  build_walk(const int32_t* perm, int32_t k, Walk* out);   // GSGD_OK or GSGD_ERR_BAD_PERM

@@ -114,6 +114,53 @@ void stats_final_kernel(int64_t n_partials, const double* __restrict__ partials,
         for (int m = 0; m < 4; ++m) result[m] = acc[m];
 }
 
+// Squared norm of every replica row (the ingredients of the diffusion
+// potential of Section 3.1).  Grid (NORM_CHUNKS, k): a block sums the squares
+// of its share of one row's tiles; a second kernel adds the NORM_CHUNKS
+// partials of each row in a fixed order.
+__global__ __launch_bounds__(BLOCK)
+void row_sqnorm_partial_kernel(Geom geo, int64_t n_tiles, const float* __restrict__ x, double* __restrict__ partials)
+{
+    __shared__ double lds[BLOCK / 64][4];
+    const int row = static_cast<int>(blockIdx.y);
+    const float* xr = x + static_cast<int64_t>(row) * geo.ld;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const Quad qd = quad_of_tile(tile, geo.d);
+        if (qd.valid == 0) continue;
+        const f32x4 xi = load_quad(xr + qd.col, qd.valid);        // lanes beyond `valid` come back as zero
+        acc[0] += static_cast<double>(xi.x) * static_cast<double>(xi.x);
+        acc[1] += static_cast<double>(xi.y) * static_cast<double>(xi.y);
+        acc[2] += static_cast<double>(xi.z) * static_cast<double>(xi.z);
+        acc[3] += static_cast<double>(xi.w) * static_cast<double>(xi.w);
+    }
+    acc[0] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    acc[1] = acc[2] = acc[3] = 0.0;
+    block_sum4(acc, lds);
+    if (threadIdx.x == 0) partials[static_cast<int64_t>(row) * gridDim.x + blockIdx.x] = acc[0];
+}
+
+__global__ __launch_bounds__(64)
+void row_sqnorm_final_kernel(int n_chunks, const double* __restrict__ partials, double* __restrict__ result)
+{
+    const int row = static_cast<int>(blockIdx.x);
+    if (threadIdx.x != 0) return;
+    double s = 0.0;
+    for (int c = 0; c < n_chunks; ++c) s += partials[static_cast<int64_t>(row) * n_chunks + c];
+    result[row] = s;
+}
+
+hipError_t launch_row_sqnorms(const Geom& geo, const float* x, double* partials, double* result, hipStream_t stream)
+{
+    hipLaunchKernelGGL(row_sqnorm_partial_kernel, dim3(NORM_CHUNKS, static_cast<unsigned>(geo.k)), dim3(BLOCK), 0,
+                       stream, geo, static_cast<int64_t>(grid_for(geo.d)), x, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(row_sqnorm_final_kernel, dim3(static_cast<unsigned>(geo.k)), dim3(64), 0, stream,
+                       NORM_CHUNKS, partials, result);
+    return hipGetLastError();
+}
+
 int64_t stats_num_blocks(int64_t d) { return static_cast<int64_t>(grid_for(d)); }
 
 hipError_t launch_stats(const Geom& geo, const float* x, const float* xstar, double* partials, double* result,

@@ -77,6 +77,11 @@ SIGNATURES = {
     "gsgd_make_perm": (C.c_int, [C.c_uint64, C.c_uint64, C.c_int32, C.POINTER(C.c_int32)]),
     "gsgd_perm_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint16)]),
     "gsgd_stats": (C.c_int, [_vp, _vp, _vp, C.POINTER(C.c_double), _vp]),
+    "gsgd_row_sqnorms": (C.c_int, [_vp, _vp, C.POINTER(C.c_double), _vp]),
+    "gsgd_weights_pull": (C.c_int, [C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_int32), C.c_double]),
+    "gsgd_weights_push": (C.c_int, [C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_int32)]),
+    "gsgd_diffusion_potential": (C.c_int, [C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_double),
+                                           C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "gsgd_strerror": (C.c_char_p, [C.c_int]),
     "gsgd_last_hip_error": (C.c_int, [_vp]),
 }
@@ -243,6 +248,11 @@ class Context:
         _check(lib().gsgd_philox_raw(self._h, int(c1), int(c2), int(c3), int(n_blocks), _ptr(out), _stream(stream)),
                "gsgd_philox_raw")
 
+    def row_sqnorms(self, x, stream=None):
+        out = (C.c_double * self.k)()
+        _check(lib().gsgd_row_sqnorms(self._h, _ptr(x), out, _stream(stream)), "gsgd_row_sqnorms")
+        return np.array(list(out), dtype=np.float64)
+
     def stats(self, x, xstar, stream=None):
         out = (C.c_double * 4)()
         _check(lib().gsgd_stats(self._h, _ptr(x), _ptr(xstar), out, _stream(stream)), "gsgd_stats")
@@ -261,6 +271,35 @@ def make_perm(seed, step, k):
     _check(lib().gsgd_make_perm(int(seed), int(step), int(k), out.ctypes.data_as(C.POINTER(C.c_int32))),
            "gsgd_make_perm")
     return out
+
+
+_f64p = C.POINTER(C.c_double)
+
+
+def _weights_arg(V):
+    if not (isinstance(V, np.ndarray) and V.dtype == np.float64 and V.flags.c_contiguous and V.ndim == 2
+            and V.shape[0] == V.shape[1]):
+        raise ValueError("V must be a C-contiguous square float64 array (updated in place)")
+    return V.ctypes.data_as(_f64p)
+
+
+def weights_pull(V, peer, beta=0.5):
+    keep, p = _perm_arg(peer)
+    _check(lib().gsgd_weights_pull(_weights_arg(V), int(V.shape[0]), p, float(beta)), "gsgd_weights_pull")
+
+
+def weights_push(V, target):
+    keep, p = _perm_arg(target)
+    _check(lib().gsgd_weights_push(_weights_arg(V), int(V.shape[0]), p), "gsgd_weights_push")
+
+
+def diffusion_potential(V, sqnorm_start, sqnorm_now):
+    a = np.ascontiguousarray(sqnorm_start, dtype=np.float64)
+    b = np.ascontiguousarray(sqnorm_now, dtype=np.float64)
+    out = C.c_double(0.0)
+    _check(lib().gsgd_diffusion_potential(_weights_arg(V), int(V.shape[0]), a.ctypes.data_as(_f64p),
+                                          b.ctypes.data_as(_f64p), C.byref(out)), "gsgd_diffusion_potential")
+    return float(out.value)
 
 
 def make_tick(seed, tick, k):

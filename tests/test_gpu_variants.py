@@ -476,3 +476,52 @@ def test_easgd_one_client_at_a_time(G, oracle, k, d, ld):
             assert_bitwise(host(c), co, "center")
         with pytest.raises(G.GsgdError):
             ctx.step_easgd_tick(x, v, g, c, k, 0.1)
+
+
+# ----------------------------------------------------------------------------
+# row norms and the diffusion potential (Section 3.1)
+
+@pytest.mark.parametrize("k,d,ld", SHAPES + [(128, 300 * 1024 + 5, None)])
+def test_row_sqnorms(G, oracle, k, d, ld):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=71)
+    with G.Context(k, d, ld) as ctx:
+        got = ctx.row_sqnorms(dev(inp.x))
+    want = (inp.x[:, :d].astype(np.float64) ** 2).sum(1)
+    assert np.allclose(got, want, rtol=1e-12, atol=0)
+
+
+@pytest.mark.parametrize("kind", ["pull", "push"])
+def test_diffusion_potential_along_pure_gossip_rounds(G, oracle, kind):
+    """Gossip rounds without gradient steps on the device; the potential from
+    the library (row norms on the device, weights on the host) against the
+    oracle's term-by-term definition on the starting vectors."""
+    k, d = 8, 3 * 1024 + 2
+    ld = W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=72)
+    theta0 = inp.x[:, :d].astype(np.float64)
+    V = np.eye(k)
+    Vo = np.eye(k)
+    with G.Context(k, d, ld, lr=0.0, momentum=0.0) as ctx:
+        x, v, g = dev(inp.x), dev(np.zeros_like(inp.v)), dev(np.zeros_like(inp.g))
+        n0 = ctx.row_sqnorms(x)
+        phi0 = G.diffusion_potential(V, n0, n0)
+        assert np.isclose(phi0, oracle.diffusion_potential(theta0, Vo), rtol=1e-10)
+        last = phi0
+        for r in range(10):
+            if kind == "pull":
+                peer = G.make_targets(SEED, r, k)
+                ctx.step_gossip_pull(x, v, g, peer, 0.5)
+                G.weights_pull(V, peer, 0.5)
+                Vo = oracle.mixing_matrix_pull(peer, 0.5) @ Vo
+            else:
+                target = G.make_targets(SEED, r, k, True)
+                ctx.step_gossip_push(x, v, g, target)
+                G.weights_push(V, target)
+                Vo = oracle.mixing_matrix_push(target) @ Vo
+            phi = G.diffusion_potential(V, n0, ctx.row_sqnorms(x))
+            assert np.isclose(phi, oracle.diffusion_potential(theta0, Vo), rtol=1e-5)
+            last = phi
+        assert last < 0.3 * phi0
+        # the device rows are the weighted averages the weights say they are
+        assert np.allclose(host(x)[:, :d], Vo @ theta0, rtol=0, atol=1e-5)

@@ -354,3 +354,75 @@ def test_push_walk_realises_the_definition(k):
         assert 1 <= gsgd.push_walk([(i - 1) // 2 if i else 0 for i in range(k)])[1] <= 8
     with pytest.raises(gsgd.GsgdError):
         gsgd.push_walk([k] * k)
+
+
+# ----------------------------------------------------------------------------
+# diffusion potential (Section 3.1)
+
+def test_diffusion_potential_special_cases(oracle):
+    rng = np.random.default_rng(3)
+    p, n = 6, 40
+    theta = rng.standard_normal((p, n))
+    # before any round V = I: each node holds only its own vector
+    assert np.isclose(oracle.diffusion_potential(theta, np.eye(p)), (1 - 1 / p) * (theta ** 2).sum(), rtol=1e-12)
+    # identical starting vectors: Phi = ||theta||^2 sum_ij (v_ij - 1/p)^2, zero once every weight is 1/p
+    same = np.tile(theta[0], (p, 1))
+    V = rng.dirichlet(np.ones(p), size=p)
+    assert np.isclose(oracle.diffusion_potential(same, V), (theta[0] ** 2).sum() * ((V - 1 / p) ** 2).sum(), rtol=1e-12)
+    assert abs(oracle.diffusion_potential(same, np.full((p, p), 1 / p))) < 1e-20
+
+
+def test_weight_matrices_and_library_potential(oracle):
+    """The library's host-side weight updates are the oracle's mixing matrices
+    applied from the left, and its closed form of the potential (from row
+    norms) equals the term-by-term definition."""
+    rng = np.random.default_rng(4)
+    for k in (1, 2, 5, 16):
+        theta = rng.standard_normal((k, 30))
+        V = np.eye(k)
+        Vo = np.eye(k)
+        for r in range(6):
+            if r % 2 == 0:
+                peer = [int(a) for a in oracle.make_targets(SEED, r, k)]
+                gsgd.weights_pull(V, peer, 0.5)
+                Vo = oracle.mixing_matrix_pull(peer, 0.5) @ Vo
+            else:
+                target = [int(a) for a in rng.integers(0, k, size=k)]
+                gsgd.weights_push(V, target)
+                Vo = oracle.mixing_matrix_push(target) @ Vo
+            assert np.allclose(V, Vo, rtol=0, atol=1e-15)
+            assert np.allclose(V.sum(1), 1.0, rtol=0, atol=1e-14)          # rows stay weighted averages
+            now = Vo @ theta
+            got = gsgd.diffusion_potential(V, (theta ** 2).sum(1), (now ** 2).sum(1))
+            assert np.isclose(got, oracle.diffusion_potential(theta, Vo), rtol=1e-10, atol=1e-12)
+    with pytest.raises(gsgd.GsgdError):
+        gsgd.weights_pull(np.eye(3), [0, 1, 3], 0.5)
+
+
+def test_diffusion_potential_decays_under_uniform_gossip(oracle):
+    """Repeated rounds of uniform gossip shrink the potential at a steady rate
+    (the property the paper quotes from the push-sum analysis).  With one
+    common starting vector the potential is ||theta||^2 sum_ij (v_ij - 1/p)^2,
+    the weight potential of that analysis, and decays geometrically towards
+    zero for push-gossip with its near-uniform weights; with distinct starting
+    vectors it falls to the spread the contributions keep at consensus."""
+    k, n = 16, 50
+    theta = np.random.default_rng(5).standard_normal((k, n))
+    same = np.tile(theta[0], (k, 1))
+    for kind in ("pull", "push"):
+        V = np.eye(k)
+        phi, phi_same = [oracle.diffusion_potential(theta, V)], [oracle.diffusion_potential(same, V)]
+        for r in range(24):
+            if kind == "pull":
+                V = oracle.mixing_matrix_pull(oracle.make_targets(SEED, r, k), 0.5) @ V
+            else:
+                V = oracle.mixing_matrix_push(oracle.make_targets(SEED, r, k, True)) @ V
+            phi.append(oracle.diffusion_potential(theta, V))
+            phi_same.append(oracle.diffusion_potential(same, V))
+        assert phi[8] < 0.2 * phi[0] and phi[-1] <= phi[8]
+        spread = V.max(0) - V.min(0)                       # near consensus: every node holds almost the same weights
+        assert spread.max() < 2e-2
+        # the first rounds, before the weights settle, shrink the common-vector potential geometrically
+        ratios = np.array(phi_same[1:7]) / np.array(phi_same[:6])
+        assert np.exp(np.log(ratios).mean()) < 0.75
+        assert phi_same[-1] < 0.05 * phi_same[0]
