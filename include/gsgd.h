@@ -24,8 +24,11 @@
  *   - Pointers named "host" are ordinary host memory, read (or written, for
  *     outputs) before the call returns.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Step calls only enqueue work; they do not synchronise.  gsgd_stats is
- *     the one call that waits for the stream.
+ *     Step calls only enqueue kernels; they do not synchronise, allocate or
+ *     clear memory, so a caller may record a run of them into a HIP graph
+ *     (peer maps, step numbers and hyper-parameters are baked in as kernel
+ *     arguments at record time).  gsgd_stats and gsgd_row_sqnorms wait for
+ *     the stream and must stay outside a capture.
  *
  * Errors: every function returns GSGD_OK (0) or a negative code; nothing
  * throws, aborts or prints.  A gsgd_ctx is not thread-safe; distinct contexts
