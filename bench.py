@@ -191,6 +191,20 @@ def main():
             extras["fused_iteration_ms"] = w_fu / n2 * 1e3
             extras["fused_iteration_replica_steps_per_s"] = k * n2 / w_fu
             extras["fused_iteration_GBps_algorithmic"] = (16.0 + 8.0 / k) * k * d / (e_fu / n2) / 1e9
+        if cfg.name == "gossip_r50":
+            # the other gossip forms on the same resident state (same 20 B per replica-element)
+            forms = {
+                "pull_gossip_iid_targets": lambda t: ctx.step_gossip_pull(x, v, g, gsgd.make_targets(cfg.seed, t, k), cfg.beta),
+                "push_gossip": lambda t: ctx.step_gossip_push(x, v, g, gsgd.make_targets(cfg.seed, t, k, True)),
+                "stale_parameter_gossip": lambda t: ctx.step_gossip_stale(x, v, g, gsgd.make_perm(cfg.seed, t, k), cfg.beta),
+                "local_step_only": lambda t: ctx.step_local(x, v, g),
+            }
+            for name, fn in forms.items():
+                for t in range(3):
+                    fn(t)
+                w_f, e_f = timed(fn, n2, 1000)
+                extras[name + "_ms"] = e_f / n2 * 1e3
+                extras[name + "_frac_of_hbm_peak"] = 20.0 * k * d / (e_f / n2) / 1e9 / HBM_PEAK_GBS
         out["extras"] = extras
         log("extras:", json.dumps(extras))
 
