@@ -1,7 +1,9 @@
-// The three aggregation-step kernels: gossip (Section 3.1 of the paper),
-// all-reduce average (Algorithm 1) and elastic averaging (Algorithm 2).
+// The aggregation-step kernels: gossip in its pull, push and stale-parameter
+// forms (Section 3.1, Algorithms 3-4, Section 6.2 of the paper), all-reduce
+// average (Algorithm 1), elastic averaging (Algorithm 2), and the local step
+// alone.
 //
-// Every rule couples only the k values of one column, so a thread owns four
+// Every exchanging rule couples only the k values of one column, so a thread owns four
 // adjacent columns (one 128-bit lane) of all k replica rows and walks the rows.
 // A wavefront reads or writes 1 KiB contiguous per access; x, v and g are each
 // read once and x, v written once: 20 bytes per replica-element, the minimum.
