@@ -245,6 +245,14 @@ int gsgd_step_easgd(gsgd_ctx* ctx, float* x, float* v, const float* g,
 int gsgd_step_gossip_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
                            const int32_t* peer_perm, float beta, uint64_t step, void* stream);
 
+/* The same for pull-gossip on an arbitrary peer map (fresh or stale parameters)
+ * and for push-gossip: gsgd_gen_grad at `step` followed by gsgd_step_gossip_pull
+ * / gsgd_step_gossip_push, with g never written to memory. */
+int gsgd_step_gossip_pull_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
+                                const int32_t* peer, float beta, int stale, uint64_t step, void* stream);
+int gsgd_step_gossip_push_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
+                                const int32_t* target, uint64_t step, void* stream);
+
 /* Raw Philox4x32-10 output for counters (q, c1, c2, c3), q = 0..n_blocks-1,
  * under the context's key: out[4q .. 4q+3] are the four words of block q.
  * The generator is the one of Salmon, Moraes, Dror and Shaw (SC'11); this

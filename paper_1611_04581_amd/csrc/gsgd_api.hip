@@ -335,19 +335,65 @@ extern "C" int gsgd_step_local(gsgd_ctx* ctx, float* x, float* v, const float* g
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
-extern "C" int gsgd_step_gossip_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
-                                      const int32_t* peer_perm, float beta, uint64_t step, void* stream)
+namespace {
+int check_fused(const gsgd_ctx* ctx, const float* x, const float* v, const float* h, const float* xstar,
+                const int32_t* map, uint64_t step)
 {
     if (!ctx || !ok_matrix(x) || !ok_matrix(v) || !ok_matrix(h) || !ok_matrix(xstar) || x == v)
         return GSGD_ERR_INVALID_ARG;
-    if (!peer_perm || !(beta == beta) || step > 0xFFFFFFFFull) return GSGD_ERR_INVALID_ARG;
-    Walk walk;
-    const int rc = build_walk(peer_perm, ctx->cfg.k, &walk);
+    if (!map || step > 0xFFFFFFFFull) return GSGD_ERR_INVALID_ARG;
+    return GSGD_OK;
+}
+}  // namespace
+
+extern "C" int gsgd_step_gossip_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
+                                      const int32_t* peer_perm, float beta, uint64_t step, void* stream)
+{
+    int rc = check_fused(ctx, x, v, h, xstar, peer_perm, step);
     if (rc != GSGD_OK) return rc;
-    const hipError_t e = launch_step_gossip_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, x, v, h, xstar,
-                                                  ctx->cfg.sigma, key_of(ctx), static_cast<uint32_t>(step),
-                                                  ctx->cfg.noise_kind, persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED),
+    if (!(beta == beta)) return GSGD_ERR_INVALID_ARG;
+    Walk walk;
+    rc = build_walk(peer_perm, ctx->cfg.k, &walk);
+    if (rc != GSGD_OK) return rc;
+    const hipError_t e = launch_step_gossip_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, false, false,
+                                                  x, v, h, xstar, ctx->cfg.sigma, key_of(ctx),
+                                                  static_cast<uint32_t>(step), ctx->cfg.noise_kind,
+                                                  persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED),
                                                   static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_step_gossip_pull_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
+                                           const int32_t* peer, float beta, int stale, uint64_t step, void* stream)
+{
+    int rc = check_fused(ctx, x, v, h, xstar, peer, step);
+    if (rc != GSGD_OK) return rc;
+    if (!(beta == beta) || (stale != 0 && stale != 1)) return GSGD_ERR_INVALID_ARG;
+    Walk walk;
+    int has_trees = 0, slots = 0;
+    rc = build_pull_walk(peer, ctx->cfg.k, &walk, &has_trees, &slots);
+    if (rc != GSGD_OK) return rc;
+    const hipError_t e = launch_step_gossip_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale != 0,
+                                                  has_trees != 0, x, v, h, xstar, ctx->cfg.sigma, key_of(ctx),
+                                                  static_cast<uint32_t>(step), ctx->cfg.noise_kind,
+                                                  persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED),
+                                                  static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_step_gossip_push_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
+                                           const int32_t* target, uint64_t step, void* stream)
+{
+    int rc = check_fused(ctx, x, v, h, xstar, target, step);
+    if (rc != GSGD_OK) return rc;
+    Walk walk;
+    int slots = 0;
+    rc = build_push_walk(target, ctx->cfg.k, &walk, &slots);
+    if (rc != GSGD_OK) return rc;
+    const hipError_t e = launch_step_gossip_push_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), walk, x, v, h, xstar,
+                                                       ctx->cfg.sigma, key_of(ctx), static_cast<uint32_t>(step),
+                                                       ctx->cfg.noise_kind, persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED),
+                                                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 

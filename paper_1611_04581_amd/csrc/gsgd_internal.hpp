@@ -108,9 +108,12 @@ hipError_t launch_easgd_tick(const Geom&, const Hyper&, const SegTable&, float a
                              float* x, float* v, const float* g, float* center, hipStream_t);
 hipError_t launch_step_local(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
                              Persist, hipStream_t);
-hipError_t launch_step_gossip_fused(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&,
-                                    float* x, float* v, const float* h, const float* xstar,
+hipError_t launch_step_gossip_fused(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&, bool stale,
+                                    bool has_trees, float* x, float* v, const float* h, const float* xstar,
                                     float sigma, RngKey key, uint32_t step, int noise_kind, Persist, hipStream_t);
+hipError_t launch_step_gossip_push_fused(const Geom&, const Hyper&, const SegTable&, const Walk&,
+                                         float* x, float* v, const float* h, const float* xstar,
+                                         float sigma, RngKey key, uint32_t step, int noise_kind, Persist, hipStream_t);
 hipError_t launch_step_allreduce(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
                                  Persist, hipStream_t);
 hipError_t launch_step_easgd(const Geom&, const Hyper&, const SegTable&, float alpha_e,

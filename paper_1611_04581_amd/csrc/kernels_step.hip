@@ -169,14 +169,22 @@ __device__ __forceinline__ f32x4 average(f64x4 sum, uint32_t count)
                  static_cast<float>(sum.z / c), static_cast<float>(sum.w / c)};
 }
 
-template <bool FULL, int U, bool EXT>
+template <bool FULL, int U, bool EXT, bool FUSED_GEN, int NOISE>
 __device__ __forceinline__
 void push_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
                     const Walk& walk, SumStack* stack,
-                    float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g)
+                    float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                    const float* __restrict__ h, const float* __restrict__ xstar,
+                    float sigma, RngKey key, uint32_t step)
 {
     const int valid = FULL ? 4 : qd.valid;
     const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
+    f32x4 h4 = {0.f, 0.f, 0.f, 0.f}, xs4 = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (FUSED_GEN) {
+        h4 = load_quad_cached<FULL>(h + qd.col, valid);
+        xs4 = load_quad_cached<FULL>(xstar + qd.col, valid);
+    }
+    const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
 
     f64x4 acc = {0.0, 0.0, 0.0, 0.0}, first_sum = {0.0, 0.0, 0.0, 0.0};
     f32x4 prev = {0.f, 0.f, 0.f, 0.f};
@@ -193,13 +201,20 @@ void push_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const
             const int64_t off = static_cast<int64_t>(w[u] & WALK_ROW_MASK) * geo.ld + qd.tile_col;
             X[u] = load_quad<FULL>(x + off + qd.lane_col, valid);
             V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
-            G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
+            if constexpr (!FUSED_GEN) G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
         }
 #pragma unroll
         for (int u = 0; u < N; ++u) {
-            const int64_t off = static_cast<int64_t>(w[u] & WALK_ROW_MASK) * geo.ld + qd.tile_col;
+            const uint32_t row = w[u] & WALK_ROW_MASK;
+            const int64_t off = static_cast<int64_t>(row) * geo.ld + qd.tile_col;
             const uint32_t count = w[u] >> PUSH_COUNT_SHIFT;
             const uint32_t slot = (w[u] & PUSH_SLOT_MASK) >> PUSH_SLOT_SHIFT;
+            if constexpr (FUSED_GEN) {
+                const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, row, step, STREAM_GRAD, key.k0, key.k1));
+                const f32x4 t1 = X[u] - xs4;
+                const f32x4 t2 = sigma * xi;
+                G[u] = fma4(h4, t1, t2);
+            }
             f32x4 vn, post;
             local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, post);
             store_quad<FULL>(v + off + qd.lane_col, vn, valid);
@@ -232,19 +247,24 @@ void push_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const
     });
 }
 
-template <int U, bool EXT>
+template <int U, bool EXT, bool FUSED_GEN = false, int NOISE = 0>
 __global__ __launch_bounds__(BLOCK)
 void push_step_kernel(Geom geo, Hyper hp, SegTable seg, Walk walk,
                       float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
-                      uint32_t* __restrict__ tickets, uint32_t n_tiles)
+                      const float* __restrict__ h, const float* __restrict__ xstar,
+                      float sigma, RngKey key, uint32_t step, uint32_t* __restrict__ tickets, uint32_t n_tiles)
 {
     __shared__ SegLds lds;
     __shared__ SumStack stack;
     stage_segments(seg, lds);
     for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
         const Quad qd = quad_of_tile(tile, geo.d);
-        if (tile_is_full(qd, geo.d)) push_step_body<true, U, EXT>(geo, hp, seg, lds, qd, walk, &stack, x, v, g);
-        else if (qd.valid > 0) push_step_body<false, U, EXT>(geo, hp, seg, lds, qd, walk, &stack, x, v, g);
+        if (tile_is_full(qd, geo.d))
+            push_step_body<true, U, EXT, FUSED_GEN, NOISE>(geo, hp, seg, lds, qd, walk, &stack, x, v, g, h, xstar, sigma,
+                                                           key, step);
+        else if (qd.valid > 0)
+            push_step_body<false, U, EXT, FUSED_GEN, NOISE>(geo, hp, seg, lds, qd, walk, &stack, x, v, g, h, xstar, sigma,
+                                                            key, step);
     });
 }
 
@@ -487,10 +507,28 @@ hipError_t launch_step_gossip(const Geom& geo, const Hyper& hp, const SegTable& 
 hipError_t launch_step_gossip_push(const Geom& geo, const Hyper& hp, const SegTable& seg, const Walk& walk,
                                    float* x, float* v, const float* g, Persist p, hipStream_t stream)
 {
+    const RngKey no_key{0u, 0u};
     if (hp.extended())
-        GSGD_LAUNCH((push_step_kernel<WALK_RIF, true>), geo, hp, seg, walk, x, v, g, p.tickets, grid_for(geo.d));
+        GSGD_LAUNCH((push_step_kernel<WALK_RIF, true>), geo, hp, seg, walk, x, v, g, nullptr, nullptr, 0.0f, no_key, 0u,
+                    p.tickets, grid_for(geo.d));
     else
-        GSGD_LAUNCH((push_step_kernel<WALK_RIF, false>), geo, hp, seg, walk, x, v, g, p.tickets, grid_for(geo.d));
+        GSGD_LAUNCH((push_step_kernel<WALK_RIF, false>), geo, hp, seg, walk, x, v, g, nullptr, nullptr, 0.0f, no_key,
+                    0u, p.tickets, grid_for(geo.d));
+    return hipGetLastError();
+}
+
+// Generator-fused push-gossip (the extended local step covers the plain one: weight decay 0, heavy ball).
+hipError_t launch_step_gossip_push_fused(const Geom& geo, const Hyper& hp, const SegTable& seg, const Walk& walk,
+                                         float* x, float* v, const float* h, const float* xstar,
+                                         float sigma, RngKey key, uint32_t step, int noise_kind, Persist p,
+                                         hipStream_t stream)
+{
+    if (noise_kind == GSGD_NOISE_UNIFORM)
+        GSGD_LAUNCH((push_step_kernel<WALK_RIF, true, true, GSGD_NOISE_UNIFORM>), geo, hp, seg, walk, x, v, nullptr, h,
+                    xstar, sigma, key, step, p.tickets, grid_for(geo.d));
+    else
+        GSGD_LAUNCH((push_step_kernel<WALK_RIF, true, true, GSGD_NOISE_GAUSSIAN>), geo, hp, seg, walk, x, v, nullptr, h,
+                    xstar, sigma, key, step, p.tickets, grid_for(geo.d));
     return hipGetLastError();
 }
 
@@ -507,12 +545,28 @@ hipError_t launch_step_local(const Geom& geo, const Hyper& hp, const SegTable& s
 }
 
 hipError_t launch_step_gossip_fused(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta,
-                                    const Walk& walk, float* x, float* v, const float* h, const float* xstar,
-                                    float sigma, RngKey key, uint32_t step, int noise_kind, Persist p,
-                                    hipStream_t stream)
+                                    const Walk& walk, bool stale, bool has_trees, float* x, float* v, const float* h,
+                                    const float* xstar, float sigma, RngKey key, uint32_t step, int noise_kind,
+                                    Persist p, hipStream_t stream)
 {
     const uint32_t tiles = grid_for(geo.d);
     const bool uniform = noise_kind == GSGD_NOISE_UNIFORM;
+#define GSGD_FUSED(NOISE, STALE, TREE) \
+    GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, true, NOISE, true, STALE, TREE>), geo, hp, seg, -beta, walk, x, v, nullptr, \
+                h, xstar, sigma, key, step, p.tickets, tiles)
+    if (stale || has_trees) {                 // the extended local step covers the plain one here
+        if (uniform) {
+            if (stale && has_trees) GSGD_FUSED(GSGD_NOISE_UNIFORM, true, true);
+            else if (stale) GSGD_FUSED(GSGD_NOISE_UNIFORM, true, false);
+            else GSGD_FUSED(GSGD_NOISE_UNIFORM, false, true);
+        } else {
+            if (stale && has_trees) GSGD_FUSED(GSGD_NOISE_GAUSSIAN, true, true);
+            else if (stale) GSGD_FUSED(GSGD_NOISE_GAUSSIAN, true, false);
+            else GSGD_FUSED(GSGD_NOISE_GAUSSIAN, false, true);
+        }
+        return hipGetLastError();
+    }
+#undef GSGD_FUSED
     if (hp.extended()) {
         if (uniform)
             GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, true, GSGD_NOISE_UNIFORM, true>), geo, hp, seg, -beta, walk, x, v,

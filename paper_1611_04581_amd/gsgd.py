@@ -73,6 +73,9 @@ SIGNATURES = {
     "gsgd_step_gossip": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, _vp]),
     "gsgd_step_easgd": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.c_float, _vp]),
     "gsgd_step_gossip_fused": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, C.c_uint64, _vp]),
+    "gsgd_step_gossip_pull_fused": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, C.c_int,
+                                              C.c_uint64, _vp]),
+    "gsgd_step_gossip_push_fused": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_uint64, _vp]),
     "gsgd_philox_raw": (C.c_int, [_vp, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int64, _vp, _vp]),
     "gsgd_make_perm": (C.c_int, [C.c_uint64, C.c_uint64, C.c_int32, C.POINTER(C.c_int32)]),
     "gsgd_perm_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint16)]),
@@ -243,6 +246,17 @@ class Context:
         keep, p = _perm_arg(peer_perm)
         _check(lib().gsgd_step_gossip_fused(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), p, float(beta),
                                             int(step), _stream(stream)), "gsgd_step_gossip_fused")
+
+    def step_gossip_pull_fused(self, x, v, h, xstar, peer, step, beta=0.5, stale=False, stream=None):
+        keep, p = _perm_arg(peer)
+        _check(lib().gsgd_step_gossip_pull_fused(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), p, float(beta),
+                                                 int(bool(stale)), int(step), _stream(stream)),
+               "gsgd_step_gossip_pull_fused")
+
+    def step_gossip_push_fused(self, x, v, h, xstar, target, step, stream=None):
+        keep, p = _perm_arg(target)
+        _check(lib().gsgd_step_gossip_push_fused(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), p, int(step),
+                                                 _stream(stream)), "gsgd_step_gossip_push_fused")
 
     def philox_raw(self, c1, c2, c3, n_blocks, out, stream=None):
         _check(lib().gsgd_philox_raw(self._h, int(c1), int(c2), int(c3), int(n_blocks), _ptr(out), _stream(stream)),

@@ -525,3 +525,47 @@ def test_diffusion_potential_along_pure_gossip_rounds(G, oracle, kind):
         assert last < 0.3 * phi0
         # the device rows are the weighted averages the weights say they are
         assert np.allclose(host(x)[:, :d], Vo @ theta0, rtol=0, atol=1e-5)
+
+
+# ----------------------------------------------------------------------------
+# generator-fused forms of pull- and push-gossip
+
+@pytest.mark.parametrize("kind", [1, 0])
+def test_fused_generator_pull_and_push(G, oracle, kind):
+    """g never touches memory: the fused calls must equal gen_grad followed by
+    the step call, and the oracle."""
+    k, d = 12, 4 * 1024 + 6
+    ld = W.round_up(d, 4)
+    inp = W.make_inputs(k, d, ld, seed=91)
+    peer = [int(t) for t in oracle.make_targets(SEED, 4, k)]
+    perm = [int(t) for t in oracle.make_perm(SEED, 4, k)]
+    target = [int(t) for t in oracle.make_targets(SEED, 5, k, True)]
+    with G.Context(k, d, ld, sigma=0.2, seed=SEED, noise_kind=kind) as ctx:
+        h, xs = dev(inp.h), dev(inp.xstar)
+        for wd, nest in ((0.0, False), (1e-4, True)):
+            ctx.set_local_step(wd, nest)
+            for name, the_map, stale in (("pull", peer, False), ("pull", peer, True), ("pull", perm, True),
+                                         ("push", target, False)):
+                xa, va, g = dev(inp.x), dev(inp.v), dev(inp.g)
+                xb, vb = dev(inp.x), dev(inp.v)
+                xo, vo, go = inp.x.copy(), inp.v.copy(), inp.g.copy()
+                ctx.gen_grad(xa, h, xs, g, 23)
+                oracle.gen_grad(xo, inp.h, inp.xstar, go, 0.2, SEED, 23, kind, n=d)
+                if name == "pull":
+                    ctx.step_gossip_pull(xa, va, g, the_map, 0.5, stale)
+                    ctx.step_gossip_pull_fused(xb, vb, h, xs, the_map, 23, 0.5, stale)
+                    oracle.step_gossip_ext(xo, vo, go, 0.05, 0.9, 0.5, the_map, wd=wd, nesterov=nest, stale=stale, n=d)
+                else:
+                    ctx.step_gossip_push(xa, va, g, the_map)
+                    ctx.step_gossip_push_fused(xb, vb, h, xs, the_map, 23)
+                    oracle.step_gossip_push(xo, vo, go, 0.05, 0.9, the_map, wd=wd, nesterov=nest, n=d)
+                assert_bitwise(host(xb), host(xa), "%s stale=%s: fused vs two kernels, x" % (name, stale))
+                assert_bitwise(host(vb), host(va), "fused vs two kernels, v")
+                if kind == 1 and name == "pull":
+                    assert_bitwise(host(xb), xo, "x against the oracle")
+                else:
+                    assert_rows_close(host(xb)[:, :d], xo[:, :d], "x against the oracle")
+        with pytest.raises(G.GsgdError):
+            ctx.step_gossip_pull_fused(xb, vb, h, xs, [k] * k, 0)
+        with pytest.raises(G.GsgdError):
+            ctx.step_gossip_push_fused(xb, vb, h, xs, target, 2**32)
