@@ -569,3 +569,32 @@ def test_fused_generator_pull_and_push(G, oracle, kind):
             ctx.step_gossip_pull_fused(xb, vb, h, xs, [k] * k, 0)
         with pytest.raises(G.GsgdError):
             ctx.step_gossip_push_fused(xb, vb, h, xs, target, 2**32)
+
+
+@pytest.mark.parametrize("width", [1, 5, 100000])
+def test_map_walks_with_segments_and_any_launch_width(G, oracle, width):
+    """Tree walk (pull), senders-first walk (push) and the stale rule with
+    per-layer step sizes, for launch widths below and above the tile count."""
+    k, d = 9, 6 * 1024 + 3
+    ld = W.round_up(d, 4)
+    off, sc = W.random_segments(d, 29, seed=6, align=1)
+    lrc = oracle.expand_lr(0.05, d, off, sc)
+    inp = W.make_inputs(k, d, ld, seed=92)
+    peer = [int(t) for t in oracle.make_targets(SEED, 8, k)]
+    target = [int(t) for t in oracle.make_targets(SEED, 9, k, True)]
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, seg_offsets=off, seg_lr_scale=sc) as ctx:
+        for kern in (G.KERNEL_GOSSIP, G.KERNEL_GOSSIP_FUSED):
+            ctx.set_launch_width(kern, width)
+        x, v, g = dev(inp.x), dev(inp.v), dev(inp.g)
+        xo, vo = inp.x.copy(), inp.v.copy()
+        for rep in range(2):
+            ctx.step_gossip_pull(x, v, g, peer, 0.5)
+            ctx.step_gossip_pull(x, v, g, peer, 0.25, True)
+            oracle.step_gossip(xo, vo, inp.g, lrc, 0.9, 0.5, peer, n=d)
+            oracle.step_gossip_ext(xo, vo, inp.g, lrc, 0.9, 0.25, peer, stale=True, n=d)
+        assert_bitwise(host(x), xo, "pull x")
+        assert_bitwise(host(v), vo, "pull v")
+        ctx.step_gossip_push(x, v, g, target)
+        oracle.step_gossip_push(xo, vo, inp.g, lrc, 0.9, target, n=d)
+        assert_rows_close(host(x)[:, :d], xo[:, :d], "push x")
+        assert_bitwise(host(v), vo, "push v")
