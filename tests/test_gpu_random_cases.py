@@ -1,0 +1,76 @@
+"""Seeded random cases through every step rule: odd replica counts (so the
+row batches have leftovers), row lengths that end inside a quad and inside a
+tile, padded strides, random peer / target maps, random segment tables, random
+hyper-parameters.  Bit-exact bar (tolerance for push-gossip's fp64 sums)."""
+import numpy as np
+import pytest
+
+from paper_1611_04581_amd import workloads as W
+from parity_util import assert_bitwise, assert_rows_close
+
+pytestmark = pytest.mark.gpu
+
+SEED = 0x161104581
+
+
+@pytest.mark.parametrize("case", range(36))
+def test_random_case(oracle, case):
+    import torch
+    from paper_1611_04581_amd import gsgd as G
+    rng = np.random.default_rng(1000 + case)
+    k = int(rng.choice([1, 2, 3, 5, 7, 10, 13, 17, 31, 33, 64, 65]))
+    d = int(rng.choice([1, 2, 3, 5, 1021, 1024, 1025, 2047, 4099, 7001]))
+    ld = W.round_up(d, 4) + 4 * int(rng.integers(0, 3))
+    lr = float(rng.choice([0.01, 0.05, 0.3]))
+    mu = float(rng.choice([0.0, 0.5, 0.9]))
+    wd = float(rng.choice([0.0, 0.0, 1e-4, 0.01]))
+    nest = bool(rng.integers(0, 2)) and mu > 0
+    beta = float(rng.choice([0.5, 0.25, 0.7]))
+    seg = {}
+    lrc = lr
+    if rng.integers(0, 2) and d >= 8:
+        n_seg = int(rng.integers(1, min(d // 2, 40) + 1))
+        off, sc = W.random_segments(d, n_seg, seed=case, align=int(rng.choice([1, 4])))
+        seg = dict(seg_offsets=off, seg_lr_scale=sc)
+        lrc = oracle.expand_lr(lr, d, off, sc)
+    inp = W.make_inputs(k, d, ld, seed=2000 + case)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    host = lambda t: t.cpu().numpy()
+    perm = [int(t) for t in rng.permutation(k)]
+    peer = [int(t) for t in rng.integers(0, k, size=k)]
+    target = [int(t) for t in rng.integers(0, k, size=k)]
+    i, j = int(rng.integers(0, k)), int(rng.integers(0, k))
+    alpha_e = 0.9 / k
+    with G.Context(k, d, ld, lr=lr, momentum=mu, **seg) as ctx:
+        ctx.set_local_step(wd, nest)
+        x, v, g, c = dev(inp.x), dev(inp.v), dev(inp.g), dev(inp.center)
+        xo, vo, co = inp.x.copy(), inp.v.copy(), inp.center.copy()
+        # a chain of different calls on the same state, so that every kernel also sees the others' output
+        ctx.step_gossip(x, v, g, perm, beta)
+        oracle.step_gossip_ext(xo, vo, inp.g, lrc, mu, beta, perm, wd=wd, nesterov=nest, n=d)
+        ctx.step_gossip_pull(x, v, g, peer, beta)
+        oracle.step_gossip_ext(xo, vo, inp.g, lrc, mu, beta, peer, wd=wd, nesterov=nest, n=d)
+        ctx.step_gossip_pull(x, v, g, peer, beta, True)
+        oracle.step_gossip_ext(xo, vo, inp.g, lrc, mu, beta, peer, wd=wd, nesterov=nest, stale=True, n=d)
+        ctx.step_gossip_stale(x, v, g, perm, beta)
+        oracle.step_gossip_ext(xo, vo, inp.g, lrc, mu, beta, perm, wd=wd, nesterov=nest, stale=True, n=d)
+        ctx.step_local(x, v, g)
+        oracle.step_gossip_ext(xo, vo, inp.g, lrc, mu, 0.0, list(range(k)), wd=wd, nesterov=nest, n=d)
+        ctx.step_async_tick(x, v, g, i, j, beta)
+        oracle.async_tick(xo, vo, inp.g[i].copy(), lrc, mu, beta, i, j, wd=wd, nesterov=nest, n=d)
+        ctx.step_easgd_tick(x, v, g, c, j, alpha_e)
+        oracle.easgd_tick(xo, vo, inp.g[j].copy(), co, lrc, mu, alpha_e, j, wd=wd, nesterov=nest, n=d)
+        ctx.step_easgd(x, v, g, c, alpha_e)
+        oracle.step_easgd_ext(xo, vo, inp.g, co, lrc, mu, alpha_e, wd=wd, nesterov=nest, n=d)
+        ctx.step_allreduce(x, v, g)
+        oracle.step_allreduce_ext(xo, vo, inp.g, lrc, mu, wd=wd, nesterov=nest, n=d)
+        assert_bitwise(host(x), xo, "x (k=%d d=%d ld=%d)" % (k, d, ld))
+        assert_bitwise(host(v), vo, "v")
+        assert_bitwise(host(c), co, "center")
+        ctx.step_gossip_push(x, v, g, target)
+        oracle.step_gossip_push(xo, vo, inp.g, lrc, mu, target, wd=wd, nesterov=nest, n=d)
+        assert_rows_close(host(x)[:, :d], xo[:, :d], "push x")
+        assert_bitwise(host(x)[:, d:], xo[:, d:], "padding")
+        assert_bitwise(host(v), vo, "push v")
+        assert np.allclose(ctx.stats(x, dev(inp.xstar)), oracle.stats(host(x), inp.xstar, n=d), rtol=1e-10, atol=1e-300)
+        assert np.allclose(ctx.row_sqnorms(x), (host(x)[:, :d].astype(np.float64) ** 2).sum(1), rtol=1e-12, atol=0)
