@@ -315,7 +315,7 @@ def _run_both(G, oracle, cfg, d, steps, kind, layout=None, mode=0, sigma=None):
 
 
 def test_tiny_config_full_trajectory(G, oracle):
-    """BASELINE config 'tiny': k=4, d=65,536, sigma=0.01, 100 gossip steps."""
+    """The 'tiny' benchmark configuration: k=4, d=65,536, sigma=0.01, 100 gossip steps."""
     cfg = W.CONFIGS["tiny"]
     x, v, c, xo, vo, co, st, inp = _run_both(G, oracle, cfg, cfg.d, cfg.steps, G.NOISE_UNIFORM)
     assert_bitwise(x, xo, "x (uniform noise: whole trajectory bit-exact)")
