@@ -24,13 +24,33 @@ def hipcc() -> str:
     return exe
 
 
+DEMO_SRC = os.path.join(HERE, "examples", "abi_demo.c")
+DEMO = os.path.join(HERE, "abi_demo")
+
+
 def build(verbose: bool = False, extra_flags=()) -> str:
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
     cmd = [hipcc(), *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-shared", *srcs, "-o", LIB]
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
+    build_demo(verbose)
     return LIB
+
+
+def build_demo(verbose: bool = False) -> str:
+    """The plain-C user of the ABI (no Python, no PyTorch): host code only, linked against libgsgd.so."""
+    rocm = os.path.dirname(os.path.dirname(os.path.realpath(hipcc())))
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if not cc:
+        raise RuntimeError("no C compiler for the ABI demo")
+    cmd = [cc, "-std=c99", "-O2", "-Wall", DEMO_SRC, "-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(rocm, "include"), "-L", HERE, "-L", os.path.join(rocm, "lib"), "-lgsgd", "-lamdhip64",
+           "-lm", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", DEMO]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return DEMO
 
 
 if __name__ == "__main__":
