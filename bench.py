@@ -47,8 +47,8 @@ def log(*a):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", default="gossip_r50")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle baseline (0 = skip)")
     ap.add_argument("--no-extras", action="store_true", help="time only the metric kernel")
@@ -168,7 +168,7 @@ def main():
 
     # ---- context: generator and full simulated iteration --------------------------------
     if not args.no_extras:
-        n2 = max(10, K // 4)
+        n2 = min(100, max(10, K // 4))
         t_next = Wm + K
         w_gen, e_gen = timed(lambda t: ctx.gen_grad(x, h, xstar, g, t), n2, t_next)
 
