@@ -37,7 +37,8 @@ MEASURED_TRAFFIC_BYTES = {
 
 KERNEL_OF_RULE = {"gossip": "gossip_step_kernel", "gossip_stale": "gossip_step_kernel (stale)",
                   "gossip_pull": "gossip_step_kernel (tree walk)", "gossip_push": "push_step_kernel",
-                  "allreduce": "allreduce_step_kernel", "easgd": "easgd_step_kernel"}
+                  "allreduce": "allreduce_step_kernel", "easgd": "easgd_step_kernel",
+                  "async_tick": "async_tick_kernel (generator fused, one launch per tick)"}
 
 
 def log(*a):
@@ -119,6 +120,8 @@ def main():
             ctx.step_gossip_push(x, v, g, gsgd.make_targets(cfg.seed, t, k, True))
         elif rule == "local":
             ctx.step_local(x, v, g)
+        elif rule == "async_tick":                      # k ticks of the one-node-per-tick model = k replica-steps
+            ctx.run_async_ticks(x, v, h, xstar, t * k, k, cfg.beta)
         elif rule == "allreduce":
             ctx.step_allreduce(x, v, g)
         else:
@@ -146,6 +149,11 @@ def main():
     bpe = BYTES_PER_REPLICA_ELEMENT.get(cfg.rule, 20.0) + (8.0 / k if cfg.rule == "easgd" else 0.0)
     alg_bytes = bpe * k * d
     kern_s = ev / K                                  # one kernel per step in the timed region
+    if cfg.rule == "async_tick":
+        # per tick and element of the ticking row: x_i, v_i, h, xstar and the peer's x read (the peer's only when
+        # j != i, probability 1 - 1/k), x_i and v_i written; k launches per step
+        alg_bytes = (28.0 - 4.0 / k) * d
+        kern_s = ev / (K * k)
     achieved = alg_bytes / kern_s / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get(cfg.name)
     log("step: %.3f ms wall, %.3f ms by HIP events -> %.0f replica-steps/s, %.0f GB/s algorithmic (%.1f%% of peak)"
@@ -226,6 +234,11 @@ def main():
             elif cfg.rule == "gossip_push":
                 oracle.step_gossip_push(inp.x, inp.v, inp.g, lrc, cfg.momentum, oracle.make_targets(cfg.seed, t, k, True),
                                         wd=cfg.weight_decay, nesterov=cfg.nesterov)
+            elif cfg.rule == "async_tick":
+                for tick in range(t * k, (t + 1) * k):
+                    i, j = oracle.make_tick(cfg.seed, tick, k)
+                    oracle.gen_grad_row(inp.x, inp.h, inp.xstar, inp.g[0], i, cfg.sigma, cfg.seed, tick)
+                    oracle.async_tick(inp.x, inp.v, inp.g[0], lrc, cfg.momentum, cfg.beta, i, j)
             elif cfg.rule == "allreduce":
                 oracle.step_allreduce(inp.x, inp.v, inp.g, lrc, cfg.momentum)
             else:
