@@ -250,12 +250,22 @@ def main():
             n_cpu += 1
         cpu_wall = time.perf_counter() - t0
         cpu_value = k * n_cpu / cpu_wall * (ds / d)      # scaled to full-length rows
+        cores = oracle.num_threads()
+        # the same oracle on one thread, a quarter of the budget
+        oracle.set_num_threads(1)
+        n_one, t1 = 0, time.perf_counter()
+        while time.perf_counter() - t1 < args.cpu_seconds / 4 or n_one == 0:
+            ostep(n_cpu + n_one + 1)
+            n_one += 1
+        one_wall = time.perf_counter() - t1
+        oracle.set_num_threads(cores)
         out["cpu_baseline"] = {
-            "value": cpu_value, "unit": "replica-steps/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "value": cpu_value, "unit": "replica-steps/s", "cores": cores, "kind": "oracle",
+            "one_thread_value": k * n_one / one_wall * (ds / d),
             "sample": "%d %s steps of the C oracle on the first %d of %d columns of all %d replicas (%.1f s); "
                       "rate scaled by %d/%d to full-length rows" % (n_cpu, cfg.rule, ds, d, k, cpu_wall, ds, d),
         }
-        log("cpu oracle: %.2f replica-steps/s on %d threads" % (cpu_value, oracle.num_threads()))
+        log("cpu oracle: %.2f replica-steps/s on %d threads, %.2f on one" % (cpu_value, cores, k * n_one / one_wall * (ds / d)))
 
     ctx.close()
     print(json.dumps(out), flush=True)

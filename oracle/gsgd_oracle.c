@@ -604,6 +604,17 @@ void oracle_stats(const float* x, const float* xstar, int32_t k, int64_t n, int6
     out[0] = cons; out[1] = dist; out[2] = mdist; out[3] = mnorm;
 }
 
+/* Limit the threads of the parallel loops above (for the benchmark's one-thread figure); n < 1 is ignored. */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    extern void omp_set_num_threads(int);
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /* How many threads the parallel loops above use (for the benchmark's report). */
 int oracle_num_threads(void)
 {

@@ -84,6 +84,8 @@ def lib():
         L.oracle_make_perm.restype = C.c_int
         L.oracle_stats.argtypes = [_f32p, _f32p, C.c_int32, C.c_int64, C.c_int64, _f64p]
         L.oracle_stats.restype = None
+        L.oracle_set_num_threads.argtypes = [C.c_int]
+        L.oracle_set_num_threads.restype = None
         L.oracle_num_threads.argtypes = []
         L.oracle_num_threads.restype = C.c_int
         _lib = L
@@ -305,6 +307,10 @@ def stats(x, xstar, n=None):
 
 def num_threads():
     return int(lib().oracle_num_threads())
+
+
+def set_num_threads(n):
+    lib().oracle_set_num_threads(int(n))
 
 
 # ----------------------------------------------------------------------------
