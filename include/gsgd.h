@@ -141,7 +141,7 @@ int gsgd_gen_grad(gsgd_ctx* ctx, const float* x, const float* h, const float* xs
 int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const float* g, void* stream);
 
 /* Gossip step: local momentum step (the two lines shared by Algorithms 2-4)
- * followed by the pairwise mix of Section 3.1 / 6.2.2 ("fresh parameters"):
+ * followed by the pairwise mix of Section 3.1 / 6.2.2 (the mix of post-step parameters):
  *   v_i <- momentum * v_i - lr_s * g_i;   x'_i = x_i + v_i;
  *   x_i <- x'_i - beta * (x'_i - x'_{peer_perm[i]}).
  * peer_perm: host, k entries, a bijection on 0..k-1 (each node is pulled from
@@ -224,8 +224,8 @@ int gsgd_run_async_ticks(gsgd_ctx* ctx, float* x, float* v, const float* h, cons
  * tau of Algorithms 2-4 is larger than 1. */
 int gsgd_step_local(gsgd_ctx* ctx, float* x, float* v, const float* g, void* stream);
 
-/* Communication schedule of Algorithms 2-4 ("if t > 0 and t = 0 mod tau",
- * exchange at the top of iteration t).  The step calls here run the local step
+/* Communication schedule of Algorithms 2-4 (an exchange opens every iteration
+ * whose index is a positive multiple of the period tau).  The step calls here run the local step
  * first and the exchange after it, so the exchange of iteration t+1 is the
  * tail of step call t: returns 1 when step call number `step` (0-based) should
  * be an exchanging call, 0 when it should be gsgd_step_local, and
@@ -261,8 +261,8 @@ int gsgd_step_gossip_push_fused(gsgd_ctx* ctx, float* x, float* v, const float* 
 int gsgd_philox_raw(gsgd_ctx* ctx, uint32_t c1, uint32_t c2, uint32_t c3, int64_t n_blocks, uint32_t* out,
                     void* stream);
 
-/* Uniformly random peer permutation for one step ("choose a target j",
- * Algorithms 3-4, with every j used once): Fisher-Yates from the top, driven
+/* Uniformly random peer permutation for one step (the target choice of
+ * Algorithms 3-4, with every node chosen once): Fisher-Yates from the top, driven
  * by Philox stream 5 at counter (i, 0, step, 5), index floor(r (i+1) / 2^32).
  * Pure host code, deterministic.  out: host, k entries. */
 int gsgd_make_perm(uint64_t seed, uint64_t step, int32_t k, int32_t* out);
@@ -271,8 +271,8 @@ int gsgd_make_perm(uint64_t seed, uint64_t step, int32_t k, int32_t* out);
  * nodes): node i takes word 0 of Philox stream 5 at counter (i, 1, step, 5).
  *   exclude_self = 0: target floor(r k / 2^32), the node itself included
  *                     (pull-gossip; a self-target is a no-op mix);
- *   exclude_self = 1: a uniform draw among the k-1 other nodes (push-gossip's
- *                     "one other random node"), floor(r (k-1) / 2^32) stepped
+ *   exclude_self = 1: a uniform draw among the k-1 other nodes (push-gossip sends to
+ *                     a node other than itself), floor(r (k-1) / 2^32) stepped
  *                     over i; needs k >= 2.
  * Pure host code, deterministic.  out: host, k entries. */
 int gsgd_make_targets(uint64_t seed, uint64_t step, int32_t k, int exclude_self, int32_t* out);

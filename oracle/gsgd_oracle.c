@@ -93,7 +93,7 @@ float oracle_u01(uint32_t r)
 
 /* Four unit-variance zero-mean noise values from four words (the analysis
  * only asks for zero mean and bounded variance, Theorem 1 / Section 6.1;
- * "Gaussian noise, for example").
+ * Gaussian noise is the example it names).
  *   kind 0: Box-Muller in fp64 on (u0,u1) -> (z0,z1) and (u2,u3) -> (z2,z3),
  *           z_even = rho cos(2 pi u'), z_odd = rho sin(2 pi u'), rho = sqrt(-2 ln u)
  *   kind 1: sqrt(3) (2u - 1), all in fp32 with one rounding (2u-1 is exact)  */
@@ -229,7 +229,7 @@ static inline float momentum_update(float v, float g, float lr, float mu)
     return fmaf(-lr, g, t3);
 }
 
-/* Gossip step (Section 3.1, the "fresh parameters" update, Section 6.2.2):
+/* Gossip step (Section 3.1; the variant of Section 6.2.2 that mixes post-step parameters):
  *   theta'_i = local momentum step of replica i
  *   theta_{t+1,i} = theta'_i - beta (theta'_i - theta'_{peer[i]})
  * peer[] may be any map into 0..k-1 (a permutation is the case where pull-
@@ -453,8 +453,8 @@ int oracle_make_perm(uint64_t seed, uint32_t step, int32_t k, int32_t* out)
  * j ~ Uniform over the nodes): node i uses word 0 of Philox(counter
  * (i, 1, step, PERM), seed).  exclude_self = 0: j = floor(r k / 2^32), the node
  * itself included (pull-gossip).  exclude_self = 1: a uniform draw among the
- * k-1 other nodes, j = floor(r (k-1) / 2^32), stepped over i ("one other random
- * node", push-gossip); needs k >= 2.                                          */
+ * k-1 other nodes, j = floor(r (k-1) / 2^32), stepped over i (push-gossip sends to
+ * a node other than itself); needs k >= 2.                                          */
 int oracle_make_targets(uint64_t seed, uint32_t step, int32_t k, int exclude_self, int32_t* out)
 {
     if (k < 1 || (exclude_self && k < 2)) return -1;

@@ -1,5 +1,5 @@
-// Host-side peer selection: the per-step random permutation ("choose a target
-// j" of Algorithms 3 and 4 of the paper, with every target used once) and its
+// Host-side peer selection: the per-step random permutation (the target choice
+// of Algorithms 3 and 4 of the paper, with every node chosen once) and its
 // decomposition into cycles, which is the order the gossip kernel walks.
 #include <string.h>
 
@@ -56,8 +56,8 @@ int build_walk(const int32_t* perm, int32_t k, Walk* out)
     return t == k ? GSGD_OK : GSGD_ERR_BAD_PERM;
 }
 
-// Visiting order for an arbitrary pull map ("each node pulls from one uniformly
-// chosen node", Section 3.1).  The map is a functional graph: cycles with trees
+// Visiting order for an arbitrary pull map (every node pulling from one node
+// drawn uniformly, Section 3.1).  The map is a functional graph: cycles with trees
 // hanging off them.  Cycles are walked as for a permutation; right after a
 // cycle node, the trees of nodes that pull (directly or through others) from
 // it are visited depth-first, parents before children, so that a tree node's

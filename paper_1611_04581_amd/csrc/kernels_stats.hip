@@ -1,5 +1,5 @@
 // Diagnostics the paper's analysis is stated in (Section 6.1): the replicas'
-// distance to their mean ("agent consensus"), their distance to the optimum,
+// distance to their mean (the agents' consensus), their distance to the optimum,
 // and the mean's own distance.  Not part of the timed step.
 //
 // Per column the replica mean and the squared deviations are taken in fp64 in
