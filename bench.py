@@ -160,7 +160,7 @@ def main():
         % (ms_per_step, kern_s * 1e3, value, achieved, 100 * achieved / HBM_PEAK_GBS))
 
     out = {
-        "metric": "replica-steps/sec, gossip step, ResNet-50-size d, k=32" if cfg.name == "gossip_r50"
+        "metric": "replica-steps/sec + achieved HBM GB/s, gossip step, ResNet-50-size d, k=32" if cfg.name == "gossip_r50"
                   else "replica-steps/sec, %s step" % cfg.rule,
         "value": value, "unit": "replica-steps/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
