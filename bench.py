@@ -199,6 +199,12 @@ def main():
             extras["fused_iteration_ms"] = w_fu / n2 * 1e3
             extras["fused_iteration_replica_steps_per_s"] = k * n2 / w_fu
             extras["fused_iteration_GBps_algorithmic"] = (16.0 + 8.0 / k) * k * d / (e_fu / n2) / 1e9
+        # what this machine's memory delivers to a plain device-to-device copy of the same matrices (read 4 B, write 4 B per
+        # element), as context for the fractions above; g is regenerated by the next gen_grad
+        scratch = torch.empty_like(g)
+        w_cp, e_cp = timed(lambda t: scratch.copy_(g), 20, 0)
+        extras["plain_copy_GBps"] = 8.0 * k * ld / (e_cp / 20) / 1e9
+        del scratch
         if cfg.name == "gossip_r50":
             # the other gossip forms on the same resident state (same 20 B per replica-element)
             forms = {
