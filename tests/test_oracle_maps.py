@@ -372,6 +372,50 @@ def test_diffusion_potential_special_cases(oracle):
     assert abs(oracle.diffusion_potential(same, np.full((p, p), 1 / p))) < 1e-20
 
 
+def test_mixing_matrices_are_the_brute_forced_step_rules(oracle):
+    """Pin of oracle.mixing_matrix_pull / mixing_matrix_push: with no gradient
+    step (lr = 0, mu = 0, v = 0) a gossip round is theta' = M theta, so for
+    every one of the k^k maps (k <= 3) M @ theta0 on dyadic theta0 must equal,
+    exactly, what oracle.step_gossip / step_gossip_push return -- and those two
+    are themselves pinned by exact-rational brute force over all maps above.
+    A transposed M, a self-target counted twice or a wrong weight fails here.
+    Dyadic inputs keep every product with 1/2 exact in fp32 and fp64; thirds
+    (push with two senders) are compared through the correctly rounded
+    quotient of the exact rational."""
+    rng = np.random.default_rng(11)
+    for k in (1, 2, 3):
+        n = 5
+        theta0 = (rng.integers(-64, 64, size=(k, n)) / 8.0).astype(np.float32)
+        zeros = np.zeros((k, n), np.float32)
+        for m in product(range(k), repeat=k):
+            # pull: row i <- (1 - beta) theta_i + beta theta_m[i]
+            for beta in (0.5, 0.25, 1.0, 0.0):
+                x = theta0.copy()
+                oracle.step_gossip(x, zeros.copy(), zeros.copy(), 0.0, 0.0, beta, list(m))
+                M = oracle.mixing_matrix_pull(list(m), beta)
+                assert np.array_equal(M @ theta0.astype(np.float64), x.astype(np.float64)), (m, beta)
+                assert np.allclose(M.sum(1), 1.0, rtol=0, atol=0)
+            # push: row r <- average of theta_r and every theta_i (i != r) with m[i] == r
+            x = theta0.copy()
+            oracle.step_gossip_push(x, zeros.copy(), zeros.copy(), 0.0, 0.0, list(m))
+            M = oracle.mixing_matrix_push(list(m))
+            for r in range(k):
+                got = [r] + [i for i in range(k) if i != r and m[i] == r]
+                for j in range(n):
+                    exact = sum(Fraction(float(theta0[i, j])) for i in got) / len(got)
+                    assert Fraction(float(x[r, j])) == Fraction(float(np.float32(float(exact)))), (m, r, j)
+                    # M's row, applied in exact rationals, is that same average
+                    row = sum(Fraction(M[r, i]).limit_denominator(6) * Fraction(float(theta0[i, j])) for i in range(k))
+                    assert row == exact, (m, r, j)
+            assert np.allclose(M.sum(1), 1.0, rtol=0, atol=1e-15)
+    # orientation: in a pull round from the map (1, 1, 0), node 0 takes from node 1 and not the other way round
+    M = oracle.mixing_matrix_pull([1, 1, 0], 0.25)
+    assert M[0, 1] == 0.25 and M[1, 0] == 0.0 and M[1, 1] == 1.0 and M[2, 0] == 0.25 and M[2, 2] == 0.75
+    # push with targets (1, 1, 0): node 1 receives from 0 (its own target is itself), node 0 from 2, node 2 from nobody
+    M = oracle.mixing_matrix_push([1, 1, 0])
+    assert np.array_equal(M, np.array([[0.5, 0, 0.5], [0.5, 0.5, 0], [0, 0, 1.0]]))
+
+
 def test_weight_matrices_and_library_potential(oracle):
     """The library's host-side weight updates are the oracle's mixing matrices
     applied from the left, and its closed form of the potential (from row
