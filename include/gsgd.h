@@ -20,7 +20,9 @@
  *     vectors of at least d elements.
  *   - Every pointer named "device" is GPU memory owned by the caller, 16-byte
  *     aligned, valid until the stream has run the call.  The library never
- *     frees or reallocates caller memory.  x, v, g, center must not overlap.
+ *     frees or reallocates caller memory.  x, v, g, center must not overlap,
+ *     and h, xstar, x0 must not overlap anything a call writes: the address
+ *     ranges are compared, and an overlap is GSGD_ERR_INVALID_ARG.
  *   - Pointers named "host" are ordinary host memory, read (or written, for
  *     outputs) before the call returns.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -29,6 +31,12 @@
  *     (peer maps, step numbers and hyper-parameters are baked in as kernel
  *     arguments at record time).  gsgd_stats and gsgd_row_sqnorms wait for
  *     the stream and must stay outside a capture.
+ *   - One context may be used from several streams at once (at most 32 over
+ *     its lifetime; a 33rd gets GSGD_ERR_UNSUPPORTED): every stream hands out
+ *     tiles through a counter pair of its own.  A recorded graph keeps the
+ *     pair of the stream it was captured on, so it must not replay while
+ *     eager calls or another replay of the same context run on that stream's
+ *     pair from a different stream.
  *
  * Errors: every function returns GSGD_OK (0) or a negative code; nothing
  * throws, aborts or prints.  A gsgd_ctx is not thread-safe; distinct contexts
@@ -51,8 +59,9 @@ enum {
     GSGD_ERR_BAD_PERM     = -2,    /* peer entry outside 0..k-1, or peer_perm not a bijection where one is required */
     GSGD_ERR_BAD_SEGMENTS = -3,    /* segment table not ascending from 0 to d */
     GSGD_ERR_HIP          = -4,    /* a HIP runtime call failed; see gsgd_last_hip_error */
-    GSGD_ERR_UNSUPPORTED  = -5,
-    GSGD_ERR_NO_MEMORY    = -6
+    GSGD_ERR_UNSUPPORTED  = -5,    /* the context has launched on 32 distinct streams already */
+    GSGD_ERR_NO_MEMORY    = -6,
+    GSGD_ERR_BAD_STATE    = -7     /* a tile counter was found non-zero on a drained stream; see gsgd_stats */
 };
 
 enum { GSGD_NOISE_GAUSSIAN = 0, GSGD_NOISE_UNIFORM = 1 };
@@ -104,8 +113,7 @@ int gsgd_set_local_step(gsgd_ctx* ctx, float weight_decay, int nesterov);
  * workgroups that pull 1024-column tiles from a ticket counter owned by the
  * context; `workgroups` sets that number for one GSGD_KERNEL_*, 0 restores the
  * default (a small multiple of the device's compute-unit count).  Results do
- * not depend on it.  Because the ticket counter belongs to the context, a
- * context must not have calls in flight on two streams at once.  Host only. */
+ * not depend on it.  Host only. */
 int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups);
 
 /* Initialisation: first line of Algorithms 1-4 (every node starts at the same
@@ -151,9 +159,8 @@ int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const float* g, void*
 int gsgd_step_gossip(gsgd_ctx* ctx, float* x, float* v, const float* g,
                      const int32_t* peer_perm, float beta, void* stream);
 
-/* Gossip with stale parameters (Section 6.2.1, "gradient step and gossip at
- * the same time"): as gsgd_step_gossip, but the mixing term is the difference
- * of the parameters from before the local step,
+/* Gossip with stale parameters (Section 6.2.1): the mix uses both nodes'
+ * parameters from before the local step.  As gsgd_step_gossip, but
  *   x_i <- x'_i - beta * (x_i - x_{peer_perm[i]}). */
 int gsgd_step_gossip_stale(gsgd_ctx* ctx, float* x, float* v, const float* g,
                            const int32_t* peer_perm, float beta, void* stream);
@@ -311,7 +318,14 @@ int gsgd_perm_walk(const int32_t* peer_perm, int32_t k, uint16_t* walk);
  * distance, over columns 0..d-1, accumulated in fp64:
  *   out[0] = sum_i ||x_i - xbar||^2, out[1] = sum_i ||x_i - xstar||^2,
  *   out[2] = ||xbar - xstar||^2,     out[3] = ||xbar||^2.
- * Waits for the stream.  out: host. */
+ * Waits for the stream.  out: host.
+ * With the stream drained, the tile counter pair of that stream must read
+ * zero; if it does not (a launch was cut short, or launches on different
+ * streams were forced onto one pair by replaying a graph elsewhere), out is
+ * still filled, the pair is cleared so that later launches visit every tile
+ * again, and GSGD_ERR_BAD_STATE is returned: results of step calls since the
+ * last clean check on this stream are suspect.  gsgd_row_sqnorms checks the
+ * same way. */
 int gsgd_stats(gsgd_ctx* ctx, const float* x, const float* xstar, double out[4], void* stream);
 
 /* Squared Euclidean norm of every replica row over columns 0..d-1, in fp64:
@@ -334,6 +348,12 @@ int gsgd_weights_pull(double* V, int32_t k, const int32_t* peer, double beta);
 int gsgd_weights_push(double* V, int32_t k, const int32_t* target);
 int gsgd_diffusion_potential(const double* V, int32_t k, const double* sqnorm_start, const double* sqnorm_now,
                              double* out);
+
+/* Test hook: set the tile counter pair of `stream` to (next_tile, finished)
+ * once the stream has drained.  (0, 0) is the only state step calls may start
+ * from; anything else makes the next gsgd_stats on that stream report
+ * GSGD_ERR_BAD_STATE. */
+int gsgd_poke_tickets(gsgd_ctx* ctx, uint32_t next_tile, uint32_t finished, void* stream);
 
 const char* gsgd_strerror(int code);
 int gsgd_last_hip_error(const gsgd_ctx* ctx);   /* raw hipError_t of the last GSGD_ERR_HIP */

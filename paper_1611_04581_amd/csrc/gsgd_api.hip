@@ -7,6 +7,13 @@
 
 using namespace gsgd;
 
+// Launches on one stream run one after the other and can share a ticket pair;
+// launches on different streams may overlap and must not.  Every stream that
+// has launched through the context owns one pair, each on a cache line of its own.
+constexpr int    TICKET_PAIRS = 32;
+constexpr size_t TICKET_STRIDE_WORDS = 32;     // 128 bytes
+constexpr size_t TICKET_BYTES = TICKET_PAIRS * TICKET_STRIDE_WORDS * sizeof(uint32_t);
+
 struct gsgd_ctx {
     gsgd_config cfg;          // host pointers inside are cleared after copying
     int         device;
@@ -14,9 +21,11 @@ struct gsgd_ctx {
     float*      d_scales;
     double*     d_partials;   // stats scratch: stats_num_blocks(d) * 4 doubles
     double*     d_result;     // max(4, k) doubles
-    double*     h_result;     // pinned host, max(4, k) doubles
+    double*     h_result;     // pinned host, max(4, k) doubles, then one more that receives a ticket pair
     double*     d_norm_partials;   // row-norm scratch: k * NORM_CHUNKS doubles
-    uint32_t*   d_tickets;    // tile tickets of the persistent kernels (2 words, zero between launches)
+    uint32_t*   d_tickets;    // tile tickets of the persistent kernels: TICKET_PAIRS pairs, zero between launches
+    hipStream_t pair_stream[TICKET_PAIRS];   // which stream launches through which pair
+    int         n_pairs;
     int         cu_count;     // compute units of the device
     unsigned    width[GSGD_KERNEL_COUNT];   // persistent workgroups per streaming kernel
     float       weight_decay;               // extras of the local step (Section 4.2); 0 / 0 = the boxed algorithms
@@ -41,7 +50,24 @@ inline int hip_fail(gsgd_ctx* ctx, hipError_t e)
 inline Geom geom_of(const gsgd_ctx* c) { return Geom{c->cfg.k, c->cfg.d, c->cfg.ld}; }
 inline Hyper hyper_of(const gsgd_ctx* c) { return Hyper{c->cfg.lr, c->cfg.momentum, c->weight_decay, c->nesterov}; }
 inline SegTable seg_of(const gsgd_ctx* c) { return SegTable{c->d_offsets, c->d_scales, c->cfg.n_seg}; }
-inline Persist persist_of(const gsgd_ctx* c, int kernel) { return Persist{c->d_tickets, c->width[kernel]}; }
+// Index of the ticket pair of `stream`, claiming a free one on first use; -1 when all are taken.
+inline int pair_of(gsgd_ctx* c, hipStream_t stream)
+{
+    for (int p = 0; p < c->n_pairs; ++p)
+        if (c->pair_stream[p] == stream) return p;
+    if (c->n_pairs == TICKET_PAIRS) return -1;
+    c->pair_stream[c->n_pairs] = stream;
+    return c->n_pairs++;
+}
+inline uint32_t* pair_words(const gsgd_ctx* c, int pair) { return c->d_tickets + static_cast<size_t>(pair) * TICKET_STRIDE_WORDS; }
+
+// Launch shape of one streaming kernel on one stream; tickets == nullptr when the context has run on
+// TICKET_PAIRS other streams already.
+inline Persist persist_of(gsgd_ctx* c, int kernel, void* stream)
+{
+    const int pair = pair_of(c, static_cast<hipStream_t>(stream));
+    return Persist{pair < 0 ? nullptr : pair_words(c, pair), c->width[kernel]};
+}
 inline RngKey key_of(const gsgd_ctx* c)
 {
     return RngKey{static_cast<uint32_t>(c->cfg.seed), static_cast<uint32_t>(c->cfg.seed >> 32)};
@@ -50,12 +76,35 @@ inline RngKey key_of(const gsgd_ctx* c)
 // Row matrices must be non-null and 16-byte aligned (rows then are, since ld % 4 == 0).
 inline bool ok_matrix(const void* p) { return p && aligned16(p); }
 
+// Bytes from the first element of a k x ld row matrix to one past the last column any kernel touches,
+// and the same for a shared d-vector.
+inline size_t matrix_span(const gsgd_ctx* c)
+{
+    return sizeof(float) * (static_cast<size_t>(c->cfg.k - 1) * static_cast<size_t>(c->cfg.ld) + static_cast<size_t>(c->cfg.d));
+}
+inline size_t vector_span(const gsgd_ctx* c) { return sizeof(float) * static_cast<size_t>(c->cfg.d); }
+
+inline bool overlap(const void* a, size_t na, const void* b, size_t nb)
+{
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+// x, v, g: distinct, non-overlapping k x ld matrices.
 int check_state(const gsgd_ctx* ctx, const float* x, const float* v, const float* g)
 {
     if (!ctx) return GSGD_ERR_INVALID_ARG;
     if (!ok_matrix(x) || !ok_matrix(v) || !ok_matrix(g)) return GSGD_ERR_INVALID_ARG;
-    if (x == v || x == g || v == g) return GSGD_ERR_INVALID_ARG;
+    const size_t m = matrix_span(ctx);
+    if (overlap(x, m, v, m) || overlap(x, m, g, m) || overlap(v, m, g, m)) return GSGD_ERR_INVALID_ARG;
     return GSGD_OK;
+}
+
+// a shared d-vector (centre, h, xstar) against the matrices a call writes
+bool vector_clear_of(const gsgd_ctx* ctx, const float* vec, const float* a, const float* b, const float* c = nullptr)
+{
+    const size_t m = matrix_span(ctx), n = vector_span(ctx);
+    return !overlap(vec, n, a, m) && !overlap(vec, n, b, m) && !(c && overlap(vec, n, c, m));
 }
 
 void release(gsgd_ctx* c)
@@ -110,12 +159,14 @@ extern "C" int gsgd_create(const gsgd_config* cfg, gsgd_ctx** out)
     const size_t n_result = static_cast<size_t>(cfg->k > 4 ? cfg->k : 4);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_result), sizeof(double) * n_result);
     if (e == hipSuccess)
-        e = hipHostMalloc(reinterpret_cast<void**>(&c->h_result), sizeof(double) * n_result, hipHostMallocDefault);
+        e = hipHostMalloc(reinterpret_cast<void**>(&c->h_result), sizeof(double) * (n_result + 1), hipHostMallocDefault);
     if (e == hipSuccess)
         e = hipMalloc(reinterpret_cast<void**>(&c->d_norm_partials),
                       sizeof(double) * static_cast<size_t>(cfg->k) * NORM_CHUNKS);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_tickets), 256);
-    if (e == hipSuccess) e = hipMemset(c->d_tickets, 0, 256);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_tickets), TICKET_BYTES);
+    if (e == hipSuccess) e = hipMemset(c->d_tickets, 0, TICKET_BYTES);
+    // the clear runs on the null stream, which a non-blocking stream does not wait for
+    if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->cu_count, hipDeviceAttributeMultiprocessorCount, c->device);
     if (e == hipSuccess) {
         if (c->cu_count < 1) c->cu_count = 1;
@@ -170,10 +221,12 @@ extern "C" int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups)
 extern "C" int gsgd_init_replicas(gsgd_ctx* ctx, float* x, float* v, float* center, const float* x0, int mode,
                                   void* stream)
 {
-    if (!ctx || !ok_matrix(x) || !ok_matrix(v) || x == v) return GSGD_ERR_INVALID_ARG;
+    if (!ctx || !ok_matrix(x) || !ok_matrix(v) || overlap(x, matrix_span(ctx), v, matrix_span(ctx)))
+        return GSGD_ERR_INVALID_ARG;
     if (mode != GSGD_INIT_BROADCAST && mode != GSGD_INIT_PER_REPLICA) return GSGD_ERR_INVALID_ARG;
     if (mode == GSGD_INIT_BROADCAST && !ok_matrix(x0)) return GSGD_ERR_INVALID_ARG;
-    if (center && !aligned16(center)) return GSGD_ERR_INVALID_ARG;
+    if (center && (!aligned16(center) || !vector_clear_of(ctx, center, x, v))) return GSGD_ERR_INVALID_ARG;
+    if (mode == GSGD_INIT_BROADCAST && !vector_clear_of(ctx, x0, x, v)) return GSGD_ERR_INVALID_ARG;
     const hipError_t e = launch_init_replicas(geom_of(ctx), x, v, center, x0, mode, key_of(ctx),
                                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
@@ -190,12 +243,16 @@ extern "C" int gsgd_fill(gsgd_ctx* ctx, float* dst, int which, void* stream)
 extern "C" int gsgd_gen_grad(gsgd_ctx* ctx, const float* x, const float* h, const float* xstar, float* g,
                              uint64_t step, void* stream)
 {
-    if (!ctx || !ok_matrix(x) || !ok_matrix(g) || !ok_matrix(h) || !ok_matrix(xstar) || x == g)
+    if (!ctx || !ok_matrix(x) || !ok_matrix(g) || !ok_matrix(h) || !ok_matrix(xstar)) return GSGD_ERR_INVALID_ARG;
+    if (overlap(x, matrix_span(ctx), g, matrix_span(ctx)) || !vector_clear_of(ctx, h, g, g) ||
+        !vector_clear_of(ctx, xstar, g, g))
         return GSGD_ERR_INVALID_ARG;
     if (step > 0xFFFFFFFFull) return GSGD_ERR_INVALID_ARG;
+    const Persist ps = persist_of(ctx, GSGD_KERNEL_GEN_GRAD, stream);
+    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_gen_grad(geom_of(ctx), x, h, xstar, g, ctx->cfg.sigma, key_of(ctx),
                                          static_cast<uint32_t>(step), ctx->cfg.noise_kind,
-                                         persist_of(ctx, GSGD_KERNEL_GEN_GRAD), static_cast<hipStream_t>(stream));
+                                         ps, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -211,8 +268,10 @@ extern "C" int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const floa
 {
     const int rc = check_state(ctx, x, v, g);
     if (rc != GSGD_OK) return rc;
+    const Persist ps = persist_of(ctx, GSGD_KERNEL_ALLREDUCE, stream);
+    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_step_allreduce(geom_of(ctx), hyper_of(ctx), seg_of(ctx), x, v, g,
-                                               persist_of(ctx, GSGD_KERNEL_ALLREDUCE), static_cast<hipStream_t>(stream));
+                                               ps, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -226,8 +285,10 @@ int gossip_on_permutation(gsgd_ctx* ctx, float* x, float* v, const float* g, con
     Walk walk;
     rc = build_walk(peer_perm, ctx->cfg.k, &walk);
     if (rc != GSGD_OK) return rc;
+    const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP, stream);
+    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale, false, x, v, g,
-                                            persist_of(ctx, GSGD_KERNEL_GOSSIP), static_cast<hipStream_t>(stream));
+                                            ps, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 }  // namespace
@@ -242,8 +303,10 @@ extern "C" int gsgd_step_gossip_pull(gsgd_ctx* ctx, float* x, float* v, const fl
     int has_trees = 0, slots = 0;
     rc = build_pull_walk(peer, ctx->cfg.k, &walk, &has_trees, &slots);
     if (rc != GSGD_OK) return rc;
+    const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP, stream);
+    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale != 0,
-                                            has_trees != 0, x, v, g, persist_of(ctx, GSGD_KERNEL_GOSSIP),
+                                            has_trees != 0, x, v, g, ps,
                                             static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
@@ -270,8 +333,10 @@ extern "C" int gsgd_step_gossip_push(gsgd_ctx* ctx, float* x, float* v, const fl
     int slots = 0;
     rc = build_push_walk(target, ctx->cfg.k, &walk, &slots);
     if (rc != GSGD_OK) return rc;
+    const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP, stream);
+    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_step_gossip_push(geom_of(ctx), hyper_of(ctx), seg_of(ctx), walk, x, v, g,
-                                                 persist_of(ctx, GSGD_KERNEL_GOSSIP), static_cast<hipStream_t>(stream));
+                                                 ps, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -291,7 +356,7 @@ extern "C" int gsgd_step_easgd_tick(gsgd_ctx* ctx, float* x, float* v, const flo
 {
     const int rc = check_state(ctx, x, v, g);
     if (rc != GSGD_OK) return rc;
-    if (!ok_matrix(center) || center == x || center == v || center == g || !(alpha_e == alpha_e))
+    if (!ok_matrix(center) || !vector_clear_of(ctx, center, x, v, g) || !(alpha_e == alpha_e))
         return GSGD_ERR_INVALID_ARG;
     if (i < 0 || i >= ctx->cfg.k) return GSGD_ERR_INVALID_ARG;
     const hipError_t e = launch_easgd_tick(geom_of(ctx), hyper_of(ctx), seg_of(ctx), alpha_e, i, x, v, g, center,
@@ -302,7 +367,9 @@ extern "C" int gsgd_step_easgd_tick(gsgd_ctx* ctx, float* x, float* v, const flo
 extern "C" int gsgd_step_async_tick_fused(gsgd_ctx* ctx, float* x, float* v, const float* h, const float* xstar,
                                           int32_t i, int32_t j, float beta, uint64_t tick, void* stream)
 {
-    if (!ctx || !ok_matrix(x) || !ok_matrix(v) || !ok_matrix(h) || !ok_matrix(xstar) || x == v)
+    if (!ctx || !ok_matrix(x) || !ok_matrix(v) || !ok_matrix(h) || !ok_matrix(xstar)) return GSGD_ERR_INVALID_ARG;
+    if (overlap(x, matrix_span(ctx), v, matrix_span(ctx)) || !vector_clear_of(ctx, h, x, v) ||
+        !vector_clear_of(ctx, xstar, x, v))
         return GSGD_ERR_INVALID_ARG;
     if (i < 0 || i >= ctx->cfg.k || j < 0 || j >= ctx->cfg.k || !(beta == beta) || tick > 0xFFFFFFFFull)
         return GSGD_ERR_INVALID_ARG;
@@ -330,8 +397,9 @@ extern "C" int gsgd_step_local(gsgd_ctx* ctx, float* x, float* v, const float* g
 {
     const int rc = check_state(ctx, x, v, g);
     if (rc != GSGD_OK) return rc;
+    const Persist ps{nullptr, 0u};                       // a plain grid: no tickets, no width
     const hipError_t e = launch_step_local(geom_of(ctx), hyper_of(ctx), seg_of(ctx), x, v, g,
-                                           persist_of(ctx, GSGD_KERNEL_LOCAL), static_cast<hipStream_t>(stream));
+                                           ps, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -339,7 +407,9 @@ namespace {
 int check_fused(const gsgd_ctx* ctx, const float* x, const float* v, const float* h, const float* xstar,
                 const int32_t* map, uint64_t step)
 {
-    if (!ctx || !ok_matrix(x) || !ok_matrix(v) || !ok_matrix(h) || !ok_matrix(xstar) || x == v)
+    if (!ctx || !ok_matrix(x) || !ok_matrix(v) || !ok_matrix(h) || !ok_matrix(xstar)) return GSGD_ERR_INVALID_ARG;
+    if (overlap(x, matrix_span(ctx), v, matrix_span(ctx)) || !vector_clear_of(ctx, h, x, v) ||
+        !vector_clear_of(ctx, xstar, x, v))
         return GSGD_ERR_INVALID_ARG;
     if (!map || step > 0xFFFFFFFFull) return GSGD_ERR_INVALID_ARG;
     return GSGD_OK;
@@ -355,10 +425,11 @@ extern "C" int gsgd_step_gossip_fused(gsgd_ctx* ctx, float* x, float* v, const f
     Walk walk;
     rc = build_walk(peer_perm, ctx->cfg.k, &walk);
     if (rc != GSGD_OK) return rc;
+    const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED, stream);
+    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_step_gossip_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, false, false,
                                                   x, v, h, xstar, ctx->cfg.sigma, key_of(ctx),
-                                                  static_cast<uint32_t>(step), ctx->cfg.noise_kind,
-                                                  persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED),
+                                                  static_cast<uint32_t>(step), ctx->cfg.noise_kind, ps,
                                                   static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
@@ -373,10 +444,11 @@ extern "C" int gsgd_step_gossip_pull_fused(gsgd_ctx* ctx, float* x, float* v, co
     int has_trees = 0, slots = 0;
     rc = build_pull_walk(peer, ctx->cfg.k, &walk, &has_trees, &slots);
     if (rc != GSGD_OK) return rc;
+    const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED, stream);
+    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_step_gossip_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale != 0,
                                                   has_trees != 0, x, v, h, xstar, ctx->cfg.sigma, key_of(ctx),
-                                                  static_cast<uint32_t>(step), ctx->cfg.noise_kind,
-                                                  persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED),
+                                                  static_cast<uint32_t>(step), ctx->cfg.noise_kind, ps,
                                                   static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
@@ -390,9 +462,11 @@ extern "C" int gsgd_step_gossip_push_fused(gsgd_ctx* ctx, float* x, float* v, co
     int slots = 0;
     rc = build_push_walk(target, ctx->cfg.k, &walk, &slots);
     if (rc != GSGD_OK) return rc;
+    const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED, stream);
+    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_step_gossip_push_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), walk, x, v, h, xstar,
                                                        ctx->cfg.sigma, key_of(ctx), static_cast<uint32_t>(step),
-                                                       ctx->cfg.noise_kind, persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED),
+                                                       ctx->cfg.noise_kind, ps,
                                                        static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
@@ -402,37 +476,88 @@ extern "C" int gsgd_step_easgd(gsgd_ctx* ctx, float* x, float* v, const float* g
 {
     const int rc = check_state(ctx, x, v, g);
     if (rc != GSGD_OK) return rc;
-    if (!ok_matrix(center) || center == x || center == v || center == g || !(alpha_e == alpha_e))
+    if (!ok_matrix(center) || !vector_clear_of(ctx, center, x, v, g) || !(alpha_e == alpha_e))
         return GSGD_ERR_INVALID_ARG;
+    const Persist ps = persist_of(ctx, GSGD_KERNEL_EASGD, stream);
+    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_step_easgd(geom_of(ctx), hyper_of(ctx), seg_of(ctx), alpha_e, x, v, g, center,
-                                           persist_of(ctx, GSGD_KERNEL_EASGD), static_cast<hipStream_t>(stream));
+                                           ps, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
+
+namespace {
+// The calls that wait for a stream also look at that stream's ticket pair: with the stream drained both
+// words must read zero.  If they do not, a launch did not run to its end (or two launches shared the pair);
+// the pair is cleared so that later launches hand out every tile again, and the caller is told.
+// Enqueues the copy of the pair behind whatever is on the stream; `slot` is the index into h_result.
+hipError_t fetch_ticket_pair(gsgd_ctx* ctx, hipStream_t s, size_t slot, int* pair_out)
+{
+    *pair_out = -1;
+    for (int p = 0; p < ctx->n_pairs; ++p)
+        if (ctx->pair_stream[p] == s) *pair_out = p;
+    if (*pair_out < 0) return hipSuccess;
+    return hipMemcpyAsync(ctx->h_result + slot, pair_words(ctx, *pair_out), 2 * sizeof(uint32_t),
+                          hipMemcpyDeviceToHost, s);
+}
+
+int verify_ticket_pair(gsgd_ctx* ctx, hipStream_t s, size_t slot, int pair)
+{
+    if (pair < 0) return GSGD_OK;
+    uint32_t words[2];
+    memcpy(words, ctx->h_result + slot, sizeof(words));
+    if (words[0] == 0u && words[1] == 0u) return GSGD_OK;
+    hipError_t e = hipMemsetAsync(pair_words(ctx, pair), 0, 2 * sizeof(uint32_t), s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return GSGD_ERR_BAD_STATE;
+}
+}  // namespace
 
 extern "C" int gsgd_stats(gsgd_ctx* ctx, const float* x, const float* xstar, double out[4], void* stream)
 {
     if (!ctx || !ok_matrix(x) || !ok_matrix(xstar) || !out) return GSGD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t slot = static_cast<size_t>(ctx->cfg.k > 4 ? ctx->cfg.k : 4);
+    int pair = -1;
     hipError_t e = launch_stats(geom_of(ctx), x, xstar, ctx->d_partials, ctx->d_result, s);
     if (e == hipSuccess) e = hipMemcpyAsync(ctx->h_result, ctx->d_result, sizeof(double) * 4, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = fetch_ticket_pair(ctx, s, slot, &pair);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return hip_fail(ctx, e);
     for (int m = 0; m < 4; ++m) out[m] = ctx->h_result[m];
-    return GSGD_OK;
+    return verify_ticket_pair(ctx, s, slot, pair);
 }
 
 extern "C" int gsgd_row_sqnorms(gsgd_ctx* ctx, const float* x, double* out, void* stream)
 {
     if (!ctx || !ok_matrix(x) || !out) return GSGD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t slot = static_cast<size_t>(ctx->cfg.k > 4 ? ctx->cfg.k : 4);
+    int pair = -1;
     hipError_t e = launch_row_sqnorms(geom_of(ctx), x, ctx->d_norm_partials, ctx->d_result, s);
     if (e == hipSuccess)
         e = hipMemcpyAsync(ctx->h_result, ctx->d_result, sizeof(double) * static_cast<size_t>(ctx->cfg.k),
                            hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = fetch_ticket_pair(ctx, s, slot, &pair);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return hip_fail(ctx, e);
     for (int32_t i = 0; i < ctx->cfg.k; ++i) out[i] = ctx->h_result[i];
-    return GSGD_OK;
+    return verify_ticket_pair(ctx, s, slot, pair);
+}
+
+// Test hook: overwrite the ticket pair of `stream` (claiming one if the stream has none yet) behind the work
+// already on the stream, and wait.
+extern "C" int gsgd_poke_tickets(gsgd_ctx* ctx, uint32_t next_tile, uint32_t finished, void* stream)
+{
+    if (!ctx) return GSGD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int pair = pair_of(ctx, s);
+    if (pair < 0) return GSGD_ERR_UNSUPPORTED;
+    const uint32_t words[2] = {next_tile, finished};
+    hipError_t e = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = hipMemcpy(pair_words(ctx, pair), words, sizeof(words), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
 // ---- the weights v_ij of Section 3.1 and the diffusion potential: host arithmetic on k x k matrices -----------
@@ -497,8 +622,9 @@ extern "C" const char* gsgd_strerror(int code)
         case GSGD_ERR_BAD_PERM: return "peer map has an entry outside 0..k-1 or is not the permutation the call requires";
         case GSGD_ERR_BAD_SEGMENTS: return "segment table must ascend strictly from 0 to d";
         case GSGD_ERR_HIP: return "HIP runtime error";
-        case GSGD_ERR_UNSUPPORTED: return "unsupported";
+        case GSGD_ERR_UNSUPPORTED: return "unsupported (a context serves at most 32 streams)";
         case GSGD_ERR_NO_MEMORY: return "out of memory";
+        case GSGD_ERR_BAD_STATE: return "a tile counter of the context was not zero on a drained stream (cleared now)";
         default: return "unknown error";
     }
 }

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libgsgd.so")
 
 MAX_K = 512
 OK, ERR_INVALID_ARG, ERR_BAD_PERM, ERR_BAD_SEGMENTS, ERR_HIP, ERR_UNSUPPORTED, ERR_NO_MEMORY = 0, -1, -2, -3, -4, -5, -6
+ERR_BAD_STATE = -7
 NOISE_GAUSSIAN, NOISE_UNIFORM = 0, 1
 INIT_BROADCAST, INIT_PER_REPLICA = 0, 1
 FILL_XSTAR, FILL_H, FILL_X0 = 2, 3, 4
@@ -85,6 +86,7 @@ SIGNATURES = {
     "gsgd_weights_push": (C.c_int, [C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_int32)]),
     "gsgd_diffusion_potential": (C.c_int, [C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_double),
                                            C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "gsgd_poke_tickets": (C.c_int, [_vp, C.c_uint32, C.c_uint32, _vp]),
     "gsgd_strerror": (C.c_char_p, [C.c_int]),
     "gsgd_last_hip_error": (C.c_int, [_vp]),
 }
@@ -116,10 +118,24 @@ def _check(rc, where):
         raise GsgdError(rc, where)
 
 
-def _ptr(t):
-    """Raw device pointer of a torch tensor (or None)."""
+def _ptr(t, need=0, dtype=None):
+    """Raw device pointer of a torch tensor (or None), after checking that it is
+    what the library will take it for: a contiguous GPU tensor of `dtype`
+    (fp32 unless given) holding at least `need` elements.  A wrong tensor would
+    otherwise become an out-of-bounds device access."""
     if t is None:
         return None
+    import torch
+    want = torch.float32 if dtype is None else dtype
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise ValueError("expected a GPU tensor, got %r" % (type(t).__name__ if not isinstance(t, torch.Tensor)
+                                                            else t.device,))
+    if t.dtype != want:
+        raise ValueError("expected dtype %s, got %s" % (want, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("expected a contiguous tensor")
+    if t.numel() < need:
+        raise ValueError("tensor holds %d elements, the call touches %d" % (t.numel(), need))
     return C.c_void_p(t.data_ptr())
 
 
@@ -130,8 +146,10 @@ def _stream(stream):
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def _perm_arg(peer_perm):
+def _perm_arg(peer_perm, k=None):
     p = np.ascontiguousarray(peer_perm, dtype=np.int32)
+    if p.ndim != 1 or (k is not None and p.shape[0] != k):
+        raise ValueError("a peer / target map needs exactly k = %s entries, got shape %s" % (k, p.shape))
     return p, p.ctypes.data_as(C.POINTER(C.c_int32))
 
 
@@ -175,6 +193,14 @@ class Context:
     def __exit__(self, *exc):
         self.close()
 
+    def _m(self, t):
+        """a k x ld row matrix: the last row may be short of the padding"""
+        return _ptr(t, (self.k - 1) * self.ld + self.d)
+
+    def _vec(self, t):
+        """a shared d-vector"""
+        return _ptr(t, self.d)
+
     def set_lr(self, lr):
         _check(lib().gsgd_set_lr(self._h, float(lr)), "gsgd_set_lr")
 
@@ -185,91 +211,97 @@ class Context:
         _check(lib().gsgd_set_launch_width(self._h, int(kernel), int(workgroups)), "gsgd_set_launch_width")
 
     def init_replicas(self, x, v, center, x0, mode=INIT_BROADCAST, stream=None):
-        _check(lib().gsgd_init_replicas(self._h, _ptr(x), _ptr(v), _ptr(center), _ptr(x0), int(mode), _stream(stream)),
+        _check(lib().gsgd_init_replicas(self._h, self._m(x), self._m(v), self._vec(center), self._vec(x0), int(mode), _stream(stream)),
                "gsgd_init_replicas")
 
     def fill(self, dst, which, stream=None):
-        _check(lib().gsgd_fill(self._h, _ptr(dst), int(which), _stream(stream)), "gsgd_fill")
+        _check(lib().gsgd_fill(self._h, self._vec(dst), int(which), _stream(stream)), "gsgd_fill")
 
     def gen_grad(self, x, h, xstar, g, step, stream=None):
-        _check(lib().gsgd_gen_grad(self._h, _ptr(x), _ptr(h), _ptr(xstar), _ptr(g), int(step), _stream(stream)),
+        _check(lib().gsgd_gen_grad(self._h, self._m(x), self._vec(h), self._vec(xstar), self._m(g), int(step), _stream(stream)),
                "gsgd_gen_grad")
 
     def step_allreduce(self, x, v, g, stream=None):
-        _check(lib().gsgd_step_allreduce(self._h, _ptr(x), _ptr(v), _ptr(g), _stream(stream)), "gsgd_step_allreduce")
+        _check(lib().gsgd_step_allreduce(self._h, self._m(x), self._m(v), self._m(g), _stream(stream)), "gsgd_step_allreduce")
 
     def step_gossip(self, x, v, g, peer_perm, beta=0.5, stream=None):
-        keep, p = _perm_arg(peer_perm)
-        _check(lib().gsgd_step_gossip(self._h, _ptr(x), _ptr(v), _ptr(g), p, float(beta), _stream(stream)),
+        keep, p = _perm_arg(peer_perm, self.k)
+        _check(lib().gsgd_step_gossip(self._h, self._m(x), self._m(v), self._m(g), p, float(beta), _stream(stream)),
                "gsgd_step_gossip")
 
     def step_gossip_stale(self, x, v, g, peer_perm, beta=0.5, stream=None):
-        keep, p = _perm_arg(peer_perm)
-        _check(lib().gsgd_step_gossip_stale(self._h, _ptr(x), _ptr(v), _ptr(g), p, float(beta), _stream(stream)),
+        keep, p = _perm_arg(peer_perm, self.k)
+        _check(lib().gsgd_step_gossip_stale(self._h, self._m(x), self._m(v), self._m(g), p, float(beta), _stream(stream)),
                "gsgd_step_gossip_stale")
 
     def step_gossip_pull(self, x, v, g, peer, beta=0.5, stale=False, stream=None):
-        keep, p = _perm_arg(peer)
-        _check(lib().gsgd_step_gossip_pull(self._h, _ptr(x), _ptr(v), _ptr(g), p, float(beta), int(bool(stale)),
+        keep, p = _perm_arg(peer, self.k)
+        _check(lib().gsgd_step_gossip_pull(self._h, self._m(x), self._m(v), self._m(g), p, float(beta), int(bool(stale)),
                                            _stream(stream)), "gsgd_step_gossip_pull")
 
     def step_gossip_push(self, x, v, g, target, stream=None):
-        keep, p = _perm_arg(target)
-        _check(lib().gsgd_step_gossip_push(self._h, _ptr(x), _ptr(v), _ptr(g), p, _stream(stream)),
+        keep, p = _perm_arg(target, self.k)
+        _check(lib().gsgd_step_gossip_push(self._h, self._m(x), self._m(v), self._m(g), p, _stream(stream)),
                "gsgd_step_gossip_push")
 
     def step_async_tick(self, x, v, g, i, j, beta=0.5, stream=None):
-        _check(lib().gsgd_step_async_tick(self._h, _ptr(x), _ptr(v), _ptr(g), int(i), int(j), float(beta),
+        _check(lib().gsgd_step_async_tick(self._h, self._m(x), self._m(v), self._m(g), int(i), int(j), float(beta),
                                           _stream(stream)), "gsgd_step_async_tick")
 
     def step_easgd_tick(self, x, v, g, center, i, alpha_e, stream=None):
-        _check(lib().gsgd_step_easgd_tick(self._h, _ptr(x), _ptr(v), _ptr(g), _ptr(center), int(i), float(alpha_e),
+        _check(lib().gsgd_step_easgd_tick(self._h, self._m(x), self._m(v), self._m(g), self._vec(center), int(i), float(alpha_e),
                                           _stream(stream)), "gsgd_step_easgd_tick")
 
     def step_async_tick_fused(self, x, v, h, xstar, i, j, tick, beta=0.5, stream=None):
-        _check(lib().gsgd_step_async_tick_fused(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), int(i), int(j),
+        _check(lib().gsgd_step_async_tick_fused(self._h, self._m(x), self._m(v), self._vec(h), self._vec(xstar), int(i), int(j),
                                                 float(beta), int(tick), _stream(stream)),
                "gsgd_step_async_tick_fused")
 
     def run_async_ticks(self, x, v, h, xstar, first_tick, n_ticks, beta=0.5, stream=None):
-        _check(lib().gsgd_run_async_ticks(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), float(beta),
+        _check(lib().gsgd_run_async_ticks(self._h, self._m(x), self._m(v), self._vec(h), self._vec(xstar), float(beta),
                                           int(first_tick), int(n_ticks), _stream(stream)), "gsgd_run_async_ticks")
 
     def step_local(self, x, v, g, stream=None):
-        _check(lib().gsgd_step_local(self._h, _ptr(x), _ptr(v), _ptr(g), _stream(stream)), "gsgd_step_local")
+        _check(lib().gsgd_step_local(self._h, self._m(x), self._m(v), self._m(g), _stream(stream)), "gsgd_step_local")
 
     def step_easgd(self, x, v, g, center, alpha_e, stream=None):
-        _check(lib().gsgd_step_easgd(self._h, _ptr(x), _ptr(v), _ptr(g), _ptr(center), float(alpha_e),
+        _check(lib().gsgd_step_easgd(self._h, self._m(x), self._m(v), self._m(g), self._vec(center), float(alpha_e),
                                      _stream(stream)), "gsgd_step_easgd")
 
     def step_gossip_fused(self, x, v, h, xstar, peer_perm, step, beta=0.5, stream=None):
-        keep, p = _perm_arg(peer_perm)
-        _check(lib().gsgd_step_gossip_fused(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), p, float(beta),
+        keep, p = _perm_arg(peer_perm, self.k)
+        _check(lib().gsgd_step_gossip_fused(self._h, self._m(x), self._m(v), self._vec(h), self._vec(xstar), p, float(beta),
                                             int(step), _stream(stream)), "gsgd_step_gossip_fused")
 
     def step_gossip_pull_fused(self, x, v, h, xstar, peer, step, beta=0.5, stale=False, stream=None):
-        keep, p = _perm_arg(peer)
-        _check(lib().gsgd_step_gossip_pull_fused(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), p, float(beta),
+        keep, p = _perm_arg(peer, self.k)
+        _check(lib().gsgd_step_gossip_pull_fused(self._h, self._m(x), self._m(v), self._vec(h), self._vec(xstar), p, float(beta),
                                                  int(bool(stale)), int(step), _stream(stream)),
                "gsgd_step_gossip_pull_fused")
 
     def step_gossip_push_fused(self, x, v, h, xstar, target, step, stream=None):
-        keep, p = _perm_arg(target)
-        _check(lib().gsgd_step_gossip_push_fused(self._h, _ptr(x), _ptr(v), _ptr(h), _ptr(xstar), p, int(step),
+        keep, p = _perm_arg(target, self.k)
+        _check(lib().gsgd_step_gossip_push_fused(self._h, self._m(x), self._m(v), self._vec(h), self._vec(xstar), p, int(step),
                                                  _stream(stream)), "gsgd_step_gossip_push_fused")
 
     def philox_raw(self, c1, c2, c3, n_blocks, out, stream=None):
-        _check(lib().gsgd_philox_raw(self._h, int(c1), int(c2), int(c3), int(n_blocks), _ptr(out), _stream(stream)),
+        import torch
+        _check(lib().gsgd_philox_raw(self._h, int(c1), int(c2), int(c3), int(n_blocks),
+                                     _ptr(out, 4 * int(n_blocks), torch.int32 if out.dtype == torch.int32 else torch.uint32),
+                                     _stream(stream)),
                "gsgd_philox_raw")
 
     def row_sqnorms(self, x, stream=None):
         out = (C.c_double * self.k)()
-        _check(lib().gsgd_row_sqnorms(self._h, _ptr(x), out, _stream(stream)), "gsgd_row_sqnorms")
+        _check(lib().gsgd_row_sqnorms(self._h, self._m(x), out, _stream(stream)), "gsgd_row_sqnorms")
         return np.array(list(out), dtype=np.float64)
+
+    def poke_tickets(self, next_tile, finished, stream=None):
+        _check(lib().gsgd_poke_tickets(self._h, int(next_tile), int(finished), _stream(stream)), "gsgd_poke_tickets")
 
     def stats(self, x, xstar, stream=None):
         out = (C.c_double * 4)()
-        _check(lib().gsgd_stats(self._h, _ptr(x), _ptr(xstar), out, _stream(stream)), "gsgd_stats")
+        _check(lib().gsgd_stats(self._h, self._m(x), self._vec(xstar), out, _stream(stream)), "gsgd_stats")
         return np.array(list(out), dtype=np.float64)
 
 

@@ -1,0 +1,184 @@
+"""What a context guarantees beyond the arithmetic: one context serves several
+streams at once (each stream hands out tiles through a counter pair of its
+own), overlapping buffers are refused by address range, a tile counter that is
+not zero on a drained stream is reported and repaired, and the binding refuses
+tensors the library would misread."""
+import numpy as np
+import pytest
+
+from paper_1611_04581_amd import workloads as W
+from parity_util import assert_bitwise
+
+pytestmark = pytest.mark.gpu
+SEED = W.DEFAULT_SEED
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    from paper_1611_04581_amd import gsgd
+    assert torch.cuda.is_available()
+    gsgd.lib()
+    return gsgd
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return np.ascontiguousarray(t.cpu().numpy())
+
+
+def test_two_streams_on_one_context_bit_exact(G, oracle):
+    """Two independent replica sets advanced through ONE context from two
+    streams with their launches interleaved and overlapping in time; both must
+    come out as the oracle computes them one after the other."""
+    import torch
+    k, d, steps = 8, 300 * 1024 + 37, 12          # 301 tiles: many more than one per workgroup when width is small
+    ld = W.round_up(d, 1024)
+    sets = [W.make_inputs(k, d, ld, seed=21), W.make_inputs(k, d, ld, seed=22)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, sigma=0.1, seed=SEED, noise_kind=G.NOISE_UNIFORM) as ctx:
+        ctx.set_launch_width(G.KERNEL_GOSSIP, 64)  # long-lived workgroups, so that the two streams really overlap
+        ctx.set_launch_width(G.KERNEL_GEN_GRAD, 64)
+        state = []
+        for inp in sets:
+            state.append(dict(x=dev(inp.x), v=dev(inp.v), g=dev(inp.g), h=dev(inp.h), xs=dev(inp.xstar)))
+        torch.cuda.synchronize()
+        for t in range(steps):
+            for s, st in zip(streams, state):
+                with torch.cuda.stream(s):
+                    ctx.gen_grad(st["x"], st["h"], st["xs"], st["g"], t)
+                    if t % 3 == 2:
+                        ctx.step_allreduce(st["x"], st["v"], st["g"])
+                    else:
+                        ctx.step_gossip(st["x"], st["v"], st["g"], G.make_perm(SEED, t, k), 0.5)
+        for s in streams:
+            s.synchronize()
+        for s, st, inp in zip(streams, state, sets):
+            with torch.cuda.stream(s):
+                ctx.stats(st["x"], st["xs"])       # also verifies that this stream's tile counters drained to zero
+            xo, vo, go = inp.x.copy(), inp.v.copy(), inp.g.copy()
+            for t in range(steps):
+                oracle.gen_grad(xo, inp.h, inp.xstar, go, 0.1, SEED, t, 1, n=d)
+                if t % 3 == 2:
+                    oracle.step_allreduce(xo, vo, go, 0.05, 0.9, n=d)
+                else:
+                    oracle.step_gossip(xo, vo, go, 0.05, 0.9, 0.5, G.make_perm(SEED, t, k), n=d)
+            assert_bitwise(host(st["x"]), xo, "x")
+            assert_bitwise(host(st["v"]), vo, "v")
+
+
+def test_overlapping_buffers_are_refused_by_range(G):
+    import torch
+    k, d = 4, 4096
+    ld = d
+    with G.Context(k, d, ld) as ctx:
+        big = torch.zeros(3 * k * ld + 64, dtype=torch.float32, device="cuda")
+        x = big[0:k * ld]
+        v_shifted = big[1024:1024 + k * ld]           # overlaps x by an offset: pointer equality would not see it
+        v_ok = big[k * ld:2 * k * ld]
+        g_ok = big[2 * k * ld:3 * k * ld]
+        c_in_x = big[ld + 8:ld + 8 + d]               # a centre lying inside x
+        c_ok = torch.zeros(d, dtype=torch.float32, device="cuda")
+        perm = list(range(k))
+        for call in (lambda: ctx.step_gossip(x, v_shifted, g_ok, perm, 0.5),
+                     lambda: ctx.step_allreduce(x, v_ok, v_shifted),
+                     lambda: ctx.step_easgd(x, v_ok, g_ok, c_in_x, 0.1),
+                     lambda: ctx.step_local(x, v_shifted, g_ok),
+                     lambda: ctx.gen_grad(x, c_ok, c_ok, v_shifted, 0),
+                     lambda: ctx.gen_grad(x, c_in_x, c_ok, x, 0),
+                     lambda: ctx.step_gossip_fused(x, v_shifted, c_ok, c_ok, perm, 0, 0.5),
+                     lambda: ctx.step_gossip_fused(x, v_ok, c_in_x, c_ok, perm, 0, 0.5),
+                     lambda: ctx.init_replicas(x, v_shifted, None, c_ok),
+                     lambda: ctx.init_replicas(x, v_ok, c_in_x, c_ok)):
+            with pytest.raises(G.GsgdError) as e:
+                call()
+            assert e.value.code == G.ERR_INVALID_ARG
+        # adjacent but disjoint buffers are fine
+        ctx.step_gossip(x, v_ok, g_ok, perm, 0.5)
+        ctx.step_easgd(x, v_ok, g_ok, c_ok, 0.1)
+        torch.cuda.synchronize()
+
+
+def test_nonzero_tile_counter_is_reported_and_repaired(G, oracle):
+    """The host forces the state a cut-short launch would leave behind; the next
+    waiting call says so and clears it, and steps after that are exact again.
+    (A step launched while the counter is wrong drains normally: every
+    workgroup leaves after one failed fetch.)"""
+    import torch
+    k, d = 4, 20 * 1024 + 5
+    ld = W.round_up(d, 1024)
+    inp = W.make_inputs(k, d, ld, seed=23)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, sigma=0.0, seed=SEED) as ctx:
+        x, v, g, xs = dev(inp.x), dev(inp.v), dev(inp.g), dev(inp.xstar)
+        ctx.step_gossip(x, v, g, list(range(k)), 0.5)
+        ctx.stats(x, xs)                                     # clean
+        ctx.poke_tickets(7, 0)
+        with pytest.raises(G.GsgdError) as e:
+            ctx.stats(x, xs)
+        assert e.value.code == G.ERR_BAD_STATE
+        ctx.stats(x, xs)                                     # repaired
+        x2, v2 = dev(inp.x), dev(inp.v)
+        ctx.step_gossip(x2, v2, g, [1, 0, 3, 2], 0.5)
+        ctx.stats(x2, xs)
+        xo, vo = inp.x.copy(), inp.v.copy()
+        oracle.step_gossip(xo, vo, inp.g, 0.05, 0.9, 0.5, [1, 0, 3, 2], n=d)
+        assert_bitwise(host(x2), xo, "x after repair")
+        # row_sqnorms checks the same way
+        ctx.poke_tickets(0, 3)
+        with pytest.raises(G.GsgdError) as e:
+            ctx.row_sqnorms(x)
+        assert e.value.code == G.ERR_BAD_STATE
+        ctx.row_sqnorms(x)
+
+
+def test_a_context_serves_at_most_32_streams(G):
+    import torch
+    k, d = 2, 4096
+    with G.Context(k, d) as ctx:
+        x = torch.zeros((k, d), dtype=torch.float32, device="cuda")
+        v, g = torch.zeros_like(x), torch.zeros_like(x)
+        streams = [torch.cuda.Stream() for _ in range(40)]
+        handles = [0]                                         # the default stream, then the pool's
+        for s in streams:                                    # torch hands out pool streams: count distinct handles
+            if s.cuda_stream not in handles:
+                handles.append(s.cuda_stream)
+        codes = []
+        for hnd in handles:
+            try:
+                ctx.step_allreduce(x, v, g, stream=hnd)
+                codes.append(G.OK)
+            except G.GsgdError as e:
+                codes.append(e.code)
+        torch.cuda.synchronize()
+        assert all(c == G.OK for c in codes[:32])
+        assert all(c == G.ERR_UNSUPPORTED for c in codes[32:])
+        ctx.step_local(x, v, g, stream=handles[-1])          # the plain-grid local step needs no counter pair
+        torch.cuda.synchronize()
+
+
+def test_binding_refuses_tensors_the_library_would_misread(G):
+    import torch
+    k, d = 4, 4096
+    with G.Context(k, d) as ctx:
+        x = torch.zeros((k, d), dtype=torch.float32, device="cuda")
+        v, g = torch.zeros_like(x), torch.zeros_like(x)
+        perm = list(range(k))
+        bad = [
+            lambda: ctx.step_gossip(x.cpu(), v, g, perm),                                  # host tensor
+            lambda: ctx.step_gossip(x.double(), v, g, perm),                               # wrong dtype
+            lambda: ctx.step_gossip(x[:, ::2], v, g, perm),                                # not contiguous
+            lambda: ctx.step_gossip(x[:k - 1], v, g, perm),                                # too few rows
+            lambda: ctx.step_gossip(x, v, g, perm[:-1]),                                   # short map
+            lambda: ctx.step_gossip(x, v, g, perm + [0]),                                  # long map
+            lambda: ctx.step_easgd(x, v, g, torch.zeros(d - 1, device="cuda"), 0.1),       # short centre
+            lambda: ctx.gen_grad(x, torch.zeros(d, device="cuda"), np.zeros(d, np.float32), g, 0),   # numpy array
+        ]
+        for call in bad:
+            with pytest.raises(ValueError):
+                call()
+        ctx.step_gossip(x, v, g, perm)
+        torch.cuda.synchronize()
