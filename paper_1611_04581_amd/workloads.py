@@ -182,3 +182,46 @@ def random_segments(d: int, n_seg: int, seed: int, align: int = 1):
     offsets = np.concatenate([[0], cuts, [d]]).astype(np.int64)
     scales = rng.uniform(0.5, 2.0, n_seg).astype(np.float32)
     return offsets, scales
+
+
+def make_special_inputs(k: int, d: int, ld: Optional[int] = None, seed: int = 0) -> Inputs:
+    """Inputs that sit where fp32 arithmetic is fragile, for bit-exact parity:
+    subnormals, +0 / -0, the smallest normals (whose products with lr, mu or
+    beta land in the subnormal range), ordinary values, and magnitudes around
+    1e36..1e37 (large, but such that no sum or difference the rules form can
+    overflow, so every result is a finite number with one defined bit
+    pattern).  Each element draws its class independently, so one column mixes
+    classes across replicas.  h stays in [0.1, 1]."""
+    ld = d if ld is None else ld
+    assert ld >= d
+    rng = np.random.default_rng(seed)
+
+    def draw(shape):
+        cls = rng.integers(0, 6, size=shape)
+        sign = rng.integers(0, 2, size=shape).astype(np.uint32) << np.uint32(31)
+        mant = rng.integers(0, 1 << 23, size=shape).astype(np.uint32)
+        bits = np.zeros(shape, np.uint32)
+        bits = np.where(cls == 0, mant, bits)                                          # subnormal (exponent field 0)
+        bits = np.where(cls == 1, np.uint32(0), bits)                                  # zero
+        bits = np.where(cls == 2, (np.uint32(1) << np.uint32(23)) | mant, bits)        # smallest normals, 1.2e-38..2.4e-38
+        bits = np.where(cls == 3, (rng.integers(120, 131, size=shape).astype(np.uint32) << np.uint32(23)) | mant, bits)   # ~1
+        bits = np.where(cls == 4, (rng.integers(246, 250, size=shape).astype(np.uint32) << np.uint32(23)) | mant, bits)   # 1e36..1e37
+        bits = np.where(cls == 5, (rng.integers(1, 30, size=shape).astype(np.uint32) << np.uint32(23)) | mant, bits)      # tiny normals
+        return (bits | sign).astype(np.uint32).view(np.float32)
+
+    def rows():
+        a = np.full((k, ld), 777.0, np.float32)
+        a[:, :d] = draw((k, d))
+        return a
+
+    def vec(vals):
+        a = np.full(ld, 777.0, np.float32)
+        a[:d] = vals
+        return a
+
+    x, v, g = rows(), rows(), rows()
+    xstar = vec(draw(d))
+    h = vec(rng.uniform(0.1, 1.0, d).astype(np.float32))
+    center = vec(draw(d))
+    x0 = vec(draw(d))
+    return Inputs(x, v, g, xstar, h, center, x0, d, ld, k)

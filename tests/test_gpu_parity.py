@@ -263,7 +263,8 @@ def test_bad_arguments_leave_state_untouched(G):
             ctx.step_gossip(x, v, x, [0, 1, 2, 3], 0.5)               # aliasing
         assert e.value.code == G.ERR_INVALID_ARG
         with pytest.raises(G.GsgdError) as e:
-            ctx.step_allreduce(x.view(-1)[1:], v, g)                   # misaligned
+            big = torch.zeros(k * d + 8, dtype=torch.float32, device="cuda")
+            ctx.step_allreduce(big[1:1 + k * d], v, g)                 # misaligned
         assert e.value.code == G.ERR_INVALID_ARG
         with pytest.raises(G.GsgdError):
             ctx.gen_grad(x, dev(inp.h), dev(inp.xstar), g, 2**32)

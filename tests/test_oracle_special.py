@@ -1,0 +1,130 @@
+"""Pins of the oracle where fp32 arithmetic is fragile: subnormal operands and
+results, signed zeros, the smallest normals (products with lr, mu, beta land in
+the subnormal range) and magnitudes near 1e37.  Every rule is replayed one
+rounding at a time on exact rationals (brute.nearest_f32 rounds to binary32
+with gradual underflow), so a flush-to-zero mode on either side, a reordered
+sum or a missing fused operation shows up as a differing bit.  CPU only."""
+from fractions import Fraction
+from itertools import product
+
+import numpy as np
+
+import brute
+from paper_1611_04581_amd import workloads as W
+
+F = lambda a: Fraction(float(a))
+
+
+def _same(got, want):
+    """bit equality, with the exact value of +0 and -0 both read as 0"""
+    return F(got) == want
+
+
+def _local(x, v, g, lr, mu):
+    t3 = brute.f32_mul(F(mu), F(v))
+    vn = brute.f32_fma(-F(lr), F(g), t3)
+    return vn, brute.f32_add(F(x), vn)
+
+
+def test_inputs_do_contain_the_fragile_classes():
+    inp = W.make_special_inputs(8, 4000, seed=1)
+    a = np.abs(inp.x[:, :4000])
+    tiny = np.float32(1.17549435e-38)
+    assert ((a > 0) & (a < tiny)).mean() > 0.1                      # subnormals
+    assert (a == 0).mean() > 0.1 and np.signbit(inp.x[inp.x == 0]).any() and not np.signbit(inp.x[inp.x == 0]).all()
+    assert (a > 1e36).mean() > 0.1 and np.isfinite(inp.x).all() and a.max() < 2e37
+
+
+def test_gossip_exact_replay_on_special_values(oracle):
+    k, n = 4, 60
+    lr, mu = np.float32(0.05), np.float32(0.9)
+    results_subnormal = 0
+    for trial, (peer, beta) in enumerate([([1, 2, 3, 0], 0.5), ([2, 2, 0, 1], 0.3), ([0, 1, 2, 3], 0.5)]):
+        beta = np.float32(beta)
+        inp = W.make_special_inputs(k, n, seed=100 + trial)
+        x0, v0, g0 = inp.x.copy(), inp.v.copy(), inp.g.copy()
+        oracle.step_gossip(inp.x, inp.v, inp.g, lr, mu, beta, peer)
+        assert np.isfinite(inp.x).all() and np.isfinite(inp.v).all()
+        post = [[_local(x0[i, j], v0[i, j], g0[i, j], lr, mu) for j in range(n)] for i in range(k)]
+        for i, j in product(range(k), range(n)):
+            vn, xp = post[i][j]
+            want = brute.f32_fma(-F(beta), brute.f32_sub(xp, post[peer[i]][j][1]), xp)
+            assert _same(inp.v[i, j], vn), (i, j)
+            assert _same(inp.x[i, j], want), (i, j)
+            results_subnormal += (0 < abs(want) < Fraction(1, 2 ** 126)) + (0 < abs(vn) < Fraction(1, 2 ** 126))
+    assert results_subnormal > 40          # the case is exercised: subnormal results must survive, not flush to zero
+
+
+def test_allreduce_and_easgd_exact_replay_on_special_values(oracle):
+    k, n = 3, 60
+    lr, mu, alpha = np.float32(0.05), np.float32(0.9), np.float32(0.3)
+    inp = W.make_special_inputs(k, n, seed=200)
+    x0, v0, g0, c0 = inp.x.copy(), inp.v.copy(), inp.g.copy(), inp.center.copy()
+    xa, va = x0.copy(), v0.copy()
+    oracle.step_allreduce(xa, va, g0, lr, mu)
+    xe, ve, ce = x0.copy(), v0.copy(), c0.copy()
+    oracle.step_easgd(xe, ve, g0, ce, lr, mu, alpha)
+    for j in range(n):
+        loc = [_local(x0[i, j], v0[i, j], g0[i, j], lr, mu) for i in range(k)]
+        # all-reduce: the fp64 sum of k fp32 values, divided by k, rounded to fp64 then to fp32
+        s = Fraction(0)
+        for vn, _ in loc:
+            s = Fraction(float(np.float64(float(s)) + np.float64(float(vn))))      # fp64 add, ascending i
+        ubar = F(np.float32(np.float64(float(s)) / np.float64(k)))
+        for i in range(k):
+            assert _same(va[i, j], ubar), (i, j)
+            assert _same(xa[i, j], brute.f32_add(F(x0[i, j]), ubar)), (i, j)
+        # elastic averaging
+        acc = np.float64(0.0)
+        for i, (vn, xp) in enumerate(loc):
+            e = brute.f32_mul(F(alpha), brute.f32_sub(xp, F(c0[j])))
+            assert _same(ve[i, j], vn) and _same(xe[i, j], brute.f32_sub(xp, e)), (i, j)
+            acc = acc + np.float64(float(e))
+        assert _same(ce[j], F(np.float32(np.float64(c0[j]) + acc))), j
+    assert np.isfinite(xa).all() and np.isfinite(xe).all() and np.isfinite(ce[:n]).all()
+
+
+def test_push_and_tick_exact_on_special_values(oracle):
+    k, n = 4, 60
+    lr, mu, beta = np.float32(0.05), np.float32(0.9), np.float32(0.5)
+    inp = W.make_special_inputs(k, n, seed=300)
+    x0, v0, g0 = inp.x.copy(), inp.v.copy(), inp.g.copy()
+    target = [1, 1, 1, 0]
+    xp_, vp_ = x0.copy(), v0.copy()
+    oracle.step_gossip_push(xp_, vp_, g0, lr, mu, target)
+    xt, vt = x0.copy(), v0.copy()
+    oracle.async_tick(xt, vt, g0[2].copy(), lr, mu, beta, 2, 0)
+    for j in range(n):
+        loc = [_local(x0[i, j], v0[i, j], g0[i, j], lr, mu) for i in range(k)]
+        for r in range(k):
+            got = [r] + [i for i in range(k) if i != r and target[i] == r]
+            exact = sum(loc[i][1] for i in got) / len(got)
+            # the oracle sums in fp64 (inexact when magnitudes differ by more than 2^53) and rounds the quotient
+            # once: within one unit in the last place of the correctly rounded exact average, and equal to it
+            # whenever the fp64 sum is exact
+            want = brute.nearest_f32(exact)
+            err = abs(F(xp_[r, j]) - want)
+            ulp = max(abs(want) * Fraction(1, 1 << 23), Fraction(1, 2 ** 149))
+            assert err <= ulp, (r, j)
+            assert _same(vp_[r, j], loc[r][0])
+        # tick: node 2 steps and mixes with node 0 as it stands; nobody else moves
+        vn, xp = loc[2]
+        assert _same(vt[2, j], vn)
+        assert _same(xt[2, j], brute.f32_fma(-F(beta), brute.f32_sub(xp, F(x0[0, j])), xp))
+        for i in (0, 1, 3):
+            assert xt[i, j].view(np.uint32) == x0[i, j].view(np.uint32) and vt[i, j].view(np.uint32) == v0[i, j].view(np.uint32)
+
+
+def test_gen_grad_uniform_exact_on_special_values(oracle):
+    k, n = 3, 40
+    sigma = np.float32(0.1)
+    seed = W.DEFAULT_SEED
+    inp = W.make_special_inputs(k, n, seed=400)
+    g = np.zeros_like(inp.x)
+    oracle.gen_grad(inp.x, inp.h, inp.xstar, g, sigma, seed, 7, 1)
+    key = (seed & 0xFFFFFFFF, seed >> 32)
+    for i, j in product(range(k), range(n)):
+        word = brute.philox4((j // 4, i, 7, 0), key)[j % 4]
+        t1 = brute.f32_sub(F(inp.x[i, j]), F(inp.xstar[j]))
+        t2 = brute.f32_mul(F(sigma), brute.uniform_noise_exact(word))
+        assert _same(g[i, j], brute.f32_fma(F(inp.h[j]), t1, t2)), (i, j)
