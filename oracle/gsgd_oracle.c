@@ -321,12 +321,14 @@ int oracle_step_easgd(float* x, float* v, const float* g, float* center, int32_t
  *
  * Local step with weight decay and optional Nesterov momentum, in the usual
  * "momentum buffer" form:
- *   gt = g + wd x;   v' = mu v - lr gt;
+ *   gt = g + wd x  (gt = g when wd is zero);   v' = mu v - lr gt;
  *   heavy ball: x' = x + v'        Nesterov: x' = (x - lr gt) + mu v'           */
 static inline void local_step_ext(float x, float v, float g, float lr, float mu, float wd, int nesterov,
                                   float* v_new, float* x_post)
 {
-    const float gt = fmaf(wd, x, g);
+    /* A weight decay of zero means the decay term is absent (the algorithm boxes have none), not "+ 0 * x":
+     * the gradient then enters as it stands, the sign of a zero included, and the step is the boxed one bit for bit. */
+    const float gt = wd != 0.0f ? fmaf(wd, x, g) : g;
     const float t3 = mu * v;
     const float vn = fmaf(-lr, gt, t3);
     *v_new = vn;
@@ -386,7 +388,7 @@ int oracle_step_allreduce_ext(float* x, float* v, const float* g, int32_t k, int
         #pragma omp parallel for schedule(static)
         for (int64_t j = 0; j < n; ++j) {
             const float xi = x[i * ld + j];
-            const float gt = fmaf(wd, xi, g[i * ld + j]);
+            const float gt = wd != 0.0f ? fmaf(wd, xi, g[i * ld + j]) : g[i * ld + j];   /* as in local_step_ext */
             const float t3 = mu * v[i * ld + j];
             const float vn = fmaf(-lr_col[j], gt, t3);
             float di = vn;

@@ -16,6 +16,7 @@ typedef double f64x4 __attribute__((ext_vector_type(4)));
 #define GSGD_BLOCK 256
 #endif
 constexpr int BLOCK = GSGD_BLOCK;     // threads per workgroup: 4 wavefronts of 64
+static_assert(BLOCK_COLUMNS == static_cast<int64_t>(BLOCK) * 4, "a workgroup tile is BLOCK quads wide");
 
 // One thread owns one "quad": four adjacent columns, one 128-bit lane of every
 // row.  A wavefront therefore streams 1 KiB contiguous per row access.
@@ -76,7 +77,7 @@ __device__ __forceinline__ f32x4 momentum_update(f32x4 v, f32x4 g, f32x4 neg_lr,
 // The local step of every rule.  EXT = false: the two lines the algorithm
 // boxes share.  EXT = true: the form the experiments of Section 4.2 use, with
 // weight decay and optionally Nesterov momentum, on the momentum buffer:
-//   gt = g + wd x;  v' = mu v - lr gt;
+//   gt = g + wd x  (gt = g when wd is zero);  v' = mu v - lr gt;
 //   heavy ball: x' = x + v'      Nesterov: x' = (x - lr gt) + mu v'
 // `gt` is returned because the all-reduce rule needs it again.
 template <bool EXT>
@@ -88,7 +89,8 @@ __device__ __forceinline__ void local_step(f32x4 x, f32x4 v, f32x4 g, f32x4 neg_
         x_post = x + v_new;
         if (gt_out) *gt_out = g;
     } else {
-        const f32x4 gt = fma4(hp.wd, x, g);
+        // zero weight decay = no decay term: g enters as it stands (so that -0 stays -0, as in the boxed step)
+        const f32x4 gt = hp.wd != 0.0f ? fma4(hp.wd, x, g) : g;
         const f32x4 t3 = hp.mu * v;
         v_new = fma4(neg_lr, gt, t3);
         if (hp.nesterov) {

@@ -1,0 +1,182 @@
+"""GPU parity where fp32 is fragile: subnormal operands and results (neither
+side may flush them), signed zeros, the smallest normals and 1e37-scale
+magnitudes, through every step rule; and a per-layer table too long for LDS
+(more than 1024 tensors, searched in global memory) through the kernels that
+the basic segmented test does not reach.
+
+The oracle side of these inputs is pinned by exact rational replay in
+test_oracle_special.py.  Bar: bit equality (push-gossip: bit equality on at
+least 99.99 % of the elements and one unit in the last place on the rest,
+because its fp64 sums run in a different order on the two sides)."""
+import numpy as np
+import pytest
+
+from paper_1611_04581_amd import workloads as W
+from parity_util import assert_bitwise
+
+pytestmark = pytest.mark.gpu
+SEED = W.DEFAULT_SEED
+SHAPES = [(4, 5 * 1024 + 7, None), (32, 2 * 1024 + 2, 4096), (7, 1023, 1024)]
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    from paper_1611_04581_amd import gsgd
+    assert torch.cuda.is_available()
+    gsgd.lib()
+    return gsgd
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return np.ascontiguousarray(t.cpu().numpy())
+
+
+def assert_ulp_close(got, want, what):
+    """bit-equal on >= 99.99 % of the elements, adjacent fp32 values elsewhere"""
+    a = np.ascontiguousarray(got).view(np.int32).astype(np.int64)
+    b = np.ascontiguousarray(want).view(np.int32).astype(np.int64)
+    # map the sign-magnitude bit patterns to a monotone integer line (so -0 and +0 are neighbours)
+    a = np.where(a < 0, -(a & 0x7FFFFFFF) - 1, a)
+    b = np.where(b < 0, -(b & 0x7FFFFFFF) - 1, b)
+    steps = np.abs(a - b)
+    assert steps.max() <= 1, "%s: %d units in the last place apart" % (what, steps.max())
+    assert (steps == 0).mean() >= 0.9999, "%s: only %.6f bit-equal" % (what, (steps == 0).mean())
+
+
+def _has_subnormals(a):
+    a = np.abs(a)
+    return bool(((a > 0) & (a < np.float32(1.17549435e-38))).any())
+
+
+@pytest.mark.parametrize("k,d,ld", SHAPES)
+def test_every_rule_bit_exact_on_special_values(G, oracle, k, d, ld):
+    ld = ld or W.round_up(d, 4)
+    inp = W.make_special_inputs(k, d, ld, seed=500 + k)
+    perm = [int(t) for t in oracle.make_perm(SEED, 2, k)]
+    peer = [int(t) for t in oracle.make_targets(SEED, 3, k)]
+    target = [int(t) for t in oracle.make_targets(SEED, 4, k, True)]
+    lr, mu = 0.05, 0.9
+    with G.Context(k, d, ld, lr=lr, momentum=mu, sigma=0.1, seed=SEED, noise_kind=G.NOISE_UNIFORM) as ctx:
+        def both(gpu_call, oracle_call, what, exact=True, center=False):
+            x, v, g, c = dev(inp.x), dev(inp.v), dev(inp.g), dev(inp.center)
+            xo, vo, co = inp.x.copy(), inp.v.copy(), inp.center.copy()
+            gpu_call(x, v, g, c)
+            oracle_call(xo, vo, inp.g, co)
+            assert np.isfinite(xo[:, :d]).all(), what
+            (assert_bitwise if exact else assert_ulp_close)(host(x), xo, what + " x")
+            assert_bitwise(host(v), vo, what + " v")
+            if center:
+                assert_bitwise(host(c), co, what + " center")
+            return xo, vo
+
+        xo, vo = both(lambda x, v, g, c: ctx.step_gossip(x, v, g, perm, 0.5),
+                      lambda x, v, g, c: oracle.step_gossip(x, v, g, lr, mu, 0.5, perm, n=d), "gossip")
+        assert _has_subnormals(xo[:, :d]) and _has_subnormals(vo[:, :d])       # subnormal results exist and matched
+        assert (xo[:, :d] == 0).any()
+        both(lambda x, v, g, c: ctx.step_gossip(x, v, g, perm, 0.3),
+             lambda x, v, g, c: oracle.step_gossip(x, v, g, lr, mu, 0.3, perm, n=d), "gossip beta 0.3")
+        both(lambda x, v, g, c: ctx.step_gossip_stale(x, v, g, perm, 0.5),
+             lambda x, v, g, c: oracle.step_gossip_ext(x, v, g, lr, mu, 0.5, perm, stale=True, n=d), "stale")
+        both(lambda x, v, g, c: ctx.step_gossip_pull(x, v, g, peer, 0.5),
+             lambda x, v, g, c: oracle.step_gossip(x, v, g, lr, mu, 0.5, peer, n=d), "pull")
+        both(lambda x, v, g, c: ctx.step_allreduce(x, v, g),
+             lambda x, v, g, c: oracle.step_allreduce(x, v, g, lr, mu, n=d), "allreduce")
+        both(lambda x, v, g, c: ctx.step_easgd(x, v, g, c, 0.9 / k),
+             lambda x, v, g, c: oracle.step_easgd(x, v, g, c, lr, mu, 0.9 / k, n=d), "easgd", center=True)
+        both(lambda x, v, g, c: ctx.step_local(x, v, g),
+             lambda x, v, g, c: oracle.step_gossip(x, v, g, lr, mu, 0.0, list(range(k)), n=d), "local")
+        both(lambda x, v, g, c: ctx.step_gossip_push(x, v, g, target),
+             lambda x, v, g, c: oracle.step_gossip_push(x, v, g, lr, mu, target, n=d), "push", exact=False)
+        i, j = k - 1, 0
+        both(lambda x, v, g, c: ctx.step_async_tick(x, v, g, i, j, 0.5),
+             lambda x, v, g, c: oracle.async_tick(x, v, g[i].copy(), lr, mu, 0.5, i, j, n=d), "tick")
+        both(lambda x, v, g, c: ctx.step_easgd_tick(x, v, g, c, i, 0.25),
+             lambda x, v, g, c: oracle.easgd_tick(x, v, g[i].copy(), c, lr, mu, 0.25, i, n=d), "easgd tick", center=True)
+        # the synthetic gradient from special x and xstar (uniform noise: no transcendental functions)
+        g = dev(inp.g)
+        ctx.gen_grad(dev(inp.x), dev(inp.h), dev(inp.xstar), g, 9)
+        go = inp.g.copy()
+        oracle.gen_grad(inp.x, inp.h, inp.xstar, go, 0.1, SEED, 9, 1, n=d)
+        assert_bitwise(host(g), go, "gen_grad")
+        # the experiments' local step (weight decay, Nesterov) on the same values
+        ctx.set_local_step(1e-4, True)
+        both(lambda x, v, g, c: ctx.step_gossip(x, v, g, perm, 0.5),
+             lambda x, v, g, c: oracle.step_gossip_ext(x, v, g, lr, mu, 0.5, perm, wd=1e-4, nesterov=True, n=d),
+             "gossip nesterov")
+        both(lambda x, v, g, c: ctx.step_allreduce(x, v, g),
+             lambda x, v, g, c: oracle.step_allreduce_ext(x, v, g, lr, mu, wd=1e-4, nesterov=True, n=d),
+             "allreduce nesterov")
+        both(lambda x, v, g, c: ctx.step_easgd(x, v, g, c, 0.9 / k),
+             lambda x, v, g, c: oracle.step_easgd_ext(x, v, g, c, lr, mu, 0.9 / k, wd=1e-4, nesterov=True, n=d),
+             "easgd nesterov", center=True)
+
+
+def test_special_values_survive_a_fused_generator_trajectory(G, oracle):
+    """20 steps of the generator-fused gossip step from special values, uniform
+    noise: the state leaves the fragile ranges within a few steps, and every
+    step on the way must agree bit for bit."""
+    k, d = 8, 3 * 1024 + 5
+    ld = W.round_up(d, 1024)
+    inp = W.make_special_inputs(k, d, ld, seed=77)
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, sigma=0.1, seed=SEED, noise_kind=G.NOISE_UNIFORM) as ctx:
+        x, v, h, xs = dev(inp.x), dev(inp.v), dev(inp.h), dev(inp.xstar)
+        xo, vo, go = inp.x.copy(), inp.v.copy(), inp.g.copy()
+        for t in range(20):
+            perm = G.make_perm(SEED, t, k)
+            ctx.step_gossip_fused(x, v, h, xs, perm, t, 0.5)
+            oracle.gen_grad(xo, inp.h, inp.xstar, go, 0.1, SEED, t, 1, n=d)
+            oracle.step_gossip(xo, vo, go, 0.05, 0.9, 0.5, perm, n=d)
+            if t in (0, 1, 5, 19):
+                assert_bitwise(host(x), xo, "x after step %d" % t)
+                assert_bitwise(host(v), vo, "v after step %d" % t)
+
+
+def test_long_segment_table_through_every_kernel(G, oracle):
+    """1500 per-layer tensors: more than the 1024 the kernels stage in LDS, so
+    the step size comes from a binary search in global memory.  Pull (tree
+    walk), stale, push, local step, asynchronous tick, elastic-averaging tick
+    and the generator-fused step -- the kernels beyond gossip / all-reduce /
+    elastic averaging, which the basic segmented test covers."""
+    k, d = 6, 7 * 1024 + 3
+    ld = W.round_up(d, 4)
+    off, sc = W.random_segments(d, 1500, seed=15, align=1)
+    lrc = oracle.expand_lr(0.05, d, off, sc)
+    inp = W.make_inputs(k, d, ld, seed=96)
+    peer = [int(t) for t in oracle.make_targets(SEED, 12, k)]
+    target = [int(t) for t in oracle.make_targets(SEED, 13, k, True)]
+    perm = [int(t) for t in oracle.make_perm(SEED, 14, k)]
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, sigma=0.1, seed=SEED, noise_kind=G.NOISE_UNIFORM,
+                   seg_offsets=off, seg_lr_scale=sc) as ctx:
+        x, v, g, c = dev(inp.x), dev(inp.v), dev(inp.g), dev(inp.center)
+        h, xs = dev(inp.h), dev(inp.xstar)
+        xo, vo, co, go = inp.x.copy(), inp.v.copy(), inp.center.copy(), inp.g.copy()
+        ctx.step_gossip_pull(x, v, g, peer, 0.5)
+        oracle.step_gossip(xo, vo, inp.g, lrc, 0.9, 0.5, peer, n=d)
+        ctx.step_gossip_stale(x, v, g, perm, 0.25)
+        oracle.step_gossip_ext(xo, vo, inp.g, lrc, 0.9, 0.25, perm, stale=True, n=d)
+        ctx.step_local(x, v, g)
+        oracle.step_gossip(xo, vo, inp.g, lrc, 0.9, 0.0, list(range(k)), n=d)
+        ctx.step_async_tick(x, v, g, 2, 4, 0.5)
+        oracle.async_tick(xo, vo, inp.g[2].copy(), lrc, 0.9, 0.5, 2, 4, n=d)
+        ctx.step_easgd_tick(x, v, g, c, 3, 0.2)
+        oracle.easgd_tick(xo, vo, inp.g[3].copy(), co, lrc, 0.9, 0.2, 3, n=d)
+        ctx.step_gossip_fused(x, v, h, xs, perm, 5, 0.5)
+        oracle.gen_grad(xo, inp.h, inp.xstar, go, 0.1, SEED, 5, 1, n=d)
+        oracle.step_gossip(xo, vo, go, lrc, 0.9, 0.5, perm, n=d)
+        ctx.step_async_tick_fused(x, v, h, xs, 1, 0, 6, 0.5)
+        grow = np.zeros(ld, np.float32)
+        oracle.gen_grad_row(xo, inp.h, inp.xstar, grow, 1, 0.1, SEED, 6, 1, n=d)
+        oracle.async_tick(xo, vo, grow, lrc, 0.9, 0.5, 1, 0, n=d)
+        assert_bitwise(host(x), xo, "x")
+        assert_bitwise(host(v), vo, "v")
+        assert_bitwise(host(c), co, "center")
+        ctx.step_gossip_push(x, v, g, target)
+        oracle.step_gossip_push(xo, vo, inp.g, lrc, 0.9, target, n=d)
+        assert_ulp_close(host(x)[:, :d], xo[:, :d], "push x")
+        assert_bitwise(host(v), vo, "push v")

@@ -128,3 +128,37 @@ def test_gen_grad_uniform_exact_on_special_values(oracle):
         t1 = brute.f32_sub(F(inp.x[i, j]), F(inp.xstar[j]))
         t2 = brute.f32_mul(F(sigma), brute.uniform_noise_exact(word))
         assert _same(g[i, j], brute.f32_fma(F(inp.h[j]), t1, t2)), (i, j)
+
+
+def test_extended_rules_reduce_to_the_boxed_ones_bitwise_on_special_values(oracle):
+    """wd = 0, heavy ball, fresh parameters: the extended functions are the
+    boxed rules bit for bit, the sign of a zero gradient included (a decay term
+    written as + 0 * x would turn g = -0 into +0 and flip the sign of a zero
+    momentum buffer)."""
+    k, n = 5, 400
+    lr, mu, beta, alpha = np.float32(0.05), np.float32(0.9), np.float32(0.5), np.float32(0.15)
+    inp = W.make_special_inputs(k, n, seed=600)
+    peer = [3, 0, 0, 4, 1]
+    eq = lambda a, b: np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    xa, va = inp.x.copy(), inp.v.copy()
+    xb, vb = inp.x.copy(), inp.v.copy()
+    oracle.step_gossip(xa, va, inp.g, lr, mu, beta, peer)
+    oracle.step_gossip_ext(xb, vb, inp.g, lr, mu, beta, peer)
+    assert eq(xa, xb) and eq(va, vb)
+    xa, va = inp.x.copy(), inp.v.copy()
+    xb, vb = inp.x.copy(), inp.v.copy()
+    oracle.step_allreduce(xa, va, inp.g, lr, mu)
+    oracle.step_allreduce_ext(xb, vb, inp.g, lr, mu)
+    assert eq(xa, xb) and eq(va, vb)
+    xa, va, ca = inp.x.copy(), inp.v.copy(), inp.center.copy()
+    xb, vb, cb = inp.x.copy(), inp.v.copy(), inp.center.copy()
+    oracle.step_easgd(xa, va, inp.g, ca, lr, mu, alpha)
+    oracle.step_easgd_ext(xb, vb, inp.g, cb, lr, mu, alpha)
+    assert eq(xa, xb) and eq(va, vb) and eq(ca, cb)
+    # push-gossip and the tick have one implementation each (extended); their momentum buffers must be the boxed step's
+    xb, vb = inp.x.copy(), inp.v.copy()
+    oracle.step_gossip_push(xb, vb, inp.g, lr, mu, peer)
+    xa, va = inp.x.copy(), inp.v.copy()
+    oracle.step_gossip(xa, va, inp.g, lr, mu, 0.0, list(range(k)))
+    assert eq(va, vb)
+    assert (np.signbit(inp.g) & (inp.g == 0)).any()            # the case is present: negative-zero gradients
