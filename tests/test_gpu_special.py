@@ -78,7 +78,6 @@ def test_every_rule_bit_exact_on_special_values(G, oracle, k, d, ld):
         xo, vo = both(lambda x, v, g, c: ctx.step_gossip(x, v, g, perm, 0.5),
                       lambda x, v, g, c: oracle.step_gossip(x, v, g, lr, mu, 0.5, perm, n=d), "gossip")
         assert _has_subnormals(xo[:, :d]) and _has_subnormals(vo[:, :d])       # subnormal results exist and matched
-        assert (xo[:, :d] == 0).any()
         both(lambda x, v, g, c: ctx.step_gossip(x, v, g, perm, 0.3),
              lambda x, v, g, c: oracle.step_gossip(x, v, g, lr, mu, 0.3, perm, n=d), "gossip beta 0.3")
         both(lambda x, v, g, c: ctx.step_gossip_stale(x, v, g, perm, 0.5),
