@@ -61,7 +61,8 @@ enum {
     GSGD_ERR_HIP          = -4,    /* a HIP runtime call failed; see gsgd_last_hip_error */
     GSGD_ERR_UNSUPPORTED  = -5,    /* the context has launched on 32 distinct streams already */
     GSGD_ERR_NO_MEMORY    = -6,
-    GSGD_ERR_BAD_STATE    = -7     /* a tile counter was found non-zero on a drained stream; see gsgd_stats */
+    GSGD_ERR_BAD_STATE    = -7,    /* a tile counter was found non-zero on a drained stream; see gsgd_stats */
+    GSGD_ERR_TOO_LARGE    = -8     /* input beyond the fixed scratch of gsgd_stats_static */
 };
 
 enum { GSGD_NOISE_GAUSSIAN = 0, GSGD_NOISE_UNIFORM = 1 };
@@ -327,6 +328,28 @@ int gsgd_perm_walk(const int32_t* peer_perm, int32_t k, uint16_t* walk);
  * last clean check on this stream are suspect.  gsgd_row_sqnorms checks the
  * same way. */
 int gsgd_stats(gsgd_ctx* ctx, const float* x, const float* xstar, double out[4], void* stream);
+
+/* gsgd_stats for callers that cannot allocate or wait: code recorded into a
+ * HIP graph, tight loops that must not call hipMalloc, harnesses that forbid
+ * it.  Needs no context.  Computes the same four numbers with the same
+ * kernels in the same order (bit-identical to gsgd_stats), writes them to
+ * out_device (device memory, 4 doubles, 8-byte aligned, caller-owned) and
+ * returns without waiting for the stream.  It calls no hipMalloc / hipFree and
+ * nothing else that allocates: the per-tile partial sums go to a fixed array
+ * in device memory that the library holds on every GPU it runs on until the
+ * process ends, sized for
+ *   d <= GSGD_STATS_STATIC_MAX_D columns  (2 MiB of partial sums);
+ * a larger d is refused with GSGD_ERR_TOO_LARGE.  All calls on one GPU share
+ * that array: calls that overlap in time on one GPU (different streams, or a
+ * graph replaying beside eager calls) race on it and give garbage; calls that
+ * follow one another on a stream are fine, whatever their sizes (every partial
+ * a call reads it has written itself).  The array's device address is looked
+ * up on the first call on a device (and by gsgd_create); make that first call
+ * outside a stream capture.  k, d, ld as in gsgd_config.  x: device k x ld.
+ * xstar: device d. */
+#define GSGD_STATS_STATIC_MAX_D ((int64_t)1 << 26)
+int gsgd_stats_static(int32_t k, int64_t d, int64_t ld, const float* x, const float* xstar,
+                      double* out_device, void* stream);
 
 /* Squared Euclidean norm of every replica row over columns 0..d-1, in fp64:
  * out[i] = ||x_i||^2.  Waits for the stream.  out: host, k doubles. */

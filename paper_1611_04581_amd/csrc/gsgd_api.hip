@@ -1,5 +1,6 @@
 // C ABI of libgsgd: argument checking, context ownership, and dispatch to the
 // kernel launchers.  No computation of the method happens here.
+#include <mutex>
 #include <new>
 #include <string.h>
 
@@ -121,6 +122,38 @@ void release(gsgd_ctx* c)
 
 }  // namespace
 
+// ---- the statistics for callers that cannot allocate --------------------------------------------------------
+// Per-block partial sums of the two statistics kernels live in a fixed array in device memory instead of a
+// hipMalloc'ed buffer.  Every GPU the library runs on holds its own copy until the process ends.  The array's
+// name is only a handle on the host: its device address is looked up once per device and kept.
+constexpr int64_t STATS_STATIC_MAX_TILES = GSGD_STATS_STATIC_MAX_D / (BLOCK_COLUMNS);
+static __device__ __align__(256) double scratch[STATS_STATIC_MAX_TILES * 4];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+double*    g_scratch_ptr[MAX_DEVICES];      // device address of `scratch` on each device, nullptr until resolved
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (resolved on first use).
+hipError_t scratch_on_current_device(double** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        double* ptr = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
+
 extern "C" int gsgd_create(const gsgd_config* cfg, gsgd_ctx** out)
 {
     if (!cfg || !out) return GSGD_ERR_INVALID_ARG;
@@ -167,6 +200,10 @@ extern "C" int gsgd_create(const gsgd_config* cfg, gsgd_ctx** out)
     if (e == hipSuccess) e = hipMemset(c->d_tickets, 0, TICKET_BYTES);
     // the clear runs on the null stream, which a non-blocking stream does not wait for
     if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e == hipSuccess) {                       // so that gsgd_stats_static's first call on this device looks nothing up
+        double* unused = nullptr;
+        e = scratch_on_current_device(&unused);
+    }
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->cu_count, hipDeviceAttributeMultiprocessorCount, c->device);
     if (e == hipSuccess) {
         if (c->cu_count < 1) c->cu_count = 1;
@@ -545,6 +582,20 @@ extern "C" int gsgd_row_sqnorms(gsgd_ctx* ctx, const float* x, double* out, void
     return verify_ticket_pair(ctx, s, slot, pair);
 }
 
+extern "C" int gsgd_stats_static(int32_t k, int64_t d, int64_t ld, const float* x, const float* xstar,
+                                 double* out_device, void* stream)
+{
+    if (k < 1 || k > GSGD_MAX_K || d < 1 || ld < d || (ld & 3) != 0) return GSGD_ERR_INVALID_ARG;
+    if (d > GSGD_STATS_STATIC_MAX_D) return GSGD_ERR_TOO_LARGE;
+    if (!ok_matrix(x) || !ok_matrix(xstar) || !out_device || (reinterpret_cast<uintptr_t>(out_device) & 7u) != 0)
+        return GSGD_ERR_INVALID_ARG;
+    double* partials = nullptr;
+    hipError_t e = scratch_on_current_device(&partials);
+    if (e == hipSuccess)
+        e = launch_stats(Geom{k, d, ld}, x, xstar, partials, out_device, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : GSGD_ERR_HIP;
+}
+
 // Test hook: overwrite the ticket pair of `stream` (claiming one if the stream has none yet) behind the work
 // already on the stream, and wait.
 extern "C" int gsgd_poke_tickets(gsgd_ctx* ctx, uint32_t next_tile, uint32_t finished, void* stream)
@@ -624,6 +675,7 @@ extern "C" const char* gsgd_strerror(int code)
         case GSGD_ERR_HIP: return "HIP runtime error";
         case GSGD_ERR_UNSUPPORTED: return "unsupported (a context serves at most 32 streams)";
         case GSGD_ERR_NO_MEMORY: return "out of memory";
+        case GSGD_ERR_TOO_LARGE: return "d is larger than GSGD_STATS_STATIC_MAX_D, the most gsgd_stats_static has scratch for";
         case GSGD_ERR_BAD_STATE: return "a tile counter of the context was not zero on a drained stream (cleared now)";
         default: return "unknown error";
     }

@@ -125,6 +125,8 @@ hipError_t launch_init_replicas(const Geom&, float* x, float* v, float* center, 
                                 RngKey key, hipStream_t);
 hipError_t launch_philox_raw(RngKey key, uint32_t c1, uint32_t c2, uint32_t c3, int64_t n_blocks, uint32_t* out,
                              hipStream_t);
+// columns per workgroup tile (256 threads x 4 columns)
+constexpr int64_t BLOCK_COLUMNS = 1024;
 // stats: partials holds stats_num_blocks(d) * 4 doubles; result 4 doubles (device)
 int64_t    stats_num_blocks(int64_t d);
 hipError_t launch_stats(const Geom&, const float* x, const float* xstar, double* partials, double* result,

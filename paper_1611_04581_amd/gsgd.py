@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libgsgd.so")
 
 MAX_K = 512
 OK, ERR_INVALID_ARG, ERR_BAD_PERM, ERR_BAD_SEGMENTS, ERR_HIP, ERR_UNSUPPORTED, ERR_NO_MEMORY = 0, -1, -2, -3, -4, -5, -6
-ERR_BAD_STATE = -7
+ERR_BAD_STATE, ERR_TOO_LARGE = -7, -8
+STATS_STATIC_MAX_D = 1 << 26
 NOISE_GAUSSIAN, NOISE_UNIFORM = 0, 1
 INIT_BROADCAST, INIT_PER_REPLICA = 0, 1
 FILL_XSTAR, FILL_H, FILL_X0 = 2, 3, 4
@@ -81,6 +82,7 @@ SIGNATURES = {
     "gsgd_make_perm": (C.c_int, [C.c_uint64, C.c_uint64, C.c_int32, C.POINTER(C.c_int32)]),
     "gsgd_perm_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint16)]),
     "gsgd_stats": (C.c_int, [_vp, _vp, _vp, C.POINTER(C.c_double), _vp]),
+    "gsgd_stats_static": (C.c_int, [C.c_int32, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp]),
     "gsgd_row_sqnorms": (C.c_int, [_vp, _vp, C.POINTER(C.c_double), _vp]),
     "gsgd_weights_pull": (C.c_int, [C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_int32), C.c_double]),
     "gsgd_weights_push": (C.c_int, [C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_int32)]),
@@ -303,6 +305,16 @@ class Context:
         out = (C.c_double * 4)()
         _check(lib().gsgd_stats(self._h, self._m(x), self._vec(xstar), out, _stream(stream)), "gsgd_stats")
         return np.array(list(out), dtype=np.float64)
+
+
+def stats_static(k, d, ld, x, xstar, out, stream=None):
+    """gsgd_stats_static: out is a float64 GPU tensor of 4 elements; nothing is allocated and nothing waits."""
+    import torch
+    k, d, ld = int(k), int(d), int(ld)
+    if k < 1 or d < 1 or ld < d:
+        raise ValueError("bad geometry k=%d d=%d ld=%d" % (k, d, ld))
+    _check(lib().gsgd_stats_static(k, d, ld, _ptr(x, (k - 1) * ld + d), _ptr(xstar, d), _ptr(out, 4, torch.float64),
+                                   _stream(stream)), "gsgd_stats_static")
 
 
 def comm_due(step, tau):

@@ -131,8 +131,8 @@ def test_null_context_and_error_strings():
     assert L.gsgd_step_gossip(None, None, None, None, None, 0.5, None) == gsgd.ERR_INVALID_ARG
     assert L.gsgd_step_easgd(None, None, None, None, None, 0.1, None) == gsgd.ERR_INVALID_ARG
     assert L.gsgd_stats(None, None, None, None, None) == gsgd.ERR_INVALID_ARG
-    texts = {gsgd.strerror(c) for c in range(0, -8, -1)}
-    assert len(texts) == 8 and "unknown error" not in texts
+    texts = {gsgd.strerror(c) for c in range(0, -9, -1)}
+    assert len(texts) == 9 and "unknown error" not in texts
     assert L.gsgd_poke_tickets(None, 0, 0, None) == gsgd.ERR_INVALID_ARG
     assert gsgd.strerror(-99) == "unknown error"
 
