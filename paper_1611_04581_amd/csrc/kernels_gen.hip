@@ -11,39 +11,43 @@ namespace gsgd {
 
 constexpr int GEN_ROWS_IN_FLIGHT = 4;
 
+template <bool FULL, int NOISE>
+__device__ __forceinline__
+void gen_grad_body(const Geom& geo, const Quad& qd, const float* __restrict__ x, const float* __restrict__ h,
+                   const float* __restrict__ xstar, float* __restrict__ g, float sigma, RngKey key, uint32_t step)
+{
+    const int valid = FULL ? 4 : qd.valid;
+    const f32x4 h4 = load_quad_cached<FULL>(h + qd.col, valid);
+    const f32x4 xs4 = load_quad_cached<FULL>(xstar + qd.col, valid);
+    const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
+    for_row_batches<GEN_ROWS_IN_FLIGHT>(geo.k, [&](auto n, int i0) {
+        constexpr int N = decltype(n)::value;
+        f32x4 X[N];
+#pragma unroll
+        for (int u = 0; u < N; ++u)
+            X[u] = load_quad<FULL>(x + static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col + qd.lane_col, valid);
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, static_cast<uint32_t>(i0 + u), step, STREAM_GRAD,
+                                                         key.k0, key.k1));
+            const f32x4 t1 = X[u] - xs4;
+            const f32x4 t2 = sigma * xi;
+            store_quad<FULL>(g + static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col + qd.lane_col, fma4(h4, t1, t2), valid);
+        }
+    });
+}
+
 template <int NOISE>
 __global__ __launch_bounds__(BLOCK)
 void gen_grad_kernel(Geom geo, const float* __restrict__ x, const float* __restrict__ h,
                      const float* __restrict__ xstar, float* __restrict__ g,
-                     float sigma, RngKey key, uint32_t step, uint32_t* __restrict__ tickets, uint32_t n_tiles)
+                     float sigma, RngKey key, uint32_t step, Persist pst, uint32_t n_tiles)
 {
-  for_each_tile(tickets, n_tiles, [&](uint32_t tile) {
-    const Quad qd = quad_of_tile(tile, geo.d);
-    if (qd.valid == 0) return;            // leaves the lambda only; the tile loop goes on for the whole workgroup
-    const int valid = qd.valid;
-    const f32x4 h4 = load_quad_cached(h + qd.col, valid);
-    const f32x4 xs4 = load_quad_cached(xstar + qd.col, valid);
-    const float* xq = x + qd.col;
-    float* gq = g + qd.col;
-    const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
-    const int k = geo.k;
-    for (int i0 = 0; i0 < k; i0 += GEN_ROWS_IN_FLIGHT) {
-        f32x4 X[GEN_ROWS_IN_FLIGHT];
-#pragma unroll
-        for (int u = 0; u < GEN_ROWS_IN_FLIGHT; ++u)
-            if (i0 + u < k) X[u] = load_quad(xq + static_cast<int64_t>(i0 + u) * geo.ld, valid);
-#pragma unroll
-        for (int u = 0; u < GEN_ROWS_IN_FLIGHT; ++u) {
-            if (i0 + u < k) {
-                const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, static_cast<uint32_t>(i0 + u), step,
-                                                             STREAM_GRAD, key.k0, key.k1));
-                const f32x4 t1 = X[u] - xs4;
-                const f32x4 t2 = sigma * xi;
-                store_quad(gq + static_cast<int64_t>(i0 + u) * geo.ld, fma4(h4, t1, t2), valid);
-            }
-        }
-    }
-  });
+    for_each_tile(pst, n_tiles, [&](uint32_t tile) {
+        const Quad qd = quad_of_tile(tile, geo.d);
+        if (tile_is_full(qd, geo.d)) gen_grad_body<true, NOISE>(geo, qd, x, h, xstar, g, sigma, key, step);
+        else if (qd.valid > 0) gen_grad_body<false, NOISE>(geo, qd, x, h, xstar, g, sigma, key, step);
+    });
 }
 
 // xstar ~ N(0,1), x0 ~ N(0,1), h = fma(0.9, u, 0.1) ~ U(0.1, 1); replica and
@@ -133,10 +137,10 @@ hipError_t launch_gen_grad(const Geom& geo, const float* x, const float* h, cons
     const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
     if (noise_kind == GSGD_NOISE_UNIFORM)
         hipLaunchKernelGGL(gen_grad_kernel<GSGD_NOISE_UNIFORM>, dim3(width), dim3(BLOCK), 0, stream,
-                           geo, x, h, xstar, g, sigma, key, step, p.tickets, tiles);
+                           geo, x, h, xstar, g, sigma, key, step, p, tiles);
     else
         hipLaunchKernelGGL(gen_grad_kernel<GSGD_NOISE_GAUSSIAN>, dim3(width), dim3(BLOCK), 0, stream,
-                           geo, x, h, xstar, g, sigma, key, step, p.tickets, tiles);
+                           geo, x, h, xstar, g, sigma, key, step, p, tiles);
     return hipGetLastError();
 }
 
