@@ -5,14 +5,21 @@ ResNet-50-sized vectors (d = 25,557,032 fp32) with k = 32 replicas, a fresh
 seeded peer permutation per step, x / v / g resident in HBM.  One JSON line on
 stdout; progress on stderr.
 
-Also reported in the same line: the roofline of the dominant kernel (the fused
-SGD+momentum+mix kernel, HBM-bound, 20 algorithmic bytes per replica-element),
-the cost of the synthetic-gradient generator and of the full simulated
-iteration, and the CPU oracle timed on a bounded sample of the same workload.
+In the same line:
+  roofline      the dominant kernel (fused SGD + momentum + mix, HBM-bound, 20
+                algorithmic bytes per replica-element) over the K timed steps,
+                plus the spread of the same measurement over fresh allocations
+                of x / v / g (the rate depends on where the driver places them);
+  extras        the synthetic-gradient generator and the generator-fused step
+                with their ALU-only and HBM-only times, the other gossip forms
+                at the metric shape, the other benchmark configurations as short
+                legs, and what a plain copy gets on this box;
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -21,28 +28,145 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
-BYTES_PER_REPLICA_ELEMENT = {   # algorithmic traffic of each kernel, fp32
-    "gossip": 20.0,             # read x, v, g; write x, v
-    "allreduce": 20.0,
-    "easgd": 20.0,              # + 8/k for the centre, added below
-}
-# HBM bytes per launch of the gossip kernel at the benchmark shape, from
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of known
-# size (see profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/gossip_step_kernel_gossip_r50.md: FETCH_SIZE 4,792,017.0 x 2.000 KiB + WRITE_SIZE 6,390,054.1 KiB
-    "gossip_r50": (4792017.0 * 2.0 + 6390054.1) * 1024.0,
-}
+SIMDS = 1024                   # 256 compute units x 4 SIMDs
+PEAK_CLOCK_HZ = 2.4e9
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per dispatch, each scaled by what the
+# same counter reads for a plain copy of known size).  These come from the profile runs summarised under profiles/,
+# NOT from the run that prints them: a bench run cannot read hardware counters.  None = no such profile yet.
+TRAFFIC_FROM_PROFILES = {
+    # name: (bytes per launch, source)
+    "gossip_r50": ((4792017.0 * 2.0 + 6390054.1) * 1024.0, "profiles/gossip_step_kernel_gossip_r50.md"),
+}
 
 KERNEL_OF_RULE = {"gossip": "gossip_step_kernel", "gossip_stale": "gossip_step_kernel (stale)",
                   "gossip_pull": "gossip_step_kernel (tree walk)", "gossip_push": "push_step_kernel",
-                  "allreduce": "allreduce_step_kernel", "easgd": "easgd_step_kernel",
+                  "allreduce": "allreduce_step_kernel", "easgd": "easgd_step_kernel", "local": "local_step_kernel",
                   "async_tick": "async_tick_kernel (generator fused, one launch per tick)"}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def bytes_per_replica_element(rule, k):
+    """Algorithmic HBM traffic of one step, fp32: x, v, g read and x, v written (+ the centre for elastic averaging)."""
+    return 20.0 + (8.0 / k if rule == "easgd" else 0.0)
+
+
+class Run:
+    """One configuration with its state resident on the GPU."""
+
+    def __init__(self, gsgd, W, cfg, launch_width=0):
+        import torch
+        self.gsgd, self.cfg, self.torch = gsgd, cfg, torch
+        k, d = cfg.k, cfg.d
+        self.k, self.d, self.ld = k, d, W.round_up(d, 1024)
+        seg = {}
+        if cfg.layout:
+            off, sc, _ = W.resnet_layout(cfg.layout)
+            seg = dict(seg_offsets=off, seg_lr_scale=sc)
+        self.ctx = gsgd.Context(k, d, self.ld, lr=cfg.lr, momentum=cfg.momentum, sigma=cfg.sigma, seed=cfg.seed,
+                                noise_kind=gsgd.NOISE_GAUSSIAN, **seg)
+        if launch_width:
+            for kern in range(gsgd.KERNEL_COUNT):
+                self.ctx.set_launch_width(kern, launch_width)
+        self.h = torch.empty(self.ld, dtype=torch.float32, device="cuda")
+        self.xstar = torch.empty_like(self.h)
+        self.x0 = torch.empty_like(self.h)
+        self.center = torch.empty_like(self.h)
+        self.ctx.fill(self.h, gsgd.FILL_H)
+        self.ctx.fill(self.xstar, gsgd.FILL_XSTAR)
+        self.ctx.fill(self.x0, gsgd.FILL_X0)
+        self.x = self.v = self.g = None
+        self.allocate()
+        self.ctx.set_local_step(cfg.weight_decay, cfg.nesterov)
+
+    def allocate(self):
+        """Fresh device allocations of x, v, g (the old ones go back to the driver first), initialised as the
+        algorithms start: every replica at x0, momentum zero, one gradient drawn."""
+        torch = self.torch
+        self.x = self.v = self.g = None
+        torch.cuda.empty_cache()
+        self.x = torch.empty((self.k, self.ld), dtype=torch.float32, device="cuda")
+        self.v = torch.empty_like(self.x)
+        self.g = torch.empty_like(self.x)
+        self.ctx.init_replicas(self.x, self.v, self.center, self.x0, self.gsgd.INIT_BROADCAST)
+        self.ctx.gen_grad(self.x, self.h, self.xstar, self.g, 0)
+        torch.cuda.synchronize()
+
+    def step(self, t):
+        gsgd, cfg, ctx, x, v, g = self.gsgd, self.cfg, self.ctx, self.x, self.v, self.g
+        rule = cfg.rule if gsgd.comm_due(t, cfg.tau) else "local"
+        if rule == "gossip":
+            ctx.step_gossip(x, v, g, gsgd.make_perm(cfg.seed, t, self.k), cfg.beta)
+        elif rule == "gossip_stale":
+            ctx.step_gossip_stale(x, v, g, gsgd.make_perm(cfg.seed, t, self.k), cfg.beta)
+        elif rule == "gossip_pull":
+            ctx.step_gossip_pull(x, v, g, gsgd.make_targets(cfg.seed, t, self.k), cfg.beta)
+        elif rule == "gossip_push":
+            ctx.step_gossip_push(x, v, g, gsgd.make_targets(cfg.seed, t, self.k, True))
+        elif rule == "local":
+            ctx.step_local(x, v, g)
+        elif rule == "async_tick":                      # k ticks of the one-node-per-tick model = k replica-steps
+            ctx.run_async_ticks(x, v, self.h, self.xstar, t * self.k, self.k, cfg.beta)
+        elif rule == "allreduce":
+            ctx.step_allreduce(x, v, g)
+        else:
+            ctx.step_easgd(x, v, g, self.center, cfg.alpha_e)
+
+    def timed(self, fn, n, t_start=0):
+        """n calls of fn(t) between two HIP events on the stream the library launches on (torch's current stream),
+        bracketed by synchronize; returns (wall seconds, HIP-event seconds)."""
+        torch = self.torch
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        w0 = time.perf_counter()
+        e0.record()
+        for t in range(t_start, t_start + n):
+            fn(t)
+        e1.record()
+        torch.cuda.synchronize()
+        w1 = time.perf_counter()
+        return w1 - w0, e0.elapsed_time(e1) * 1e-3
+
+    def algorithmic_bytes(self):
+        cfg = self.cfg
+        if cfg.rule == "async_tick":
+            # per tick and element of the ticking row: x_i, v_i, h, xstar and the peer's x read (the peer's only when
+            # j != i, probability 1 - 1/k), x_i and v_i written
+            return (28.0 - 4.0 / self.k) * self.d
+        return bytes_per_replica_element(cfg.rule, self.k) * self.k * self.d
+
+    def launches_per_step(self):
+        return self.k if self.cfg.rule == "async_tick" else 1
+
+    def close(self):
+        self.x = self.v = self.g = None
+        self.ctx.close()
+        self.torch.cuda.empty_cache()
+
+
+def short_leg(gsgd, W, name, warmup=5, steps=30, repeats=3):
+    """One of the other benchmark configurations as a short leg: median kernel time of `repeats` timed runs."""
+    cfg = W.CONFIGS[name]
+    run = Run(gsgd, W, cfg)
+    try:
+        for t in range(warmup):
+            run.step(t)
+        ms = []
+        for r in range(repeats):
+            _, ev = run.timed(run.step, steps, warmup + r * steps)
+            ms.append(ev / (steps * run.launches_per_step()) * 1e3)
+        med = statistics.median(ms)
+        out = {"rule": cfg.rule, "k": cfg.k, "d": cfg.d, "layout": cfg.layout or "flat", "kernel_ms": med,
+               "kernel_ms_min": min(ms), "kernel_ms_max": max(ms),
+               "replica_steps_per_s": cfg.k / (med * run.launches_per_step() * 1e-3)}
+        if name != "tiny":           # the tiny configuration lives in cache and is launch-bound: no bandwidth figure
+            out["frac_of_hbm_peak"] = run.algorithmic_bytes() / (med * 1e-3) / 1e9 / HBM_PEAK_GBS
+        return out
+    finally:
+        run.close()
 
 
 def main():
@@ -51,9 +175,12 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", default="gossip_r50")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="fresh allocations of x / v / g over which the kernel is timed (the first is the K-step run)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle baseline (0 = skip)")
     ap.add_argument("--no-extras", action="store_true", help="time only the metric kernel")
     ap.add_argument("--no-fused", action="store_true", help="skip the fused-generator extra")
+    ap.add_argument("--no-legs", action="store_true", help="skip the other benchmark configurations")
     ap.add_argument("--launch-width", type=int, default=0,
                     help="persistent workgroups per streaming kernel (0 = the library's default)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -71,33 +198,11 @@ def main():
         sys.exit("bench.py: no GPU visible; the library has no CPU fallback")
     torch.cuda.set_device(0)
     cfg = W.CONFIGS[args.config]
-    k, d = cfg.k, cfg.d
-    ld = W.round_up(d, 1024)
-    seg = {}
-    if cfg.layout:
-        off, sc, _ = W.resnet_layout(cfg.layout)
-        seg = dict(seg_offsets=off, seg_lr_scale=sc)
     K, Wm = args.steps, args.warmup
+    run = Run(gsgd, W, cfg, args.launch_width)
+    k, d, ld = run.k, run.d, run.ld
+    ctx, x, v, g, h, xstar = run.ctx, run.x, run.v, run.g, run.h, run.xstar
     log("config %s: rule=%s k=%d d=%d ld=%d steps=%d warmup=%d" % (cfg.name, cfg.rule, k, d, ld, K, Wm))
-
-    ctx = gsgd.Context(k, d, ld, lr=cfg.lr, momentum=cfg.momentum, sigma=cfg.sigma, seed=cfg.seed,
-                       noise_kind=gsgd.NOISE_GAUSSIAN, **seg)
-    if args.launch_width:
-        for kern in range(gsgd.KERNEL_COUNT):
-            ctx.set_launch_width(kern, args.launch_width)
-    x = torch.empty((k, ld), dtype=torch.float32, device="cuda")
-    v = torch.empty_like(x)
-    g = torch.empty_like(x)
-    h = torch.empty(ld, dtype=torch.float32, device="cuda")
-    xstar = torch.empty_like(h)
-    x0 = torch.empty_like(h)
-    center = torch.empty_like(h)
-    ctx.fill(h, gsgd.FILL_H)
-    ctx.fill(xstar, gsgd.FILL_XSTAR)
-    ctx.fill(x0, gsgd.FILL_X0)
-    ctx.init_replicas(x, v, center, x0, gsgd.INIT_BROADCAST)
-    ctx.gen_grad(x, h, xstar, g, 0)
-    torch.cuda.synchronize()
     if args.calibrate_copy:
         # reads k*ld*4 bytes and writes k*ld*4 bytes; g is regenerated right after
         torch.mul(x, 1.0, out=g)
@@ -106,59 +211,31 @@ def main():
         ctx.gen_grad(x, h, xstar, g, 0)
         torch.cuda.synchronize()
 
-    ctx.set_local_step(cfg.weight_decay, cfg.nesterov)
-
-    def one_step(t):
-        rule = cfg.rule if gsgd.comm_due(t, cfg.tau) else "local"
-        if rule == "gossip":
-            ctx.step_gossip(x, v, g, gsgd.make_perm(cfg.seed, t, k), cfg.beta)
-        elif rule == "gossip_stale":
-            ctx.step_gossip_stale(x, v, g, gsgd.make_perm(cfg.seed, t, k), cfg.beta)
-        elif rule == "gossip_pull":
-            ctx.step_gossip_pull(x, v, g, gsgd.make_targets(cfg.seed, t, k), cfg.beta)
-        elif rule == "gossip_push":
-            ctx.step_gossip_push(x, v, g, gsgd.make_targets(cfg.seed, t, k, True))
-        elif rule == "local":
-            ctx.step_local(x, v, g)
-        elif rule == "async_tick":                      # k ticks of the one-node-per-tick model = k replica-steps
-            ctx.run_async_ticks(x, v, h, xstar, t * k, k, cfg.beta)
-        elif rule == "allreduce":
-            ctx.step_allreduce(x, v, g)
-        else:
-            ctx.step_easgd(x, v, g, center, cfg.alpha_e)
-
-    def timed(fn, n, t_start):
-        """n calls of fn(t) bracketed by synchronize; returns (wall seconds, HIP-event seconds)."""
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        w0 = time.perf_counter()
-        e0.record()
-        for t in range(t_start, t_start + n):
-            fn(t)
-        e1.record()
-        torch.cuda.synchronize()
-        w1 = time.perf_counter()
-        return w1 - w0, e0.elapsed_time(e1) * 1e-3
-
     # ---- the metric: K step calls on resident x, v, g -----------------------------------
     for t in range(Wm):
-        one_step(t)
-    wall, ev = timed(one_step, K, Wm)
+        run.step(t)
+    wall, ev = run.timed(run.step, K, Wm)
     ms_per_step = wall / K * 1e3
     value = k * K / wall
-    bpe = BYTES_PER_REPLICA_ELEMENT.get(cfg.rule, 20.0) + (8.0 / k if cfg.rule == "easgd" else 0.0)
-    alg_bytes = bpe * k * d
-    kern_s = ev / K                                  # one kernel per step in the timed region
-    if cfg.rule == "async_tick":
-        # per tick and element of the ticking row: x_i, v_i, h, xstar and the peer's x read (the peer's only when
-        # j != i, probability 1 - 1/k), x_i and v_i written; k launches per step
-        alg_bytes = (28.0 - 4.0 / k) * d
-        kern_s = ev / (K * k)
+    alg_bytes = run.algorithmic_bytes()
+    kern_s = ev / (K * run.launches_per_step())      # one kernel per launch in the timed region
     achieved = alg_bytes / kern_s / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(cfg.name)
     log("step: %.3f ms wall, %.3f ms by HIP events -> %.0f replica-steps/s, %.0f GB/s algorithmic (%.1f%% of peak)"
         % (ms_per_step, kern_s * 1e3, value, achieved, 100 * achieved / HBM_PEAK_GBS))
 
+    # ---- the same kernel on fresh allocations: the rate depends on the physical placement ----
+    fracs = [achieved / HBM_PEAK_GBS]
+    n_rep = max(10, min(K, 100))
+    for r in range(1, max(1, args.repeats)):
+        run.allocate()
+        for t in range(10):
+            run.step(t)
+        _, ev_r = run.timed(run.step, n_rep, 10)
+        fracs.append(alg_bytes / (ev_r / (n_rep * run.launches_per_step())) / 1e9 / HBM_PEAK_GBS)
+        log("  fresh allocation %d: %.1f%% of peak" % (r, 100 * fracs[-1]))
+    x, v, g = run.x, run.v, run.g
+
+    traffic, traffic_source = TRAFFIC_FROM_PROFILES.get(cfg.name, (None, None))
     out = {
         "metric": "replica-steps/sec + achieved HBM GB/s, gossip step, ResNet-50-size d, k=32" if cfg.name == "gossip_r50"
                   else "replica-steps/sec, %s step" % cfg.rule,
@@ -171,40 +248,77 @@ def main():
                    "beta": cfg.beta, "sigma": cfg.sigma, "layout": cfg.layout or "flat"},
         "roofline": {"bound": "hbm", "kernel": KERNEL_OF_RULE[cfg.rule], "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kern_s * 1e3},
+                     "traffic_source": (traffic_source + " (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by a "
+                                        "plain copy of known size; a separate profile run, not this run)")
+                                       if traffic_source else None,
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kern_s * 1e3,
+                     "fresh_allocations": {"n": len(fracs), "steps_each": [K] + [n_rep] * (len(fracs) - 1),
+                                           "frac_median": statistics.median(fracs), "frac_min": min(fracs),
+                                           "frac_max": max(fracs), "frac_each": fracs}},
     }
 
-    # ---- context: generator and full simulated iteration --------------------------------
+    # ---- context: generator, full simulated iteration, other forms, other configurations -----------
     if not args.no_extras:
         n2 = min(100, max(10, K // 4))
         t_next = Wm + K
-        w_gen, e_gen = timed(lambda t: ctx.gen_grad(x, h, xstar, g, t), n2, t_next)
+        extras = {}
+        # what this machine's memory delivers to a plain device-to-device copy of the same matrices (read 4 B, write 4 B
+        # per element), as context for every fraction here; g is regenerated by the next gen_grad
+        scratch = torch.empty_like(g)
+        _, e_cp = run.timed(lambda t: scratch.copy_(g), 20)
+        copy_gbs = 8.0 * k * ld / (e_cp / 20) / 1e9
+        extras["plain_copy_GBps"] = copy_gbs
+        del scratch
+        torch.cuda.empty_cache()
+
+        # the generator's arithmetic alone (no memory traffic): the ALU side of the generator kernels' roofline
+        wgs, iters = 2048, 512
+        probe_out = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+        ctx.noise_alu_probe(wgs, 8, probe_out)
+        _, e_alu = run.timed(lambda t: ctx.noise_alu_probe(wgs, iters, probe_out), 5)
+        s_per_quad = (e_alu / 5) / (wgs * 256.0 * iters)             # seconds per Philox block + 4 noise values, whole chip
+        quads = k * ((d + 3) // 4)
+        alu_ms = quads * s_per_quad * 1e3
+        extras["generator_alu"] = {
+            "what": "Philox4x32-10 block + Box-Muller for 4 values, registers only (gsgd_noise_alu_probe)",
+            "blocks_per_s": 1.0 / s_per_quad,
+            "simd_cycles_per_wavefront_block_at_2.4GHz": s_per_quad * 64 * SIMDS * PEAK_CLOCK_HZ,
+            "alu_only_ms_for_k_x_d": alu_ms,
+        }
+        del probe_out
+
+        def roof(ms, bpe, with_generator):
+            """Measured time of a kernel beside its two floors: HBM-only (algorithmic bytes at the 8 TB/s peak and at
+            this box's plain-copy rate) and, for the kernels that draw noise, ALU-only (the probe above)."""
+            nbytes = bpe * k * d
+            r = {"kernel_ms": ms, "algorithmic_GBps": nbytes / (ms * 1e-3) / 1e9,
+                 "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                 "hbm_only_ms_at_peak": nbytes / (HBM_PEAK_GBS * 1e9) * 1e3,
+                 "hbm_only_ms_at_plain_copy_rate": nbytes / (copy_gbs * 1e9) * 1e3}
+            if with_generator:
+                r["alu_only_ms"] = alu_ms
+                r["bound"] = "alu" if alu_ms > r["hbm_only_ms_at_plain_copy_rate"] else "hbm"
+            else:
+                r["bound"] = "hbm"
+            return r
+
+        _, e_gen = run.timed(lambda t: ctx.gen_grad(x, h, xstar, g, t), n2, t_next)
+        extras["gen_grad"] = roof(e_gen / n2 * 1e3, 8.0 + 8.0 / k, True)
 
         def full(t):
             ctx.gen_grad(x, h, xstar, g, t)
-            one_step(t)
-        w_full, e_full = timed(full, n2, t_next + n2)
-        extras = {
-            "gen_grad_ms": e_gen / n2 * 1e3,
-            "gen_grad_GBps_algorithmic": (8.0 + 8.0 / k) * k * d / (e_gen / n2) / 1e9,
-            "full_iteration_ms": w_full / n2 * 1e3,
-            "full_iteration_replica_steps_per_s": k * n2 / w_full,
-        }
+            run.step(t)
+        w_full, _ = run.timed(full, n2, t_next + n2)
+        extras["full_iteration_ms"] = w_full / n2 * 1e3
+        extras["full_iteration_replica_steps_per_s"] = k * n2 / w_full
         if cfg.rule == "gossip" and not args.no_fused:
             def fused(t):
                 ctx.step_gossip_fused(x, v, h, xstar, gsgd.make_perm(cfg.seed, t, k), t, cfg.beta)
             for t in range(3):
                 fused(t_next + 2 * n2 + t)
-            w_fu, e_fu = timed(fused, n2, t_next + 2 * n2 + 3)
-            extras["fused_iteration_ms"] = w_fu / n2 * 1e3
-            extras["fused_iteration_replica_steps_per_s"] = k * n2 / w_fu
-            extras["fused_iteration_GBps_algorithmic"] = (16.0 + 8.0 / k) * k * d / (e_fu / n2) / 1e9
-        # what this machine's memory delivers to a plain device-to-device copy of the same matrices (read 4 B, write 4 B per
-        # element), as context for the fractions above; g is regenerated by the next gen_grad
-        scratch = torch.empty_like(g)
-        w_cp, e_cp = timed(lambda t: scratch.copy_(g), 20, 0)
-        extras["plain_copy_GBps"] = 8.0 * k * ld / (e_cp / 20) / 1e9
-        del scratch
+            w_fu, e_fu = run.timed(fused, n2, t_next + 2 * n2 + 3)
+            extras["fused_iteration"] = roof(e_fu / n2 * 1e3, 16.0 + 8.0 / k, True)
+            extras["fused_iteration"]["replica_steps_per_s"] = k * n2 / w_fu
         if cfg.name == "gossip_r50":
             # the other gossip forms on the same resident state (same 20 B per replica-element)
             forms = {
@@ -216,18 +330,29 @@ def main():
             for name, fn in forms.items():
                 for t in range(3):
                     fn(t)
-                w_f, e_f = timed(fn, n2, 1000)
+                _, e_f = run.timed(fn, n2, 1000)
                 extras[name + "_ms"] = e_f / n2 * 1e3
                 extras[name + "_frac_of_hbm_peak"] = 20.0 * k * d / (e_f / n2) / 1e9 / HBM_PEAK_GBS
         out["extras"] = extras
         log("extras:", json.dumps(extras))
+
+    run.close()
+    del x, v, g, run
+    torch.cuda.empty_cache()
+
+    if not args.no_extras and not args.no_legs and cfg.name == "gossip_r50":
+        # the other benchmark configurations (and the gossip step at ResNet-18 size), each a short leg of its own
+        legs = {}
+        for name in ("tiny", "allreduce_r18", "gossip_r18", "easgd_r50", "seg_gossip_r50_k128"):
+            legs[name] = short_leg(gsgd, W, name)
+            log("leg %s: %s" % (name, json.dumps(legs[name])))
+        out["extras"]["other_configs"] = legs
 
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample ---------------------
     if args.cpu_seconds > 0:
         from oracle import oracle
         ds = min(d, 1 << 20)                       # first 2^20 columns of every replica row
         inp = W.make_inputs(k, ds, seed=5)
-        perm0 = oracle.make_perm(cfg.seed, 0, k)
         lrc = np.full(ds, np.float32(cfg.lr), np.float32)
 
         def ostep(t):
@@ -247,6 +372,8 @@ def main():
                     oracle.async_tick(inp.x, inp.v, inp.g[0], lrc, cfg.momentum, cfg.beta, i, j)
             elif cfg.rule == "allreduce":
                 oracle.step_allreduce(inp.x, inp.v, inp.g, lrc, cfg.momentum)
+            elif cfg.rule == "local":
+                oracle.step_gossip(inp.x, inp.v, inp.g, lrc, cfg.momentum, 0.0, list(range(k)))
             else:
                 oracle.step_easgd(inp.x, inp.v, inp.g, inp.center, lrc, cfg.momentum, cfg.alpha_e)
         ostep(0)
@@ -273,7 +400,6 @@ def main():
         }
         log("cpu oracle: %.2f replica-steps/s on %d threads, %.2f on one" % (cpu_value, cores, k * n_one / one_wall * (ds / d)))
 
-    ctx.close()
     print(json.dumps(out), flush=True)
 
 

@@ -269,6 +269,15 @@ int gsgd_step_gossip_push_fused(gsgd_ctx* ctx, float* x, float* v, const float* 
 int gsgd_philox_raw(gsgd_ctx* ctx, uint32_t c1, uint32_t c2, uint32_t c3, int64_t n_blocks, uint32_t* out,
                     void* stream);
 
+/* Measurement hook for the ALU side of the generator's roofline: `workgroups`
+ * workgroups of 256 threads each draw `iters` Philox blocks per thread and turn
+ * them into the context's kind of noise (the device functions gsgd_gen_grad and
+ * the fused steps use), keeping everything in registers; thread t stores one
+ * float to out[t].  Timed by the caller, it gives the generator's cost per
+ * block of four values with no memory traffic in the way.
+ * out: device, workgroups * 256 floats. */
+int gsgd_noise_alu_probe(gsgd_ctx* ctx, int32_t workgroups, uint32_t iters, float* out, void* stream);
+
 /* Uniformly random peer permutation for one step (the target choice of
  * Algorithms 3-4, with every node chosen once): Fisher-Yates from the top, driven
  * by Philox stream 5 at counter (i, 0, step, 5), index floor(r (i+1) / 2^32).

@@ -170,11 +170,27 @@ __device__ __forceinline__ void sincospi_box_muller(float t, float* s, float* c)
     pc = __fmaf_rn(pc, r2, 4.058712126416768f);                       //  pi^4 / 4!
     pc = __fmaf_rn(pc, r2, -4.934802200544679f);                      // -pi^2 / 2!
     const float cr = __fmaf_rn(pc, r2, 1.0f);
-    const int q = static_cast<int>(n) & 3;                            // quadrant: angle = pi (q/2 + r)
-    const float ss = (q & 1) ? cr : sr;
-    const float cc = (q & 1) ? sr : cr;
-    *s = (q & 2) ? -ss : ss;
-    *c = ((q + 1) & 2) ? -cc : cc;
+    const uint32_t q = static_cast<uint32_t>(static_cast<int>(n));    // quadrant: angle = pi (q/2 + r)
+    const bool odd = (q & 1u) != 0u;
+    const float ss = odd ? cr : sr;
+    const float cc = odd ? sr : cr;
+    // sine changes sign in quadrants 2, 3, cosine in 1, 2: flip the sign bit rather than select
+    *s = __uint_as_float(__float_as_uint(ss) ^ ((q & 2u) << 30));
+    *c = __uint_as_float(__float_as_uint(cc) ^ (((q + 1u) & 2u) << 30));
+}
+
+// ln u for u = (2b+1) / 2^24 (a normal number in [2^-24, 1)): the hardware base-2 logarithm times ln 2, with
+// ln 2 held as the sum of two floats and the product's rounding error recovered by a fused multiply-add, so the
+// result is as accurate as the instruction itself (about one unit in the last place).  The library's logf does the
+// same after scaling and special-case tests that these arguments never need.
+__device__ __forceinline__ float ln_u01(float u)
+{
+    constexpr float LN2_HI = 0x1.62e430p-1f;       // nearest float to ln 2
+    constexpr float LN2_LO = -0x1.05c610p-29f;     // ln 2 - LN2_HI
+    const float y = __builtin_amdgcn_logf(u);
+    const float hi = y * LN2_HI;
+    const float err = __fmaf_rn(y, LN2_HI, -hi);
+    return hi + __fmaf_rn(y, LN2_LO, err);
 }
 
 // Four zero-mean unit-variance values (the noise model of Theorem 1).
@@ -193,8 +209,10 @@ __device__ __forceinline__ f32x4 noise4(const u32x4& r)
         z.w = sqrt3 * __fmaf_rn(2.0f, u01(r.w[3]), -1.0f);
         return z;
     } else {
-        const float rho0 = sqrtf(-2.0f * logf(u01(r.w[0])));
-        const float rho1 = sqrtf(-2.0f * logf(u01(r.w[2])));
+        // -2 ln u lies in [1.2e-7, 33.3]: always a normal number, so the hardware square root (one unit in the
+        // last place) needs none of the scaling and fix-up steps of the library's correctly rounded one
+        const float rho0 = __builtin_amdgcn_sqrtf(-2.0f * ln_u01(u01(r.w[0])));
+        const float rho1 = __builtin_amdgcn_sqrtf(-2.0f * ln_u01(u01(r.w[2])));
         float s0, c0, s1, c1;
         sincospi_box_muller(2.0f * u01(r.w[1]), &s0, &c0);
         sincospi_box_muller(2.0f * u01(r.w[3]), &s1, &c1);

@@ -301,6 +301,14 @@ extern "C" int gsgd_philox_raw(gsgd_ctx* ctx, uint32_t c1, uint32_t c2, uint32_t
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
+extern "C" int gsgd_noise_alu_probe(gsgd_ctx* ctx, int32_t workgroups, uint32_t iters, float* out, void* stream)
+{
+    if (!ctx || !out || workgroups < 1 || workgroups > (1 << 20) || iters < 1) return GSGD_ERR_INVALID_ARG;
+    const hipError_t e = launch_noise_alu(key_of(ctx), ctx->cfg.noise_kind, static_cast<uint32_t>(workgroups), iters, out,
+                                          static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
 extern "C" int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const float* g, void* stream)
 {
     const int rc = check_state(ctx, x, v, g);

@@ -123,6 +123,7 @@ hipError_t launch_gen_grad(const Geom&, const float* x, const float* h, const fl
 hipError_t launch_fill(int64_t d, float* dst, int which, RngKey key, hipStream_t);
 hipError_t launch_init_replicas(const Geom&, float* x, float* v, float* center, const float* x0, int mode,
                                 RngKey key, hipStream_t);
+hipError_t launch_noise_alu(RngKey key, int noise_kind, uint32_t workgroups, uint32_t iters, float* out, hipStream_t);
 hipError_t launch_philox_raw(RngKey key, uint32_t c1, uint32_t c2, uint32_t c3, int64_t n_blocks, uint32_t* out,
                              hipStream_t);
 // columns per workgroup tile (256 threads x 4 columns)

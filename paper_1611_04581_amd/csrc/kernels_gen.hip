@@ -122,6 +122,32 @@ void philox_raw_kernel(RngKey key, uint32_t c1, uint32_t c2, uint32_t c3, int64_
     for (int m = 0; m < 4; ++m) out[q * 4 + m] = r.w[m];
 }
 
+// The generator's arithmetic alone, for the ALU side of the roofline: every thread draws `iters` blocks
+// (counter (thread, iteration, 0, gradient stream)), turns each into four noise values and folds them into one
+// float that it stores at the end, so the only memory traffic is 4 bytes per thread.  The replica and step words
+// are uniform over the wavefront as they are in the real kernels (the compiler keeps their share of the rounds in
+// scalar registers in both).
+template <int NOISE>
+__global__ __launch_bounds__(BLOCK)
+void noise_alu_kernel(RngKey key, uint32_t iters, float* __restrict__ out)
+{
+    const uint32_t q = blockIdx.x * BLOCK + threadIdx.x;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t it = 0; it < iters; ++it)
+        acc += noise4<NOISE>(philox4x32_10(q, it, 0u, STREAM_GRAD, key.k0, key.k1));
+    out[q] = (acc.x + acc.y) + (acc.z + acc.w);
+}
+
+hipError_t launch_noise_alu(RngKey key, int noise_kind, uint32_t workgroups, uint32_t iters, float* out,
+                            hipStream_t stream)
+{
+    if (noise_kind == GSGD_NOISE_UNIFORM)
+        hipLaunchKernelGGL(noise_alu_kernel<GSGD_NOISE_UNIFORM>, dim3(workgroups), dim3(BLOCK), 0, stream, key, iters, out);
+    else
+        hipLaunchKernelGGL(noise_alu_kernel<GSGD_NOISE_GAUSSIAN>, dim3(workgroups), dim3(BLOCK), 0, stream, key, iters, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_philox_raw(RngKey key, uint32_t c1, uint32_t c2, uint32_t c3, int64_t n_blocks, uint32_t* out,
                              hipStream_t stream)
 {

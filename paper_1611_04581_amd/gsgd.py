@@ -79,6 +79,7 @@ SIGNATURES = {
                                               C.c_uint64, _vp]),
     "gsgd_step_gossip_push_fused": (C.c_int, [_vp, _vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_uint64, _vp]),
     "gsgd_philox_raw": (C.c_int, [_vp, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int64, _vp, _vp]),
+    "gsgd_noise_alu_probe": (C.c_int, [_vp, C.c_int32, C.c_uint32, _vp, _vp]),
     "gsgd_make_perm": (C.c_int, [C.c_uint64, C.c_uint64, C.c_int32, C.POINTER(C.c_int32)]),
     "gsgd_perm_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint16)]),
     "gsgd_stats": (C.c_int, [_vp, _vp, _vp, C.POINTER(C.c_double), _vp]),
@@ -292,6 +293,10 @@ class Context:
                                      _ptr(out, 4 * int(n_blocks), torch.int32 if out.dtype == torch.int32 else torch.uint32),
                                      _stream(stream)),
                "gsgd_philox_raw")
+
+    def noise_alu_probe(self, workgroups, iters, out, stream=None):
+        _check(lib().gsgd_noise_alu_probe(self._h, int(workgroups), int(iters), _ptr(out, int(workgroups) * 256),
+                                          _stream(stream)), "gsgd_noise_alu_probe")
 
     def row_sqnorms(self, x, stream=None):
         out = (C.c_double * self.k)()

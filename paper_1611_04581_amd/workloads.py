@@ -86,7 +86,7 @@ RESNET50_D = 25_557_032
 @dataclass
 class Config:
     name: str
-    rule: str                 # "gossip" | "gossip_stale" | "gossip_pull" | "gossip_push" | "async_tick" | "allreduce" | "easgd"
+    rule: str                 # "gossip" | "gossip_stale" | "gossip_pull" | "gossip_push" | "async_tick" | "allreduce" | "easgd" | "local"
     k: int
     d: int
     steps: int
@@ -114,6 +114,7 @@ CONFIGS = {
     "push_gossip_r50": Config("push_gossip_r50", "gossip_push", 32, RESNET50_D, 100),       # Algorithm 4
     "stale_gossip_r50": Config("stale_gossip_r50", "gossip_stale", 32, RESNET50_D, 100),    # Section 6.2.1
     "async_r50": Config("async_r50", "async_tick", 32, RESNET50_D, 100),                    # Section 6.1.2, one step = k ticks
+    "local_r50": Config("local_r50", "local", 32, RESNET50_D, 100),                         # no exchange: tau -> infinity
     "paper_setup_r18": Config("paper_setup_r18", "gossip_push", 16, RESNET18_D, 100, lr=0.1,  # Section 4.2's recipe
                               weight_decay=1e-4, nesterov=True, tau=10),
 }

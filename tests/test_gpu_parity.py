@@ -66,6 +66,49 @@ def test_philox_words_bit_exact(G, oracle):
                 assert tuple(int(w) for w in got[q]) == want, (q, c1, c2, c3)
 
 
+def test_noise_alu_probe_is_the_generators_arithmetic(G, oracle):
+    """The measurement hook folds the same Philox blocks and noise values the
+    gradient generator draws: uniform kind bit for bit, Gaussian at tolerance."""
+    import torch
+    wgs, iters = 2, 5
+    for kind in (G.NOISE_UNIFORM, G.NOISE_GAUSSIAN):
+        with G.Context(4, 64, seed=SEED, noise_kind=kind) as ctx:
+            out = torch.zeros(wgs * 256, dtype=torch.float32, device="cuda")
+            ctx.noise_alu_probe(wgs, iters, out)
+            got = host(out)
+        key = (SEED & 0xFFFFFFFF, SEED >> 32)
+        for t in (0, 1, 63, 64, 255, 256, 511):
+            acc = np.zeros(4, np.float32)
+            for it in range(iters):
+                acc = (acc + oracle.noise4(oracle.philox4x32_10((t, it, 0, 0), key), kind)).astype(np.float32)
+            want = np.float32(np.float32(acc[0] + acc[1]) + np.float32(acc[2] + acc[3]))
+            if kind == G.NOISE_UNIFORM:
+                assert got[t].view(np.uint32) == want.view(np.uint32), t
+            else:
+                assert abs(float(got[t]) - float(want)) <= 2e-6 * max(1.0, abs(float(want))), t
+
+
+def test_gaussian_transform_accuracy_over_two_million_draws(G, oracle):
+    """The device Box-Muller (hardware log2 and square root, series sine / cosine,
+    all fp32) against the oracle's fp64 transform rounded once, on 2^21 draws
+    that reach |xi| = 5: the bound is a few units in the last place of the
+    largest values (one unit at 4..8 is 4.8e-7), far inside the 1e-6 bar once
+    scaled by sigma * lr in a step."""
+    import torch
+    d = (1 << 21) + 3
+    ld = W.round_up(d, 4)
+    with G.Context(2, d, ld, seed=SEED) as ctx:
+        t = torch.zeros(ld, device="cuda")
+        ctx.fill(t, G.FILL_X0)
+        got = host(t)[:d].astype(np.float64)
+    want = oracle.fill(d, SEED, oracle.STREAM_X0).astype(np.float64)
+    err = np.abs(got - want)
+    assert np.abs(want).max() > 4.5
+    assert err.max() <= 1.5e-6, err.max()
+    assert np.sqrt((err ** 2).mean()) <= 1.2e-7
+    assert (got == want).mean() > 0.4          # about half the draws round to the same float
+
+
 def test_fill_and_init(G, oracle):
     import torch
     k, d, ld = 5, 3 * 1024 + 5, 3 * 1024 + 8
