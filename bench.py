@@ -348,6 +348,31 @@ def main():
             log("leg %s: %s" % (name, json.dumps(legs[name])))
         out["extras"]["other_configs"] = legs
 
+    if not args.no_extras and not args.no_legs and cfg.name == "gossip_r50":
+        # Section 4.3's observation on the quadratic: gossip's consensus floor moves with the step size.  The
+        # generator-fused gossip step at ResNet-18 size with the experiments' local step (Nesterov 0.9, weight decay
+        # 1e-4), step size 0.1 annealed by 0.1 twice; per stage the consensus distance per parameter and replica
+        # beside the second-moment prediction (paper_1611_04581_amd.theory).
+        from paper_1611_04581_amd import theory
+        acfg = W.CONFIGS["paper_setup_r18"]
+        arun = Run(gsgd, W, acfg)
+        arun.ctx.set_local_step(1e-4, True)
+        hh = arun.h[:acfg.d].cpu().numpy()
+        stages, t, rows = (0.1, 0.01, 0.001), 0, []
+        for lr in stages:
+            arun.ctx.set_lr(lr)
+            for s in range(150):
+                arun.ctx.step_gossip_fused(arun.x, arun.v, arun.h, arun.xstar, gsgd.make_perm(acfg.seed, t, acfg.k), t, 0.5)
+                t += 1
+            cons = arun.ctx.stats(arun.x, arun.xstar)[0]
+            pred = acfg.k * float(theory.gossip_consensus_floor(hh, lr, acfg.momentum, acfg.sigma, acfg.k, 0.5, 1e-4, True).sum())
+            rows.append({"lr": lr, "consensus_distance": cons, "predicted": pred,
+                         "rms_deviation_per_parameter": (cons / (acfg.k * acfg.d)) ** 0.5})
+        out["extras"]["annealing_gossip_r18_k16"] = rows
+        log("annealing:", json.dumps(rows))
+        arun.close()
+        del arun
+
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample ---------------------
     if args.cpu_seconds > 0:
         from oracle import oracle

@@ -29,7 +29,8 @@ _f64p = C.POINTER(C.c_double)
 def lib():
     global _lib
     if _lib is None:
-        path = _build.LIB if os.path.exists(_build.LIB) else _build.build()
+        # GSGD_ORACLE_LIB points the tests at another build of the same source (the sanitizer build)
+        path = os.environ.get("GSGD_ORACLE_LIB") or (_build.LIB if os.path.exists(_build.LIB) else _build.build())
         L = C.CDLL(path)
         L.oracle_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
         L.oracle_philox4x32_10.restype = None
