@@ -201,14 +201,14 @@ def main():
     K, Wm = args.steps, args.warmup
     run = Run(gsgd, W, cfg, args.launch_width)
     k, d, ld = run.k, run.d, run.ld
-    ctx, x, v, g, h, xstar = run.ctx, run.x, run.v, run.g, run.h, run.xstar
+    ctx, h, xstar = run.ctx, run.h, run.xstar
     log("config %s: rule=%s k=%d d=%d ld=%d steps=%d warmup=%d" % (cfg.name, cfg.rule, k, d, ld, K, Wm))
     if args.calibrate_copy:
         # reads k*ld*4 bytes and writes k*ld*4 bytes; g is regenerated right after
-        torch.mul(x, 1.0, out=g)
+        torch.mul(run.x, 1.0, out=run.g)
         torch.cuda.synchronize()
         log("calibration copy: %d bytes read, %d bytes written" % (k * ld * 4, k * ld * 4))
-        ctx.gen_grad(x, h, xstar, g, 0)
+        ctx.gen_grad(run.x, h, xstar, run.g, 0)
         torch.cuda.synchronize()
 
     # ---- the metric: K step calls on resident x, v, g -----------------------------------
@@ -221,9 +221,12 @@ def main():
     kern_s = ev / (K * run.launches_per_step())      # one kernel per launch in the timed region
     achieved = alg_bytes / kern_s / 1e9
     log("step: %.3f ms wall, %.3f ms by HIP events -> %.0f replica-steps/s, %.0f GB/s algorithmic (%.1f%% of peak)"
-        % (ms_per_step, kern_s * 1e3, value, achieved, 100 * achieved / HBM_PEAK_GBS))
+        "  (x, v, g at 0x%x 0x%x 0x%x)" % (ms_per_step, kern_s * 1e3, value, achieved, 100 * achieved / HBM_PEAK_GBS,
+                                          run.x.data_ptr(), run.v.data_ptr(), run.g.data_ptr()))
 
     # ---- the same kernel on fresh allocations: the rate depends on the physical placement ----
+    # (no reference to the old tensors may survive here, or the new ones are carved out next to them instead of
+    # replacing them)
     fracs = [achieved / HBM_PEAK_GBS]
     n_rep = max(10, min(K, 100))
     for r in range(1, max(1, args.repeats)):
@@ -232,7 +235,8 @@ def main():
             run.step(t)
         _, ev_r = run.timed(run.step, n_rep, 10)
         fracs.append(alg_bytes / (ev_r / (n_rep * run.launches_per_step())) / 1e9 / HBM_PEAK_GBS)
-        log("  fresh allocation %d: %.1f%% of peak" % (r, 100 * fracs[-1]))
+        log("  fresh allocation %d: %.1f%% of peak  (x, v, g at 0x%x 0x%x 0x%x)"
+            % (r, 100 * fracs[-1], run.x.data_ptr(), run.v.data_ptr(), run.g.data_ptr()))
     x, v, g = run.x, run.v, run.g
 
     traffic, traffic_source = TRAFFIC_FROM_PROFILES.get(cfg.name, (None, None))

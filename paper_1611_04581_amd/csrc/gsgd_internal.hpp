@@ -127,7 +127,10 @@ hipError_t launch_noise_alu(RngKey key, int noise_kind, uint32_t workgroups, uin
 hipError_t launch_philox_raw(RngKey key, uint32_t c1, uint32_t c2, uint32_t c3, int64_t n_blocks, uint32_t* out,
                              hipStream_t);
 // columns per workgroup tile (256 threads x 4 columns)
-constexpr int64_t BLOCK_COLUMNS = 1024;
+#ifndef GSGD_BLOCK
+#define GSGD_BLOCK 256
+#endif
+constexpr int64_t BLOCK_COLUMNS = static_cast<int64_t>(GSGD_BLOCK) * 4;
 // stats: partials holds stats_num_blocks(d) * 4 doubles; result 4 doubles (device)
 int64_t    stats_num_blocks(int64_t d);
 hipError_t launch_stats(const Geom&, const float* x, const float* xstar, double* partials, double* result,
