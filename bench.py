@@ -34,10 +34,36 @@ PEAK_CLOCK_HZ = 2.4e9
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (KiB per dispatch, each scaled by what the
 # same counter reads for a plain copy of known size).  These come from the profile runs summarised under profiles/,
 # NOT from the run that prints them: a bench run cannot read hardware counters.  None = no such profile yet.
+def _kib(fetch_size, write_size):
+    """FETCH_SIZE reads half the KiB fetched, WRITE_SIZE the KiB written (both calibrated on a plain copy)."""
+    return (fetch_size * 2.0 + write_size) * 1024.0
+
+
+_GOSSIP_R50 = "profiles/gossip_step_kernel_gossip_r50.md"
+_OTHERS = "profiles/step_kernels_other_workloads.md"
+_GENERATOR = "profiles/generator_kernels_alu_vs_hbm.md"
 TRAFFIC_FROM_PROFILES = {
     # name: (bytes per launch, source)
-    "gossip_r50": ((4792017.0 * 2.0 + 6390054.1) * 1024.0, "profiles/gossip_step_kernel_gossip_r50.md"),
+    "gossip_r50": (_kib(4792022.9, 6390054.2), _GOSSIP_R50),
+    "stale_gossip_r50": (_kib(4792006.8, 6390054.2), _GOSSIP_R50),
+    "pull_gossip_r50": (_kib(4792027.0, 6390054.1), _GOSSIP_R50),
+    "push_gossip_r50": (_kib(4792073.0, 6390054.2), _GOSSIP_R50),
+    "local_r50": (_kib(4791973.5, 6389258.3), _GOSSIP_R50),
+    "allreduce_r18": (_kib(548031.5, 731004.7), _OTHERS),
+    "gossip_r18": (_kib(2191848.0, 2922750.9), _OTHERS),
+    "easgd_r50": (_kib(2445960.3, 3295257.2), _OTHERS),
+    "seg_gossip_r50_k128": (_kib(19167863.0, 25557829.0), _OTHERS),
+    "gen_grad@gossip_r50": (_kib(1697275.5, 3195507.2), _GENERATOR),
+    "fused@gossip_r50": (_kib(3294593.0, 6390077.4), _GENERATOR),
 }
+TRAFFIC_NOTE = ("rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size; a separate "
+                "profile run, not this run")
+
+
+def traffic_of(name):
+    t, src = TRAFFIC_FROM_PROFILES.get(name, (None, None))
+    return {"traffic": t, "traffic_source": "%s (%s)" % (src, TRAFFIC_NOTE) if src else None}
+
 
 KERNEL_OF_RULE = {"gossip": "gossip_step_kernel", "gossip_stale": "gossip_step_kernel (stale)",
                   "gossip_pull": "gossip_step_kernel (tree walk)", "gossip_push": "push_step_kernel",
@@ -164,6 +190,8 @@ def short_leg(gsgd, W, name, warmup=5, steps=30, repeats=3):
                "replica_steps_per_s": cfg.k / (med * run.launches_per_step() * 1e-3)}
         if name != "tiny":           # the tiny configuration lives in cache and is launch-bound: no bandwidth figure
             out["frac_of_hbm_peak"] = run.algorithmic_bytes() / (med * 1e-3) / 1e9 / HBM_PEAK_GBS
+            out["algorithmic_bytes_per_launch"] = run.algorithmic_bytes()
+            out.update(traffic_of(name))
         return out
     finally:
         run.close()
@@ -239,7 +267,6 @@ def main():
             % (r, 100 * fracs[-1], run.x.data_ptr(), run.v.data_ptr(), run.g.data_ptr()))
     x, v, g = run.x, run.v, run.g
 
-    traffic, traffic_source = TRAFFIC_FROM_PROFILES.get(cfg.name, (None, None))
     out = {
         "metric": "replica-steps/sec + achieved HBM GB/s, gossip step, ResNet-50-size d, k=32" if cfg.name == "gossip_r50"
                   else "replica-steps/sec, %s step" % cfg.rule,
@@ -251,10 +278,7 @@ def main():
                    "k": k, "d": d, "ld": ld, "rule": cfg.rule, "lr": cfg.lr, "momentum": cfg.momentum,
                    "beta": cfg.beta, "sigma": cfg.sigma, "layout": cfg.layout or "flat"},
         "roofline": {"bound": "hbm", "kernel": KERNEL_OF_RULE[cfg.rule], "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "traffic_source": (traffic_source + " (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by a "
-                                        "plain copy of known size; a separate profile run, not this run)")
-                                       if traffic_source else None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, **traffic_of(cfg.name),
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kern_s * 1e3,
                      "fresh_allocations": {"n": len(fracs), "steps_each": [K] + [n_rep] * (len(fracs) - 1),
                                            "frac_median": statistics.median(fracs), "frac_min": min(fracs),
@@ -308,6 +332,7 @@ def main():
 
         _, e_gen = run.timed(lambda t: ctx.gen_grad(x, h, xstar, g, t), n2, t_next)
         extras["gen_grad"] = roof(e_gen / n2 * 1e3, 8.0 + 8.0 / k, True)
+        extras["gen_grad"].update(traffic_of("gen_grad@" + cfg.name))
 
         def full(t):
             ctx.gen_grad(x, h, xstar, g, t)
@@ -323,6 +348,7 @@ def main():
             w_fu, e_fu = run.timed(fused, n2, t_next + 2 * n2 + 3)
             extras["fused_iteration"] = roof(e_fu / n2 * 1e3, 16.0 + 8.0 / k, True)
             extras["fused_iteration"]["replica_steps_per_s"] = k * n2 / w_fu
+            extras["fused_iteration"].update(traffic_of("fused@" + cfg.name))
         if cfg.name == "gossip_r50":
             # the other gossip forms on the same resident state (same 20 B per replica-element)
             forms = {

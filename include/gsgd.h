@@ -68,6 +68,7 @@ enum {
 enum { GSGD_NOISE_GAUSSIAN = 0, GSGD_NOISE_UNIFORM = 1 };
 enum { GSGD_INIT_BROADCAST = 0, GSGD_INIT_PER_REPLICA = 1 };
 enum { GSGD_FILL_XSTAR = 2, GSGD_FILL_H = 3, GSGD_FILL_X0 = 4 };
+enum { GSGD_ROW_SPLIT_AUTO = 0, GSGD_ROW_SPLIT_OFF = 1, GSGD_ROW_SPLIT_ON = 2 };
 /* the streaming kernels, for gsgd_set_launch_width (GSGD_KERNEL_LOCAL is accepted and ignored: the local step
  * is launched as a plain grid) */
 enum { GSGD_KERNEL_GOSSIP = 0, GSGD_KERNEL_ALLREDUCE = 1, GSGD_KERNEL_EASGD = 2, GSGD_KERNEL_GEN_GRAD = 3,
@@ -117,6 +118,21 @@ int gsgd_set_local_step(gsgd_ctx* ctx, float weight_decay, int nesterov);
  * not depend on it.  Host only. */
 int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups);
 
+/* How the k-way sums of gsgd_step_allreduce and gsgd_step_easgd are laid out.
+ *   GSGD_ROW_SPLIT_OFF : one thread per four columns adds all k rows in fp64 in
+ *                        ascending order (bit-identical to a serial sum);
+ *   GSGD_ROW_SPLIT_ON  : the rows are split into blocks over the wavefronts of
+ *                        a workgroup, each block summed in ascending order, the
+ *                        block sums staged through LDS and added in ascending
+ *                        block order.  Same fp64 additions, associated
+ *                        differently: a result can differ from OFF in the last
+ *                        place where the fp64 sum is itself inexact.  Faster
+ *                        when d is too short to fill the GPU with d/4 threads;
+ *   GSGD_ROW_SPLIT_AUTO: ON when d has fewer 1024-column tiles than the device
+ *                        has compute units and k >= 16, else OFF (the default).
+ * Host only. */
+int gsgd_set_row_split(gsgd_ctx* ctx, int mode);
+
 /* Initialisation: first line of Algorithms 1-4 (every node starts at the same
  * theta_0; the elastic-averaging server's centre starts there too).
  *   mode GSGD_INIT_BROADCAST   : x_i <- x0 for all i; center <- x0
@@ -145,7 +161,8 @@ int gsgd_gen_grad(gsgd_ctx* ctx, const float* x, const float* h, const float* xs
 /* Synchronous all-reduce step, Algorithm 1:
  *   u_i = momentum * v_i - lr_s * g_i;  ubar = (1/k) sum_i u_i;
  *   v_i <- ubar;  x_i <- x_i + ubar          for every replica i.
- * The k-way sum runs in fp64 in ascending i and is rounded once to fp32.
+ * The k-way sum runs in fp64 in ascending i and is rounded once to fp32
+ * (for short vectors in blocks of rows, see gsgd_set_row_split).
  * x, v: device k x ld, updated in place.  g: device k x ld, read. */
 int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const float* g, void* stream);
 

@@ -31,6 +31,7 @@ struct gsgd_ctx {
     unsigned    width[GSGD_KERNEL_COUNT];   // persistent workgroups per streaming kernel
     float       weight_decay;               // extras of the local step (Section 4.2); 0 / 0 = the boxed algorithms
     int         nesterov;
+    int         row_split;                  // GSGD_ROW_SPLIT_*: how the k-way sums of short vectors are laid out
     int         last_hip;
 };
 
@@ -69,6 +70,19 @@ inline Persist persist_of(gsgd_ctx* c, int kernel, void* stream)
     const int pair = pair_of(c, static_cast<hipStream_t>(stream));
     return Persist{pair < 0 ? nullptr : pair_words(c, pair), c->width[kernel]};
 }
+// Rows split over the wavefronts of a workgroup when one thread per four columns cannot fill the chip: fewer
+// 1024-column tiles than compute units, and enough rows for the split to shorten the walk.  Measured on MI355X
+// (serial / split, microseconds per all-reduce step): d = 16,384: k = 8 8.8 / 8.8, k = 32 14.9 / 8.9, k = 128
+// 45.6 / 10.9, k = 512 170 / 40; d = 65,536: 8.3 / 8.8, 17.1 / 8.8, 56 / 33, 217 / 116; d = 262,144 (as many tiles
+// as compute units): 13.1 / 8.4, 31 / 28, 118 / 126, 479 / 543; from d = 1,048,576 on the serial walk wins.
+inline bool row_split_of(const gsgd_ctx* c)
+{
+    if (c->row_split == GSGD_ROW_SPLIT_ON) return true;
+    if (c->row_split == GSGD_ROW_SPLIT_OFF) return false;
+    const int64_t tiles = (c->cfg.d + BLOCK_COLUMNS - 1) / BLOCK_COLUMNS;
+    return tiles < c->cu_count && c->cfg.k >= 16;
+}
+
 inline RngKey key_of(const gsgd_ctx* c)
 {
     return RngKey{static_cast<uint32_t>(c->cfg.seed), static_cast<uint32_t>(c->cfg.seed >> 32)};
@@ -240,6 +254,14 @@ extern "C" int gsgd_set_local_step(gsgd_ctx* ctx, float weight_decay, int nester
     return GSGD_OK;
 }
 
+extern "C" int gsgd_set_row_split(gsgd_ctx* ctx, int mode)
+{
+    if (!ctx || (mode != GSGD_ROW_SPLIT_AUTO && mode != GSGD_ROW_SPLIT_OFF && mode != GSGD_ROW_SPLIT_ON))
+        return GSGD_ERR_INVALID_ARG;
+    ctx->row_split = mode;
+    return GSGD_OK;
+}
+
 extern "C" int gsgd_comm_due(uint64_t step, uint32_t tau)
 {
     if (tau == 0) return GSGD_ERR_INVALID_ARG;
@@ -313,10 +335,14 @@ extern "C" int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const floa
 {
     const int rc = check_state(ctx, x, v, g);
     if (rc != GSGD_OK) return rc;
-    const Persist ps = persist_of(ctx, GSGD_KERNEL_ALLREDUCE, stream);
-    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
-    const hipError_t e = launch_step_allreduce(geom_of(ctx), hyper_of(ctx), seg_of(ctx), x, v, g,
-                                               ps, static_cast<hipStream_t>(stream));
+    const bool split = row_split_of(ctx);
+    Persist ps{nullptr, 0u};                              // the row-split kernels are plain grids
+    if (!split) {
+        ps = persist_of(ctx, GSGD_KERNEL_ALLREDUCE, stream);
+        if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
+    }
+    const hipError_t e = launch_step_allreduce(geom_of(ctx), hyper_of(ctx), seg_of(ctx), x, v, g, ps, split,
+                                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -523,10 +549,14 @@ extern "C" int gsgd_step_easgd(gsgd_ctx* ctx, float* x, float* v, const float* g
     if (rc != GSGD_OK) return rc;
     if (!ok_matrix(center) || !vector_clear_of(ctx, center, x, v, g) || !(alpha_e == alpha_e))
         return GSGD_ERR_INVALID_ARG;
-    const Persist ps = persist_of(ctx, GSGD_KERNEL_EASGD, stream);
-    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
-    const hipError_t e = launch_step_easgd(geom_of(ctx), hyper_of(ctx), seg_of(ctx), alpha_e, x, v, g, center,
-                                           ps, static_cast<hipStream_t>(stream));
+    const bool split = row_split_of(ctx);
+    Persist ps{nullptr, 0u};
+    if (!split) {
+        ps = persist_of(ctx, GSGD_KERNEL_EASGD, stream);
+        if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
+    }
+    const hipError_t e = launch_step_easgd(geom_of(ctx), hyper_of(ctx), seg_of(ctx), alpha_e, x, v, g, center, ps,
+                                           split, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 

@@ -115,9 +115,9 @@ hipError_t launch_step_gossip_push_fused(const Geom&, const Hyper&, const SegTab
                                          float* x, float* v, const float* h, const float* xstar,
                                          float sigma, RngKey key, uint32_t step, int noise_kind, Persist, hipStream_t);
 hipError_t launch_step_allreduce(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
-                                 Persist, hipStream_t);
+                                 Persist, bool row_split, hipStream_t);
 hipError_t launch_step_easgd(const Geom&, const Hyper&, const SegTable&, float alpha_e,
-                             float* x, float* v, const float* g, float* center, Persist, hipStream_t);
+                             float* x, float* v, const float* g, float* center, Persist, bool row_split, hipStream_t);
 hipError_t launch_gen_grad(const Geom&, const float* x, const float* h, const float* xstar, float* g,
                            float sigma, RngKey key, uint32_t step, int noise_kind, Persist, hipStream_t);
 hipError_t launch_fill(int64_t d, float* dst, int which, RngKey key, hipStream_t);

@@ -406,6 +406,149 @@ void easgd_step_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e,
 }
 
 // ---------------------------------------------------------------------------
+// The k-way sums with the rows split over the wavefronts of a workgroup, for vectors too short to fill the chip
+// with one thread per four columns walking all k rows (fewer 1024-column tiles than compute units).  A workgroup of
+// WAVES wavefronts owns a tile of 64 quads (256 columns); wavefront w takes the w-th block of ceil(k / WAVES)
+// consecutive rows, accumulates its part of the sum in fp64 in ascending row order and parks it in LDS; after one
+// barrier every wavefront adds the WAVES partial sums in ascending w and finishes its own rows.  The chip sees 4 x
+// as many workgroups and WAVES x as many rows in flight per column, which is what a latency-bound walk needs.
+// The sum is the same set of fp64 additions associated differently ((rows of wave 0) + (rows of wave 1) + ...
+// instead of one ascending chain), so a result can differ from the serial kernels' in the last place where the fp64
+// sum is itself inexact; everything else (local step, per-row updates) is the same arithmetic.
+constexpr int SPLIT_QUADS = 64;                    // quads (lanes) per tile: one wavefront wide
+constexpr int SPLIT_COLUMNS = SPLIT_QUADS * 4;
+
+__device__ __forceinline__ void store_quad_cached(float* p, f32x4 r, int valid)
+{
+    if (valid == 4) { *reinterpret_cast<f32x4*>(p) = r; return; }
+    if (valid > 0) p[0] = r.x;
+    if (valid > 1) p[1] = r.y;
+    if (valid > 2) p[2] = r.z;
+}
+
+__device__ __forceinline__ void add_into(f64x4& acc, f32x4 a)
+{
+    acc.x += static_cast<double>(a.x);
+    acc.y += static_cast<double>(a.y);
+    acc.z += static_cast<double>(a.z);
+    acc.w += static_cast<double>(a.w);
+}
+
+template <int WAVES, bool EXT>
+__global__ __launch_bounds__(WAVES * 64)
+void allreduce_rowsplit_kernel(Geom geo, Hyper hp, SegTable seg,
+                               float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g)
+{
+    __shared__ SegLds lds;
+    __shared__ f64x4 part_v[WAVES][SPLIT_QUADS];
+    __shared__ f64x4 part_d[EXT ? WAVES : 1][EXT ? SPLIT_QUADS : 1];
+    stage_segments(seg, lds);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t col = static_cast<int64_t>(blockIdx.x) * SPLIT_COLUMNS + lane * 4;
+    const int64_t left = geo.d - col;
+    const int valid = left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0);
+    const int k = geo.k;
+    const int rows_per_wave = (k + WAVES - 1) / WAVES;
+    const int r0 = wave * rows_per_wave < k ? wave * rows_per_wave : k;
+    const int r1 = r0 + rows_per_wave < k ? r0 + rows_per_wave : k;
+    const bool need_x = EXT && hp.wd != 0.0f;
+    const bool nesterov = EXT && hp.nesterov != 0;
+    const f32x4 neg_lr = valid > 0 ? -quad_lr(seg, lds, col, valid, hp.lr) : f32x4{0.f, 0.f, 0.f, 0.f};
+
+    f64x4 acc_v = {0.0, 0.0, 0.0, 0.0}, acc_d = {0.0, 0.0, 0.0, 0.0};
+    if (valid > 0) {
+        for (int i = r0; i < r1; ++i) {
+            const int64_t off = static_cast<int64_t>(i) * geo.ld + col;
+            const f32x4 V = load_quad_cached(v + off, valid);
+            const f32x4 G = load_quad_cached(g + off, valid);
+            f32x4 X = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (EXT) { if (need_x) X = load_quad_cached(x + off, valid); }
+            f32x4 un, xp_unused, gt;
+            local_step<EXT>(X, V, G, neg_lr, hp, un, xp_unused, &gt);
+            add_into(acc_v, un);
+            if constexpr (EXT) {
+                if (nesterov) {
+                    const f32x4 t5 = hp.mu * un;
+                    add_into(acc_d, fma4(neg_lr, gt, t5));
+                }
+            }
+        }
+    }
+    part_v[wave][lane] = acc_v;
+    if constexpr (EXT) part_d[wave][lane] = acc_d;
+    __syncthreads();
+    if (valid == 0) return;
+    f64x4 sum_v = part_v[0][lane];
+    for (int w = 1; w < WAVES; ++w) sum_v += part_v[w][lane];
+    const double kd = static_cast<double>(k);
+    const f32x4 ubar = {static_cast<float>(sum_v.x / kd), static_cast<float>(sum_v.y / kd),
+                        static_cast<float>(sum_v.z / kd), static_cast<float>(sum_v.w / kd)};
+    f32x4 dbar = ubar;
+    if constexpr (EXT) {
+        if (nesterov) {
+            f64x4 sum_d = part_d[0][lane];
+            for (int w = 1; w < WAVES; ++w) sum_d += part_d[w][lane];
+            dbar = f32x4{static_cast<float>(sum_d.x / kd), static_cast<float>(sum_d.y / kd),
+                         static_cast<float>(sum_d.z / kd), static_cast<float>(sum_d.w / kd)};
+        }
+    }
+    for (int i = r0; i < r1; ++i) {
+        const int64_t off = static_cast<int64_t>(i) * geo.ld + col;
+        const f32x4 X = load_quad_cached(x + off, valid);
+        store_quad_cached(v + off, ubar, valid);
+        store_quad_cached(x + off, X + dbar, valid);
+    }
+}
+
+template <int WAVES, bool EXT>
+__global__ __launch_bounds__(WAVES * 64)
+void easgd_rowsplit_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e,
+                           float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                           float* __restrict__ center)
+{
+    __shared__ SegLds lds;
+    __shared__ f64x4 part[WAVES][SPLIT_QUADS];
+    stage_segments(seg, lds);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t col = static_cast<int64_t>(blockIdx.x) * SPLIT_COLUMNS + lane * 4;
+    const int64_t left = geo.d - col;
+    const int valid = left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0);
+    const int k = geo.k;
+    const int rows_per_wave = (k + WAVES - 1) / WAVES;
+    const int r0 = wave * rows_per_wave < k ? wave * rows_per_wave : k;
+    const int r1 = r0 + rows_per_wave < k ? r0 + rows_per_wave : k;
+
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+    f32x4 c4 = {0.f, 0.f, 0.f, 0.f};
+    if (valid > 0) {
+        const f32x4 neg_lr = -quad_lr(seg, lds, col, valid, hp.lr);
+        c4 = load_quad_cached(center + col, valid);
+        for (int i = r0; i < r1; ++i) {
+            const int64_t off = static_cast<int64_t>(i) * geo.ld + col;
+            const f32x4 X = load_quad_cached(x + off, valid);
+            const f32x4 V = load_quad_cached(v + off, valid);
+            const f32x4 G = load_quad_cached(g + off, valid);
+            f32x4 vn, xp;
+            local_step<EXT>(X, V, G, neg_lr, hp, vn, xp);
+            const f32x4 e = alpha_e * (xp - c4);
+            store_quad_cached(v + off, vn, valid);
+            store_quad_cached(x + off, xp - e, valid);
+            add_into(acc, e);
+        }
+    }
+    part[wave][lane] = acc;
+    __syncthreads();                                  // also orders every wave's read of the centre before its update
+    if (valid == 0 || wave != 0) return;
+    f64x4 sum = part[0][lane];
+    for (int w = 1; w < WAVES; ++w) sum += part[w][lane];
+    const f32x4 cn = {static_cast<float>(static_cast<double>(c4.x) + sum.x),
+                      static_cast<float>(static_cast<double>(c4.y) + sum.y),
+                      static_cast<float>(static_cast<double>(c4.z) + sum.z),
+                      static_cast<float>(static_cast<double>(c4.w) + sum.w)};
+    store_quad_cached(center + col, cn, valid);
+}
+
+// ---------------------------------------------------------------------------
 // Local step alone: what a node does in the iterations between two exchanges
 // when the communication period tau of Algorithms 2-4 is larger than 1.
 // Nothing couples the rows here, so this is a flat kernel: one workgroup per
@@ -572,9 +715,32 @@ hipError_t launch_step_gossip_fused(const Geom& geo, const Hyper& hp, const SegT
     return hipGetLastError();
 }
 
-hipError_t launch_step_allreduce(const Geom& geo, const Hyper& hp, const SegTable& seg,
-                                 float* x, float* v, const float* g, Persist p, hipStream_t stream)
+// Wavefronts per workgroup of the row-split kernels: enough that a wavefront's share is a handful of rows.
+static inline int split_waves(int k) { return k >= 48 ? 16 : 4; }
+
+static inline unsigned split_grid(const Geom& geo)
 {
+    return static_cast<unsigned>((geo.d + SPLIT_COLUMNS - 1) / SPLIT_COLUMNS);
+}
+
+hipError_t launch_step_allreduce(const Geom& geo, const Hyper& hp, const SegTable& seg,
+                                 float* x, float* v, const float* g, Persist p, bool row_split, hipStream_t stream)
+{
+    if (row_split) {
+        const dim3 grid(split_grid(geo));
+        if (split_waves(geo.k) == 16) {
+            if (hp.extended())
+                hipLaunchKernelGGL((allreduce_rowsplit_kernel<16, true>), grid, dim3(1024), 0, stream, geo, hp, seg, x, v, g);
+            else
+                hipLaunchKernelGGL((allreduce_rowsplit_kernel<16, false>), grid, dim3(1024), 0, stream, geo, hp, seg, x, v, g);
+        } else {
+            if (hp.extended())
+                hipLaunchKernelGGL((allreduce_rowsplit_kernel<4, true>), grid, dim3(256), 0, stream, geo, hp, seg, x, v, g);
+            else
+                hipLaunchKernelGGL((allreduce_rowsplit_kernel<4, false>), grid, dim3(256), 0, stream, geo, hp, seg, x, v, g);
+        }
+        return hipGetLastError();
+    }
     if (hp.extended())
         GSGD_LAUNCH((allreduce_step_kernel<RIF, true>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
     else
@@ -589,8 +755,24 @@ constexpr int EASGD_RIF_MANY_REPLICAS = 2;
 constexpr int EASGD_MANY_REPLICAS = 48;
 
 hipError_t launch_step_easgd(const Geom& geo, const Hyper& hp, const SegTable& seg, float alpha_e,
-                             float* x, float* v, const float* g, float* center, Persist p, hipStream_t stream)
+                             float* x, float* v, const float* g, float* center, Persist p, bool row_split,
+                             hipStream_t stream)
 {
+    if (row_split) {
+        const dim3 grid(split_grid(geo));
+        if (split_waves(geo.k) == 16) {
+            if (hp.extended())
+                hipLaunchKernelGGL((easgd_rowsplit_kernel<16, true>), grid, dim3(1024), 0, stream, geo, hp, seg, alpha_e, x, v, g, center);
+            else
+                hipLaunchKernelGGL((easgd_rowsplit_kernel<16, false>), grid, dim3(1024), 0, stream, geo, hp, seg, alpha_e, x, v, g, center);
+        } else {
+            if (hp.extended())
+                hipLaunchKernelGGL((easgd_rowsplit_kernel<4, true>), grid, dim3(256), 0, stream, geo, hp, seg, alpha_e, x, v, g, center);
+            else
+                hipLaunchKernelGGL((easgd_rowsplit_kernel<4, false>), grid, dim3(256), 0, stream, geo, hp, seg, alpha_e, x, v, g, center);
+        }
+        return hipGetLastError();
+    }
     const bool many = geo.k >= EASGD_MANY_REPLICAS;
     if (hp.extended()) {
         if (many)

@@ -41,3 +41,17 @@ def mean_preserved(before, after, rtol=MEAN_RTOL):
     ma = np.asarray(after, dtype=np.float64).mean(0)
     bound = rtol * max(1.0, np.abs(mb).max())
     assert np.abs(ma - mb).max() <= bound, "replica mean moved by %.3e > %.3e" % (np.abs(ma - mb).max(), bound)
+
+
+def assert_ulp_close(got, want, what="x", min_equal=0.9999):
+    """fp32 arrays bit-equal on at least `min_equal` of the elements and adjacent
+    floats elsewhere: the bar for results that round one fp64 sum whose
+    additions the two sides associate differently."""
+    a = np.ascontiguousarray(got).view(np.int32).astype(np.int64)
+    b = np.ascontiguousarray(want).view(np.int32).astype(np.int64)
+    # map the sign-magnitude bit patterns to a monotone integer line (so -0 and +0 are neighbours)
+    a = np.where(a < 0, -(a & 0x7FFFFFFF) - 1, a)
+    b = np.where(b < 0, -(b & 0x7FFFFFFF) - 1, b)
+    steps = np.abs(a - b)
+    assert steps.max() <= 1, "%s: %d units in the last place apart" % (what, steps.max())
+    assert (steps == 0).mean() >= min_equal, "%s: only %.6f bit-equal" % (what, (steps == 0).mean())

@@ -120,8 +120,8 @@ def test_fill_and_init(G, oracle):
             bufs[which] = host(t)
             assert (bufs[which][d:] == 777.0).all()
         assert_bitwise(bufs[G.FILL_H][:d], oracle.fill(d, SEED, oracle.STREAM_H), "h")
-        assert_rows_close(bufs[G.FILL_XSTAR][:d], oracle.fill(d, SEED, oracle.STREAM_XSTAR), "xstar", rtol=2e-6)
-        assert_rows_close(bufs[G.FILL_X0][:d], oracle.fill(d, SEED, oracle.STREAM_X0), "x0", rtol=2e-6)
+        assert_rows_close(bufs[G.FILL_XSTAR][:d], oracle.fill(d, SEED, oracle.STREAM_XSTAR), "xstar")
+        assert_rows_close(bufs[G.FILL_X0][:d], oracle.fill(d, SEED, oracle.STREAM_X0), "x0")
 
         inp = W.make_inputs(k, d, ld, seed=1)
         x, v, c = dev(inp.x), dev(inp.v), dev(inp.center)
@@ -134,9 +134,9 @@ def test_fill_and_init(G, oracle):
 
         ctx.init_replicas(x, v, c, None, G.INIT_PER_REPLICA)
         oracle.init_replicas(xo, vo, co, None, SEED, 1, n=d)
-        assert_rows_close(host(x)[:, :d], xo[:, :d], "x", rtol=2e-6)
+        assert_rows_close(host(x)[:, :d], xo[:, :d], "x")
         assert_bitwise(host(v), vo, "v")
-        assert_rows_close(host(c)[:d], co[:d], "center", rtol=2e-6)
+        assert_rows_close(host(c)[:d], co[:d], "center")
         assert (host(x)[:, d:] == 777.0).all() and (host(c)[d:] == 777.0).all()
         ctx.init_replicas(x, v, None, None, G.INIT_PER_REPLICA)     # centre is optional
 
@@ -366,7 +366,11 @@ def test_tiny_config_full_trajectory(G, oracle):
     assert_bitwise(v, vo, "v")
     x, v, c, xo, vo, co, st, inp = _run_both(G, oracle, cfg, cfg.d, cfg.steps, G.NOISE_GAUSSIAN)
     assert_rows_close(x[:, :cfg.d], xo[:, :cfg.d], "x")
+    # v is a small difference quantity (|v| ~ lr * sigma ~ 1e-3 near x*) formed from O(1) parameters: the two sides'
+    # x agree to ~1e-7 absolutely, so v agrees to lr * h * 1e-7 / (1 - mu) ~ 1e-8 absolutely, which is 1e-5 of |v|
     assert_rows_close(v[:, :cfg.d], vo[:, :cfg.d], "v", rtol=1e-5)
+    # the statistics are sums of squares of differences ~3e-3 of parameters ~1 that agree to ~1e-7: 2 * 1e-7 / 3e-3
+    # ~ 1e-4 relative in the worst case (the bit-exact uniform-noise runs compare them at 1e-10)
     assert np.allclose(st, oracle.stats(xo, inp.xstar, n=cfg.d), rtol=1e-4)
     # converged towards x*: distance shrank by orders of magnitude from the start
     d0 = ((inp.x0[:cfg.d].astype(np.float64) - inp.xstar[:cfg.d]) ** 2).sum() * cfg.k

@@ -12,7 +12,7 @@ import numpy as np
 import pytest
 
 from paper_1611_04581_amd import workloads as W
-from parity_util import assert_bitwise
+from parity_util import assert_bitwise, assert_ulp_close
 
 pytestmark = pytest.mark.gpu
 SEED = W.DEFAULT_SEED
@@ -35,18 +35,6 @@ def dev(a):
 
 def host(t):
     return np.ascontiguousarray(t.cpu().numpy())
-
-
-def assert_ulp_close(got, want, what):
-    """bit-equal on >= 99.99 % of the elements, adjacent fp32 values elsewhere"""
-    a = np.ascontiguousarray(got).view(np.int32).astype(np.int64)
-    b = np.ascontiguousarray(want).view(np.int32).astype(np.int64)
-    # map the sign-magnitude bit patterns to a monotone integer line (so -0 and +0 are neighbours)
-    a = np.where(a < 0, -(a & 0x7FFFFFFF) - 1, a)
-    b = np.where(b < 0, -(b & 0x7FFFFFFF) - 1, b)
-    steps = np.abs(a - b)
-    assert steps.max() <= 1, "%s: %d units in the last place apart" % (what, steps.max())
-    assert (steps == 0).mean() >= 0.9999, "%s: only %.6f bit-equal" % (what, (steps == 0).mean())
 
 
 def _has_subnormals(a):
