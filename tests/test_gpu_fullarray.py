@@ -13,6 +13,8 @@ the wrong columns cannot hide:
     12 and 20 steps;
   * elastic averaging (k = 16, ResNet-50 size): FULL arrays and the centre
     after 5 steps;
+  * pull-gossip on iid targets (tree walk), stale-parameter gossip and
+    push-gossip (k = 32, ResNet-18 size): FULL arrays after 6 steps;
   * segmented gossip at k = 128 (ResNet-50 layout, 39 GB of state): one whole
     quad of every tile, at a lane that changes from tile to tile, through 4
     steps (the oracle recomputes the gathered columns from the device's own g;
@@ -98,6 +100,18 @@ class _Run:
                 perm = G.make_perm(cfg.seed, t, self.k)
                 self.ctx.step_gossip(self.x, self.v, self.g, perm, cfg.beta)
                 o.step_gossip(self.xo, self.vo, self.go, self.lrc, cfg.momentum, cfg.beta, perm, n=d)
+            elif cfg.rule == "gossip_pull":                       # iid targets: the tree walk
+                peer = G.make_targets(cfg.seed, t, self.k)
+                self.ctx.step_gossip_pull(self.x, self.v, self.g, peer, cfg.beta)
+                o.step_gossip(self.xo, self.vo, self.go, self.lrc, cfg.momentum, cfg.beta, peer, n=d)
+            elif cfg.rule == "gossip_stale":
+                perm = G.make_perm(cfg.seed, t, self.k)
+                self.ctx.step_gossip_stale(self.x, self.v, self.g, perm, cfg.beta)
+                o.step_gossip_ext(self.xo, self.vo, self.go, self.lrc, cfg.momentum, cfg.beta, perm, stale=True, n=d)
+            elif cfg.rule == "gossip_push":                       # senders-first walk, fp64 sums in visiting order
+                target = G.make_targets(cfg.seed, t, self.k, True)
+                self.ctx.step_gossip_push(self.x, self.v, self.g, target)
+                o.step_gossip_push(self.xo, self.vo, self.go, self.lrc, cfg.momentum, target, n=d)
             elif cfg.rule == "allreduce":
                 self.ctx.step_allreduce(self.x, self.v, self.g)
                 o.step_allreduce(self.xo, self.vo, self.go, self.lrc, cfg.momentum, n=d)
@@ -108,6 +122,14 @@ class _Run:
 
     def check(self):
         what = "%s after %d steps" % (self.cfg.name, self.t)
+        if self.cfg.rule == "gossip_push":
+            # both sides round fp64 sums taken in different orders: adjacent floats at worst, and a last-place
+            # difference then travels through the later steps, so the bar is the parameter tolerance on every element
+            got = self.x.cpu().numpy()[:, :self.d]
+            ref = self.xo[:, :self.d]
+            assert np.abs(got.astype(np.float64) - ref).max() <= 1e-6 * max(1.0, np.abs(ref).max()), what
+            assert (got.view(np.uint32) == ref.view(np.uint32)).mean() >= 0.9999, what
+            return
         _assert_full_equal(self.x, self.xo, self.d, what + ": x")
         _assert_full_equal(self.v, self.vo, self.d, what + ": v")
         if self.cfg.rule == "easgd":
@@ -142,6 +164,20 @@ def test_easgd_resnet50_full_arrays_5_steps(G, oracle):
     run = _Run(G, oracle, W.CONFIGS["easgd_r50"])
     try:
         run.advance(5)
+        run.check()
+    finally:
+        run.close()
+
+
+@pytest.mark.parametrize("rule", ["gossip_pull", "gossip_stale", "gossip_push"])
+def test_other_gossip_forms_resnet18_full_arrays(G, oracle, rule):
+    """Tree walk (iid pull targets), stale parameters and the senders-first push walk, k = 32 at ResNet-18 size,
+    every tile, 6 steps from a common start (the noise spreads the replicas from the first step on)."""
+    base = W.CONFIGS["gossip_r18"]
+    cfg = W.Config("%s_r18" % rule, rule, base.k, base.d, 6)
+    run = _Run(G, oracle, cfg)
+    try:
+        run.advance(6)
         run.check()
     finally:
         run.close()
