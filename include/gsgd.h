@@ -118,7 +118,8 @@ int gsgd_set_local_step(gsgd_ctx* ctx, float weight_decay, int nesterov);
  * not depend on it.  Host only. */
 int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups);
 
-/* How the k-way sums of gsgd_step_allreduce and gsgd_step_easgd are laid out.
+/* How the k-way sums of gsgd_step_allreduce (the average of Algorithm 1) and
+ * gsgd_step_easgd (the server's sum of Algorithm 2) are laid out.
  *   GSGD_ROW_SPLIT_OFF : one thread per four columns adds all k rows in fp64 in
  *                        ascending order (bit-identical to a serial sum);
  *   GSGD_ROW_SPLIT_ON  : the rows are split into blocks over the wavefronts of
