@@ -35,6 +35,7 @@ def test_captured_steps_replay_like_eager_runs(oracle):
         x, v, g, c = dev(inp.x), dev(inp.v), dev(inp.g), dev(inp.center)
         h, xs = dev(inp.h), dev(inp.xstar)
         x_init, v_init, c_init = x.clone(), v.clone(), c.clone()
+        stats_out = torch.zeros(4, dtype=torch.float64, device="cuda")
 
         def run():
             for t in range(steps):
@@ -45,6 +46,8 @@ def test_captured_steps_replay_like_eager_runs(oracle):
                     ctx.step_gossip_pull(x, v, g, G.make_targets(SEED, t, k), 0.5)
                 else:
                     ctx.step_easgd(x, v, g, c, 0.1)
+            # the statistics call that neither allocates nor waits can be recorded with the steps
+            G.stats_static(k, d, ld, x, xs, stats_out)
 
         run()                                            # eager
         torch.cuda.synchronize()
@@ -63,6 +66,10 @@ def test_captured_steps_replay_like_eager_runs(oracle):
             assert_bitwise(x.cpu().numpy(), xo, "replay %d x" % replay)
             assert_bitwise(v.cpu().numpy(), vo, "replay %d v" % replay)
             assert_bitwise(c.cpu().numpy(), co, "replay %d center" % replay)
+            recorded = stats_out.cpu().numpy().copy()
+            assert np.array_equal(recorded, ctx.stats(x, xs)), "replay %d statistics" % replay
+            assert np.allclose(recorded, oracle.stats(xo, inp.xstar, n=d), rtol=1e-11, atol=0)
+            stats_out.fill_(-1.0)
             # unrelated eager work through the same context between replays
             scratch_x, scratch_v = x.clone(), v.clone()
             ctx.step_allreduce(scratch_x, scratch_v, g)
