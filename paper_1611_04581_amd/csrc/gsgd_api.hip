@@ -39,7 +39,8 @@ namespace {
 
 // Persistent workgroups per compute unit for each streaming kernel
 // (GSGD_KERNEL_* order).  Measured on MI355X at the benchmark shapes.
-constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 4u, 2u, 1u};
+// (the generator and the local step are plain grids: for the generator the width is its tiles per band, 0 = default)
+constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 0u, 2u, 1u};
 
 // Elastic averaging with few replicas is not limited by the memory system but by what one workgroup per compute
 // unit keeps in flight over its short tiles (almost no DRAM-credit stalls at k = 16): two per compute unit gain
@@ -317,11 +318,9 @@ extern "C" int gsgd_gen_grad(gsgd_ctx* ctx, const float* x, const float* h, cons
         !vector_clear_of(ctx, xstar, g, g))
         return GSGD_ERR_INVALID_ARG;
     if (step > 0xFFFFFFFFull) return GSGD_ERR_INVALID_ARG;
-    const Persist ps = persist_of(ctx, GSGD_KERNEL_GEN_GRAD, stream);
-    if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_gen_grad(geom_of(ctx), x, h, xstar, g, ctx->cfg.sigma, key_of(ctx),
                                          static_cast<uint32_t>(step), ctx->cfg.noise_kind,
-                                         ps, static_cast<hipStream_t>(stream));
+                                         ctx->width[GSGD_KERNEL_GEN_GRAD], static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 

@@ -118,8 +118,9 @@ hipError_t launch_step_allreduce(const Geom&, const Hyper&, const SegTable&, flo
                                  Persist, bool row_split, hipStream_t);
 hipError_t launch_step_easgd(const Geom&, const Hyper&, const SegTable&, float alpha_e,
                              float* x, float* v, const float* g, float* center, Persist, bool row_split, hipStream_t);
+// band_tiles: 1024-column tiles per band of the plain grid, 0 = the default
 hipError_t launch_gen_grad(const Geom&, const float* x, const float* h, const float* xstar, float* g,
-                           float sigma, RngKey key, uint32_t step, int noise_kind, Persist, hipStream_t);
+                           float sigma, RngKey key, uint32_t step, int noise_kind, unsigned band_tiles, hipStream_t);
 hipError_t launch_fill(int64_t d, float* dst, int which, RngKey key, hipStream_t);
 hipError_t launch_init_replicas(const Geom&, float* x, float* v, float* center, const float* x0, int mode,
                                 RngKey key, hipStream_t);
