@@ -412,6 +412,30 @@ def main():
         arun.close()
         del arun
 
+    if not args.no_extras and not args.no_legs and cfg.name == "gossip_r50":
+        # short vectors: the k-way sums with the rows split over the wavefronts of a workgroup (LDS-staged block sums)
+        # against one thread per four columns walking all k rows
+        rows = {}
+        for (ks, ds) in ((128, 16384), (128, 65536), (32, 65536)):
+            scfg = W.Config("short", "allreduce", ks, ds, 0)
+            srun = Run(gsgd, W, scfg)
+            cell = {}
+            for label, mode in (("serial_us", gsgd.ROW_SPLIT_OFF), ("row_split_us", gsgd.ROW_SPLIT_ON)):
+                srun.ctx.set_row_split(mode)
+                for t in range(5):
+                    srun.step(t)
+                cell["allreduce_" + label] = srun.kernel_seconds(srun.step, 50) * 1e6
+            srun.cfg = W.Config("short", "easgd", ks, ds, 0, alpha_e=0.9 / ks)
+            for label, mode in (("serial_us", gsgd.ROW_SPLIT_OFF), ("row_split_us", gsgd.ROW_SPLIT_ON)):
+                srun.ctx.set_row_split(mode)
+                for t in range(5):
+                    srun.step(t)
+                cell["easgd_" + label] = srun.kernel_seconds(srun.step, 50) * 1e6
+            rows["k=%d,d=%d" % (ks, ds)] = cell
+            srun.close()
+        out["extras"]["short_vectors_step_us"] = rows
+        log("short vectors:", json.dumps(rows))
+
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample ---------------------
     if args.cpu_seconds > 0:
         from oracle import oracle
