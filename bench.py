@@ -83,11 +83,11 @@ def bytes_per_replica_element(rule, k):
 class Run:
     """One configuration with its state resident on the GPU."""
 
-    def __init__(self, gsgd, W, cfg, launch_width=0):
+    def __init__(self, gsgd, W, cfg, launch_width=0, ld=0):
         import torch
         self.gsgd, self.cfg, self.torch = gsgd, cfg, torch
         k, d = cfg.k, cfg.d
-        self.k, self.d, self.ld = k, d, W.round_up(d, 1024)
+        self.k, self.d, self.ld = k, d, (ld if ld else W.round_up(d, 1024))
         seg = {}
         if cfg.layout:
             off, sc, _ = W.resnet_layout(cfg.layout)
@@ -182,17 +182,21 @@ class Run:
         self.torch.cuda.empty_cache()
 
 
-def short_leg(gsgd, W, name, warmup=5, steps=30, repeats=3):
-    """One of the other benchmark configurations as a short leg: median kernel time of `repeats` timed runs."""
+def short_leg(gsgd, W, name, warmup=5, steps=30, repeats=3, fresh_allocations=0):
+    """One of the other benchmark configurations as a short leg: median kernel time of `repeats` timed runs, and
+    optionally the same measurement on `fresh_allocations` further allocations of x / v / g."""
     cfg = W.CONFIGS[name]
     run = Run(gsgd, W, cfg)
     try:
-        for t in range(warmup):
-            run.step(t)
-        ms = []
-        for r in range(repeats):
-            _, ev = run.timed(run.step, steps, warmup + r * steps)
-            ms.append(ev / (steps * run.launches_per_step()) * 1e3)
+        def measure():
+            for t in range(warmup):
+                run.step(t)
+            ms = []
+            for r in range(repeats):
+                _, ev = run.timed(run.step, steps, warmup + r * steps)
+                ms.append(ev / (steps * run.launches_per_step()) * 1e3)
+            return ms
+        ms = measure()
         med = statistics.median(ms)
         out = {"rule": cfg.rule, "k": cfg.k, "d": cfg.d, "layout": cfg.layout or "flat", "kernel_ms": med,
                "kernel_ms_min": min(ms), "kernel_ms_max": max(ms),
@@ -201,6 +205,12 @@ def short_leg(gsgd, W, name, warmup=5, steps=30, repeats=3):
             out["frac_of_hbm_peak"] = run.algorithmic_bytes() / (med * 1e-3) / 1e9 / HBM_PEAK_GBS
             out["algorithmic_bytes_per_launch"] = run.algorithmic_bytes()
             out.update(traffic_of(name))
+            if fresh_allocations:
+                fr = [out["frac_of_hbm_peak"]]
+                for a in range(fresh_allocations):
+                    run.allocate()
+                    fr.append(run.algorithmic_bytes() / (statistics.median(measure()) * 1e-3) / 1e9 / HBM_PEAK_GBS)
+                out["frac_of_hbm_peak_fresh_allocations"] = fr
         return out
     finally:
         run.close()
@@ -220,6 +230,8 @@ def main():
     ap.add_argument("--no-legs", action="store_true", help="skip the other benchmark configurations")
     ap.add_argument("--launch-width", type=int, default=0,
                     help="persistent workgroups per streaming kernel (0 = the library's default)")
+    ap.add_argument("--ld", type=int, default=0,
+                    help="row stride of x / v / g in elements (a multiple of 4, >= d; 0 = d rounded up to 1024)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain elementwise copy of a k x ld fp32 matrix (known size), so that a "
                          "rocprofv3 --pmc run has a reference dispatch to scale FETCH_SIZE / WRITE_SIZE by")
@@ -236,7 +248,7 @@ def main():
     torch.cuda.set_device(0)
     cfg = W.CONFIGS[args.config]
     K, Wm = args.steps, args.warmup
-    run = Run(gsgd, W, cfg, args.launch_width)
+    run = Run(gsgd, W, cfg, args.launch_width, args.ld)
     k, d, ld = run.k, run.d, run.ld
     ctx, h, xstar = run.ctx, run.h, run.xstar
     log("config %s: rule=%s k=%d d=%d ld=%d steps=%d warmup=%d" % (cfg.name, cfg.rule, k, d, ld, K, Wm))
@@ -383,7 +395,8 @@ def main():
         # the other benchmark configurations (and the gossip step at ResNet-18 size), each a short leg of its own
         legs = {}
         for name in ("tiny", "allreduce_r18", "gossip_r18", "easgd_r50", "seg_gossip_r50_k128"):
-            legs[name] = short_leg(gsgd, W, name)
+            # the 39 GB configuration is the one whose rate depends most on where its arrays land: three placements
+            legs[name] = short_leg(gsgd, W, name, fresh_allocations=2 if name == "seg_gossip_r50_k128" else 0)
             log("leg %s: %s" % (name, json.dumps(legs[name])))
         out["extras"]["other_configs"] = legs
 
