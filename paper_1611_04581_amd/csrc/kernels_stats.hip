@@ -3,7 +3,7 @@
 // and the mean's own distance.  Not part of the timed step.
 //
 // Per column the replica mean and the squared deviations are taken in fp64 in
-// two passes over the rows (second pass re-reads x).  Across columns the
+// one pass over the rows (x is read once).  Across columns the
 // reduction is wavefront-wide by DPP lane exchanges, block-wide through LDS,
 // and grid-wide through a partials buffer summed by a second one-block kernel
 // in a fixed order, so the result is reproducible run to run.
@@ -51,6 +51,15 @@ __device__ __forceinline__ void block_sum4(double val[4], double (*lds)[4])
     }
 }
 
+// Rows of x in flight per thread in the statistics pass.
+constexpr int STATS_ROWS_IN_FLIGHT = 4;
+
+// One pass over the rows.  Per column the deviations are taken from the first
+// row's value r instead of from the mean, which is not known yet:
+//   sum_i (x_i - xbar)^2 = sum_i (x_i - r)^2 - (sum_i (x_i - r))^2 / k,   xbar = r + (sum_i (x_i - r)) / k.
+// x_i - r is exact in fp64 for fp32 inputs, and since r is one of the k values, (xbar - r)^2 <= the left side, so
+// the subtraction loses at most a factor k + 1 of fp64's precision; k equal values give exactly zero.
+// Lanes past the vector's end load zeros for x and xstar and so add nothing.
 __global__ __launch_bounds__(BLOCK)
 void stats_partial_kernel(Geom geo, const float* __restrict__ x, const float* __restrict__ xstar,
                           double* __restrict__ partials)
@@ -62,39 +71,45 @@ void stats_partial_kernel(Geom geo, const float* __restrict__ x, const float* __
         const int valid = qd.valid;
         const float* xq = x + qd.col;
         const f32x4 xs4 = load_quad_cached(xstar + qd.col, valid);
-        double sum[4] = {0.0, 0.0, 0.0, 0.0};
-        for (int i = 0; i < geo.k; ++i) {
-            const f32x4 xi = load_quad_cached(xq + static_cast<int64_t>(i) * geo.ld, valid);
-            sum[0] += static_cast<double>(xi.x);
-            sum[1] += static_cast<double>(xi.y);
-            sum[2] += static_cast<double>(xi.z);
-            sum[3] += static_cast<double>(xi.w);
-        }
-        const double kd = static_cast<double>(geo.k);
-        const double xbar[4] = {sum[0] / kd, sum[1] / kd, sum[2] / kd, sum[3] / kd};
+        const f32x4 r4 = load_quad(xq, valid);
         const double xs[4] = {static_cast<double>(xs4.x), static_cast<double>(xs4.y),
                               static_cast<double>(xs4.z), static_cast<double>(xs4.w)};
-        for (int i = 0; i < geo.k; ++i) {
-            const f32x4 xi = load_quad_cached(xq + static_cast<int64_t>(i) * geo.ld, valid);
+        const double ref[4] = {static_cast<double>(r4.x), static_cast<double>(r4.y),
+                               static_cast<double>(r4.z), static_cast<double>(r4.w)};
+        double s1[4] = {0.0, 0.0, 0.0, 0.0}, s2[4] = {0.0, 0.0, 0.0, 0.0};
+        auto visit = [&](f32x4 xi) {
             const double xv[4] = {static_cast<double>(xi.x), static_cast<double>(xi.y),
                                   static_cast<double>(xi.z), static_cast<double>(xi.w)};
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                if (m < valid) {
-                    const double a = xv[m] - xbar[m];
-                    const double b = xv[m] - xs[m];
-                    acc[0] += a * a;
-                    acc[1] += b * b;
-                }
+                const double a = xv[m] - ref[m];
+                const double b = xv[m] - xs[m];
+                s1[m] += a;
+                s2[m] += a * a;
+                acc[1] += b * b;
             }
+        };
+        visit(r4);                                            // row 0: deviation zero, distance counted
+        int i = 1;
+        for (; i + STATS_ROWS_IN_FLIGHT <= geo.k; i += STATS_ROWS_IN_FLIGHT) {
+            f32x4 xi[STATS_ROWS_IN_FLIGHT];
+#pragma unroll
+            for (int u = 0; u < STATS_ROWS_IN_FLIGHT; ++u)
+                xi[u] = load_quad(xq + static_cast<int64_t>(i + u) * geo.ld, valid);
+#pragma unroll
+            for (int u = 0; u < STATS_ROWS_IN_FLIGHT; ++u) visit(xi[u]);
         }
+        for (; i < geo.k; ++i) visit(load_quad(xq + static_cast<int64_t>(i) * geo.ld, valid));
+        const double kd = static_cast<double>(geo.k);
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
-            if (m < valid) {
-                const double c = xbar[m] - xs[m];
-                acc[2] += c * c;
-                acc[3] += xbar[m] * xbar[m];
-            }
+            const double shift = s1[m] / kd;                  // xbar - ref
+            const double dev = s2[m] - s1[m] * shift;
+            const double xbar = ref[m] + shift;
+            const double c = xbar - xs[m];
+            acc[0] += dev > 0.0 ? dev : 0.0;
+            acc[2] += c * c;
+            acc[3] += xbar * xbar;
         }
     }
     block_sum4(acc, lds);

@@ -292,6 +292,43 @@ def test_stats(G, oracle):
         assert ctx.stats(dev(inp2.x), dev(inp2.xstar))[0] == 0.0
 
 
+def _stats_cases():
+    rng = np.random.default_rng(5)
+    k, d = 13, 3 * 1024 + 2
+    yield "clustered_far_from_zero", (3.0 + 1e-5 * rng.standard_normal((k, d))).astype(np.float32)
+    a = (1e-3 * rng.standard_normal((k, d))).astype(np.float32)
+    a[0] = 1e3
+    yield "first_row_an_outlier", a
+    b = (1e-3 * rng.standard_normal((k, d))).astype(np.float32)
+    b[-1] = -1e3
+    yield "last_row_an_outlier", b
+    yield "one_replica", rng.standard_normal((1, d)).astype(np.float32)
+    yield "most_replicas", rng.standard_normal((128, 1024 + 1)).astype(np.float32)
+    yield "huge", (1e18 * rng.standard_normal((k, d))).astype(np.float32)
+    yield "subnormal", (1e-41 * rng.standard_normal((k, d))).astype(np.float32)
+    c = np.repeat(rng.standard_normal((1, d)).astype(np.float32), k, axis=0)
+    c[5, 7] = np.nextafter(c[5, 7], np.float32(9))
+    yield "one_value_one_ulp_off", c
+
+
+@pytest.mark.parametrize("name,x", list(_stats_cases()), ids=[n for n, _ in _stats_cases()])
+def test_stats_where_one_pass_could_cancel(G, oracle, name, x):
+    """The kernel reads x once and takes deviations from the first row; the oracle is the two-pass definition
+    (Section 6.1's quantities).  Inputs where a one-pass sum of squares would lose everything."""
+    k, d = x.shape
+    ld = W.round_up(d, 4)
+    xp = np.zeros((k, ld), np.float32)
+    xp[:, :d] = x
+    xs = np.zeros(ld, np.float32)
+    xs[:d] = np.random.default_rng(1).standard_normal(d).astype(np.float32)
+    want = oracle.stats(xp, xs, n=d)
+    with G.Context(k, d, ld) as ctx:
+        got = ctx.stats(dev(xp), dev(xs))
+    assert np.allclose(got, want, rtol=1e-11, atol=0), (name, got, want)
+    if k == 1:
+        assert got[0] == 0.0
+
+
 def test_bad_arguments_leave_state_untouched(G):
     import torch
     k, d = 4, 1024
