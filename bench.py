@@ -384,6 +384,11 @@ def main():
                 s_f = run.kernel_seconds(fn, n3, 1000)
                 extras[name + "_ms"] = s_f * 1e3
                 extras[name + "_frac_of_hbm_peak"] = 20.0 * k * d / s_f / 1e9 / HBM_PEAK_GBS
+        # the diagnostics (not part of a step): one read of x, 4 B per replica-element
+        if d <= gsgd.STATS_STATIC_MAX_D:
+            stats_out = torch.empty(4, dtype=torch.float64, device="cuda")
+            s_st = run.kernel_seconds(lambda t: gsgd.stats_static(k, d, ld, x, xstar, stats_out), n3)
+            extras["stats"] = roof(s_st * 1e3, 4.0 + 4.0 / k, False)
         out["extras"] = extras
         log("extras:", json.dumps(extras))
 
