@@ -83,17 +83,21 @@ def bytes_per_replica_element(rule, k):
 class Run:
     """One configuration with its state resident on the GPU."""
 
-    def __init__(self, gsgd, W, cfg, launch_width=0, ld=0):
+    def __init__(self, gsgd, W, cfg, launch_width=0, ld=0, block_columns=None):
+        """block_columns: None = the blocked layout the configuration names, 0 = row-major matrices."""
         import torch
         self.gsgd, self.cfg, self.torch = gsgd, cfg, torch
         k, d = cfg.k, cfg.d
-        self.k, self.d, self.ld = k, d, (ld if ld else W.round_up(d, 1024))
+        if block_columns is None:
+            block_columns = 0 if ld else cfg.block_columns           # an explicit row stride means row-major
+        self.k, self.d, self.ld = k, d, (ld if ld else W.round_up(d, block_columns if block_columns else 1024))
+        self.block_columns = block_columns
         seg = {}
         if cfg.layout:
             off, sc, _ = W.resnet_layout(cfg.layout)
             seg = dict(seg_offsets=off, seg_lr_scale=sc)
         self.ctx = gsgd.Context(k, d, self.ld, lr=cfg.lr, momentum=cfg.momentum, sigma=cfg.sigma, seed=cfg.seed,
-                                noise_kind=gsgd.NOISE_GAUSSIAN, **seg)
+                                noise_kind=gsgd.NOISE_GAUSSIAN, block_columns=block_columns, **seg)
         if launch_width:
             for kern in range(gsgd.KERNEL_COUNT):
                 self.ctx.set_launch_width(kern, launch_width)
@@ -198,7 +202,8 @@ def short_leg(gsgd, W, name, warmup=5, steps=30, repeats=3, fresh_allocations=0)
             return ms
         ms = measure()
         med = statistics.median(ms)
-        out = {"rule": cfg.rule, "k": cfg.k, "d": cfg.d, "layout": cfg.layout or "flat", "kernel_ms": med,
+        out = {"rule": cfg.rule, "k": cfg.k, "d": cfg.d, "layout": cfg.layout or "flat",
+               "block_columns": run.block_columns, "kernel_ms": med,
                "kernel_ms_min": min(ms), "kernel_ms_max": max(ms),
                "replica_steps_per_s": cfg.k / (med * run.launches_per_step() * 1e-3)}
         if name != "tiny":           # the tiny configuration lives in cache and is launch-bound: no bandwidth figure
@@ -231,7 +236,10 @@ def main():
     ap.add_argument("--launch-width", type=int, default=0,
                     help="persistent workgroups per streaming kernel (0 = the library's default)")
     ap.add_argument("--ld", type=int, default=0,
-                    help="row stride of x / v / g in elements (a multiple of 4, >= d; 0 = d rounded up to 1024)")
+                    help="row-major x / v / g with this row stride in elements (a multiple of 4, >= d)")
+    ap.add_argument("--block-columns", type=int, default=-1,
+                    help="columns per block of the blocked matrix layout (a power of two >= 1024); 0 = row-major "
+                         "matrices with the row stride rounded up to 1024; default: what the configuration names")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain elementwise copy of a k x ld fp32 matrix (known size), so that a "
                          "rocprofv3 --pmc run has a reference dispatch to scale FETCH_SIZE / WRITE_SIZE by")
@@ -248,7 +256,7 @@ def main():
     torch.cuda.set_device(0)
     cfg = W.CONFIGS[args.config]
     K, Wm = args.steps, args.warmup
-    run = Run(gsgd, W, cfg, args.launch_width, args.ld)
+    run = Run(gsgd, W, cfg, args.launch_width, args.ld, None if args.block_columns < 0 else args.block_columns)
     k, d, ld = run.k, run.d, run.ld
     ctx, h, xstar = run.ctx, run.h, run.xstar
     log("config %s: rule=%s k=%d d=%d ld=%d steps=%d warmup=%d" % (cfg.name, cfg.rule, k, d, ld, K, Wm))
@@ -294,9 +302,11 @@ def main():
         "value": value, "unit": "replica-steps/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: k=%d replicas, d=%d fp32 (row stride %d), rule=%s, fresh Philox peer permutation "
-                               "per step, x/v/g resident in HBM" % (cfg.name, k, d, ld, cfg.rule),
-                   "k": k, "d": d, "ld": ld, "rule": cfg.rule, "lr": cfg.lr, "momentum": cfg.momentum,
+        "config": {"workload": "%s: k=%d replicas, d=%d fp32 (%s), rule=%s, fresh Philox peer permutation "
+                               "per step, x/v/g resident in HBM"
+                               % (cfg.name, k, d, "blocks of %d columns, k x %d elements per matrix" % (run.block_columns, ld)
+                                  if run.block_columns else "row-major, row stride %d" % ld, cfg.rule),
+                   "k": k, "d": d, "ld": ld, "block_columns": run.block_columns, "rule": cfg.rule, "lr": cfg.lr, "momentum": cfg.momentum,
                    "beta": cfg.beta, "sigma": cfg.sigma, "layout": cfg.layout or "flat"},
         "roofline": {"bound": "hbm", "kernel": KERNEL_OF_RULE[cfg.rule], "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, **traffic_of(cfg.name),
@@ -385,16 +395,35 @@ def main():
                 extras[name + "_ms"] = s_f * 1e3
                 extras[name + "_frac_of_hbm_peak"] = 20.0 * k * d / s_f / 1e9 / HBM_PEAK_GBS
         # the diagnostics (not part of a step): one read of x, 4 B per replica-element
-        if d <= gsgd.STATS_STATIC_MAX_D:
+        if d <= gsgd.STATS_STATIC_MAX_D and not run.block_columns:      # that entry point reads row-major matrices
             stats_out = torch.empty(4, dtype=torch.float64, device="cuda")
             s_st = run.kernel_seconds(lambda t: gsgd.stats_static(k, d, ld, x, xstar, stats_out), n3)
             extras["stats"] = roof(s_st * 1e3, 4.0 + 4.0 / k, False)
         out["extras"] = extras
         log("extras:", json.dumps(extras))
 
+    blocked = run.block_columns
     run.close()
     del x, v, g, run
     torch.cuda.empty_cache()
+
+    if not args.no_extras and blocked:
+        # the same step on row-major matrices (row stride rounded up to 1024), for comparison, and the statistics
+        # kernel through the entry point that allocates nothing (it reads row-major matrices)
+        rm = Run(gsgd, W, cfg, args.launch_width, 0, 0)
+        for t in range(5):
+            rm.step(t)
+        s_rm = rm.kernel_seconds(rm.step, n3, 5) / rm.launches_per_step()
+        cmp_rm = {"ld": rm.ld, "kernel_ms": s_rm * 1e3, "frac_of_hbm_peak": alg_bytes / s_rm / 1e9 / HBM_PEAK_GBS}
+        if d <= gsgd.STATS_STATIC_MAX_D:
+            stats_out = torch.empty(4, dtype=torch.float64, device="cuda")
+            s_st = rm.kernel_seconds(lambda t: gsgd.stats_static(k, d, rm.ld, rm.x, rm.xstar, stats_out), n3)
+            cmp_rm["stats"] = roof(s_st * 1e3, 4.0 + 4.0 / k, False)
+        out["extras"]["row_major_layout"] = cmp_rm
+        log("row-major layout:", json.dumps(cmp_rm))
+        rm.close()
+        del rm
+        torch.cuda.empty_cache()
 
     if not args.no_extras and not args.no_legs and cfg.name == "gossip_r50":
         # the other benchmark configurations (and the gossip step at ResNet-18 size), each a short leg of its own

@@ -18,6 +18,14 @@
  *     elements (ld >= d, ld % 4 == 0); element (i, j) is at base[i*ld + j].
  *     Only columns 0..d-1 are read or written.  center, h, xstar, x0 are fp32
  *     vectors of at least d elements.
+ *   - Blocked layout (gsgd_config.block_columns = B > 0, a power of two >= 1024,
+ *     ld a multiple of B): the same k * ld elements hold the columns in blocks
+ *     of B, each block with its k row pieces back to back; element (i, j) is at
+ *     base[(j / B) * k * B + i * B + j % B].  A replica's vector is then a
+ *     sequence of B-element pieces k * B apart, and the k values of a column
+ *     lie B elements apart instead of ld, which is what the kernels that walk
+ *     a column's replicas stream fastest.  Every entry point that takes a
+ *     context follows the context's layout; vectors are plain in both.
  *   - Every pointer named "device" is GPU memory owned by the caller, 16-byte
  *     aligned, valid until the stream has run the call.  The library never
  *     frees or reallocates caller memory.  x, v, g, center must not overlap,
@@ -89,6 +97,7 @@ typedef struct gsgd_config {
     int32_t  n_seg;                 /* 0 = flat vector; else number of per-layer tensors laid back to back */
     const int64_t* seg_offsets;     /* host, n_seg+1 entries, [0] = 0, strictly ascending, [n_seg] = d; copied */
     const float*   seg_lr_scale;    /* host, n_seg entries; segment s steps with lr * seg_lr_scale[s]; copied */
+    int64_t  block_columns;         /* 0 = row-major matrices; else the blocked layout's B (see "Memory model") */
 } gsgd_config;
 
 /* Create / destroy a context.  gsgd_create validates the configuration, copies
@@ -373,8 +382,8 @@ int gsgd_stats(gsgd_ctx* ctx, const float* x, const float* xstar, double out[4],
  * follow one another on a stream are fine, whatever their sizes (every partial
  * a call reads it has written itself).  The array's device address is looked
  * up on the first call on a device (and by gsgd_create); make that first call
- * outside a stream capture.  k, d, ld as in gsgd_config.  x: device k x ld.
- * xstar: device d. */
+ * outside a stream capture.  k, d, ld as in gsgd_config.  x: device k x ld,
+ * row-major (there is no context to say otherwise).  xstar: device d. */
 #define GSGD_STATS_STATIC_MAX_D ((int64_t)1 << 26)
 int gsgd_stats_static(int32_t k, int64_t d, int64_t ld, const float* x, const float* xstar,
                       double* out_device, void* stream);

@@ -268,22 +268,34 @@ __device__ __forceinline__ f32x4 quad_lr(const SegTable& seg, const SegLds& lds,
     return seg_lookup(seg.offsets, seg.scales, seg.n_seg, col, valid, lr);
 }
 
-// Quad geometry of a thread.  Addresses are formed as
-//   (array + row * ld + tile_col)  +  lane_col
+// Where column `col` of row 0 sits in a matrix (uniform arithmetic when `col` is).
+__device__ __forceinline__ int64_t column_origin(const Geom& geo, int64_t col)
+{
+    if (geo.block_log2 < 0) return col;
+    const int b = geo.block_log2;
+    return (((col >> b) * geo.k) << b) + (col & ((static_cast<int64_t>(1) << b) - 1));
+}
+
+// Quad geometry of a thread.  Matrix addresses are formed as
+//   (array + row * rs + mat)  +  lane_col
 // with the first part uniform over the workgroup (scalar registers, scalar
 // arithmetic) and only the small lane offset per thread, so that row accesses
-// compile to scalar-base + 32-bit-offset global loads and stores.
+// compile to scalar-base + 32-bit-offset global loads and stores.  The shared
+// vectors (h, xstar, center) are plain arrays indexed by `col`.
 struct Quad {
     int64_t  tile_col;   // first column of the workgroup's tile (uniform)
+    int64_t  mat;        // where that column of row 0 sits in a matrix (uniform)
     uint32_t lane_col;   // this thread's first column inside the tile
     int64_t  col;        // tile_col + lane_col
     int      valid;      // 0 (no work), 1..3 (ragged tail) or 4
 };
 
+// Vectors only (no matrix in sight): `mat` is the column itself.
 __device__ __forceinline__ Quad quad_of_tile(int64_t tile, int64_t d)
 {
     Quad out;
     out.tile_col = tile * (BLOCK * 4);
+    out.mat = out.tile_col;
     out.lane_col = threadIdx.x * 4u;
     out.col = out.tile_col + out.lane_col;
     const int64_t left = d - out.col;
@@ -291,8 +303,16 @@ __device__ __forceinline__ Quad quad_of_tile(int64_t tile, int64_t d)
     return out;
 }
 
+__device__ __forceinline__ Quad quad_of_tile(int64_t tile, const Geom& geo)
+{
+    Quad out = quad_of_tile(tile, geo.d);
+    out.mat = column_origin(geo, out.tile_col);
+    return out;
+}
+
 // One tile per workgroup, tile = workgroup index (the cold kernels).
 __device__ __forceinline__ Quad my_quad(int64_t d) { return quad_of_tile(static_cast<int64_t>(blockIdx.x), d); }
+__device__ __forceinline__ Quad my_quad(const Geom& geo) { return quad_of_tile(static_cast<int64_t>(blockIdx.x), geo); }
 
 // Persistent workgroups for the streaming kernels.  A launch has far fewer
 // workgroups than tiles (about one per compute unit); each pulls the next
@@ -354,5 +374,34 @@ __device__ __forceinline__ bool tile_is_full(const Quad& qd, int64_t d)
 
 inline int64_t num_quads(int64_t d) { return (d + 3) / 4; }
 inline unsigned grid_for(int64_t d) { return static_cast<unsigned>((num_quads(d) + BLOCK - 1) / BLOCK); }
+
+// Grid of the plain (one tile of one row per workgroup) kernels: x = tile inside a band of `band` consecutive
+// tiles, y = row, z = band; a kernel's tile is blockIdx.z * band + blockIdx.x.  Workgroups are dispatched x
+// first, then y: a band's k row pieces follow one another, so what the rows share (h, xstar of the band's
+// columns) is still cached, and in the blocked layout, where a band is a block, the sweep is in address order.
+// `row_major_band` is the band for row-major matrices (0: the whole row); blocked matrices use it only if it
+// is a proper divisor of the block.
+struct FlatGrid {
+    dim3     grid;
+    unsigned band;
+};
+inline FlatGrid flat_grid(const Geom& geo, unsigned row_major_band)
+{
+    const unsigned tiles = grid_for(geo.d);
+    unsigned band = row_major_band == 0 ? tiles : row_major_band;
+    if (geo.block_log2 >= 0) {
+        // a block, or the requested part of one if that divides it
+        const unsigned per_block = static_cast<unsigned>(geo.rs / (BLOCK * 4));
+        band = (row_major_band != 0 && row_major_band < per_block && per_block % row_major_band == 0) ? row_major_band : per_block;
+    }
+    if (band > tiles) band = tiles;
+    unsigned bands = (tiles + band - 1) / band;
+    if (bands > 65535u) {                                  // the grid's z extent is 16 bits: whole multiples of a band
+        const unsigned per = (bands + 65534u) / 65535u;
+        band *= per;
+        bands = (tiles + band - 1) / band;
+    }
+    return FlatGrid{dim3(band, static_cast<unsigned>(geo.k), bands), band};
+}
 
 }  // namespace gsgd

@@ -39,8 +39,8 @@ namespace {
 
 // Persistent workgroups per compute unit for each streaming kernel
 // (GSGD_KERNEL_* order).  Measured on MI355X at the benchmark shapes.
-// (the generator and the local step are plain grids: for the generator the width is its tiles per band, 0 = default)
-constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 0u, 2u, 1u};
+// (the generator and the local step are plain grids: their width is the tiles per band of the grid, 0 = default)
+constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 0u, 2u, 0u};
 
 // Elastic averaging with few replicas is not limited by the memory system but by what one workgroup per compute
 // unit keeps in flight over its short tiles (almost no DRAM-credit stalls at k = 16): two per compute unit gain
@@ -62,7 +62,7 @@ inline int hip_fail(gsgd_ctx* ctx, hipError_t e)
     return GSGD_ERR_HIP;
 }
 
-inline Geom geom_of(const gsgd_ctx* c) { return Geom{c->cfg.k, c->cfg.d, c->cfg.ld}; }
+inline Geom geom_of(const gsgd_ctx* c) { return make_geom(c->cfg.k, c->cfg.d, c->cfg.ld, c->cfg.block_columns); }
 inline Hyper hyper_of(const gsgd_ctx* c) { return Hyper{c->cfg.lr, c->cfg.momentum, c->weight_decay, c->nesterov}; }
 inline SegTable seg_of(const gsgd_ctx* c) { return SegTable{c->d_offsets, c->d_scales, c->cfg.n_seg}; }
 // Index of the ticket pair of `stream`, claiming a free one on first use; -1 when all are taken.
@@ -108,7 +108,14 @@ inline bool ok_matrix(const void* p) { return p && aligned16(p); }
 // and the same for a shared d-vector.
 inline size_t matrix_span(const gsgd_ctx* c)
 {
-    return sizeof(float) * (static_cast<size_t>(c->cfg.k - 1) * static_cast<size_t>(c->cfg.ld) + static_cast<size_t>(c->cfg.d));
+    const size_t k = static_cast<size_t>(c->cfg.k), d = static_cast<size_t>(c->cfg.d);
+    if (c->cfg.block_columns > 0) {
+        // every block before the one holding column d - 1 in full, then that block up to the last row's piece
+        const size_t b = static_cast<size_t>(c->cfg.block_columns);
+        const size_t last = (d - 1) / b;
+        return sizeof(float) * (last * k * b + (k - 1) * b + (d - last * b));
+    }
+    return sizeof(float) * ((k - 1) * static_cast<size_t>(c->cfg.ld) + d);
 }
 inline size_t vector_span(const gsgd_ctx* c) { return sizeof(float) * static_cast<size_t>(c->cfg.d); }
 
@@ -188,6 +195,11 @@ extern "C" int gsgd_create(const gsgd_config* cfg, gsgd_ctx** out)
     if (cfg->k < 1 || cfg->k > GSGD_MAX_K || cfg->d < 1 || cfg->ld < cfg->d || (cfg->ld & 3) != 0)
         return GSGD_ERR_INVALID_ARG;
     if (cfg->d > (static_cast<int64_t>(1) << 34)) return GSGD_ERR_INVALID_ARG;   // quad index is a 32-bit counter word
+    if (cfg->block_columns != 0) {
+        const int64_t b = cfg->block_columns;
+        // a power of two that every tile width divides, and whole blocks only
+        if (b < BLOCK_COLUMNS || (b & (b - 1)) != 0 || cfg->ld % b != 0) return GSGD_ERR_INVALID_ARG;
+    }
     if (cfg->noise_kind != GSGD_NOISE_GAUSSIAN && cfg->noise_kind != GSGD_NOISE_UNIFORM) return GSGD_ERR_INVALID_ARG;
     if (!(cfg->sigma >= 0.0f) || !(cfg->lr == cfg->lr) || !(cfg->momentum == cfg->momentum)) return GSGD_ERR_INVALID_ARG;
     if (cfg->n_seg < 0) return GSGD_ERR_INVALID_ARG;
@@ -477,9 +489,8 @@ extern "C" int gsgd_step_local(gsgd_ctx* ctx, float* x, float* v, const float* g
 {
     const int rc = check_state(ctx, x, v, g);
     if (rc != GSGD_OK) return rc;
-    const Persist ps{nullptr, 0u};                       // a plain grid: no tickets, no width
     const hipError_t e = launch_step_local(geom_of(ctx), hyper_of(ctx), seg_of(ctx), x, v, g,
-                                           ps, static_cast<hipStream_t>(stream));
+                                           ctx->width[GSGD_KERNEL_LOCAL], static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -639,7 +650,7 @@ extern "C" int gsgd_stats_static(int32_t k, int64_t d, int64_t ld, const float* 
     double* partials = nullptr;
     hipError_t e = scratch_on_current_device(&partials);
     if (e == hipSuccess)
-        e = launch_stats(Geom{k, d, ld}, x, xstar, partials, out_device, static_cast<hipStream_t>(stream));
+        e = launch_stats(make_geom(k, d, ld, 0), x, xstar, partials, out_device, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : GSGD_ERR_HIP;
 }
 

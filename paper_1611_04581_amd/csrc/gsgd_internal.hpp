@@ -65,12 +65,28 @@ struct SegTable {
     int32_t        n_seg;
 };
 
-// Problem geometry common to every kernel.
+// Problem geometry common to every kernel.  A matrix holds k rows of ld
+// columns in k * ld elements; element (i, j) sits at  origin(j) + i * rs.
+//   row-major:  origin(j) = j,  rs = ld;
+//   blocked (blocks of B = 2^block_log2 columns, a block holding its k row
+//   pieces back to back):  origin(j) = (j / B) * k * B + j % B,  rs = B.
+// B is a multiple of every tile width, so a tile never straddles a block.
 struct Geom {
     int32_t k;
+    int32_t block_log2;   // -1: row-major
     int64_t d;
     int64_t ld;
+    int64_t rs;           // distance between rows i and i + 1 of a column
 };
+
+// block_columns == 0: row-major; otherwise a power of two (checked by the caller).
+inline Geom make_geom(int32_t k, int64_t d, int64_t ld, int64_t block_columns)
+{
+    if (block_columns <= 0) return Geom{k, -1, d, ld, ld};
+    int32_t lg = 0;
+    while ((static_cast<int64_t>(1) << lg) < block_columns) ++lg;
+    return Geom{k, lg, d, ld, block_columns};
+}
 
 // Step size, momentum, and the two extras of the experiments' local step
 // (Section 4.2): weight decay and the Nesterov flag.  Kernels compiled without
@@ -107,7 +123,7 @@ hipError_t launch_async_tick_fused(const Geom&, const Hyper&, const SegTable&, f
 hipError_t launch_easgd_tick(const Geom&, const Hyper&, const SegTable&, float alpha_e, int32_t i,
                              float* x, float* v, const float* g, float* center, hipStream_t);
 hipError_t launch_step_local(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
-                             Persist, hipStream_t);
+                             unsigned band_tiles, hipStream_t);
 hipError_t launch_step_gossip_fused(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&, bool stale,
                                     bool has_trees, float* x, float* v, const float* h, const float* xstar,
                                     float sigma, RngKey key, uint32_t step, int noise_kind, Persist, hipStream_t);

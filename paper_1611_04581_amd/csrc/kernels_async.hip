@@ -19,11 +19,11 @@ void async_tick_body(const Geom& geo, const Hyper& hp, const SegTable& seg, cons
                      float sigma, RngKey key, uint32_t tick)
 {
     const int valid = FULL ? 4 : qd.valid;
-    const int64_t mine_off = static_cast<int64_t>(i) * geo.ld + qd.col;
+    const int64_t mine_off = static_cast<int64_t>(i) * geo.rs + qd.mat + qd.lane_col;
     const f32x4 X = load_quad<FULL>(x + mine_off, valid);
     const f32x4 V = load_quad<FULL>(v + mine_off, valid);
     f32x4 G, theirs = {0.f, 0.f, 0.f, 0.f};
-    if (j != i) theirs = load_quad<FULL>(x + static_cast<int64_t>(j) * geo.ld + qd.col, valid);   // uniform branch
+    if (j != i) theirs = load_quad<FULL>(x + static_cast<int64_t>(j) * geo.rs + qd.mat + qd.lane_col, valid);   // uniform branch
     if constexpr (FUSED_GEN) {
         const f32x4 h4 = load_quad<FULL>(h + qd.col, valid);
         const f32x4 xs4 = load_quad<FULL>(xstar + qd.col, valid);
@@ -52,7 +52,7 @@ void async_tick_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, int32_t
 {
     __shared__ SegLds lds;
     stage_segments(seg, lds);
-    const Quad qd = my_quad(geo.d);
+    const Quad qd = my_quad(geo);
     if (tile_is_full(qd, geo.d))
         async_tick_body<true, FUSED_GEN, NOISE, EXT>(geo, hp, seg, lds, qd, neg_beta, i, j, x, v, g, h, xstar, sigma,
                                                      key, tick);
@@ -71,7 +71,7 @@ void easgd_tick_body(const Geom& geo, const Hyper& hp, const SegTable& seg, cons
                      const float* __restrict__ g, float* __restrict__ center)
 {
     const int valid = FULL ? 4 : qd.valid;
-    const int64_t mine_off = static_cast<int64_t>(i) * geo.ld + qd.col;
+    const int64_t mine_off = static_cast<int64_t>(i) * geo.rs + qd.mat + qd.lane_col;
     const f32x4 X = load_quad<FULL>(x + mine_off, valid);
     const f32x4 V = load_quad<FULL>(v + mine_off, valid);
     const f32x4 G = load_quad<FULL>(g + mine_off, valid);
@@ -93,7 +93,7 @@ void easgd_tick_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e, int32_t 
 {
     __shared__ SegLds lds;
     stage_segments(seg, lds);
-    const Quad qd = my_quad(geo.d);
+    const Quad qd = my_quad(geo);
     if (tile_is_full(qd, geo.d)) easgd_tick_body<true, EXT>(geo, hp, seg, lds, qd, alpha_e, i, x, v, g, center);
     else if (qd.valid > 0) easgd_tick_body<false, EXT>(geo, hp, seg, lds, qd, alpha_e, i, x, v, g, center);
 }

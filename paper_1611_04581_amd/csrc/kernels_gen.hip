@@ -18,6 +18,9 @@ namespace gsgd {
 // a row; h and xstar of a band 8 MiB) are best or tied with 768 ... 3072 at every shape; from 4096 tiles on h and
 // xstar fall out of the caches between rows and the rate drops to 50 %.
 constexpr unsigned GEN_BAND_TILES = 1024;
+// In the blocked layout a band never leaves a block.  Bands of 32 tiles (128 KiB of a row piece) measured best
+// there: blocks of 64 Ki columns 78 % against 71 % with the whole block as one band, 74 / 72 / 62 % with 16 / 8 / 4.
+constexpr unsigned GEN_BLOCKED_BAND_TILES = 32;
 
 
 template <int NOISE>
@@ -29,9 +32,9 @@ void gen_grad_kernel(Geom geo, const float* __restrict__ x, const float* __restr
     const uint32_t tile = blockIdx.z * band_tiles + blockIdx.x;
     if (tile >= n_tiles) return;
     const uint32_t row = blockIdx.y;
-    const Quad qd = quad_of_tile(tile, geo.d);
+    const Quad qd = quad_of_tile(tile, geo);
     if (qd.valid == 0) return;
-    const int64_t off = static_cast<int64_t>(row) * geo.ld + qd.tile_col + qd.lane_col;
+    const int64_t off = static_cast<int64_t>(row) * geo.rs + qd.mat + qd.lane_col;
     const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
     if (tile_is_full(qd, geo.d)) {
         const f32x4 X = load_quad<true>(x + off, 4);
@@ -74,19 +77,19 @@ __global__ __launch_bounds__(BLOCK)
 void init_replicas_kernel(Geom geo, float* __restrict__ x, float* __restrict__ v, float* __restrict__ center,
                           const float* __restrict__ x0, RngKey key)
 {
-    const Quad qd = my_quad(geo.d);
+    const Quad qd = my_quad(geo);
     if (qd.valid == 0) return;
     const int valid = qd.valid;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    float* xq = x + qd.col;
-    float* vq = v + qd.col;
+    float* xq = x + qd.mat + qd.lane_col;
+    float* vq = v + qd.mat + qd.lane_col;
     if constexpr (PER_REPLICA) {
         const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
         f64x4 acc = {0.0, 0.0, 0.0, 0.0};
         for (int i = 0; i < geo.k; ++i) {
             const f32x4 xi = noise4<GSGD_NOISE_GAUSSIAN>(
                 philox4x32_10(quad_index, static_cast<uint32_t>(i), 0u, STREAM_INIT, key.k0, key.k1));
-            const int64_t off = static_cast<int64_t>(i) * geo.ld;
+            const int64_t off = static_cast<int64_t>(i) * geo.rs;
             store_quad(xq + off, xi, valid);
             store_quad(vq + off, zero, valid);
             acc.x += static_cast<double>(xi.x);
@@ -103,7 +106,7 @@ void init_replicas_kernel(Geom geo, float* __restrict__ x, float* __restrict__ v
     } else {
         const f32x4 x04 = load_quad_cached(x0 + qd.col, valid);
         for (int i = 0; i < geo.k; ++i) {
-            const int64_t off = static_cast<int64_t>(i) * geo.ld;
+            const int64_t off = static_cast<int64_t>(i) * geo.rs;
             store_quad(xq + off, x04, valid);
             store_quad(vq + off, zero, valid);
         }
@@ -159,10 +162,10 @@ hipError_t launch_gen_grad(const Geom& geo, const float* x, const float* h, cons
                            hipStream_t stream)
 {
     const unsigned tiles = grid_for(geo.d);
-    if (band_tiles == 0) band_tiles = GEN_BAND_TILES;
-    unsigned band = band_tiles < tiles ? band_tiles : tiles;
-    if ((tiles + band - 1) / band > 65535u) band = (tiles + 65534u) / 65535u;      // the grid's z extent is 16 bits
-    const dim3 grid(band, static_cast<unsigned>(geo.k), (tiles + band - 1) / band);
+    const unsigned default_band = geo.block_log2 >= 0 ? GEN_BLOCKED_BAND_TILES : GEN_BAND_TILES;
+    const FlatGrid fg = flat_grid(geo, band_tiles == 0 ? default_band : band_tiles);
+    const dim3 grid = fg.grid;
+    const unsigned band = fg.band;
     if (noise_kind == GSGD_NOISE_UNIFORM)
         hipLaunchKernelGGL(gen_grad_kernel<GSGD_NOISE_UNIFORM>, grid, dim3(BLOCK), 0, stream,
                            geo, x, h, xstar, g, sigma, key, step, band, tiles);

@@ -65,11 +65,11 @@ void stats_partial_kernel(Geom geo, const float* __restrict__ x, const float* __
                           double* __restrict__ partials)
 {
     __shared__ double lds[BLOCK / 64][4];
-    const Quad qd = my_quad(geo.d);
+    const Quad qd = my_quad(geo);
     double acc[4] = {0.0, 0.0, 0.0, 0.0};     // consensus, distance, mean distance, mean norm
     if (qd.valid > 0) {
         const int valid = qd.valid;
-        const float* xq = x + qd.col;
+        const float* xq = x + qd.mat + qd.lane_col;
         const f32x4 xs4 = load_quad_cached(xstar + qd.col, valid);
         const f32x4 r4 = load_quad(xq, valid);
         const double xs[4] = {static_cast<double>(xs4.x), static_cast<double>(xs4.y),
@@ -95,11 +95,11 @@ void stats_partial_kernel(Geom geo, const float* __restrict__ x, const float* __
             f32x4 xi[STATS_ROWS_IN_FLIGHT];
 #pragma unroll
             for (int u = 0; u < STATS_ROWS_IN_FLIGHT; ++u)
-                xi[u] = load_quad(xq + static_cast<int64_t>(i + u) * geo.ld, valid);
+                xi[u] = load_quad(xq + static_cast<int64_t>(i + u) * geo.rs, valid);
 #pragma unroll
             for (int u = 0; u < STATS_ROWS_IN_FLIGHT; ++u) visit(xi[u]);
         }
-        for (; i < geo.k; ++i) visit(load_quad(xq + static_cast<int64_t>(i) * geo.ld, valid));
+        for (; i < geo.k; ++i) visit(load_quad(xq + static_cast<int64_t>(i) * geo.rs, valid));
         const double kd = static_cast<double>(geo.k);
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
@@ -138,12 +138,12 @@ void row_sqnorm_partial_kernel(Geom geo, int64_t n_tiles, const float* __restric
 {
     __shared__ double lds[BLOCK / 64][4];
     const int row = static_cast<int>(blockIdx.y);
-    const float* xr = x + static_cast<int64_t>(row) * geo.ld;
+    const float* xr = x + static_cast<int64_t>(row) * geo.rs;
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const Quad qd = quad_of_tile(tile, geo.d);
+        const Quad qd = quad_of_tile(tile, geo);
         if (qd.valid == 0) continue;
-        const f32x4 xi = load_quad(xr + qd.col, qd.valid);        // lanes beyond `valid` come back as zero
+        const f32x4 xi = load_quad(xr + qd.mat + qd.lane_col, qd.valid);        // lanes beyond `valid` come back as zero
         acc[0] += static_cast<double>(xi.x) * static_cast<double>(xi.x);
         acc[1] += static_cast<double>(xi.y) * static_cast<double>(xi.y);
         acc[2] += static_cast<double>(xi.z) * static_cast<double>(xi.z);

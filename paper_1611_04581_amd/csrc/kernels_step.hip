@@ -72,7 +72,7 @@ void gossip_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, con
 #pragma unroll
         for (int u = 0; u < N; ++u) {
             w[u] = walk.seq[t0 + u];
-            const int64_t off = static_cast<int64_t>(w[u] & WALK_ROW_MASK) * geo.ld + qd.tile_col;
+            const int64_t off = static_cast<int64_t>(w[u] & WALK_ROW_MASK) * geo.rs + qd.mat;
             X[u] = load_quad<FULL>(x + off + qd.lane_col, valid);
             V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
             if constexpr (!FUSED_GEN) G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
@@ -80,7 +80,7 @@ void gossip_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, con
 #pragma unroll
         for (int u = 0; u < N; ++u) {
             const uint32_t row = w[u] & WALK_ROW_MASK;
-            const int64_t off = static_cast<int64_t>(row) * geo.ld + qd.tile_col;
+            const int64_t off = static_cast<int64_t>(row) * geo.rs + qd.mat;
             if constexpr (FUSED_GEN) {
                 const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, row, step, STREAM_GRAD, key.k0, key.k1));
                 const f32x4 t1 = X[u] - xs4;
@@ -124,7 +124,7 @@ void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk w
     KeyStack* stack = reinterpret_cast<KeyStack*>(&stack_mem[0][0]);     // only dereferenced when TREE
     stage_segments(seg, lds);
     for_each_tile(pst, n_tiles, [&](uint32_t tile) {
-        const Quad qd = quad_of_tile(tile, geo.d);
+        const Quad qd = quad_of_tile(tile, geo);
         if (tile_is_full(qd, geo.d))
             gossip_step_body<true, U, FUSED_GEN, NOISE, EXT, STALE, TREE>(geo, hp, seg, lds, qd, neg_beta, walk, stack,
                                                                           x, v, g, h, xstar, sigma, key, step);
@@ -185,7 +185,7 @@ void push_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const
 #pragma unroll
         for (int u = 0; u < N; ++u) {
             w[u] = walk.seq[t0 + u];
-            const int64_t off = static_cast<int64_t>(w[u] & WALK_ROW_MASK) * geo.ld + qd.tile_col;
+            const int64_t off = static_cast<int64_t>(w[u] & WALK_ROW_MASK) * geo.rs + qd.mat;
             X[u] = load_quad<FULL>(x + off + qd.lane_col, valid);
             V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
             if constexpr (!FUSED_GEN) G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
@@ -193,7 +193,7 @@ void push_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const
 #pragma unroll
         for (int u = 0; u < N; ++u) {
             const uint32_t row = w[u] & WALK_ROW_MASK;
-            const int64_t off = static_cast<int64_t>(row) * geo.ld + qd.tile_col;
+            const int64_t off = static_cast<int64_t>(row) * geo.rs + qd.mat;
             const uint32_t count = w[u] >> PUSH_COUNT_SHIFT;
             const uint32_t slot = (w[u] & PUSH_SLOT_MASK) >> PUSH_SLOT_SHIFT;
             if constexpr (FUSED_GEN) {
@@ -245,7 +245,7 @@ void push_step_kernel(Geom geo, Hyper hp, SegTable seg, Walk walk,
     __shared__ SumStack stack;
     stage_segments(seg, lds);
     for_each_tile(pst, n_tiles, [&](uint32_t tile) {
-        const Quad qd = quad_of_tile(tile, geo.d);
+        const Quad qd = quad_of_tile(tile, geo);
         if (tile_is_full(qd, geo.d))
             push_step_body<true, U, EXT, FUSED_GEN, NOISE>(geo, hp, seg, lds, qd, walk, &stack, x, v, g, h, xstar, sigma,
                                                            key, step);
@@ -279,7 +279,7 @@ void allreduce_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, 
         f32x4 X[N], V[N], G[N];
 #pragma unroll
         for (int u = 0; u < N; ++u) {
-            const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.rs + qd.mat;
             V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
             G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
             X[u] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -319,10 +319,10 @@ void allreduce_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, 
         f32x4 X[N];
 #pragma unroll
         for (int u = 0; u < N; ++u)
-            X[u] = load_quad<FULL>(x + static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col + qd.lane_col, valid);
+            X[u] = load_quad<FULL>(x + static_cast<int64_t>(i0 + u) * geo.rs + qd.mat + qd.lane_col, valid);
 #pragma unroll
         for (int u = 0; u < N; ++u) {
-            const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.rs + qd.mat;
             store_quad<FULL>(v + off + qd.lane_col, ubar, valid);
             store_quad<FULL>(x + off + qd.lane_col, X[u] + dbar, valid);
         }
@@ -338,7 +338,7 @@ void allreduce_step_kernel(Geom geo, Hyper hp, SegTable seg,
     __shared__ SegLds lds;
     stage_segments(seg, lds);
     for_each_tile(pst, n_tiles, [&](uint32_t tile) {
-        const Quad qd = quad_of_tile(tile, geo.d);
+        const Quad qd = quad_of_tile(tile, geo);
         if (tile_is_full(qd, geo.d)) allreduce_step_body<true, U, EXT>(geo, hp, seg, lds, qd, x, v, g);
         else if (qd.valid > 0) allreduce_step_body<false, U, EXT>(geo, hp, seg, lds, qd, x, v, g);
     });
@@ -364,14 +364,14 @@ void easgd_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, cons
         f32x4 X[N], V[N], G[N];
 #pragma unroll
         for (int u = 0; u < N; ++u) {
-            const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.rs + qd.mat;
             X[u] = load_quad<FULL>(x + off + qd.lane_col, valid);
             V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
             G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
         }
 #pragma unroll
         for (int u = 0; u < N; ++u) {
-            const int64_t off = static_cast<int64_t>(i0 + u) * geo.ld + qd.tile_col;
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.rs + qd.mat;
             f32x4 vn, xp;
             local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, xp);
             const f32x4 e = alpha_e * (xp - c4);
@@ -399,7 +399,7 @@ void easgd_step_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e,
     __shared__ SegLds lds;
     stage_segments(seg, lds);
     for_each_tile(pst, n_tiles, [&](uint32_t tile) {
-        const Quad qd = quad_of_tile(tile, geo.d);
+        const Quad qd = quad_of_tile(tile, geo);
         if (tile_is_full(qd, geo.d)) easgd_step_body<true, U, EXT>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
         else if (qd.valid > 0) easgd_step_body<false, U, EXT>(geo, hp, seg, lds, qd, alpha_e, x, v, g, center);
     });
@@ -445,6 +445,7 @@ void allreduce_rowsplit_kernel(Geom geo, Hyper hp, SegTable seg,
     stage_segments(seg, lds);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t col = static_cast<int64_t>(blockIdx.x) * SPLIT_COLUMNS + lane * 4;
+    const int64_t mcol = column_origin(geo, col);       // a quad never straddles a block
     const int64_t left = geo.d - col;
     const int valid = left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0);
     const int k = geo.k;
@@ -458,7 +459,7 @@ void allreduce_rowsplit_kernel(Geom geo, Hyper hp, SegTable seg,
     f64x4 acc_v = {0.0, 0.0, 0.0, 0.0}, acc_d = {0.0, 0.0, 0.0, 0.0};
     if (valid > 0) {
         for (int i = r0; i < r1; ++i) {
-            const int64_t off = static_cast<int64_t>(i) * geo.ld + col;
+            const int64_t off = static_cast<int64_t>(i) * geo.rs + mcol;
             const f32x4 V = load_quad_cached(v + off, valid);
             const f32x4 G = load_quad_cached(g + off, valid);
             f32x4 X = {0.f, 0.f, 0.f, 0.f};
@@ -493,7 +494,7 @@ void allreduce_rowsplit_kernel(Geom geo, Hyper hp, SegTable seg,
         }
     }
     for (int i = r0; i < r1; ++i) {
-        const int64_t off = static_cast<int64_t>(i) * geo.ld + col;
+        const int64_t off = static_cast<int64_t>(i) * geo.rs + mcol;
         const f32x4 X = load_quad_cached(x + off, valid);
         store_quad_cached(v + off, ubar, valid);
         store_quad_cached(x + off, X + dbar, valid);
@@ -511,6 +512,7 @@ void easgd_rowsplit_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e,
     stage_segments(seg, lds);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t col = static_cast<int64_t>(blockIdx.x) * SPLIT_COLUMNS + lane * 4;
+    const int64_t mcol = column_origin(geo, col);       // a quad never straddles a block
     const int64_t left = geo.d - col;
     const int valid = left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0);
     const int k = geo.k;
@@ -524,7 +526,7 @@ void easgd_rowsplit_kernel(Geom geo, Hyper hp, SegTable seg, float alpha_e,
         const f32x4 neg_lr = -quad_lr(seg, lds, col, valid, hp.lr);
         c4 = load_quad_cached(center + col, valid);
         for (int i = r0; i < r1; ++i) {
-            const int64_t off = static_cast<int64_t>(i) * geo.ld + col;
+            const int64_t off = static_cast<int64_t>(i) * geo.rs + mcol;
             const f32x4 X = load_quad_cached(x + off, valid);
             const f32x4 V = load_quad_cached(v + off, valid);
             const f32x4 G = load_quad_cached(g + off, valid);
@@ -563,7 +565,7 @@ void local_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, cons
                      float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g)
 {
     const int valid = FULL ? 4 : qd.valid;
-    const int64_t off = static_cast<int64_t>(row) * geo.ld + qd.tile_col;
+    const int64_t off = static_cast<int64_t>(row) * geo.rs + qd.mat;
     const f32x4 X = load_quad<FULL>(x + off + qd.lane_col, valid);
     const f32x4 V = load_quad<FULL>(v + off + qd.lane_col, valid);
     const f32x4 G = load_quad<FULL>(g + off + qd.lane_col, valid);
@@ -578,9 +580,12 @@ void local_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, cons
 template <bool EXT>
 __global__ __launch_bounds__(BLOCK)
 void local_step_kernel(Geom geo, Hyper hp, SegTable seg,
-                       float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g)
+                       float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                       uint32_t band_tiles, uint32_t n_tiles)
 {
-    const Quad qd = my_quad(geo.d);
+    const uint32_t tile = blockIdx.z * band_tiles + blockIdx.x;
+    if (tile >= n_tiles) return;
+    const Quad qd = quad_of_tile(tile, geo);
     const int row = static_cast<int>(blockIdx.y);
     if (tile_is_full(qd, geo.d)) local_step_body<true, EXT>(geo, hp, seg, qd, row, x, v, g);
     else if (qd.valid > 0) local_step_body<false, EXT>(geo, hp, seg, qd, row, x, v, g);
@@ -663,14 +668,14 @@ hipError_t launch_step_gossip_push_fused(const Geom& geo, const Hyper& hp, const
 }
 
 hipError_t launch_step_local(const Geom& geo, const Hyper& hp, const SegTable& seg,
-                             float* x, float* v, const float* g, Persist p, hipStream_t stream)
+                             float* x, float* v, const float* g, unsigned band_tiles, hipStream_t stream)
 {
-    (void)p;                                              // flat launch: no tickets, no width
-    const dim3 grid(grid_for(geo.d), static_cast<unsigned>(geo.k));
+    const FlatGrid fg = flat_grid(geo, band_tiles);
+    const unsigned tiles = grid_for(geo.d);
     if (hp.extended())
-        hipLaunchKernelGGL(local_step_kernel<true>, grid, dim3(BLOCK), 0, stream, geo, hp, seg, x, v, g);
+        hipLaunchKernelGGL(local_step_kernel<true>, fg.grid, dim3(BLOCK), 0, stream, geo, hp, seg, x, v, g, fg.band, tiles);
     else
-        hipLaunchKernelGGL(local_step_kernel<false>, grid, dim3(BLOCK), 0, stream, geo, hp, seg, x, v, g);
+        hipLaunchKernelGGL(local_step_kernel<false>, fg.grid, dim3(BLOCK), 0, stream, geo, hp, seg, x, v, g, fg.band, tiles);
     return hipGetLastError();
 }
 

@@ -42,7 +42,8 @@ class _Config(C.Structure):
     _fields_ = [("k", C.c_int32), ("d", C.c_int64), ("ld", C.c_int64),
                 ("lr", C.c_float), ("momentum", C.c_float), ("sigma", C.c_float),
                 ("seed", C.c_uint64), ("noise_kind", C.c_int32), ("n_seg", C.c_int32),
-                ("seg_offsets", C.POINTER(C.c_int64)), ("seg_lr_scale", C.POINTER(C.c_float))]
+                ("seg_offsets", C.POINTER(C.c_int64)), ("seg_lr_scale", C.POINTER(C.c_float)),
+                ("block_columns", C.c_int64)]
 
 
 _lib = None
@@ -160,13 +161,15 @@ def _perm_arg(peer_perm, k=None):
 
 class Context:
     """Owns a gsgd_ctx.  Tensors passed to the methods must be fp32 CUDA
-    tensors laid out as the header describes (k x ld rows, or d-vectors)."""
+    tensors laid out as the header describes (k x ld rows, row-major or, with
+    block_columns > 0, in blocks of that many columns; or d-vectors)."""
 
     def __init__(self, k, d, ld=None, lr=0.05, momentum=0.9, sigma=0.1, seed=0x161104581,
-                 noise_kind=NOISE_GAUSSIAN, seg_offsets=None, seg_lr_scale=None):
+                 noise_kind=NOISE_GAUSSIAN, seg_offsets=None, seg_lr_scale=None, block_columns=0):
         ld = d if ld is None else ld
         cfg = _Config()
         cfg.k, cfg.d, cfg.ld = int(k), int(d), int(ld)
+        cfg.block_columns = int(block_columns)
         cfg.lr, cfg.momentum, cfg.sigma = float(lr), float(momentum), float(sigma)
         cfg.seed, cfg.noise_kind = int(seed), int(noise_kind)
         self._keep = None
@@ -181,7 +184,7 @@ class Context:
             self._keep = (off, sc)
         else:
             cfg.n_seg = 0
-        self.k, self.d, self.ld = cfg.k, cfg.d, cfg.ld
+        self.k, self.d, self.ld, self.block_columns = cfg.k, cfg.d, cfg.ld, cfg.block_columns
         self._h = _vp()
         _check(lib().gsgd_create(C.byref(cfg), C.byref(self._h)), "gsgd_create")
 
@@ -199,7 +202,11 @@ class Context:
         self.close()
 
     def _m(self, t):
-        """a k x ld row matrix: the last row may be short of the padding"""
+        """a k x ld matrix: the last row (row-major) or the last block's last piece (blocked) may be short of
+        the padding"""
+        if self.block_columns > 0:
+            b, last = self.block_columns, (self.d - 1) // self.block_columns
+            return _ptr(t, last * self.k * b + (self.k - 1) * b + (self.d - last * b))
         return _ptr(t, (self.k - 1) * self.ld + self.d)
 
     def _vec(self, t):

@@ -100,23 +100,27 @@ class Config:
     weight_decay: float = 0.0         # extras of the paper's training runs (Section 4.2)
     nesterov: bool = False
     tau: int = 1                      # communication period: exchange on every tau-th step, local steps between
+    # matrix layout the benchmark runs the configuration in: 0 = row-major, else the blocked layout's columns per
+    # block (the width each rule's kernel streamed fastest at, measured on MI355X)
+    block_columns: int = 0
 
 
 CONFIGS = {
     "tiny": Config("tiny", "gossip", 4, 65_536, 100, sigma=0.01),
-    "allreduce_r18": Config("allreduce_r18", "allreduce", 8, RESNET18_D, 200),
-    "gossip_r18": Config("gossip_r18", "gossip", 32, RESNET18_D, 200),
-    "gossip_r50": Config("gossip_r50", "gossip", 32, RESNET50_D, 200),
-    "easgd_r50": Config("easgd_r50", "easgd", 16, RESNET50_D, 200, alpha_e=0.9 / 16),
-    "seg_gossip_r50_k128": Config("seg_gossip_r50_k128", "gossip", 128, RESNET50_D, 100, layout="resnet50"),
+    "allreduce_r18": Config("allreduce_r18", "allreduce", 8, RESNET18_D, 200, block_columns=8192),
+    "gossip_r18": Config("gossip_r18", "gossip", 32, RESNET18_D, 200, block_columns=65536),
+    "gossip_r50": Config("gossip_r50", "gossip", 32, RESNET50_D, 200, block_columns=65536),
+    "easgd_r50": Config("easgd_r50", "easgd", 16, RESNET50_D, 200, alpha_e=0.9 / 16, block_columns=16384),
+    "seg_gossip_r50_k128": Config("seg_gossip_r50_k128", "gossip", 128, RESNET50_D, 100, layout="resnet50",
+                                  block_columns=16384),
     # beyond the five benchmark configurations: the other gossip forms the paper describes, at the metric shape
-    "pull_gossip_r50": Config("pull_gossip_r50", "gossip_pull", 32, RESNET50_D, 100),       # iid targets, Algorithm 3
-    "push_gossip_r50": Config("push_gossip_r50", "gossip_push", 32, RESNET50_D, 100),       # Algorithm 4
-    "stale_gossip_r50": Config("stale_gossip_r50", "gossip_stale", 32, RESNET50_D, 100),    # Section 6.2.1
-    "async_r50": Config("async_r50", "async_tick", 32, RESNET50_D, 100),                    # Section 6.1.2, one step = k ticks
-    "local_r50": Config("local_r50", "local", 32, RESNET50_D, 100),                         # no exchange: tau -> infinity
+    "pull_gossip_r50": Config("pull_gossip_r50", "gossip_pull", 32, RESNET50_D, 100, block_columns=65536),       # iid targets, Algorithm 3
+    "push_gossip_r50": Config("push_gossip_r50", "gossip_push", 32, RESNET50_D, 100, block_columns=65536),       # Algorithm 4
+    "stale_gossip_r50": Config("stale_gossip_r50", "gossip_stale", 32, RESNET50_D, 100, block_columns=65536),    # Section 6.2.1
+    "async_r50": Config("async_r50", "async_tick", 32, RESNET50_D, 100, block_columns=65536),                    # Section 6.1.2, one step = k ticks
+    "local_r50": Config("local_r50", "local", 32, RESNET50_D, 100, block_columns=65536),                         # no exchange: tau -> infinity
     "paper_setup_r18": Config("paper_setup_r18", "gossip_push", 16, RESNET18_D, 100, lr=0.1,  # Section 4.2's recipe
-                              weight_decay=1e-4, nesterov=True, tau=10),
+                              weight_decay=1e-4, nesterov=True, tau=10, block_columns=65536),
 }
 
 
@@ -169,6 +173,29 @@ def make_inputs(k: int, d: int, ld: Optional[int] = None, seed: int = 0, identic
     center = vec(rng.standard_normal)
     x0 = vec(rng.standard_normal)
     return Inputs(x, v, g, xstar, h, center, x0, d, ld, k)
+
+
+def to_blocked(a, block_columns: int):
+    """The (k, ld) row-major matrix `a` (numpy array or torch tensor) in the
+    library's blocked layout: blocks of `block_columns` columns, each block
+    holding its k row pieces back to back.  Returned with the same (k, ld)
+    shape; only the order of the k * ld elements in memory differs."""
+    k, ld = a.shape
+    assert block_columns > 0 and ld % block_columns == 0
+    pieces = a.reshape(k, ld // block_columns, block_columns)
+    if hasattr(pieces, "permute"):
+        return pieces.permute(1, 0, 2).contiguous().reshape(k, ld)
+    return np.ascontiguousarray(pieces.transpose(1, 0, 2)).reshape(k, ld)
+
+
+def from_blocked(b, block_columns: int):
+    """Inverse of `to_blocked`."""
+    k, ld = b.shape
+    assert block_columns > 0 and ld % block_columns == 0
+    pieces = b.reshape(ld // block_columns, k, block_columns)
+    if hasattr(pieces, "permute"):
+        return pieces.permute(1, 0, 2).contiguous().reshape(k, ld)
+    return np.ascontiguousarray(pieces.transpose(1, 0, 2)).reshape(k, ld)
 
 
 def random_segments(d: int, n_seg: int, seed: int, align: int = 1):

@@ -1,6 +1,8 @@
 """Tile-complete parity at the benchmark sizes, in the launch configuration
 bench.py times (persistent workgroups pulling 1024-column tiles through the
-ticket counter, row stride rounded up to 1024).
+ticket counter; matrices in the blocked layout each configuration is
+benchmarked in, row length rounded up to whole blocks) and in the row-major
+layout (row stride rounded up to 1024).
 
 The small parity tests run at most a handful of tiles; here every one of the
 11,416 (ResNet-18 size) or 24,959 (ResNet-50 size) tiles is compared with the
@@ -51,8 +53,21 @@ def _shared(d, ld, seed):
     return xstar, h, x0
 
 
-def _assert_full_equal(dev_t, ref, d, what):
+LAYOUTS = ["blocked", "row_major"]
+
+
+def _block_columns(cfg, layout):
+    """The blocked layout the benchmark runs this configuration in, or 0 for row-major."""
+    if layout == "row_major":
+        return 0
+    assert cfg.block_columns > 0
+    return cfg.block_columns
+
+
+def _assert_full_equal(dev_t, ref, d, what, block_columns=0):
     """Whole k x d array on the device against the oracle's, bit for bit; names the first differing tile."""
+    if block_columns and dev_t.dim() == 2 and dev_t.shape[0] > 1:
+        dev_t = W.from_blocked(dev_t, block_columns)
     got = dev_t.cpu().numpy()
     a = got[:, :d].view(np.uint32)
     b = ref[:, :d].view(np.uint32)
@@ -67,15 +82,15 @@ def _assert_full_equal(dev_t, ref, d, what):
 class _Run:
     """One benchmark configuration advanced step by step on both sides, whole arrays."""
 
-    def __init__(self, G, oracle, cfg):
+    def __init__(self, G, oracle, cfg, block_columns=0):
         import torch
-        self.G, self.oracle, self.cfg = G, oracle, cfg
+        self.G, self.oracle, self.cfg, self.b = G, oracle, cfg, block_columns
         k, d = cfg.k, cfg.d
-        self.k, self.d, self.ld = k, d, W.round_up(d, 1024)
+        self.k, self.d, self.ld = k, d, W.round_up(d, block_columns or 1024)
         ld = self.ld
         self.xstar, self.h, x0 = _shared(d, ld, seed=1234)
         self.ctx = G.Context(k, d, ld, lr=cfg.lr, momentum=cfg.momentum, sigma=SIGMA, seed=cfg.seed,
-                             noise_kind=G.NOISE_UNIFORM)
+                             noise_kind=G.NOISE_UNIFORM, block_columns=block_columns)
         self.x = torch.empty((k, ld), dtype=torch.float32, device="cuda")
         self.v = torch.empty_like(self.x)
         self.g = torch.empty_like(self.x)
@@ -120,18 +135,22 @@ class _Run:
                 o.step_easgd(self.xo, self.vo, self.go, self.co, self.lrc, cfg.momentum, cfg.alpha_e, n=d)
             self.t += 1
 
+    def rows(self, t):
+        """A device matrix as k row-major rows, whatever layout the context keeps it in."""
+        return W.from_blocked(t, self.b) if self.b else t
+
     def check(self):
-        what = "%s after %d steps" % (self.cfg.name, self.t)
+        what = "%s after %d steps (block_columns %d)" % (self.cfg.name, self.t, self.b)
         if self.cfg.rule == "gossip_push":
             # both sides round fp64 sums taken in different orders: adjacent floats at worst, and a last-place
             # difference then travels through the later steps, so the bar is the parameter tolerance on every element
-            got = self.x.cpu().numpy()[:, :self.d]
+            got = self.rows(self.x).cpu().numpy()[:, :self.d]
             ref = self.xo[:, :self.d]
             assert np.abs(got.astype(np.float64) - ref).max() <= 1e-6 * max(1.0, np.abs(ref).max()), what
             assert (got.view(np.uint32) == ref.view(np.uint32)).mean() >= 0.9999, what
             return
-        _assert_full_equal(self.x, self.xo, self.d, what + ": x")
-        _assert_full_equal(self.v, self.vo, self.d, what + ": v")
+        _assert_full_equal(self.x, self.xo, self.d, what + ": x", self.b)
+        _assert_full_equal(self.v, self.vo, self.d, what + ": v", self.b)
         if self.cfg.rule == "easgd":
             _assert_full_equal(self.c[None], self.co[None], self.d, what + ": center")
         st = self.ctx.stats(self.x, self.dxs)          # also checks that the stream's tile counters drained to zero
@@ -141,18 +160,23 @@ class _Run:
         self.ctx.close()
 
 
-def test_allreduce_resnet18_full_arrays_20_steps(G, oracle):
-    run = _Run(G, oracle, W.CONFIGS["allreduce_r18"])
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_allreduce_resnet18_full_arrays_20_steps(G, oracle, layout):
+    cfg = W.CONFIGS["allreduce_r18"]
+    run = _Run(G, oracle, cfg, _block_columns(cfg, layout))
     try:
         run.advance(20)
         run.check()
-        assert bool((run.x[1:, :run.d] == run.x[0, :run.d]).all())      # identical start: replicas stay identical
+        xr = run.rows(run.x)
+        assert bool((xr[1:, :run.d] == xr[0, :run.d]).all())      # identical start: replicas stay identical
     finally:
         run.close()
 
 
-def test_gossip_resnet18_full_arrays_20_steps(G, oracle):
-    run = _Run(G, oracle, W.CONFIGS["gossip_r18"])
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_gossip_resnet18_full_arrays_20_steps(G, oracle, layout):
+    cfg = W.CONFIGS["gossip_r18"]
+    run = _Run(G, oracle, cfg, _block_columns(cfg, layout))
     try:
         run.advance(20)
         run.check()
@@ -160,8 +184,10 @@ def test_gossip_resnet18_full_arrays_20_steps(G, oracle):
         run.close()
 
 
-def test_easgd_resnet50_full_arrays_5_steps(G, oracle):
-    run = _Run(G, oracle, W.CONFIGS["easgd_r50"])
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_easgd_resnet50_full_arrays_5_steps(G, oracle, layout):
+    cfg = W.CONFIGS["easgd_r50"]
+    run = _Run(G, oracle, cfg, _block_columns(cfg, layout))
     try:
         run.advance(5)
         run.check()
@@ -169,13 +195,14 @@ def test_easgd_resnet50_full_arrays_5_steps(G, oracle):
         run.close()
 
 
+@pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("rule", ["gossip_pull", "gossip_stale", "gossip_push"])
-def test_other_gossip_forms_resnet18_full_arrays(G, oracle, rule):
+def test_other_gossip_forms_resnet18_full_arrays(G, oracle, rule, layout):
     """Tree walk (iid pull targets), stale parameters and the senders-first push walk, k = 32 at ResNet-18 size,
     every tile, 6 steps from a common start (the noise spreads the replicas from the first step on)."""
     base = W.CONFIGS["gossip_r18"]
-    cfg = W.Config("%s_r18" % rule, rule, base.k, base.d, 6)
-    run = _Run(G, oracle, cfg)
+    cfg = W.Config("%s_r18" % rule, rule, base.k, base.d, 6, block_columns=base.block_columns)
+    run = _Run(G, oracle, cfg, _block_columns(cfg, layout))
     try:
         run.advance(6)
         run.check()
@@ -183,9 +210,10 @@ def test_other_gossip_forms_resnet18_full_arrays(G, oracle, rule):
         run.close()
 
 
-@pytest.fixture(scope="module")
-def metric_run(G, oracle):
-    run = _Run(G, oracle, W.CONFIGS["gossip_r50"])
+@pytest.fixture(scope="module", params=LAYOUTS)
+def metric_run(request, G, oracle):
+    cfg = W.CONFIGS["gossip_r50"]
+    run = _Run(G, oracle, cfg, _block_columns(cfg, request.param))
     yield run
     run.close()
 
@@ -198,13 +226,15 @@ def test_gossip_metric_shape_full_arrays(metric_run, until):
     metric_run.check()
 
 
-def test_segmented_gossip_k128_one_quad_of_every_tile(G, oracle):
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_segmented_gossip_k128_one_quad_of_every_tile(G, oracle, layout):
     import torch
     cfg = W.CONFIGS["seg_gossip_r50_k128"]
     k, d = cfg.k, cfg.d
-    ld = W.round_up(d, 1024)
+    b = _block_columns(cfg, layout)
+    ld = W.round_up(d, b or 1024)
     off, sc, _ = W.resnet_layout(cfg.layout)
-    n_tiles = ld // 1024
+    n_tiles = W.round_up(d, 1024) // 1024
     tiles = np.arange(n_tiles, dtype=np.int64)
     lane = (tiles * 37 + 11) % 256                       # a different lane of the workgroup in every tile
     first = tiles * 1024 + lane * 4
@@ -215,8 +245,12 @@ def test_segmented_gossip_k128_one_quad_of_every_tile(G, oracle):
     lr_cols = np.ascontiguousarray(lr_full[cols])
     xstar, h, x0 = _shared(d, ld, seed=4321)
     cols_t = torch.from_numpy(cols).cuda()
+    if b:
+        # where the blocked layout keeps element (i, col): (col / b) * k * b + i * b + col % b
+        flat_t = (torch.from_numpy((cols // b) * k * b + cols % b).cuda()[None, :]
+                  + torch.arange(k, device="cuda", dtype=torch.int64)[:, None] * b)
     with G.Context(k, d, ld, lr=cfg.lr, momentum=cfg.momentum, sigma=SIGMA, seed=cfg.seed, noise_kind=G.NOISE_UNIFORM,
-                   seg_offsets=off, seg_lr_scale=sc) as ctx:
+                   seg_offsets=off, seg_lr_scale=sc, block_columns=b) as ctx:
         x = torch.empty((k, ld), dtype=torch.float32, device="cuda")
         v = torch.empty_like(x)
         g = torch.empty_like(x)
@@ -224,6 +258,8 @@ def test_segmented_gossip_k128_one_quad_of_every_tile(G, oracle):
         ctx.init_replicas(x, v, None, None, G.INIT_PER_REPLICA)    # a spread start: every row differs
 
         def gather(t):
+            if b:
+                return np.ascontiguousarray(torch.take(t, flat_t).cpu().numpy())
             return np.ascontiguousarray(t.index_select(1, cols_t).cpu().numpy())
 
         for t in range(4):

@@ -1,6 +1,7 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch
-configuration bench.py times (same library calls, row stride rounded up to
-1024, flat or ResNet-segmented layout).
+configuration bench.py times (same library calls, matrices in the blocked
+layout each configuration is benchmarked in, flat or ResNet-segmented step
+sizes); the metric shape also with row-major matrices.
 
 Every rule is independent per column, and the random streams are indexed by
 the global column, so the oracle recomputes sampled column slices of the
@@ -49,10 +50,21 @@ def _slices(d, layout):
     return s
 
 
-def _run(G, oracle, cfg, steps, kind, mode=0, check_identical_rows=False):
+def _columns(t, c0, n, k, b):
+    """Columns c0 .. c0+n-1 of every row of a device matrix (k x n, host), whatever layout it is kept in."""
+    import torch
+    if not b:
+        return np.ascontiguousarray(t[:, c0:c0 + n].cpu().numpy())
+    j = torch.arange(c0, c0 + n, device="cuda", dtype=torch.int64)
+    flat = ((j // b) * (k * b) + j % b)[None, :] + torch.arange(k, device="cuda", dtype=torch.int64)[:, None] * b
+    return np.ascontiguousarray(torch.take(t, flat).cpu().numpy())
+
+
+def _run(G, oracle, cfg, steps, kind, mode=0, check_identical_rows=False, block_columns=None):
     import torch
     k, d = cfg.k, cfg.d
-    ld = W.round_up(d, 1024)
+    b = cfg.block_columns if block_columns is None else block_columns
+    ld = W.round_up(d, b or 1024)
     layout = None
     seg = {}
     if cfg.layout:
@@ -63,7 +75,7 @@ def _run(G, oracle, cfg, steps, kind, mode=0, check_identical_rows=False):
     slices = _slices(d, layout)
     wd, nest = cfg.weight_decay, cfg.nesterov
     with G.Context(k, d, ld, lr=cfg.lr, momentum=cfg.momentum, sigma=cfg.sigma, seed=cfg.seed, noise_kind=kind,
-                   **seg) as ctx:
+                   block_columns=b, **seg) as ctx:
         ctx.set_local_step(wd, nest)
         x = torch.empty((k, ld), dtype=torch.float32, device="cuda")
         v = torch.empty_like(x)
@@ -78,7 +90,7 @@ def _run(G, oracle, cfg, steps, kind, mode=0, check_identical_rows=False):
                 xo = np.tile(x0[c0:c0 + n], (k, 1)).copy()
                 co = x0[c0:c0 + n].copy()
             else:                       # per-replica Gaussian start: take the device's values as the common start
-                xo = np.ascontiguousarray(x[:, c0:c0 + n].cpu().numpy())
+                xo = _columns(x, c0, n, k, b)
                 co = np.ascontiguousarray(c[c0:c0 + n].cpu().numpy())
             lrc = oracle.expand_lr(cfg.lr, n, *(layout or (None, None)), col0=c0)
             st.append(dict(c0=c0, n=n, x=xo, v=np.zeros((k, n), np.float32), g=np.zeros((k, n), np.float32), c=co,
@@ -127,8 +139,8 @@ def _run(G, oracle, cfg, steps, kind, mode=0, check_identical_rows=False):
         cons.append(final[0])
         for s in st:
             c0, n = s["c0"], s["n"]
-            gx = np.ascontiguousarray(x[:, c0:c0 + n].cpu().numpy())
-            gv = np.ascontiguousarray(v[:, c0:c0 + n].cpu().numpy())
+            gx = _columns(x, c0, n, k, b)
+            gv = _columns(v, c0, n, k, b)
             if kind == G.NOISE_UNIFORM and cfg.rule != "gossip_push":
                 assert_bitwise(gx, s["x"], "x cols %d..%d" % (c0, c0 + n))
                 assert_bitwise(gv, s["v"], "v cols %d..%d" % (c0, c0 + n))
@@ -141,7 +153,9 @@ def _run(G, oracle, cfg, steps, kind, mode=0, check_identical_rows=False):
                 else:
                     assert_rows_close(gc, s["c"], "center")
         if check_identical_rows:
-            assert bool((x[1:, :d] == x[0, :d]).all()) and bool((v[1:, :d] == v[0, :d]).all())
+            xr, vr = (W.from_blocked(t, b) if b else t for t in (x, v))
+            assert bool((xr[1:, :d] == xr[0, :d]).all()) and bool((vr[1:, :d] == vr[0, :d]).all())
+            del xr, vr
         # padding columns were never written by any step kernel (init leaves them as allocated)
         return cons, final, (x, v, g, dxs, ctx, d)
 
@@ -177,11 +191,11 @@ def test_gossip_resnet18_200_steps_mean_and_consensus(G, oracle):
         assert bool((v == vl).all())
 
 
-@pytest.mark.parametrize("kind", [1, 0])
-def test_gossip_resnet50_metric_shape(G, oracle, kind):
+@pytest.mark.parametrize("kind,row_major", [(1, False), (0, False), (1, True)])
+def test_gossip_resnet50_metric_shape(G, oracle, kind, row_major):
     cfg = W.CONFIGS["gossip_r50"]
     steps = cfg.steps if kind == 1 else 60
-    cons, final, _ = _run(G, oracle, cfg, steps, kind)
+    cons, final, _ = _run(G, oracle, cfg, steps, kind, block_columns=0 if row_major else None)
     assert cons[0] == 0.0 and cons[-1] > 0.0             # identical start: consensus distance rises to its noise floor
 
 
