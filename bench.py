@@ -44,17 +44,17 @@ _OTHERS = "profiles/step_kernels_other_workloads.md"
 _GENERATOR = "profiles/generator_kernels_alu_vs_hbm.md"
 TRAFFIC_FROM_PROFILES = {
     # name: (bytes per launch, source)
-    "gossip_r50": (_kib(4792022.9, 6390054.2), _GOSSIP_R50),
-    "stale_gossip_r50": (_kib(4792006.8, 6390054.2), _GOSSIP_R50),
-    "pull_gossip_r50": (_kib(4792027.0, 6390054.1), _GOSSIP_R50),
-    "push_gossip_r50": (_kib(4792073.0, 6390054.2), _GOSSIP_R50),
-    "local_r50": (_kib(4791973.5, 6389258.3), _GOSSIP_R50),
-    "allreduce_r18": (_kib(548031.5, 731004.7), _OTHERS),
-    "gossip_r18": (_kib(2191848.0, 2922750.9), _OTHERS),
-    "easgd_r50": (_kib(2445960.3, 3295257.2), _OTHERS),
-    "seg_gossip_r50_k128": (_kib(19167863.0, 25557829.0), _OTHERS),
-    "gen_grad@gossip_r50": (_kib(1697187.0, 3194629.0), _GENERATOR),
-    "fused@gossip_r50": (_kib(3294593.0, 6390077.4), _GENERATOR),
+    "gossip_r50": (_kib(4792023.3, 6390054.1), _GOSSIP_R50),
+    "stale_gossip_r50": (_kib(4792010.9, 6390054.0), _GOSSIP_R50),
+    "pull_gossip_r50": (_kib(4792029.3, 6390054.1), _GOSSIP_R50),
+    "push_gossip_r50": (_kib(4792082.7, 6390054.1), _GOSSIP_R50),
+    "local_r50": (_kib(4791972.8, 6389258.3), _GOSSIP_R50),
+    "allreduce_r18": (_kib(548033.4, 731031.8), _OTHERS),
+    "gossip_r18": (_kib(2191849.0, 2922750.9), _OTHERS),
+    "easgd_r50": (_kib(2445965.4, 3295274.3), _OTHERS),
+    "seg_gossip_r50_k128": (_kib(19167869.4, 25557828.9), _OTHERS),
+    "gen_grad@gossip_r50": (_kib(1697174.3, 3194629.0), _GENERATOR),
+    "fused@gossip_r50": (_kib(3294588.1, 6390083.1), _GENERATOR),
 }
 TRAFFIC_NOTE = ("rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size; a separate "
                 "profile run, not this run")

@@ -117,7 +117,7 @@ CONFIGS = {
     "pull_gossip_r50": Config("pull_gossip_r50", "gossip_pull", 32, RESNET50_D, 100, block_columns=65536),       # iid targets, Algorithm 3
     "push_gossip_r50": Config("push_gossip_r50", "gossip_push", 32, RESNET50_D, 100, block_columns=65536),       # Algorithm 4
     "stale_gossip_r50": Config("stale_gossip_r50", "gossip_stale", 32, RESNET50_D, 100, block_columns=65536),    # Section 6.2.1
-    "async_r50": Config("async_r50", "async_tick", 32, RESNET50_D, 100, block_columns=65536),                    # Section 6.1.2, one step = k ticks
+    "async_r50": Config("async_r50", "async_tick", 32, RESNET50_D, 100),   # Section 6.1.2, one step = k ticks; one row per tick: row-major
     "local_r50": Config("local_r50", "local", 32, RESNET50_D, 100, block_columns=65536),                         # no exchange: tau -> infinity
     "paper_setup_r18": Config("paper_setup_r18", "gossip_push", 16, RESNET18_D, 100, lr=0.1,  # Section 4.2's recipe
                               weight_decay=1e-4, nesterov=True, tau=10, block_columns=65536),
