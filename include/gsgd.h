@@ -77,6 +77,7 @@ enum { GSGD_NOISE_GAUSSIAN = 0, GSGD_NOISE_UNIFORM = 1 };
 enum { GSGD_INIT_BROADCAST = 0, GSGD_INIT_PER_REPLICA = 1 };
 enum { GSGD_FILL_XSTAR = 2, GSGD_FILL_H = 3, GSGD_FILL_X0 = 4 };
 enum { GSGD_ROW_SPLIT_AUTO = 0, GSGD_ROW_SPLIT_OFF = 1, GSGD_ROW_SPLIT_ON = 2 };
+enum { GSGD_GOSSIP_AUTO = 0, GSGD_GOSSIP_WALK = 1, GSGD_GOSSIP_SWEEP = 2, GSGD_GOSSIP_SWEEP_SPLIT = 3 };
 /* the streaming kernels, for gsgd_set_launch_width (GSGD_KERNEL_LOCAL is accepted and ignored: the local step
  * is launched as a plain grid; so is the gradient generator, for which the number is the 1024-column tiles per
  * band of that grid) */
@@ -127,6 +128,22 @@ int gsgd_set_local_step(gsgd_ctx* ctx, float weight_decay, int nesterov);
  * default (a small multiple of the device's compute-unit count).  Results do
  * not depend on it.  Host only. */
 int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups);
+
+/* Which kernel form the gossip calls (gsgd_step_gossip, _stale, _pull, _push and their generator-fused variants)
+ * take.  Both forms compute the same update bit for bit (Section 3.1's mix of post-step parameters; Section 6.2.1's
+ * with stale ones), read x, v, g once and write x, v once:
+ *   GSGD_GOSSIP_WALK         rows visited along the cycles (and trees) of the peer map, values handed from row to
+ *                            row in registers;
+ *   GSGD_GOSSIP_SWEEP        rows visited in ascending order twice, the values a row's mix needs parked in LDS in
+ *                            between; a workgroup owns 1024 columns (at most 36 replicas, 16 for the stale rule);
+ *   GSGD_GOSSIP_SWEEP_SPLIT  the same with 256 columns per workgroup and the rows split over its four wavefronts
+ *                            (at most 144 replicas, 72 for the stale rule);
+ *   GSGD_GOSSIP_AUTO         (default) the walk on row-major matrices, the sweeps on blocked ones: the memory system
+ *                            serves the row pieces of a block fastest in address order.
+ * Push-gossip's fp64 sums are taken own value first, then the senders in ascending index by the sweep forms, and in
+ * visiting order by the walk (the two can differ in the last place of the rounded average).
+ * A sweep form asked for with more replicas than it can park falls back (SWEEP -> SWEEP_SPLIT -> WALK).  Host only. */
+int gsgd_set_gossip_form(gsgd_ctx* ctx, int form);
 
 /* How the k-way sums of gsgd_step_allreduce (the average of Algorithm 1) and
  * gsgd_step_easgd (the server's sum of Algorithm 2) are laid out.

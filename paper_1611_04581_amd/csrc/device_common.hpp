@@ -380,7 +380,7 @@ inline unsigned grid_for(int64_t d) { return static_cast<unsigned>((num_quads(d)
 // first, then y: a band's k row pieces follow one another, so what the rows share (h, xstar of the band's
 // columns) is still cached, and in the blocked layout, where a band is a block, the sweep is in address order.
 // `row_major_band` is the band for row-major matrices (0: the whole row); blocked matrices use it only if it
-// is a proper divisor of the block.
+// divides a block or is a whole number of blocks.
 struct FlatGrid {
     dim3     grid;
     unsigned band;
@@ -390,9 +390,10 @@ inline FlatGrid flat_grid(const Geom& geo, unsigned row_major_band)
     const unsigned tiles = grid_for(geo.d);
     unsigned band = row_major_band == 0 ? tiles : row_major_band;
     if (geo.block_log2 >= 0) {
-        // a block, or the requested part of one if that divides it
+        // a block, or the requested band if it is a whole part or a whole multiple of one
         const unsigned per_block = static_cast<unsigned>(geo.rs / (BLOCK * 4));
-        band = (row_major_band != 0 && row_major_band < per_block && per_block % row_major_band == 0) ? row_major_band : per_block;
+        const bool fits = row_major_band != 0 && (per_block % row_major_band == 0 || row_major_band % per_block == 0);
+        band = fits ? row_major_band : per_block;
     }
     if (band > tiles) band = tiles;
     unsigned bands = (tiles + band - 1) / band;

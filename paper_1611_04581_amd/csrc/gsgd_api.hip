@@ -32,6 +32,7 @@ struct gsgd_ctx {
     float       weight_decay;               // extras of the local step (Section 4.2); 0 / 0 = the boxed algorithms
     int         nesterov;
     int         row_split;                  // GSGD_ROW_SPLIT_*: how the k-way sums of short vectors are laid out
+    int         gossip_form;                // GSGD_GOSSIP_*: cycle walk or two ascending sweeps
     int         last_hip;
 };
 
@@ -46,6 +47,10 @@ constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 0
 // unit keeps in flight over its short tiles (almost no DRAM-credit stalls at k = 16): two per compute unit gain
 // 1.5-2 points at k = 16 and 32; from k = 48 on (two rows in flight) one is better by as much.
 constexpr int EASGD_FEW_REPLICAS = 48;
+
+// Up to this many replicas the two-sweep gossip kernel keeps whole 1024-column tiles per workgroup; beyond, 256-column
+// tiles with the rows split over the wavefronts.
+constexpr int SWEEP_WHOLE_UP_TO = 36;
 
 inline unsigned default_width(const gsgd_ctx* c, int kernel)
 {
@@ -278,6 +283,13 @@ extern "C" int gsgd_set_local_step(gsgd_ctx* ctx, float weight_decay, int nester
     return GSGD_OK;
 }
 
+extern "C" int gsgd_set_gossip_form(gsgd_ctx* ctx, int form)
+{
+    if (!ctx || form < GSGD_GOSSIP_AUTO || form > GSGD_GOSSIP_SWEEP_SPLIT) return GSGD_ERR_INVALID_ARG;
+    ctx->gossip_form = form;
+    return GSGD_OK;
+}
+
 extern "C" int gsgd_set_row_split(gsgd_ctx* ctx, int mode)
 {
     if (!ctx || (mode != GSGD_ROW_SPLIT_AUTO && mode != GSGD_ROW_SPLIT_OFF && mode != GSGD_ROW_SPLIT_ON))
@@ -368,6 +380,81 @@ extern "C" int gsgd_step_allreduce(gsgd_ctx* ctx, float* x, float* v, const floa
 }
 
 namespace {
+// Which kernel form a gossip call takes: GSGD_GOSSIP_WALK, _SWEEP or _SWEEP_SPLIT (never AUTO).  Measured on MI355X:
+// on row-major matrices the walk along the peer map is the faster form (71 against 65-69 % of the HBM peak at the
+// benchmark shape), on blocked ones the two ascending sweeps are (80-84 against 72-75 %; 81 against 67 % at k = 128).
+// A form that cannot park k rows falls back to the next one.
+int gossip_form_of(const gsgd_ctx* c, bool stale)
+{
+    int form = c->gossip_form;
+    if (form == GSGD_GOSSIP_AUTO)
+        form = c->cfg.block_columns == 0 ? GSGD_GOSSIP_WALK
+                                         : (c->cfg.k <= SWEEP_WHOLE_UP_TO ? GSGD_GOSSIP_SWEEP : GSGD_GOSSIP_SWEEP_SPLIT);
+    if (form == GSGD_GOSSIP_SWEEP && c->cfg.k > sweep_capacity(false, stale)) form = GSGD_GOSSIP_SWEEP_SPLIT;
+    if (form == GSGD_GOSSIP_SWEEP_SPLIT && c->cfg.k > sweep_capacity(true, stale)) form = GSGD_GOSSIP_WALK;
+    return form;
+}
+
+// The peer map as the sweep kernels take it: entry i = the row that row i mixes with (validated by the caller).
+Walk peers_of(const int32_t* peer, int32_t k)
+{
+    Walk w;
+    for (int32_t i = 0; i < k; ++i) w.seq[i] = static_cast<uint32_t>(peer[i]);
+    return w;
+}
+
+// One gossip step on a validated peer map: `walk` is its cycle (or cycle-and-tree) order, `peer` the map itself.
+hipError_t launch_gossip(gsgd_ctx* ctx, const Walk& walk, const int32_t* peer, bool stale, bool has_trees, bool fused,
+                         float beta, float* x, float* v, const float* g, const float* h, const float* xstar,
+                         uint64_t step, const Persist& ps, void* stream)
+{
+    const hipStream_t st = static_cast<hipStream_t>(stream);
+    const int form = gossip_form_of(ctx, stale);
+    if (form != GSGD_GOSSIP_WALK)
+        return launch_step_gossip_sweep(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, peers_of(peer, ctx->cfg.k), stale,
+                                        form == GSGD_GOSSIP_SWEEP_SPLIT, fused, x, v, g, h, xstar, ctx->cfg.sigma,
+                                        key_of(ctx), static_cast<uint32_t>(step), ctx->cfg.noise_kind, ps, st);
+    if (fused)
+        return launch_step_gossip_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale, has_trees, x, v, h,
+                                        xstar, ctx->cfg.sigma, key_of(ctx), static_cast<uint32_t>(step),
+                                        ctx->cfg.noise_kind, ps, st);
+    return launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale, has_trees, x, v, g, ps, st);
+}
+
+// One push-gossip step on a validated target map: `walk` is its senders-first order for the walk kernel; the sweep
+// kernels take the senders of every row instead (ascending, self-sends left out: a node always keeps its own copy).
+hipError_t launch_push(gsgd_ctx* ctx, const Walk& walk, const int32_t* target, bool fused, float* x, float* v,
+                       const float* g, const float* h, const float* xstar, uint64_t step, const Persist& ps, void* stream)
+{
+    const hipStream_t st = static_cast<hipStream_t>(stream);
+    const int form = gossip_form_of(ctx, false);
+    if (form != GSGD_GOSSIP_WALK) {
+        const int32_t k = ctx->cfg.k;
+        Walk index{}, senders{};
+        uint32_t count[GSGD_MAX_K];
+        for (int32_t r = 0; r < k; ++r) count[r] = 0;
+        for (int32_t i = 0; i < k; ++i)
+            if (target[i] != i) ++count[target[i]];
+        uint32_t at = 0;
+        for (int32_t r = 0; r < k; ++r) {
+            index.seq[r] = at | (count[r] << 16);
+            at += count[r];
+            count[r] = 0;                                   // reused below as the fill position inside the group
+        }
+        for (int32_t i = 0; i < k; ++i) {                   // ascending i: every group ends up in ascending order
+            const int32_t r = target[i];
+            if (r != i) senders.seq[(index.seq[r] & 0xFFFFu) + count[r]++] = static_cast<uint32_t>(i);
+        }
+        return launch_step_gossip_push_sweep(geom_of(ctx), hyper_of(ctx), seg_of(ctx), index, senders,
+                                             form == GSGD_GOSSIP_SWEEP_SPLIT, fused, x, v, g, h, xstar, ctx->cfg.sigma,
+                                             key_of(ctx), static_cast<uint32_t>(step), ctx->cfg.noise_kind, ps, st);
+    }
+    if (fused)
+        return launch_step_gossip_push_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), walk, x, v, h, xstar, ctx->cfg.sigma,
+                                             key_of(ctx), static_cast<uint32_t>(step), ctx->cfg.noise_kind, ps, st);
+    return launch_step_gossip_push(geom_of(ctx), hyper_of(ctx), seg_of(ctx), walk, x, v, g, ps, st);
+}
+
 int gossip_on_permutation(gsgd_ctx* ctx, float* x, float* v, const float* g, const int32_t* peer_perm, float beta,
                           bool stale, void* stream)
 {
@@ -379,8 +466,8 @@ int gossip_on_permutation(gsgd_ctx* ctx, float* x, float* v, const float* g, con
     if (rc != GSGD_OK) return rc;
     const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP, stream);
     if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
-    const hipError_t e = launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale, false, x, v, g,
-                                            ps, static_cast<hipStream_t>(stream));
+    const hipError_t e = launch_gossip(ctx, walk, peer_perm, stale, false, false, beta, x, v, g, nullptr, nullptr, 0, ps,
+                                       stream);
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 }  // namespace
@@ -397,9 +484,8 @@ extern "C" int gsgd_step_gossip_pull(gsgd_ctx* ctx, float* x, float* v, const fl
     if (rc != GSGD_OK) return rc;
     const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP, stream);
     if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
-    const hipError_t e = launch_step_gossip(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale != 0,
-                                            has_trees != 0, x, v, g, ps,
-                                            static_cast<hipStream_t>(stream));
+    const hipError_t e = launch_gossip(ctx, walk, peer, stale != 0, has_trees != 0, false, beta, x, v, g, nullptr, nullptr,
+                                       0, ps, stream);
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -427,8 +513,7 @@ extern "C" int gsgd_step_gossip_push(gsgd_ctx* ctx, float* x, float* v, const fl
     if (rc != GSGD_OK) return rc;
     const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP, stream);
     if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
-    const hipError_t e = launch_step_gossip_push(geom_of(ctx), hyper_of(ctx), seg_of(ctx), walk, x, v, g,
-                                                 ps, static_cast<hipStream_t>(stream));
+    const hipError_t e = launch_push(ctx, walk, target, false, x, v, g, nullptr, nullptr, 0, ps, stream);
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -518,10 +603,8 @@ extern "C" int gsgd_step_gossip_fused(gsgd_ctx* ctx, float* x, float* v, const f
     if (rc != GSGD_OK) return rc;
     const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED, stream);
     if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
-    const hipError_t e = launch_step_gossip_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, false, false,
-                                                  x, v, h, xstar, ctx->cfg.sigma, key_of(ctx),
-                                                  static_cast<uint32_t>(step), ctx->cfg.noise_kind, ps,
-                                                  static_cast<hipStream_t>(stream));
+    const hipError_t e = launch_gossip(ctx, walk, peer_perm, false, false, true, beta, x, v, nullptr, h, xstar, step, ps,
+                                       stream);
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -537,10 +620,8 @@ extern "C" int gsgd_step_gossip_pull_fused(gsgd_ctx* ctx, float* x, float* v, co
     if (rc != GSGD_OK) return rc;
     const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED, stream);
     if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
-    const hipError_t e = launch_step_gossip_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, walk, stale != 0,
-                                                  has_trees != 0, x, v, h, xstar, ctx->cfg.sigma, key_of(ctx),
-                                                  static_cast<uint32_t>(step), ctx->cfg.noise_kind, ps,
-                                                  static_cast<hipStream_t>(stream));
+    const hipError_t e = launch_gossip(ctx, walk, peer, stale != 0, has_trees != 0, true, beta, x, v, nullptr, h, xstar,
+                                       step, ps, stream);
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -555,10 +636,7 @@ extern "C" int gsgd_step_gossip_push_fused(gsgd_ctx* ctx, float* x, float* v, co
     if (rc != GSGD_OK) return rc;
     const Persist ps = persist_of(ctx, GSGD_KERNEL_GOSSIP_FUSED, stream);
     if (!ps.tickets) return GSGD_ERR_UNSUPPORTED;
-    const hipError_t e = launch_step_gossip_push_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), walk, x, v, h, xstar,
-                                                       ctx->cfg.sigma, key_of(ctx), static_cast<uint32_t>(step),
-                                                       ctx->cfg.noise_kind, ps,
-                                                       static_cast<hipStream_t>(stream));
+    const hipError_t e = launch_push(ctx, walk, target, true, x, v, nullptr, h, xstar, step, ps, stream);
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 

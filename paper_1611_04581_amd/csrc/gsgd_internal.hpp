@@ -124,6 +124,15 @@ hipError_t launch_easgd_tick(const Geom&, const Hyper&, const SegTable&, float a
                              float* x, float* v, const float* g, float* center, hipStream_t);
 hipError_t launch_step_local(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
                              unsigned band_tiles, hipStream_t);
+int        sweep_capacity(bool split, bool stale);      // most replicas the two-sweep gossip kernels can park
+hipError_t launch_step_gossip_push_sweep(const Geom&, const Hyper&, const SegTable&, const Walk& index,
+                                         const Walk& senders, bool split, bool fused, float* x, float* v, const float* g,
+                                         const float* h, const float* xstar, float sigma, RngKey key, uint32_t step,
+                                         int noise_kind, Persist, hipStream_t);
+hipError_t launch_step_gossip_sweep(const Geom&, const Hyper&, const SegTable&, float beta, const Walk& peers,
+                                    bool stale, bool split, bool fused, float* x, float* v, const float* g,
+                                    const float* h, const float* xstar, float sigma, RngKey key, uint32_t step,
+                                    int noise_kind, Persist, hipStream_t);
 hipError_t launch_step_gossip_fused(const Geom&, const Hyper&, const SegTable&, float beta, const Walk&, bool stale,
                                     bool has_trees, float* x, float* v, const float* h, const float* xstar,
                                     float sigma, RngKey key, uint32_t step, int noise_kind, Persist, hipStream_t);

@@ -18,8 +18,9 @@ namespace gsgd {
 // a row; h and xstar of a band 8 MiB) are best or tied with 768 ... 3072 at every shape; from 4096 tiles on h and
 // xstar fall out of the caches between rows and the rate drops to 50 %.
 constexpr unsigned GEN_BAND_TILES = 1024;
-// In the blocked layout a band never leaves a block.  Bands of 32 tiles (128 KiB of a row piece) measured best
-// there: blocks of 64 Ki columns 78 % against 71 % with the whole block as one band, 74 / 72 / 62 % with 16 / 8 / 4.
+// In the blocked layout bands of 32 tiles (128 KiB of a row, in one block or two) measured best: blocks of 64 Ki
+// columns 78 % against 71 % with the whole block as one band, 74 / 72 / 62 % with 16 / 8 / 4 tiles; blocks of 16 Ki
+// columns 75 % against 73 % with one block (16 tiles) and 69 / 61 / 67 % with 64 / 128 / 1024.
 constexpr unsigned GEN_BLOCKED_BAND_TILES = 32;
 
 

@@ -44,6 +44,19 @@ namespace gsgd {
 // for the few keys that must outlive a sibling subtree.
 typedef f32x4 KeyStack[WALK_SLOTS][BLOCK];
 
+__device__ __forceinline__ f64x4 widen(f32x4 a)
+{
+    return f64x4{static_cast<double>(a.x), static_cast<double>(a.y), static_cast<double>(a.z), static_cast<double>(a.w)};
+}
+
+// average of `count` received values whose fp64 sum is `sum`, rounded once
+__device__ __forceinline__ f32x4 average(f64x4 sum, uint32_t count)
+{
+    const double c = static_cast<double>(count);
+    return f32x4{static_cast<float>(sum.x / c), static_cast<float>(sum.y / c),
+                 static_cast<float>(sum.z / c), static_cast<float>(sum.w / c)};
+}
+
 template <bool FULL, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE, bool TREE>
 __device__ __forceinline__
 void gossip_step_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
@@ -135,6 +148,175 @@ void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk w
 }
 
 // ---------------------------------------------------------------------------
+// Gossip as two sweeps (the form for blocked matrices).  The cycle walk above
+// visits the rows in the order of the peer map, i.e. in a random order; in the
+// blocked layout the k row pieces of a tile are neighbours in memory, and the
+// memory system serves them markedly faster when they are visited in address
+// order (one sequential stream per block instead of jumps inside it).  So the
+// rows are visited in ascending order twice:
+//   sweep 1: load x, v, g of a row, take the local step, store v, park the
+//            row's key (and, for the stale rule, its x' as well) in LDS;
+//   sweep 2: finish every row from its own and its peer's parked values and
+//            store x.
+// Each of x, v, g is still read once and x, v written once (20 bytes per
+// replica-element); the parked values cost 16 bytes of LDS per thread and row.
+// Any peer map works (no cycles or trees to follow).
+//
+// SPLIT = false: a workgroup owns a 1024-column tile, a thread parks its own
+// quads of all k rows (rows <= ROWS, ROWS * 4 KiB of LDS, no barrier at all).
+// SPLIT = true: a workgroup owns a 256-column tile and its four wavefronts
+// take a quarter of the rows each (ROWS KiB of LDS, one barrier between the
+// sweeps): the form for many replicas.
+constexpr int SWEEP_SPLIT_COLUMNS = 256;
+
+template <bool SPLIT, bool FULL, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE, bool PUSH = false>
+__device__ __forceinline__
+void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds,
+                       int64_t tile_col, int64_t mat, float neg_beta, const Walk& peers, const Walk& senders,
+                       f32x4* __restrict__ park_key, f32x4* __restrict__ park_post,
+                       float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                       const float* __restrict__ h, const float* __restrict__ xstar,
+                       float sigma, RngKey key, uint32_t step)
+{
+    constexpr int SLOTS = SPLIT ? 64 : BLOCK;                   // parked quads per row
+    const int slot = SPLIT ? static_cast<int>(threadIdx.x & 63u) : static_cast<int>(threadIdx.x);
+    const uint32_t lane_col = static_cast<uint32_t>(slot) * 4u;
+    const int64_t col = tile_col + lane_col;
+    const int64_t left = geo.d - col;
+    const int valid = FULL ? 4 : (left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0));
+    // rows of this thread: all of them, or its wavefront's quarter
+    int r0 = 0, r1 = geo.k;
+    if constexpr (SPLIT) {
+        const int wave = static_cast<int>(threadIdx.x >> 6);
+        const int per = (geo.k + BLOCK / 64 - 1) / (BLOCK / 64);
+        r0 = wave * per < geo.k ? wave * per : geo.k;
+        r1 = r0 + per < geo.k ? r0 + per : geo.k;
+    }
+    if (FULL || valid > 0) {
+        const f32x4 neg_lr = -quad_lr(seg, lds, col, valid, hp.lr);
+        f32x4 h4 = {0.f, 0.f, 0.f, 0.f}, xs4 = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (FUSED_GEN) {
+            h4 = load_quad_cached<FULL>(h + col, valid);
+            xs4 = load_quad_cached<FULL>(xstar + col, valid);
+        }
+        const uint32_t quad_index = static_cast<uint32_t>(col >> 2);
+        int i0 = r0;
+        auto batch = [&](auto n) {
+            constexpr int N = decltype(n)::value;
+            f32x4 X[N], V[N], G[N];
+#pragma unroll
+            for (int u = 0; u < N; ++u) {
+                const int64_t off = static_cast<int64_t>(i0 + u) * geo.rs + mat;
+                X[u] = load_quad<FULL>(x + off + lane_col, valid);
+                V[u] = load_quad<FULL>(v + off + lane_col, valid);
+                if constexpr (!FUSED_GEN) G[u] = load_quad<FULL>(g + off + lane_col, valid);
+            }
+#pragma unroll
+            for (int u = 0; u < N; ++u) {
+                const int row = i0 + u;
+                const int64_t off = static_cast<int64_t>(row) * geo.rs + mat;
+                if constexpr (FUSED_GEN) {
+                    const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, static_cast<uint32_t>(row), step, STREAM_GRAD,
+                                                                 key.k0, key.k1));
+                    const f32x4 t1 = X[u] - xs4;
+                    const f32x4 t2 = sigma * xi;
+                    G[u] = fma4(h4, t1, t2);
+                }
+                f32x4 vn, post;
+                local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, post);
+                store_quad<FULL>(v + off + lane_col, vn, valid);
+                park_key[row * SLOTS + slot] = STALE ? X[u] : post;
+                if constexpr (STALE) park_post[row * SLOTS + slot] = post;
+            }
+            i0 += N;
+        };
+        while (i0 + U <= r1) batch(Count<U>{});
+        while (i0 < r1) batch(Count<1>{});
+    }
+    if constexpr (SPLIT) __syncthreads();             // a row's peer may be parked by another wavefront
+    if (FULL || valid > 0) {
+        for (int row = r0; row < r1; ++row) {
+            const f32x4 mine = park_key[row * SLOTS + slot];
+            f32x4 out;
+            if constexpr (PUSH) {
+                // Algorithm 4: the average of the row's own x' and of every x' sent to it, summed in fp64, own
+                // value first, then the senders in ascending index.  peers.seq[row] = first sender's place in
+                // `senders` (low half) and how many there are (high half).
+                const uint32_t start = peers.seq[row] & 0xFFFFu, count = peers.seq[row] >> 16;
+                f64x4 sum = widen(mine);
+                for (uint32_t t = 0; t < count; ++t)
+                    sum = sum + widen(park_key[static_cast<int>(senders.seq[start + t]) * SLOTS + slot]);
+                out = count == 0 ? mine : average(sum, count + 1u);
+            } else {
+                const f32x4 theirs = park_key[static_cast<int>(peers.seq[row]) * SLOTS + slot];
+                const f32x4 post = STALE ? park_post[row * SLOTS + slot] : mine;
+                out = mix_keys(post, mine, theirs, neg_beta);
+            }
+            store_quad<FULL>(x + static_cast<int64_t>(row) * geo.rs + mat + lane_col, out, valid);
+        }
+    }
+}
+
+// `peers.seq[i]` is the plain index of the row that row i mixes with.  n_tiles counts tiles of the kernel's own
+// width (1024 columns, or 256 when SPLIT).  Needs k <= ROWS (checked by the launcher).
+template <bool SPLIT, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE>
+__global__ __launch_bounds__(BLOCK)
+void gossip_sweep_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk peers,
+                         float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                         const float* __restrict__ h, const float* __restrict__ xstar,
+                         float sigma, RngKey key, uint32_t step, Persist pst, uint32_t n_tiles)
+{
+    constexpr int SLOTS = SPLIT ? 64 : BLOCK;
+    constexpr int TILE_COLUMNS = SPLIT ? SWEEP_SPLIT_COLUMNS : BLOCK * 4;
+    __shared__ SegLds lds;
+    __shared__ f32x4 park_key[ROWS * SLOTS];
+    __shared__ f32x4 park_post[STALE ? ROWS * SLOTS : 1];
+    stage_segments(seg, lds);
+    for_each_tile(pst, n_tiles, [&](uint32_t tile) {
+        const int64_t tile_col = static_cast<int64_t>(tile) * TILE_COLUMNS;
+        const int64_t mat = column_origin(geo, tile_col);
+        // every thread takes the same branch (the barrier inside the body is reached by all or by none)
+        if (tile_col + TILE_COLUMNS <= geo.d)
+            gossip_sweep_body<SPLIT, true, ROWS, U, FUSED_GEN, NOISE, EXT, STALE>(
+                geo, hp, seg, lds, tile_col, mat, neg_beta, peers, peers, park_key, park_post, x, v, g, h, xstar, sigma, key,
+                step);
+        else
+            gossip_sweep_body<SPLIT, false, ROWS, U, FUSED_GEN, NOISE, EXT, STALE>(
+                geo, hp, seg, lds, tile_col, mat, neg_beta, peers, peers, park_key, park_post, x, v, g, h, xstar, sigma, key,
+                step);
+    });
+}
+
+// Push-gossip (Algorithm 4) in the same two sweeps: sweep 2 averages what a row received.  `index.seq[r]` = place of
+// row r's first sender in `senders` (low 16 bits) and the number of its senders (high 16 bits); `senders.seq` lists
+// the senders of row 0, then of row 1, ..., each group in ascending order, self-sends left out.
+template <bool SPLIT, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT>
+__global__ __launch_bounds__(BLOCK)
+void push_sweep_kernel(Geom geo, Hyper hp, SegTable seg, Walk index, Walk senders,
+                       float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                       const float* __restrict__ h, const float* __restrict__ xstar,
+                       float sigma, RngKey key, uint32_t step, Persist pst, uint32_t n_tiles)
+{
+    constexpr int SLOTS = SPLIT ? 64 : BLOCK;
+    constexpr int TILE_COLUMNS = SPLIT ? SWEEP_SPLIT_COLUMNS : BLOCK * 4;
+    __shared__ SegLds lds;
+    __shared__ f32x4 park_key[ROWS * SLOTS];
+    stage_segments(seg, lds);
+    for_each_tile(pst, n_tiles, [&](uint32_t tile) {
+        const int64_t tile_col = static_cast<int64_t>(tile) * TILE_COLUMNS;
+        const int64_t mat = column_origin(geo, tile_col);
+        if (tile_col + TILE_COLUMNS <= geo.d)
+            gossip_sweep_body<SPLIT, true, ROWS, U, FUSED_GEN, NOISE, EXT, false, true>(
+                geo, hp, seg, lds, tile_col, mat, 0.0f, index, senders, park_key, park_key, x, v, g, h, xstar, sigma, key,
+                step);
+        else
+            gossip_sweep_body<SPLIT, false, ROWS, U, FUSED_GEN, NOISE, EXT, false, true>(
+                geo, hp, seg, lds, tile_col, mat, 0.0f, index, senders, park_key, park_key, x, v, g, h, xstar, sigma, key,
+                step);
+    });
+}
+
+// ---------------------------------------------------------------------------
 // Push-gossip (Algorithm 4): every node sends x' to itself and to its target;
 // a node's new parameters are the average of what it received.  Rows are
 // visited senders first (see build_push_walk), so when a row is loaded the
@@ -142,19 +324,6 @@ void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk w
 // a cycle row's cycle predecessor rides in `prev`, and the first row of a
 // cycle waits in `first_sum` for the last.  One in-place pass, as for pull.
 typedef f64x4 SumStack[WALK_SLOTS][BLOCK];
-
-__device__ __forceinline__ f64x4 widen(f32x4 a)
-{
-    return f64x4{static_cast<double>(a.x), static_cast<double>(a.y), static_cast<double>(a.z), static_cast<double>(a.w)};
-}
-
-// average of `count` received values whose fp64 sum is `sum`, rounded once
-__device__ __forceinline__ f32x4 average(f64x4 sum, uint32_t count)
-{
-    const double c = static_cast<double>(count);
-    return f32x4{static_cast<float>(sum.x / c), static_cast<float>(sum.y / c),
-                 static_cast<float>(sum.z / c), static_cast<float>(sum.w / c)};
-}
 
 template <bool FULL, int U, bool EXT, bool FUSED_GEN, int NOISE>
 __device__ __forceinline__
@@ -636,6 +805,85 @@ hipError_t launch_step_gossip(const Geom& geo, const Hyper& hp, const SegTable& 
     else
         GSGD_LAUNCH((gossip_step_kernel<WALK_RIF, false, 0>), geo, hp, seg, -beta, walk, x, v, g, nullptr, nullptr,
                     0.0f, no_key, 0u, p, tiles);
+    return hipGetLastError();
+}
+
+// Rows in flight per thread in the first sweep.
+#ifndef GSGD_SWEEP_ROWS_IN_FLIGHT
+#define GSGD_SWEEP_ROWS_IN_FLIGHT 4
+#endif
+constexpr int SWEEP_RIF = GSGD_SWEEP_ROWS_IN_FLIGHT;
+// Parking space compiled in (rows): what fits the 160 KiB of LDS beside the segment table.
+constexpr int SWEEP_ROWS_WHOLE = 36, SWEEP_ROWS_WHOLE_STALE = 16;           // 1024-column tiles: 4 KiB per row
+constexpr int SWEEP_ROWS_SPLIT_FEW = 48, SWEEP_ROWS_SPLIT = 144, SWEEP_ROWS_SPLIT_STALE = 72;   // 256-column tiles: 1 KiB
+
+int sweep_capacity(bool split, bool stale)
+{
+    if (split) return stale ? SWEEP_ROWS_SPLIT_STALE : SWEEP_ROWS_SPLIT;
+    return stale ? SWEEP_ROWS_WHOLE_STALE : SWEEP_ROWS_WHOLE;
+}
+
+// The gossip step in its two-sweep form; `fused` takes g from the generator (h, xstar, sigma, key, step) instead
+// of reading it.  The caller has checked geo.k <= sweep_capacity(split, stale).
+hipError_t launch_step_gossip_sweep(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta, const Walk& peers,
+                                    bool stale, bool split, bool fused, float* x, float* v, const float* g,
+                                    const float* h, const float* xstar, float sigma, RngKey key, uint32_t step,
+                                    int noise_kind, Persist p, hipStream_t stream)
+{
+    const uint32_t tiles = split ? static_cast<uint32_t>((geo.d + SWEEP_SPLIT_COLUMNS - 1) / SWEEP_SPLIT_COLUMNS)
+                                 : grid_for(geo.d);
+    const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
+#define GSGD_SWEEP(SPLIT, ROWS, FUSED, NOISE, EXT, STALE) \
+    hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, SWEEP_RIF, FUSED, NOISE, EXT, STALE>), dim3(width), dim3(BLOCK), 0, \
+                       stream, geo, hp, seg, -beta, peers, x, v, g, h, xstar, sigma, key, step, p, tiles)
+    // the extended local step covers the plain one (no weight decay, heavy ball) wherever only one is compiled
+#define GSGD_SWEEP_FLAGS(SPLIT, ROWS, ROWS_STALE) \
+    do { \
+        if (fused) { \
+            if (noise_kind == GSGD_NOISE_UNIFORM) { \
+                if (stale) GSGD_SWEEP(SPLIT, ROWS_STALE, true, GSGD_NOISE_UNIFORM, true, true); \
+                else GSGD_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_UNIFORM, true, false); \
+            } else { \
+                if (stale) GSGD_SWEEP(SPLIT, ROWS_STALE, true, GSGD_NOISE_GAUSSIAN, true, true); \
+                else GSGD_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_GAUSSIAN, true, false); \
+            } \
+        } else if (stale) GSGD_SWEEP(SPLIT, ROWS_STALE, false, 0, true, true); \
+        else if (hp.extended()) GSGD_SWEEP(SPLIT, ROWS, false, 0, true, false); \
+        else GSGD_SWEEP(SPLIT, ROWS, false, 0, false, false); \
+    } while (0)
+    if (!split) GSGD_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE, SWEEP_ROWS_WHOLE_STALE);
+    else if (geo.k <= SWEEP_ROWS_SPLIT_FEW && !stale) GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW, SWEEP_ROWS_SPLIT_STALE);
+    else GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT, SWEEP_ROWS_SPLIT_STALE);
+#undef GSGD_SWEEP_FLAGS
+#undef GSGD_SWEEP
+    return hipGetLastError();
+}
+
+// Push-gossip in the two-sweep form; `index` / `senders` as push_sweep_kernel takes them.  The caller has checked
+// geo.k <= sweep_capacity(split, false).
+hipError_t launch_step_gossip_push_sweep(const Geom& geo, const Hyper& hp, const SegTable& seg, const Walk& index,
+                                         const Walk& senders, bool split, bool fused, float* x, float* v, const float* g,
+                                         const float* h, const float* xstar, float sigma, RngKey key, uint32_t step,
+                                         int noise_kind, Persist p, hipStream_t stream)
+{
+    const uint32_t tiles = split ? static_cast<uint32_t>((geo.d + SWEEP_SPLIT_COLUMNS - 1) / SWEEP_SPLIT_COLUMNS)
+                                 : grid_for(geo.d);
+    const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
+#define GSGD_PUSH_SWEEP(SPLIT, ROWS, FUSED, NOISE, EXT) \
+    hipLaunchKernelGGL((push_sweep_kernel<SPLIT, ROWS, SWEEP_RIF, FUSED, NOISE, EXT>), dim3(width), dim3(BLOCK), 0, stream, \
+                       geo, hp, seg, index, senders, x, v, g, h, xstar, sigma, key, step, p, tiles)
+#define GSGD_PUSH_SWEEP_FLAGS(SPLIT, ROWS) \
+    do { \
+        if (fused && noise_kind == GSGD_NOISE_UNIFORM) GSGD_PUSH_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_UNIFORM, true); \
+        else if (fused) GSGD_PUSH_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_GAUSSIAN, true); \
+        else if (hp.extended()) GSGD_PUSH_SWEEP(SPLIT, ROWS, false, 0, true); \
+        else GSGD_PUSH_SWEEP(SPLIT, ROWS, false, 0, false); \
+    } while (0)
+    if (!split) GSGD_PUSH_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE);
+    else if (geo.k <= SWEEP_ROWS_SPLIT_FEW) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW);
+    else GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT);
+#undef GSGD_PUSH_SWEEP_FLAGS
+#undef GSGD_PUSH_SWEEP
     return hipGetLastError();
 }
 

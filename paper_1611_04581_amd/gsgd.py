@@ -23,6 +23,7 @@ NOISE_GAUSSIAN, NOISE_UNIFORM = 0, 1
 INIT_BROADCAST, INIT_PER_REPLICA = 0, 1
 FILL_XSTAR, FILL_H, FILL_X0 = 2, 3, 4
 ROW_SPLIT_AUTO, ROW_SPLIT_OFF, ROW_SPLIT_ON = 0, 1, 2
+GOSSIP_AUTO, GOSSIP_WALK, GOSSIP_SWEEP, GOSSIP_SWEEP_SPLIT = 0, 1, 2, 3
 
 KERNEL_GOSSIP, KERNEL_ALLREDUCE, KERNEL_EASGD, KERNEL_GEN_GRAD, KERNEL_GOSSIP_FUSED, KERNEL_LOCAL = range(6)
 KERNEL_COUNT = 6
@@ -57,6 +58,7 @@ SIGNATURES = {
     "gsgd_set_launch_width": (C.c_int, [_vp, C.c_int, C.c_int]),
     "gsgd_set_local_step": (C.c_int, [_vp, C.c_float, C.c_int]),
     "gsgd_set_row_split": (C.c_int, [_vp, C.c_int]),
+    "gsgd_set_gossip_form": (C.c_int, [_vp, C.c_int]),
     "gsgd_comm_due": (C.c_int, [C.c_uint64, C.c_uint32]),
     "gsgd_step_gossip_stale": (C.c_int, [_vp, _vp, _vp, _vp, C.POINTER(C.c_int32), C.c_float, _vp]),
     "gsgd_step_local": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
@@ -221,6 +223,9 @@ class Context:
 
     def set_row_split(self, mode):
         _check(lib().gsgd_set_row_split(self._h, int(mode)), "gsgd_set_row_split")
+
+    def set_gossip_form(self, form):
+        _check(lib().gsgd_set_gossip_form(self._h, int(form)), "gsgd_set_gossip_form")
 
     def set_launch_width(self, kernel, workgroups):
         _check(lib().gsgd_set_launch_width(self._h, int(kernel), int(workgroups)), "gsgd_set_launch_width")

@@ -101,26 +101,26 @@ class Config:
     nesterov: bool = False
     tau: int = 1                      # communication period: exchange on every tau-th step, local steps between
     # matrix layout the benchmark runs the configuration in: 0 = row-major, else the blocked layout's columns per
-    # block (the width each rule's kernel streamed fastest at, measured on MI355X)
+    # block (16 Ki columns is where every rule's kernel streamed fastest or within a point of it on MI355X)
     block_columns: int = 0
 
 
 CONFIGS = {
     "tiny": Config("tiny", "gossip", 4, 65_536, 100, sigma=0.01),
-    "allreduce_r18": Config("allreduce_r18", "allreduce", 8, RESNET18_D, 200, block_columns=8192),
-    "gossip_r18": Config("gossip_r18", "gossip", 32, RESNET18_D, 200, block_columns=65536),
-    "gossip_r50": Config("gossip_r50", "gossip", 32, RESNET50_D, 200, block_columns=65536),
+    "allreduce_r18": Config("allreduce_r18", "allreduce", 8, RESNET18_D, 200, block_columns=16384),
+    "gossip_r18": Config("gossip_r18", "gossip", 32, RESNET18_D, 200, block_columns=16384),
+    "gossip_r50": Config("gossip_r50", "gossip", 32, RESNET50_D, 200, block_columns=16384),
     "easgd_r50": Config("easgd_r50", "easgd", 16, RESNET50_D, 200, alpha_e=0.9 / 16, block_columns=16384),
     "seg_gossip_r50_k128": Config("seg_gossip_r50_k128", "gossip", 128, RESNET50_D, 100, layout="resnet50",
                                   block_columns=16384),
     # beyond the five benchmark configurations: the other gossip forms the paper describes, at the metric shape
-    "pull_gossip_r50": Config("pull_gossip_r50", "gossip_pull", 32, RESNET50_D, 100, block_columns=65536),       # iid targets, Algorithm 3
-    "push_gossip_r50": Config("push_gossip_r50", "gossip_push", 32, RESNET50_D, 100, block_columns=65536),       # Algorithm 4
-    "stale_gossip_r50": Config("stale_gossip_r50", "gossip_stale", 32, RESNET50_D, 100, block_columns=65536),    # Section 6.2.1
+    "pull_gossip_r50": Config("pull_gossip_r50", "gossip_pull", 32, RESNET50_D, 100, block_columns=16384),       # iid targets, Algorithm 3
+    "push_gossip_r50": Config("push_gossip_r50", "gossip_push", 32, RESNET50_D, 100, block_columns=16384),       # Algorithm 4
+    "stale_gossip_r50": Config("stale_gossip_r50", "gossip_stale", 32, RESNET50_D, 100, block_columns=16384),    # Section 6.2.1
     "async_r50": Config("async_r50", "async_tick", 32, RESNET50_D, 100),   # Section 6.1.2, one step = k ticks; one row per tick: row-major
-    "local_r50": Config("local_r50", "local", 32, RESNET50_D, 100, block_columns=65536),                         # no exchange: tau -> infinity
+    "local_r50": Config("local_r50", "local", 32, RESNET50_D, 100, block_columns=16384),                         # no exchange: tau -> infinity
     "paper_setup_r18": Config("paper_setup_r18", "gossip_push", 16, RESNET18_D, 100, lr=0.1,  # Section 4.2's recipe
-                              weight_decay=1e-4, nesterov=True, tau=10, block_columns=65536),
+                              weight_decay=1e-4, nesterov=True, tau=10, block_columns=16384),
 }
 
 

@@ -70,10 +70,12 @@ def test_random_case_blocked(oracle, case):
     i, j = int(rng.integers(0, k)), int(rng.integers(0, k))
     alpha_e = 0.9 / k
     split = int(rng.choice([G.ROW_SPLIT_AUTO, G.ROW_SPLIT_OFF, G.ROW_SPLIT_ON]))
-    what = "k=%d d=%d ld=%d block=%d" % (k, d, ld, b)
+    form = int(rng.choice([G.GOSSIP_AUTO, G.GOSSIP_WALK, G.GOSSIP_SWEEP, G.GOSSIP_SWEEP_SPLIT]))
+    what = "k=%d d=%d ld=%d block=%d gossip form %d" % (k, d, ld, b, form)
     with G.Context(k, d, ld, lr=lr, momentum=mu, block_columns=b, **seg) as ctx:
         ctx.set_local_step(wd, nest)
         ctx.set_row_split(split)
+        ctx.set_gossip_form(form)
         x, v, g, c = _blocked(inp.x, b), _blocked(inp.v, b), _blocked(inp.g, b), _dev(inp.center)
         xo, vo, co = inp.x.copy(), inp.v.copy(), inp.center.copy()
         ctx.step_gossip(x, v, g, perm, beta)
@@ -190,6 +192,71 @@ def test_generator_and_fused_steps_blocked(oracle, k, d, b, kind):
                 oracle.async_tick(xo, vo, g_row, 0.05, 0.9, 0.5, i, j, n=d)
             assert_bitwise(_rowmajor(x, b), xo, "ticks x")
             assert_bitwise(_rowmajor(v, b), vo, "ticks v")
+
+
+@pytest.mark.parametrize("b", [0, 1024, 4096])
+@pytest.mark.parametrize("k", [1, 2, 16, 17, 36, 37, 72, 73, 144, 145, 200])
+def test_gossip_forms_at_their_capacity_edges(oracle, k, b):
+    """The walk and the two sweep forms of the pull-gossip step (fresh and stale parameters, gradient given or drawn
+    by the fused generator), forced one after the other in one context, in both layouts: all bit-equal to the
+    oracle.  The replica counts sit on either side of what each sweep form can park (36 / 144 rows, 16 / 72 for the
+    stale rule); beyond it the call falls back to the next form."""
+    from paper_1611_04581_amd import gsgd as G
+    d = 2 * 1024 + 256 + 7                      # two whole 1024-column tiles, one whole 256-column tile, a ragged rest
+    ld = W.round_up(d, b or 4)
+    inp = W.make_inputs(k, d, ld, seed=300 + k)
+    rng = np.random.default_rng(k)
+    sigma = 0.2
+    lay = (lambda a: _blocked(a, b)) if b else _dev
+    back = (lambda t: _rowmajor(t, b)) if b else (lambda t: t.cpu().numpy())
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, sigma=sigma, seed=SEED, noise_kind=G.NOISE_UNIFORM,
+                   block_columns=b) as ctx:
+        h, xs = _dev(inp.h), _dev(inp.xstar)
+        for form in (G.GOSSIP_WALK, G.GOSSIP_SWEEP, G.GOSSIP_SWEEP_SPLIT, G.GOSSIP_AUTO):
+            ctx.set_gossip_form(form)
+            x, v, g = lay(inp.x), lay(inp.v), lay(inp.g)
+            xo, vo, go = inp.x.copy(), inp.v.copy(), inp.g.copy()
+            perm = [int(t) for t in rng.permutation(k)]
+            peer = [int(t) for t in rng.integers(0, k, size=k)]
+            ctx.step_gossip(x, v, g, perm, 0.5)
+            oracle.step_gossip(xo, vo, go, 0.05, 0.9, 0.5, perm, n=d)
+            ctx.step_gossip_stale(x, v, g, perm, 0.3)
+            oracle.step_gossip_ext(xo, vo, go, 0.05, 0.9, 0.3, perm, stale=True, n=d)
+            ctx.step_gossip_pull(x, v, g, peer, 0.5)
+            oracle.step_gossip(xo, vo, go, 0.05, 0.9, 0.5, peer, n=d)
+            ctx.step_gossip_pull(x, v, g, peer, 0.7, True)
+            oracle.step_gossip_ext(xo, vo, go, 0.05, 0.9, 0.7, peer, stale=True, n=d)
+            ctx.step_gossip_fused(x, v, h, xs, perm, 11, 0.5)
+            oracle.gen_grad(xo, inp.h, inp.xstar, go, sigma, SEED, 11, 1, n=d)
+            oracle.step_gossip(xo, vo, go, 0.05, 0.9, 0.5, perm, n=d)
+            ctx.step_gossip_pull_fused(x, v, h, xs, peer, 12, 0.5, True)
+            oracle.gen_grad(xo, inp.h, inp.xstar, go, sigma, SEED, 12, 1, n=d)
+            oracle.step_gossip_ext(xo, vo, go, 0.05, 0.9, 0.5, peer, stale=True, n=d)
+            ctx.set_local_step(1e-3, True)          # the extended local step through the same forms
+            ctx.step_gossip(x, v, g, perm, 0.5)
+            oracle.step_gossip_ext(xo, vo, inp.g, 0.05, 0.9, 0.5, perm, wd=1e-3, nesterov=True, n=d)
+            ctx.set_local_step(0.0, False)
+            assert_bitwise(back(x), xo, "x (k=%d block=%d form=%d)" % (k, b, form))
+            assert_bitwise(back(v), vo, "v (k=%d block=%d form=%d)" % (k, b, form))
+            assert_bitwise(back(g), inp.g, "g is read-only")
+            # push-gossip: the sweep forms add what a row received in the oracle's order (own value, then senders
+            # ascending) and are bit-equal to it; the walk adds in visiting order (adjacent floats at worst)
+            target = [int(t) for t in rng.integers(0, k, size=k)]
+            ctx.step_gossip_push(x, v, g, target)
+            oracle.step_gossip_push(xo, vo, inp.g, 0.05, 0.9, target, n=d)
+            ctx.step_gossip_push_fused(x, v, h, xs, target, 13)
+            oracle.gen_grad(xo, inp.h, inp.xstar, go, sigma, SEED, 13, 1, n=d)
+            oracle.step_gossip_push(xo, vo, go, 0.05, 0.9, target, n=d)
+            swept = form != G.GOSSIP_WALK and (form != G.GOSSIP_AUTO or b != 0) and k <= 144
+            if swept:
+                assert_bitwise(back(x), xo, "push x (k=%d block=%d form=%d)" % (k, b, form))
+                assert_bitwise(back(v), vo, "push v")
+            else:
+                assert_rows_close(back(x)[:, :d], xo[:, :d], "push x (k=%d block=%d form=%d)" % (k, b, form))
+                assert_bitwise(back(x)[:, d:], xo[:, d:], "push x padding")
+        with pytest.raises(G.GsgdError) as e:
+            ctx.set_gossip_form(4)
+        assert e.value.code == G.ERR_INVALID_ARG
 
 
 def test_blocked_and_row_major_contexts_agree_bitwise():
