@@ -88,6 +88,28 @@ inline Persist persist_of(gsgd_ctx* c, int kernel, void* stream)
     const int pair = pair_of(c, static_cast<hipStream_t>(stream));
     return Persist{pair < 0 ? nullptr : pair_words(c, pair), c->width[kernel]};
 }
+// The two kernels that do not couple the rows (local step, gradient generator) run as persistent workgroups walking
+// the rows of a tile in ascending order on blocked matrices, where that is the address order of a block, and as plain
+// banded grids (tickets == nullptr) on row-major ones.  Measured on MI355X, blocks of 16 Ki columns, ResNet-50 size
+// (% of the HBM peak, grid -> walk): local step k = 16 / 32 / 128: 70 / 76 / 73 -> 84 / 84 / 82 with one workgroup per
+// compute unit (79 / 79 / 78 with two); generator k = 32 / 128: 73 / 71 -> 82 / 79 with two per compute unit
+// (64 / 63 with one); at k = 8 the generator's grid stays ahead (77 against 68), hence the threshold.
+constexpr unsigned LOCAL_WALK_WGS_PER_CU = 1, GEN_WALK_WGS_PER_CU = 2;
+constexpr int GEN_WALK_FROM_K = 16;
+// `set_width`: what gsgd_set_launch_width left for the kernel (0 = default); as a walk it counts workgroups.
+inline Persist row_walk_of(gsgd_ctx* c, int kernel, void* stream)
+{
+    if (c->cfg.block_columns == 0) return Persist{nullptr, 0u};
+    if (kernel == GSGD_KERNEL_GEN_GRAD && c->cfg.k < GEN_WALK_FROM_K) return Persist{nullptr, 0u};
+    const unsigned per_cu = kernel == GSGD_KERNEL_GEN_GRAD ? GEN_WALK_WGS_PER_CU : LOCAL_WALK_WGS_PER_CU;
+    const unsigned width = c->width[kernel] ? c->width[kernel] : static_cast<unsigned>(c->cu_count) * per_cu;
+    const int pair = pair_of(c, static_cast<hipStream_t>(stream));
+    return Persist{pair < 0 ? nullptr : pair_words(c, pair), width};
+}
+inline bool row_walk_wanted(const gsgd_ctx* c, int kernel)
+{
+    return c->cfg.block_columns > 0 && !(kernel == GSGD_KERNEL_GEN_GRAD && c->cfg.k < GEN_WALK_FROM_K);
+}
 // Rows split over the wavefronts of a workgroup when one thread per four columns cannot fill the chip: fewer
 // 1024-column tiles than compute units, and enough rows for the split to shorten the walk.  Measured on MI355X
 // (serial / split, microseconds per all-reduce step): d = 16,384: k = 8 8.8 / 8.8, k = 32 14.9 / 8.9, k = 128
@@ -342,9 +364,11 @@ extern "C" int gsgd_gen_grad(gsgd_ctx* ctx, const float* x, const float* h, cons
         !vector_clear_of(ctx, xstar, g, g))
         return GSGD_ERR_INVALID_ARG;
     if (step > 0xFFFFFFFFull) return GSGD_ERR_INVALID_ARG;
+    const Persist ps = row_walk_of(ctx, GSGD_KERNEL_GEN_GRAD, stream);
+    if (row_walk_wanted(ctx, GSGD_KERNEL_GEN_GRAD) && !ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_gen_grad(geom_of(ctx), x, h, xstar, g, ctx->cfg.sigma, key_of(ctx),
                                          static_cast<uint32_t>(step), ctx->cfg.noise_kind,
-                                         ctx->width[GSGD_KERNEL_GEN_GRAD], static_cast<hipStream_t>(stream));
+                                         ctx->width[GSGD_KERNEL_GEN_GRAD], ps, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 
@@ -574,8 +598,10 @@ extern "C" int gsgd_step_local(gsgd_ctx* ctx, float* x, float* v, const float* g
 {
     const int rc = check_state(ctx, x, v, g);
     if (rc != GSGD_OK) return rc;
+    const Persist ps = row_walk_of(ctx, GSGD_KERNEL_LOCAL, stream);
+    if (row_walk_wanted(ctx, GSGD_KERNEL_LOCAL) && !ps.tickets) return GSGD_ERR_UNSUPPORTED;
     const hipError_t e = launch_step_local(geom_of(ctx), hyper_of(ctx), seg_of(ctx), x, v, g,
-                                           ctx->width[GSGD_KERNEL_LOCAL], static_cast<hipStream_t>(stream));
+                                           ctx->width[GSGD_KERNEL_LOCAL], ps, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
 }
 

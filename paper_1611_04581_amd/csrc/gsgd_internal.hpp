@@ -122,8 +122,9 @@ hipError_t launch_async_tick_fused(const Geom&, const Hyper&, const SegTable&, f
                                    float sigma, RngKey key, uint32_t tick, int noise_kind, hipStream_t);
 hipError_t launch_easgd_tick(const Geom&, const Hyper&, const SegTable&, float alpha_e, int32_t i,
                              float* x, float* v, const float* g, float* center, hipStream_t);
+// Persist with tickets: persistent workgroups walking the rows; without (tickets == nullptr): the plain banded grid
 hipError_t launch_step_local(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
-                             unsigned band_tiles, hipStream_t);
+                             unsigned band_tiles, Persist, hipStream_t);
 int        sweep_capacity(bool split, bool stale);      // most replicas the two-sweep gossip kernels can park
 hipError_t launch_step_gossip_push_sweep(const Geom&, const Hyper&, const SegTable&, const Walk& index,
                                          const Walk& senders, bool split, bool fused, float* x, float* v, const float* g,
@@ -144,8 +145,10 @@ hipError_t launch_step_allreduce(const Geom&, const Hyper&, const SegTable&, flo
 hipError_t launch_step_easgd(const Geom&, const Hyper&, const SegTable&, float alpha_e,
                              float* x, float* v, const float* g, float* center, Persist, bool row_split, hipStream_t);
 // band_tiles: 1024-column tiles per band of the plain grid, 0 = the default
+// Persist with tickets: persistent workgroups walking the rows; without (tickets == nullptr): the plain banded grid
 hipError_t launch_gen_grad(const Geom&, const float* x, const float* h, const float* xstar, float* g,
-                           float sigma, RngKey key, uint32_t step, int noise_kind, unsigned band_tiles, hipStream_t);
+                           float sigma, RngKey key, uint32_t step, int noise_kind, unsigned band_tiles, Persist,
+                           hipStream_t);
 hipError_t launch_fill(int64_t d, float* dst, int which, RngKey key, hipStream_t);
 hipError_t launch_init_replicas(const Geom&, float* x, float* v, float* center, const float* x0, int mode,
                                 RngKey key, hipStream_t);

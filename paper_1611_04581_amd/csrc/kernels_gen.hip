@@ -52,6 +52,49 @@ void gen_grad_kernel(Geom geo, const float* __restrict__ x, const float* __restr
     }
 }
 
+// The same generator as persistent workgroups that walk the k rows of a tile in ascending order (h and xstar of the
+// tile held in registers): the form for blocked matrices, where that order is the address order of a block.
+constexpr int GEN_WALK_ROWS_IN_FLIGHT = 4;
+
+template <bool FULL, int NOISE>
+__device__ __forceinline__
+void gen_grad_walk_body(const Geom& geo, const Quad& qd, const float* __restrict__ x, const float* __restrict__ h,
+                        const float* __restrict__ xstar, float* __restrict__ g, float sigma, RngKey key, uint32_t step)
+{
+    constexpr int U = GEN_WALK_ROWS_IN_FLIGHT;
+    const int valid = FULL ? 4 : qd.valid;
+    const f32x4 h4 = load_quad_cached<FULL>(h + qd.col, valid);
+    const f32x4 xs4 = load_quad_cached<FULL>(xstar + qd.col, valid);
+    const uint32_t quad_index = static_cast<uint32_t>(qd.col >> 2);
+    for_row_batches<U>(geo.k, [&](auto n, int i0) {
+        constexpr int N = decltype(n)::value;
+        f32x4 X[N];
+#pragma unroll
+        for (int u = 0; u < N; ++u)
+            X[u] = load_quad<FULL>(x + static_cast<int64_t>(i0 + u) * geo.rs + qd.mat + qd.lane_col, valid);
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const uint32_t row = static_cast<uint32_t>(i0 + u);
+            const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, row, step, STREAM_GRAD, key.k0, key.k1));
+            store_quad<FULL>(g + static_cast<int64_t>(row) * geo.rs + qd.mat + qd.lane_col, fma4(h4, X[u] - xs4, sigma * xi),
+                             valid);
+        }
+    });
+}
+
+template <int NOISE>
+__global__ __launch_bounds__(BLOCK)
+void gen_grad_walk_kernel(Geom geo, const float* __restrict__ x, const float* __restrict__ h,
+                          const float* __restrict__ xstar, float* __restrict__ g,
+                          float sigma, RngKey key, uint32_t step, Persist pst, uint32_t n_tiles)
+{
+    for_each_tile(pst, n_tiles, [&](uint32_t tile) {
+        const Quad qd = quad_of_tile(tile, geo);
+        if (tile_is_full(qd, geo.d)) gen_grad_walk_body<true, NOISE>(geo, qd, x, h, xstar, g, sigma, key, step);
+        else if (qd.valid > 0) gen_grad_walk_body<false, NOISE>(geo, qd, x, h, xstar, g, sigma, key, step);
+    });
+}
+
 // xstar ~ N(0,1), x0 ~ N(0,1), h = fma(0.9, u, 0.1) ~ U(0.1, 1); replica and
 // step counter words are zero for these shared vectors.
 __global__ __launch_bounds__(BLOCK)
@@ -159,10 +202,20 @@ hipError_t launch_philox_raw(RngKey key, uint32_t c1, uint32_t c2, uint32_t c3, 
 }
 
 hipError_t launch_gen_grad(const Geom& geo, const float* x, const float* h, const float* xstar, float* g,
-                           float sigma, RngKey key, uint32_t step, int noise_kind, unsigned band_tiles,
+                           float sigma, RngKey key, uint32_t step, int noise_kind, unsigned band_tiles, Persist p,
                            hipStream_t stream)
 {
     const unsigned tiles = grid_for(geo.d);
+    if (p.tickets) {                                 // persistent workgroups walking the rows
+        const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
+        if (noise_kind == GSGD_NOISE_UNIFORM)
+            hipLaunchKernelGGL(gen_grad_walk_kernel<GSGD_NOISE_UNIFORM>, dim3(width), dim3(BLOCK), 0, stream,
+                               geo, x, h, xstar, g, sigma, key, step, p, tiles);
+        else
+            hipLaunchKernelGGL(gen_grad_walk_kernel<GSGD_NOISE_GAUSSIAN>, dim3(width), dim3(BLOCK), 0, stream,
+                               geo, x, h, xstar, g, sigma, key, step, p, tiles);
+        return hipGetLastError();
+    }
     const unsigned default_band = geo.block_log2 >= 0 ? GEN_BLOCKED_BAND_TILES : GEN_BAND_TILES;
     const FlatGrid fg = flat_grid(geo, band_tiles == 0 ? default_band : band_tiles);
     const dim3 grid = fg.grid;

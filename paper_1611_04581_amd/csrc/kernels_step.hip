@@ -760,6 +760,51 @@ void local_step_kernel(Geom geo, Hyper hp, SegTable seg,
     else if (qd.valid > 0) local_step_body<false, EXT>(geo, hp, seg, qd, row, x, v, g);
 }
 
+// The local step as persistent workgroups that walk the k rows of a tile in ascending order: the form for blocked
+// matrices, where that order is the address order of a block (the plain grid above is the form for row-major ones).
+template <bool FULL, int U, bool EXT>
+__device__ __forceinline__
+void local_walk_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds, const Quad& qd,
+                     float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g)
+{
+    const int valid = FULL ? 4 : qd.valid;
+    const f32x4 neg_lr = -quad_lr(seg, lds, qd.col, valid, hp.lr);
+    for_row_batches<U>(geo.k, [&](auto n, int i0) {
+        constexpr int N = decltype(n)::value;
+        f32x4 X[N], V[N], G[N];
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.rs + qd.mat;
+            X[u] = load_quad<FULL>(x + off + qd.lane_col, valid);
+            V[u] = load_quad<FULL>(v + off + qd.lane_col, valid);
+            G[u] = load_quad<FULL>(g + off + qd.lane_col, valid);
+        }
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int64_t off = static_cast<int64_t>(i0 + u) * geo.rs + qd.mat;
+            f32x4 vn, xp;
+            local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, xp);
+            store_quad<FULL>(v + off + qd.lane_col, vn, valid);
+            store_quad<FULL>(x + off + qd.lane_col, xp, valid);
+        }
+    });
+}
+
+template <int U, bool EXT>
+__global__ __launch_bounds__(BLOCK)
+void local_walk_kernel(Geom geo, Hyper hp, SegTable seg,
+                       float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                       Persist pst, uint32_t n_tiles)
+{
+    __shared__ SegLds lds;
+    stage_segments(seg, lds);
+    for_each_tile(pst, n_tiles, [&](uint32_t tile) {
+        const Quad qd = quad_of_tile(tile, geo);
+        if (tile_is_full(qd, geo.d)) local_walk_body<true, U, EXT>(geo, hp, seg, lds, qd, x, v, g);
+        else if (qd.valid > 0) local_walk_body<false, U, EXT>(geo, hp, seg, lds, qd, x, v, g);
+    });
+}
+
 // ---------------------------------------------------------------------------
 #ifndef GSGD_NO_LAUNCHERS
 constexpr int RIF = GSGD_ROWS_IN_FLIGHT;
@@ -916,8 +961,13 @@ hipError_t launch_step_gossip_push_fused(const Geom& geo, const Hyper& hp, const
 }
 
 hipError_t launch_step_local(const Geom& geo, const Hyper& hp, const SegTable& seg,
-                             float* x, float* v, const float* g, unsigned band_tiles, hipStream_t stream)
+                             float* x, float* v, const float* g, unsigned band_tiles, Persist p, hipStream_t stream)
 {
+    if (p.tickets) {                                 // persistent workgroups walking the rows (blocked matrices)
+        if (hp.extended()) GSGD_LAUNCH((local_walk_kernel<RIF, true>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
+        else GSGD_LAUNCH((local_walk_kernel<RIF, false>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
+        return hipGetLastError();
+    }
     const FlatGrid fg = flat_grid(geo, band_tiles);
     const unsigned tiles = grid_for(geo.d);
     if (hp.extended())

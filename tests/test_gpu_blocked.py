@@ -287,6 +287,31 @@ def test_blocked_and_row_major_contexts_agree_bitwise():
         assert np.array_equal(row.stats(x1, xs), blk.stats(x2, xs))
 
 
+@pytest.mark.parametrize("k", [5, 20])
+def test_launch_widths_do_not_change_results_blocked(oracle, k):
+    """On blocked matrices the local step and (from 16 replicas on) the generator run as persistent workgroups whose
+    number gsgd_set_launch_width sets; below, the generator is a banded grid and the number is its band."""
+    from paper_1611_04581_amd import gsgd as G
+    b, d = 2048, 9 * 1024 + 5
+    ld = W.round_up(d, b)
+    inp = W.make_inputs(k, d, ld, seed=88)
+    xo, vo, go = inp.x.copy(), inp.v.copy(), inp.g.copy()
+    oracle.gen_grad(xo, inp.h, inp.xstar, go, 0.1, SEED, 4, 1, n=d)
+    oracle.step_gossip_ext(xo, vo, go, 0.05, 0.9, 0.0, list(range(k)), n=d)
+    with G.Context(k, d, ld, sigma=0.1, seed=SEED, noise_kind=G.NOISE_UNIFORM, block_columns=b) as ctx:
+        h, xs = _dev(inp.h), _dev(inp.xstar)
+        for width in (0, 1, 2, 3, 7, 64, 5000):
+            for kern in (G.KERNEL_GEN_GRAD, G.KERNEL_LOCAL):
+                ctx.set_launch_width(kern, width)
+            x, v, g = _blocked(inp.x, b), _blocked(inp.v, b), _blocked(inp.g, b)
+            ctx.gen_grad(x, h, xs, g, 4)
+            ctx.step_local(x, v, g)
+            assert_bitwise(_rowmajor(g, b), go, "g (width %d)" % width)
+            assert_bitwise(_rowmajor(x, b), xo, "x (width %d)" % width)
+            assert_bitwise(_rowmajor(v, b), vo, "v (width %d)" % width)
+        ctx.stats(x, xs)          # the tile counters of every launch above drained to zero
+
+
 def test_block_columns_validation():
     from paper_1611_04581_amd import gsgd as G
     for bad in (-1024, 512, 1000, 3072):                  # negative, below a tile, not a power of two (twice)
