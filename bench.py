@@ -44,17 +44,17 @@ _OTHERS = "profiles/step_kernels_other_workloads.md"
 _GENERATOR = "profiles/generator_kernels_alu_vs_hbm.md"
 TRAFFIC_FROM_PROFILES = {
     # name: (bytes per launch, source)
-    "gossip_r50": (_kib(4792023.3, 6390054.1), _GOSSIP_R50),
-    "stale_gossip_r50": (_kib(4792010.9, 6390054.0), _GOSSIP_R50),
-    "pull_gossip_r50": (_kib(4792029.3, 6390054.1), _GOSSIP_R50),
-    "push_gossip_r50": (_kib(4792082.7, 6390054.1), _GOSSIP_R50),
-    "local_r50": (_kib(4791972.8, 6389258.3), _GOSSIP_R50),
-    "allreduce_r18": (_kib(548033.4, 731031.8), _OTHERS),
-    "gossip_r18": (_kib(2191849.0, 2922750.9), _OTHERS),
-    "easgd_r50": (_kib(2445965.4, 3295274.3), _OTHERS),
-    "seg_gossip_r50_k128": (_kib(19167869.4, 25557828.9), _OTHERS),
-    "gen_grad@gossip_r50": (_kib(1697174.3, 3194629.0), _GENERATOR),
-    "fused@gossip_r50": (_kib(3294588.1, 6390083.1), _GENERATOR),
+    "gossip_r50": (_kib(4792046.0, 6390790.8), _GOSSIP_R50),
+    "stale_gossip_r50": (_kib(4792118.6, 6395147.1), _GOSSIP_R50),
+    "pull_gossip_r50": (_kib(4792045.7, 6390877.3), _OTHERS),
+    "push_gossip_r50": (_kib(4792030.3, 6399408.0), _GOSSIP_R50),
+    "local_r50": (_kib(4792026.3, 6390055.0), _GOSSIP_R50),
+    "allreduce_r18": (_kib(548034.8, 731019.0), _OTHERS),
+    "gossip_r18": (_kib(2191860.2, 2923273.1), _OTHERS),
+    "easgd_r50": (_kib(2445976.6, 3295273.5), _OTHERS),
+    "seg_gossip_r50_k128": (_kib(19167923.2, 25563397.5), _OTHERS),
+    "gen_grad@gossip_r50": (_kib(1697280.3, 3195543.9), _GENERATOR),
+    "fused@gossip_r50": (_kib(3294615.4, 6391103.2), _GENERATOR),
 }
 TRAFFIC_NOTE = ("rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size; a separate "
                 "profile run, not this run")
@@ -69,6 +69,16 @@ KERNEL_OF_RULE = {"gossip": "gossip_step_kernel", "gossip_stale": "gossip_step_k
                   "gossip_pull": "gossip_step_kernel (tree walk)", "gossip_push": "push_step_kernel",
                   "allreduce": "allreduce_step_kernel", "easgd": "easgd_step_kernel", "local": "local_step_kernel",
                   "async_tick": "async_tick_kernel (generator fused, one launch per tick)"}
+# on blocked matrices the gossip rules run as two ascending sweeps, the local step as a row walk
+KERNEL_OF_RULE_BLOCKED = {"gossip": "gossip_sweep_kernel", "gossip_stale": "gossip_sweep_kernel (stale)",
+                          "gossip_pull": "gossip_sweep_kernel", "gossip_push": "push_sweep_kernel",
+                          "local": "local_walk_kernel"}
+
+
+def kernel_of(rule, block_columns):
+    if block_columns and rule in KERNEL_OF_RULE_BLOCKED:
+        return KERNEL_OF_RULE_BLOCKED[rule]
+    return KERNEL_OF_RULE[rule]
 
 
 def log(*a):
@@ -308,7 +318,7 @@ def main():
                                   if run.block_columns else "row-major, row stride %d" % ld, cfg.rule),
                    "k": k, "d": d, "ld": ld, "block_columns": run.block_columns, "rule": cfg.rule, "lr": cfg.lr, "momentum": cfg.momentum,
                    "beta": cfg.beta, "sigma": cfg.sigma, "layout": cfg.layout or "flat"},
-        "roofline": {"bound": "hbm", "kernel": KERNEL_OF_RULE[cfg.rule], "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": kernel_of(cfg.rule, run.block_columns), "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, **traffic_of(cfg.name),
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kern_s * 1e3,
                      "fresh_allocations": {"n": len(fracs), "steps_each": [K] + [n_rep] * (len(fracs) - 1),

@@ -858,6 +858,10 @@ hipError_t launch_step_gossip(const Geom& geo, const Hyper& hp, const SegTable& 
 #define GSGD_SWEEP_ROWS_IN_FLIGHT 4
 #endif
 constexpr int SWEEP_RIF = GSGD_SWEEP_ROWS_IN_FLIGHT;
+// With the generator fused and the rows split over the wavefronts a deeper batch hides the generator's arithmetic
+// behind the loads (k = 128: 76.7 % of the HBM peak with 8 rows against 73.7 % with 4; k = 32 and the kernels that
+// read g: 4 is best or tied, 3 / 5 / 6 / 8 rows 81.8 / 81.2 / 81.9 / 80.1 % against 83.0 % at the benchmark shape).
+constexpr int SWEEP_RIF_FUSED_SPLIT = 8;
 // Parking space compiled in (rows): what fits the 160 KiB of LDS beside the segment table.
 constexpr int SWEEP_ROWS_WHOLE = 36, SWEEP_ROWS_WHOLE_STALE = 16;           // 1024-column tiles: 4 KiB per row
 constexpr int SWEEP_ROWS_SPLIT_FEW = 48, SWEEP_ROWS_SPLIT = 144, SWEEP_ROWS_SPLIT_STALE = 72;   // 256-column tiles: 1 KiB
@@ -879,7 +883,8 @@ hipError_t launch_step_gossip_sweep(const Geom& geo, const Hyper& hp, const SegT
                                  : grid_for(geo.d);
     const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
 #define GSGD_SWEEP(SPLIT, ROWS, FUSED, NOISE, EXT, STALE) \
-    hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, SWEEP_RIF, FUSED, NOISE, EXT, STALE>), dim3(width), dim3(BLOCK), 0, \
+    hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, (SPLIT && FUSED) ? SWEEP_RIF_FUSED_SPLIT : SWEEP_RIF, FUSED, NOISE, \
+                                            EXT, STALE>), dim3(width), dim3(BLOCK), 0, \
                        stream, geo, hp, seg, -beta, peers, x, v, g, h, xstar, sigma, key, step, p, tiles)
     // the extended local step covers the plain one (no weight decay, heavy ball) wherever only one is compiled
 #define GSGD_SWEEP_FLAGS(SPLIT, ROWS, ROWS_STALE) \
