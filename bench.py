@@ -405,9 +405,10 @@ def main():
                 extras[name + "_ms"] = s_f * 1e3
                 extras[name + "_frac_of_hbm_peak"] = 20.0 * k * d / s_f / 1e9 / HBM_PEAK_GBS
         # the diagnostics (not part of a step): one read of x, 4 B per replica-element
-        if d <= gsgd.STATS_STATIC_MAX_D and not run.block_columns:      # that entry point reads row-major matrices
+        if d <= gsgd.STATS_STATIC_MAX_D:
             stats_out = torch.empty(4, dtype=torch.float64, device="cuda")
-            s_st = run.kernel_seconds(lambda t: gsgd.stats_static(k, d, ld, x, xstar, stats_out), n3)
+            s_st = run.kernel_seconds(lambda t: gsgd.stats_static(k, d, ld, x, xstar, stats_out,
+                                                                  block_columns=run.block_columns), n3)
             extras["stats"] = roof(s_st * 1e3, 4.0 + 4.0 / k, False)
         out["extras"] = extras
         log("extras:", json.dumps(extras))
@@ -418,17 +419,12 @@ def main():
     torch.cuda.empty_cache()
 
     if not args.no_extras and blocked:
-        # the same step on row-major matrices (row stride rounded up to 1024), for comparison, and the statistics
-        # kernel through the entry point that allocates nothing (it reads row-major matrices)
+        # the same step on row-major matrices (row stride rounded up to 1024), for comparison
         rm = Run(gsgd, W, cfg, args.launch_width, 0, 0)
         for t in range(5):
             rm.step(t)
         s_rm = rm.kernel_seconds(rm.step, n3, 5) / rm.launches_per_step()
         cmp_rm = {"ld": rm.ld, "kernel_ms": s_rm * 1e3, "frac_of_hbm_peak": alg_bytes / s_rm / 1e9 / HBM_PEAK_GBS}
-        if d <= gsgd.STATS_STATIC_MAX_D:
-            stats_out = torch.empty(4, dtype=torch.float64, device="cuda")
-            s_st = rm.kernel_seconds(lambda t: gsgd.stats_static(k, d, rm.ld, rm.x, rm.xstar, stats_out), n3)
-            cmp_rm["stats"] = roof(s_st * 1e3, 4.0 + 4.0 / k, False)
         out["extras"]["row_major_layout"] = cmp_rm
         log("row-major layout:", json.dumps(cmp_rm))
         rm.close()

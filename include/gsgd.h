@@ -399,10 +399,10 @@ int gsgd_stats(gsgd_ctx* ctx, const float* x, const float* xstar, double out[4],
  * follow one another on a stream are fine, whatever their sizes (every partial
  * a call reads it has written itself).  The array's device address is looked
  * up on the first call on a device (and by gsgd_create); make that first call
- * outside a stream capture.  k, d, ld as in gsgd_config.  x: device k x ld,
- * row-major (there is no context to say otherwise).  xstar: device d. */
+ * outside a stream capture.  k, d, ld, block_columns as in gsgd_config (there is
+ * no context to take the layout from).  x: device k x ld.  xstar: device d. */
 #define GSGD_STATS_STATIC_MAX_D ((int64_t)1 << 26)
-int gsgd_stats_static(int32_t k, int64_t d, int64_t ld, const float* x, const float* xstar,
+int gsgd_stats_static(int32_t k, int64_t d, int64_t ld, int64_t block_columns, const float* x, const float* xstar,
                       double* out_device, void* stream);
 
 /* Squared Euclidean norm of every replica row over columns 0..d-1, in fp64:

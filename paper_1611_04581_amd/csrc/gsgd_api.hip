@@ -61,6 +61,12 @@ inline unsigned default_width(const gsgd_ctx* c, int kernel)
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// 0 (row-major), or the blocked layout's block: a power of two that every tile width divides, and whole blocks only
+inline bool ok_block_columns(int64_t b, int64_t ld)
+{
+    return b == 0 || (b >= BLOCK_COLUMNS && (b & (b - 1)) == 0 && ld % b == 0);
+}
+
 inline int hip_fail(gsgd_ctx* ctx, hipError_t e)
 {
     if (ctx) ctx->last_hip = static_cast<int>(e);
@@ -222,11 +228,7 @@ extern "C" int gsgd_create(const gsgd_config* cfg, gsgd_ctx** out)
     if (cfg->k < 1 || cfg->k > GSGD_MAX_K || cfg->d < 1 || cfg->ld < cfg->d || (cfg->ld & 3) != 0)
         return GSGD_ERR_INVALID_ARG;
     if (cfg->d > (static_cast<int64_t>(1) << 34)) return GSGD_ERR_INVALID_ARG;   // quad index is a 32-bit counter word
-    if (cfg->block_columns != 0) {
-        const int64_t b = cfg->block_columns;
-        // a power of two that every tile width divides, and whole blocks only
-        if (b < BLOCK_COLUMNS || (b & (b - 1)) != 0 || cfg->ld % b != 0) return GSGD_ERR_INVALID_ARG;
-    }
+    if (!ok_block_columns(cfg->block_columns, cfg->ld)) return GSGD_ERR_INVALID_ARG;
     if (cfg->noise_kind != GSGD_NOISE_GAUSSIAN && cfg->noise_kind != GSGD_NOISE_UNIFORM) return GSGD_ERR_INVALID_ARG;
     if (!(cfg->sigma >= 0.0f) || !(cfg->lr == cfg->lr) || !(cfg->momentum == cfg->momentum)) return GSGD_ERR_INVALID_ARG;
     if (cfg->n_seg < 0) return GSGD_ERR_INVALID_ARG;
@@ -744,17 +746,19 @@ extern "C" int gsgd_row_sqnorms(gsgd_ctx* ctx, const float* x, double* out, void
     return verify_ticket_pair(ctx, s, slot, pair);
 }
 
-extern "C" int gsgd_stats_static(int32_t k, int64_t d, int64_t ld, const float* x, const float* xstar,
-                                 double* out_device, void* stream)
+extern "C" int gsgd_stats_static(int32_t k, int64_t d, int64_t ld, int64_t block_columns, const float* x,
+                                 const float* xstar, double* out_device, void* stream)
 {
     if (k < 1 || k > GSGD_MAX_K || d < 1 || ld < d || (ld & 3) != 0) return GSGD_ERR_INVALID_ARG;
+    if (!ok_block_columns(block_columns, ld)) return GSGD_ERR_INVALID_ARG;
     if (d > GSGD_STATS_STATIC_MAX_D) return GSGD_ERR_TOO_LARGE;
     if (!ok_matrix(x) || !ok_matrix(xstar) || !out_device || (reinterpret_cast<uintptr_t>(out_device) & 7u) != 0)
         return GSGD_ERR_INVALID_ARG;
     double* partials = nullptr;
     hipError_t e = scratch_on_current_device(&partials);
     if (e == hipSuccess)
-        e = launch_stats(make_geom(k, d, ld, 0), x, xstar, partials, out_device, static_cast<hipStream_t>(stream));
+        e = launch_stats(make_geom(k, d, ld, block_columns), x, xstar, partials, out_device,
+                         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : GSGD_ERR_HIP;
 }
 

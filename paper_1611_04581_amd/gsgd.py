@@ -88,7 +88,7 @@ SIGNATURES = {
     "gsgd_make_perm": (C.c_int, [C.c_uint64, C.c_uint64, C.c_int32, C.POINTER(C.c_int32)]),
     "gsgd_perm_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint16)]),
     "gsgd_stats": (C.c_int, [_vp, _vp, _vp, C.POINTER(C.c_double), _vp]),
-    "gsgd_stats_static": (C.c_int, [C.c_int32, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp]),
+    "gsgd_stats_static": (C.c_int, [C.c_int32, C.c_int64, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp]),
     "gsgd_row_sqnorms": (C.c_int, [_vp, _vp, C.POINTER(C.c_double), _vp]),
     "gsgd_weights_pull": (C.c_int, [C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_int32), C.c_double]),
     "gsgd_weights_push": (C.c_int, [C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_int32)]),
@@ -329,13 +329,17 @@ class Context:
         return np.array(list(out), dtype=np.float64)
 
 
-def stats_static(k, d, ld, x, xstar, out, stream=None):
+def stats_static(k, d, ld, x, xstar, out, stream=None, block_columns=0):
     """gsgd_stats_static: out is a float64 GPU tensor of 4 elements; nothing is allocated and nothing waits."""
     import torch
-    k, d, ld = int(k), int(d), int(ld)
-    if k < 1 or d < 1 or ld < d:
-        raise ValueError("bad geometry k=%d d=%d ld=%d" % (k, d, ld))
-    _check(lib().gsgd_stats_static(k, d, ld, _ptr(x, (k - 1) * ld + d), _ptr(xstar, d), _ptr(out, 4, torch.float64),
+    k, d, ld, b = int(k), int(d), int(ld), int(block_columns)
+    if k < 1 or d < 1 or ld < d or b < 0:
+        raise ValueError("bad geometry k=%d d=%d ld=%d block_columns=%d" % (k, d, ld, b))
+    need = (k - 1) * ld + d
+    if b > 0:
+        last = (d - 1) // b
+        need = last * k * b + (k - 1) * b + (d - last * b)
+    _check(lib().gsgd_stats_static(k, d, ld, b, _ptr(x, need), _ptr(xstar, d), _ptr(out, 4, torch.float64),
                                    _stream(stream)), "gsgd_stats_static")
 
 

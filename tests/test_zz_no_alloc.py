@@ -15,18 +15,19 @@ def test_stats_static_matches_stats_twice_in_a_row_second_smaller():
     from paper_1611_04581_amd import gsgd as G
     assert torch.cuda.is_available()
     out = torch.zeros(4, dtype=torch.float64, device="cuda")
-    for (k, d) in [(8, 700 * 1024 + 13), (5, 9 * 1024 + 2)]:          # 701 tiles of partial sums, then 10
-        ld = W.round_up(d, 1024)
+    # 701 tiles of partial sums, then 10; then the same pair on blocked matrices (blocks of 2048 columns)
+    for (k, d, b) in [(8, 700 * 1024 + 13, 0), (5, 9 * 1024 + 2, 0), (8, 700 * 1024 + 13, 2048), (5, 9 * 1024 + 2, 2048)]:
+        ld = W.round_up(d, b or 1024)
         inp = W.make_inputs(k, d, ld, seed=31 + k)
-        x = torch.from_numpy(inp.x).cuda()
+        x = torch.from_numpy(W.to_blocked(inp.x, b) if b else inp.x).cuda()
         xs = torch.from_numpy(inp.xstar).cuda()
         out.fill_(-1.0)
-        G.stats_static(k, d, ld, x, xs, out)
+        G.stats_static(k, d, ld, x, xs, out, block_columns=b)
         torch.cuda.synchronize()
         got = out.cpu().numpy()
-        with G.Context(k, d, ld) as ctx:
+        with G.Context(k, d, ld, block_columns=b) as ctx:
             want = ctx.stats(x, xs)
-        assert np.array_equal(got, want), (k, d, got, want)
+        assert np.array_equal(got, want), (k, d, b, got, want)
         # and both are the plain fp64 definition to rounding
         x64 = inp.x[:, :d].astype(np.float64)
         xbar = x64.mean(0)
@@ -43,10 +44,13 @@ def test_stats_static_rejects_what_it_has_no_scratch_for():
     L = G.lib()
     too_big = G.STATS_STATIC_MAX_D + 4
     # sizes beyond the fixed scratch are refused before anything is launched (the pointers are never followed)
-    assert L.gsgd_stats_static(1, too_big, too_big, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == G.ERR_TOO_LARGE
+    assert L.gsgd_stats_static(1, too_big, too_big, 0, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == G.ERR_TOO_LARGE
     assert "GSGD_STATS_STATIC_MAX_D" in G.strerror(G.ERR_TOO_LARGE)
-    assert L.gsgd_stats_static(0, 16, 16, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == G.ERR_INVALID_ARG
-    assert L.gsgd_stats_static(1, 16, 18, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == G.ERR_INVALID_ARG
-    assert L.gsgd_stats_static(1, 16, 16, x.data_ptr(), x.data_ptr(), None, None) == G.ERR_INVALID_ARG
+    assert L.gsgd_stats_static(0, 16, 16, 0, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == G.ERR_INVALID_ARG
+    assert L.gsgd_stats_static(1, 16, 18, 0, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == G.ERR_INVALID_ARG
+    assert L.gsgd_stats_static(1, 16, 16, 0, x.data_ptr(), x.data_ptr(), None, None) == G.ERR_INVALID_ARG
+    # a block that is not a power of two, or that does not divide the row length
+    assert L.gsgd_stats_static(1, 3000, 3072, 3072, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == G.ERR_INVALID_ARG
+    assert L.gsgd_stats_static(1, 3000, 3072, 2048, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == G.ERR_INVALID_ARG
     with pytest.raises(ValueError):
         G.stats_static(1, 16, 16, x, x, out.float())
