@@ -53,6 +53,10 @@ __device__ __forceinline__ void block_sum4(double val[4], double (*lds)[4])
 
 // Rows of x in flight per thread in the statistics pass.
 constexpr int STATS_ROWS_IN_FLIGHT = 4;
+// Most workgroups of the statistics pass: one per tile measured best for this read-only kernel (256 / 512 / 2048
+// striding workgroups: 44 / 69 / 71 % of the HBM peak at k = 32 against 70-78 % with one per tile), so the cap only
+// bounds the grid for very long vectors.
+constexpr unsigned STATS_WORKGROUPS = 1u << 20;
 
 // One pass over the rows.  Per column the deviations are taken from the first
 // row's value r instead of from the mean, which is not known yet:
@@ -61,11 +65,13 @@ constexpr int STATS_ROWS_IN_FLIGHT = 4;
 // the subtraction loses at most a factor k + 1 of fp64's precision; k equal values give exactly zero.
 // Lanes past the vector's end load zeros for x and xstar and so add nothing.
 __global__ __launch_bounds__(BLOCK)
-void stats_partial_kernel(Geom geo, const float* __restrict__ x, const float* __restrict__ xstar,
+void stats_partial_kernel(Geom geo, int64_t n_tiles, const float* __restrict__ x, const float* __restrict__ xstar,
                           double* __restrict__ partials)
 {
     __shared__ double lds[BLOCK / 64][4];
-    const Quad qd = my_quad(geo);
+    // every tile leaves its own partial sums, so the result does not depend on the grid
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const Quad qd = quad_of_tile(tile, geo);
     double acc[4] = {0.0, 0.0, 0.0, 0.0};     // consensus, distance, mean distance, mean norm
     if (qd.valid > 0) {
         const int valid = qd.valid;
@@ -114,7 +120,9 @@ void stats_partial_kernel(Geom geo, const float* __restrict__ x, const float* __
     }
     block_sum4(acc, lds);
     if (threadIdx.x == 0)
-        for (int m = 0; m < 4; ++m) partials[static_cast<int64_t>(blockIdx.x) * 4 + m] = acc[m];
+        for (int m = 0; m < 4; ++m) partials[tile * 4 + m] = acc[m];
+    __syncthreads();                          // thread 0 has read the wave sums before the next tile overwrites them
+    }
 }
 
 __global__ __launch_bounds__(BLOCK)
@@ -182,7 +190,9 @@ hipError_t launch_stats(const Geom& geo, const float* x, const float* xstar, dou
                         hipStream_t stream)
 {
     const unsigned nb = grid_for(geo.d);
-    hipLaunchKernelGGL(stats_partial_kernel, dim3(nb), dim3(BLOCK), 0, stream, geo, x, xstar, partials);
+    const unsigned wgs = nb < STATS_WORKGROUPS ? nb : STATS_WORKGROUPS;
+    hipLaunchKernelGGL(stats_partial_kernel, dim3(wgs), dim3(BLOCK), 0, stream, geo, static_cast<int64_t>(nb), x, xstar,
+                       partials);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(stats_final_kernel, dim3(1), dim3(BLOCK), 0, stream, static_cast<int64_t>(nb), partials, result);

@@ -8,7 +8,8 @@
  * (consensus distance falls by orders of magnitude), they approach the
  * optimum, and a step whose mix is a permutation leaves the replica mean
  * where the local step put it.  Exit status 0 and a line "abi_demo ok" on
- * success.
+ * success.  Optional argument: columns per block of the matrix layout (default
+ * 16384; 0 = row-major).
  *
  * Build (done by the package's build step):
  *   gcc -std=c99 abi_demo.c -I <repo>/include -I /opt/rocm/include -L <dir of libgsgd.so> -L /opt/rocm/lib \
@@ -29,12 +30,16 @@
 #define CHECK_GSGD(call) do { int rc_ = (call); if (rc_ != GSGD_OK) { \
     fprintf(stderr, "%s failed: %s (%d)\n", #call, gsgd_strerror(rc_), rc_); return 3; } } while (0)
 
-int main(void)
+int main(int argc, char** argv)
 {
     enum { K = 8 };
-    const int64_t d = 300 * 1000 + 3, ld = (d + 1023) / 1024 * 1024;
+    /* matrices in blocks of 16,384 columns (the layout the kernels stream fastest), or what the first argument says
+     * (0 = row-major with the row stride rounded up to 1024) */
+    const int64_t block = argc > 1 ? atoll(argv[1]) : 16384;
+    const int64_t unit = block > 0 ? block : 1024;
+    const int64_t d = 300 * 1000 + 3, ld = (d + unit - 1) / unit * unit;
     const uint64_t seed = 0x161104581ull;
-    gsgd_config cfg = { K, d, ld, 0.05f, 0.9f, 0.05f, seed, GSGD_NOISE_GAUSSIAN, 0, NULL, NULL };
+    gsgd_config cfg = { K, d, ld, 0.05f, 0.9f, 0.05f, seed, GSGD_NOISE_GAUSSIAN, 0, NULL, NULL, block };
     gsgd_ctx* ctx = NULL;
     CHECK_GSGD(gsgd_create(&cfg, &ctx));
 
