@@ -466,8 +466,8 @@ def main():
         del arun
 
     if not args.no_extras and not args.no_legs and cfg.name == "gossip_r50":
-        # short vectors: the k-way sums with the rows split over the wavefronts of a workgroup (LDS-staged block sums)
-        # against one thread per four columns walking all k rows
+        # short vectors: the k-way sums (LDS-staged block sums) and the gossip step (two sweeps) with the rows split
+        # over the wavefronts of a workgroup, against one thread per four columns walking all k rows
         rows = {}
         for (ks, ds) in ((128, 16384), (128, 65536), (32, 65536)):
             scfg = W.Config("short", "allreduce", ks, ds, 0)
@@ -484,6 +484,12 @@ def main():
                 for t in range(5):
                     srun.step(t)
                 cell["easgd_" + label] = srun.kernel_seconds(srun.step, 50) * 1e6
+            srun.cfg = W.Config("short", "gossip", ks, ds, 0)
+            for label, form in (("walk_us", gsgd.GOSSIP_WALK), ("split_sweeps_us", gsgd.GOSSIP_SWEEP_SPLIT)):
+                srun.ctx.set_gossip_form(form)
+                for t in range(5):
+                    srun.step(t)
+                cell["gossip_" + label] = srun.kernel_seconds(srun.step, 50) * 1e6
             rows["k=%d,d=%d" % (ks, ds)] = cell
             srun.close()
         out["extras"]["short_vectors_step_us"] = rows

@@ -139,7 +139,8 @@ int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups);
  *   GSGD_GOSSIP_SWEEP_SPLIT  the same with 256 columns per workgroup and the rows split over its four wavefronts
  *                            (at most 144 replicas, 72 for the stale rule);
  *   GSGD_GOSSIP_AUTO         (default) the walk on row-major matrices, the sweeps on blocked ones: the memory system
- *                            serves the row pieces of a block fastest in address order.
+ *                            serves the row pieces of a block fastest in address order; in either layout the
+ *                            split sweeps for vectors too short to fill the chip with 1024-column tiles.
  * Push-gossip's fp64 sums are taken own value first, then the senders in ascending index by the sweep forms, and in
  * visiting order by the walk (the two can differ in the last place of the rounded average).
  * A sweep form asked for with more replicas than it can park falls back (SWEEP -> SWEEP_SPLIT -> WALK).  Host only. */

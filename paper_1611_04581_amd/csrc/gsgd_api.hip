@@ -48,6 +48,9 @@ constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 0
 // 1.5-2 points at k = 16 and 32; from k = 48 on (two rows in flight) one is better by as much.
 constexpr int EASGD_FEW_REPLICAS = 48;
 
+// From this many replicas on, short vectors split the rows of a tile over the wavefronts of a workgroup.
+constexpr int ROW_SPLIT_MIN_K = 16;
+
 // Up to this many replicas the two-sweep gossip kernel keeps whole 1024-column tiles per workgroup; beyond, 256-column
 // tiles with the rows split over the wavefronts.
 constexpr int SWEEP_WHOLE_UP_TO = 36;
@@ -126,7 +129,7 @@ inline bool row_split_of(const gsgd_ctx* c)
     if (c->row_split == GSGD_ROW_SPLIT_ON) return true;
     if (c->row_split == GSGD_ROW_SPLIT_OFF) return false;
     const int64_t tiles = (c->cfg.d + BLOCK_COLUMNS - 1) / BLOCK_COLUMNS;
-    return tiles < c->cu_count && c->cfg.k >= 16;
+    return tiles < c->cu_count && c->cfg.k >= ROW_SPLIT_MIN_K;
 }
 
 inline RngKey key_of(const gsgd_ctx* c)
@@ -409,13 +412,19 @@ namespace {
 // Which kernel form a gossip call takes: GSGD_GOSSIP_WALK, _SWEEP or _SWEEP_SPLIT (never AUTO).  Measured on MI355X:
 // on row-major matrices the walk along the peer map is the faster form (71 against 65-69 % of the HBM peak at the
 // benchmark shape), on blocked ones the two ascending sweeps are (80-84 against 72-75 %; 81 against 67 % at k = 128).
-// A form that cannot park k rows falls back to the next one.
+// Short vectors (fewer 1024-column tiles than compute units) with 16 replicas or more take the split sweeps in either
+// layout: four times the workgroups and a quarter of the rows per wavefront (microseconds per step, walk -> split,
+// row-major: d = 16,384: k = 32 17.1 -> 10.6, k = 128 58 -> 20; d = 65,536: 19.9 -> 14.3, 66 -> 37; at d = 262,144 the
+// walk is level or ahead).  A form that cannot park k rows falls back to the next one.
 int gossip_form_of(const gsgd_ctx* c, bool stale)
 {
     int form = c->gossip_form;
-    if (form == GSGD_GOSSIP_AUTO)
-        form = c->cfg.block_columns == 0 ? GSGD_GOSSIP_WALK
-                                         : (c->cfg.k <= SWEEP_WHOLE_UP_TO ? GSGD_GOSSIP_SWEEP : GSGD_GOSSIP_SWEEP_SPLIT);
+    if (form == GSGD_GOSSIP_AUTO) {
+        const int64_t tiles = (c->cfg.d + BLOCK_COLUMNS - 1) / BLOCK_COLUMNS;
+        if (tiles < c->cu_count && c->cfg.k >= ROW_SPLIT_MIN_K) form = GSGD_GOSSIP_SWEEP_SPLIT;
+        else if (c->cfg.block_columns == 0) form = GSGD_GOSSIP_WALK;
+        else form = c->cfg.k <= SWEEP_WHOLE_UP_TO ? GSGD_GOSSIP_SWEEP : GSGD_GOSSIP_SWEEP_SPLIT;
+    }
     if (form == GSGD_GOSSIP_SWEEP && c->cfg.k > sweep_capacity(false, stale)) form = GSGD_GOSSIP_SWEEP_SPLIT;
     if (form == GSGD_GOSSIP_SWEEP_SPLIT && c->cfg.k > sweep_capacity(true, stale)) form = GSGD_GOSSIP_WALK;
     return form;
