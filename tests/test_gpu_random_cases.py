@@ -1,7 +1,8 @@
 """Seeded random cases through every step rule: odd replica counts (so the
 row batches have leftovers), row lengths that end inside a quad and inside a
 tile, padded strides, random peer / target maps, random segment tables, random
-hyper-parameters.  Bit-exact bar (tolerance for push-gossip's fp64 sums)."""
+hyper-parameters, every form of the gossip kernels.  Bit-exact bar (tolerance for
+push-gossip's fp64 sums, which the walk form takes in visiting order)."""
 import numpy as np
 import pytest
 
@@ -43,6 +44,8 @@ def test_random_case(oracle, case):
     alpha_e = 0.9 / k
     with G.Context(k, d, ld, lr=lr, momentum=mu, **seg) as ctx:
         ctx.set_local_step(wd, nest)
+        # the form of the gossip kernels: what the library would pick, the walk along the peer map, the two sweeps
+        ctx.set_gossip_form((G.GOSSIP_AUTO, G.GOSSIP_WALK, G.GOSSIP_SWEEP, G.GOSSIP_SWEEP_SPLIT)[case % 4])
         x, v, g, c = dev(inp.x), dev(inp.v), dev(inp.g), dev(inp.center)
         xo, vo, co = inp.x.copy(), inp.v.copy(), inp.center.copy()
         # a chain of different calls on the same state, so that every kernel also sees the others' output
