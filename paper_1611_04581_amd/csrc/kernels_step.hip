@@ -8,6 +8,16 @@
 // A wavefront reads or writes 1 KiB contiguous per access; x, v and g are each
 // read once and x, v written once: 20 bytes per replica-element, the minimum.
 //
+// The order the rows are visited in is what the memory system feels.  On
+// row-major matrices (rows tens of MB apart) it does not matter, and gossip
+// follows the peer map so that values can be handed from row to row in
+// registers (gossip_step_kernel, push_step_kernel).  On blocked matrices the
+// k row pieces of a tile are neighbours, ascending order is address order, and
+// every kernel visits them that way: gossip in two sweeps with the values a
+// mix needs parked in LDS (gossip_sweep_kernel, push_sweep_kernel), the local
+// step as a row walk (local_walk_kernel); all-reduce and elastic averaging
+// sum in ascending order anyway.
+//
 // Rows are fetched in batches of U: all loads of a batch are issued before the
 // first dependent instruction, the batch loop has no conditionals around the
 // loads (the k % U leftover rows run through a batch of one), and the row
