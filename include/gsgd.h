@@ -172,6 +172,13 @@ int gsgd_set_row_split(gsgd_ctx* ctx, int mode);
  * x0: device d. */
 int gsgd_init_replicas(gsgd_ctx* ctx, float* x, float* v, float* center, const float* x0, int mode, void* stream);
 
+/* Copy a k x d matrix from one layout of the memory model into another (row-major with any row stride, blocked with
+ * any block width), e.g. replicas loaded as flat vectors into the blocked layout the kernels stream fastest, or back.
+ * Needs no context.  src, dst: device, k x src_ld / k x dst_ld elements, not overlapping; padding columns of dst are
+ * left as they are.  Asynchronous on `stream`. */
+int gsgd_relayout(int32_t k, int64_t d, int64_t src_ld, int64_t src_block_columns, const float* src,
+                  int64_t dst_ld, int64_t dst_block_columns, float* dst, void* stream);
+
 /* Fill a device vector of d elements with one of the shared synthetic vectors
  * of the noisy quadratic f(x) = 1/2 sum_j h_j (x_j - xstar_j)^2, which is
  * m-strongly convex with L-Lipschitz gradient for m = min h, L = max h

@@ -142,17 +142,17 @@ inline bool ok_matrix(const void* p) { return p && aligned16(p); }
 
 // Bytes from the first element of a k x ld row matrix to one past the last column any kernel touches,
 // and the same for a shared d-vector.
-inline size_t matrix_span(const gsgd_ctx* c)
+inline size_t span_of(int32_t k, int64_t d, int64_t ld, int64_t block_columns)
 {
-    const size_t k = static_cast<size_t>(c->cfg.k), d = static_cast<size_t>(c->cfg.d);
-    if (c->cfg.block_columns > 0) {
+    const size_t kk = static_cast<size_t>(k), dd = static_cast<size_t>(d);
+    if (block_columns > 0) {
         // every block before the one holding column d - 1 in full, then that block up to the last row's piece
-        const size_t b = static_cast<size_t>(c->cfg.block_columns);
-        const size_t last = (d - 1) / b;
-        return sizeof(float) * (last * k * b + (k - 1) * b + (d - last * b));
+        const size_t b = static_cast<size_t>(block_columns), last = (dd - 1) / b;
+        return sizeof(float) * (last * kk * b + (kk - 1) * b + (dd - last * b));
     }
-    return sizeof(float) * ((k - 1) * static_cast<size_t>(c->cfg.ld) + d);
+    return sizeof(float) * ((kk - 1) * static_cast<size_t>(ld) + dd);
 }
+inline size_t matrix_span(const gsgd_ctx* c) { return span_of(c->cfg.k, c->cfg.d, c->cfg.ld, c->cfg.block_columns); }
 inline size_t vector_span(const gsgd_ctx* c) { return sizeof(float) * static_cast<size_t>(c->cfg.d); }
 
 inline bool overlap(const void* a, size_t na, const void* b, size_t nb)
@@ -359,6 +359,21 @@ extern "C" int gsgd_fill(gsgd_ctx* ctx, float* dst, int which, void* stream)
     if (which != GSGD_FILL_XSTAR && which != GSGD_FILL_H && which != GSGD_FILL_X0) return GSGD_ERR_INVALID_ARG;
     const hipError_t e = launch_fill(ctx->cfg.d, dst, which, key_of(ctx), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSGD_OK : hip_fail(ctx, e);
+}
+
+extern "C" int gsgd_relayout(int32_t k, int64_t d, int64_t src_ld, int64_t src_block_columns, const float* src,
+                             int64_t dst_ld, int64_t dst_block_columns, float* dst, void* stream)
+{
+    if (k < 1 || k > GSGD_MAX_K || d < 1 || d > (static_cast<int64_t>(1) << 34)) return GSGD_ERR_INVALID_ARG;
+    if (src_ld < d || (src_ld & 3) != 0 || dst_ld < d || (dst_ld & 3) != 0) return GSGD_ERR_INVALID_ARG;
+    if (!ok_block_columns(src_block_columns, src_ld) || !ok_block_columns(dst_block_columns, dst_ld))
+        return GSGD_ERR_INVALID_ARG;
+    if (!ok_matrix(src) || !ok_matrix(dst)) return GSGD_ERR_INVALID_ARG;
+    if (overlap(src, span_of(k, d, src_ld, src_block_columns), dst, span_of(k, d, dst_ld, dst_block_columns)))
+        return GSGD_ERR_INVALID_ARG;
+    const hipError_t e = launch_relayout(make_geom(k, d, src_ld, src_block_columns), make_geom(k, d, dst_ld, dst_block_columns),
+                                         src, dst, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSGD_OK : GSGD_ERR_HIP;
 }
 
 extern "C" int gsgd_gen_grad(gsgd_ctx* ctx, const float* x, const float* h, const float* xstar, float* g,

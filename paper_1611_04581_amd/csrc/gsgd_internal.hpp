@@ -150,6 +150,7 @@ hipError_t launch_gen_grad(const Geom&, const float* x, const float* h, const fl
                            float sigma, RngKey key, uint32_t step, int noise_kind, unsigned band_tiles, Persist,
                            hipStream_t);
 hipError_t launch_fill(int64_t d, float* dst, int which, RngKey key, hipStream_t);
+hipError_t launch_relayout(const Geom& from, const Geom& to, const float* src, float* dst, hipStream_t);
 hipError_t launch_init_replicas(const Geom&, float* x, float* v, float* center, const float* x0, int mode,
                                 RngKey key, hipStream_t);
 hipError_t launch_noise_alu(RngKey key, int noise_kind, uint32_t workgroups, uint32_t iters, float* out, hipStream_t);

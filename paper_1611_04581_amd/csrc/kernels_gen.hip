@@ -229,6 +229,28 @@ hipError_t launch_gen_grad(const Geom& geo, const float* x, const float* h, cons
     return hipGetLastError();
 }
 
+// Copy a matrix from one layout into another (row-major with any row stride, or blocked with any block width):
+// one workgroup per (tile, row), dispatched in the order of the destination's addresses.
+__global__ __launch_bounds__(BLOCK)
+void relayout_kernel(Geom from, Geom to, const float* __restrict__ src, float* __restrict__ dst,
+                     uint32_t band_tiles, uint32_t n_tiles)
+{
+    const uint32_t tile = blockIdx.z * band_tiles + blockIdx.x;
+    if (tile >= n_tiles) return;
+    const int64_t row = blockIdx.y;
+    const Quad qa = quad_of_tile(tile, from), qb = quad_of_tile(tile, to);
+    if (qa.valid == 0) return;
+    const f32x4 val = load_quad(src + row * from.rs + qa.mat + qa.lane_col, qa.valid);
+    store_quad(dst + row * to.rs + qb.mat + qb.lane_col, val, qa.valid);
+}
+
+hipError_t launch_relayout(const Geom& from, const Geom& to, const float* src, float* dst, hipStream_t stream)
+{
+    const FlatGrid fg = flat_grid(to, 0);
+    hipLaunchKernelGGL(relayout_kernel, fg.grid, dim3(BLOCK), 0, stream, from, to, src, dst, fg.band, grid_for(to.d));
+    return hipGetLastError();
+}
+
 hipError_t launch_fill(int64_t d, float* dst, int which, RngKey key, hipStream_t stream)
 {
     hipLaunchKernelGGL(fill_kernel, dim3(grid_for(d)), dim3(BLOCK), 0, stream, d, dst, static_cast<uint32_t>(which), key);

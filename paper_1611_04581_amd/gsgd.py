@@ -88,6 +88,7 @@ SIGNATURES = {
     "gsgd_make_perm": (C.c_int, [C.c_uint64, C.c_uint64, C.c_int32, C.POINTER(C.c_int32)]),
     "gsgd_perm_walk": (C.c_int, [C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_uint16)]),
     "gsgd_stats": (C.c_int, [_vp, _vp, _vp, C.POINTER(C.c_double), _vp]),
+    "gsgd_relayout": (C.c_int, [C.c_int32, C.c_int64, C.c_int64, C.c_int64, _vp, C.c_int64, C.c_int64, _vp, _vp]),
     "gsgd_stats_static": (C.c_int, [C.c_int32, C.c_int64, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp]),
     "gsgd_row_sqnorms": (C.c_int, [_vp, _vp, C.POINTER(C.c_double), _vp]),
     "gsgd_weights_pull": (C.c_int, [C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_int32), C.c_double]),
@@ -341,6 +342,24 @@ def stats_static(k, d, ld, x, xstar, out, stream=None, block_columns=0):
         need = last * k * b + (k - 1) * b + (d - last * b)
     _check(lib().gsgd_stats_static(k, d, ld, b, _ptr(x, need), _ptr(xstar, d), _ptr(out, 4, torch.float64),
                                    _stream(stream)), "gsgd_stats_static")
+
+
+def _span(k, d, ld, b):
+    """elements a k x ld matrix of d used columns spans in its layout (b = columns per block, 0 = row-major)"""
+    if b > 0:
+        last = (d - 1) // b
+        return last * k * b + (k - 1) * b + (d - last * b)
+    return (k - 1) * ld + d
+
+
+def relayout(k, d, src, src_ld, src_block_columns, dst, dst_ld, dst_block_columns, stream=None):
+    """gsgd_relayout: copy a k x d matrix between layouts on the device."""
+    k, d = int(k), int(d)
+    sl, sb, dl, db = int(src_ld), int(src_block_columns), int(dst_ld), int(dst_block_columns)
+    if k < 1 or d < 1 or sl < d or dl < d or sb < 0 or db < 0:
+        raise ValueError("bad geometry")
+    _check(lib().gsgd_relayout(k, d, sl, sb, _ptr(src, _span(k, d, sl, sb)), dl, db, _ptr(dst, _span(k, d, dl, db)),
+                               _stream(stream)), "gsgd_relayout")
 
 
 def comm_due(step, tau):

@@ -312,6 +312,33 @@ def test_launch_widths_do_not_change_results_blocked(oracle, k):
         ctx.stats(x, xs)          # the tile counters of every launch above drained to zero
 
 
+@pytest.mark.parametrize("k,d", [(1, 5), (3, 1024), (7, 9 * 1024 + 6), (33, 70001)])
+def test_relayout_moves_every_element_and_nothing_else(k, d):
+    """gsgd_relayout against the host-side converters: row-major -> blocked -> another row stride -> another block
+    width -> row-major; padding columns of every destination keep what they held."""
+    import torch
+    from paper_1611_04581_amd import gsgd as G
+    rng = np.random.default_rng(k)
+    src_ld = W.round_up(d, 4) + 8
+    a = np.full((k, src_ld), -5.0, np.float32)
+    a[:, :d] = rng.standard_normal((k, d)).astype(np.float32)
+    cur, cur_ld, cur_b = _dev(a), src_ld, 0
+    for (ld_unit, b) in ((2048, 2048), (4, 0), (65536, 65536), (1024, 1024), (4, 0)):
+        ld = W.round_up(d, ld_unit) + (12 if b == 0 else 0)
+        dst = torch.full((k, ld), 777.0, dtype=torch.float32, device="cuda")
+        G.relayout(k, d, cur, cur_ld, cur_b, dst, ld, b)
+        want = np.full((k, ld), 777.0, np.float32)
+        want[:, :d] = a[:, :d]
+        got = W.from_blocked(dst.cpu().numpy(), b) if b else dst.cpu().numpy()
+        assert_bitwise(got, want, "k=%d d=%d into ld=%d block=%d" % (k, d, ld, b))
+        cur, cur_ld, cur_b = dst, ld, b
+    L = G.lib()
+    p = cur.data_ptr()
+    assert L.gsgd_relayout(k, d, cur_ld, 0, p, cur_ld, 0, p, None) == G.ERR_INVALID_ARG           # onto itself
+    assert L.gsgd_relayout(k, d, cur_ld, 0, p, 3000, 3000, p + 4 * k * cur_ld, None) == G.ERR_INVALID_ARG
+    assert L.gsgd_relayout(0, d, cur_ld, 0, p, cur_ld, 0, p, None) == G.ERR_INVALID_ARG
+
+
 def test_block_columns_validation():
     from paper_1611_04581_amd import gsgd as G
     for bad in (-1024, 512, 1000, 3072):                  # negative, below a tile, not a power of two (twice)
