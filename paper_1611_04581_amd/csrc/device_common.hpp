@@ -23,7 +23,10 @@ static_assert(BLOCK_COLUMNS == static_cast<int64_t>(BLOCK) * 4, "a workgroup til
 // One thread owns one "quad": four adjacent columns, one 128-bit lane of every
 // row.  A wavefront therefore streams 1 KiB contiguous per row access.
 // `valid` is 4 for a full quad and 1..3 for the ragged last quad of a row
-// whose length is not a multiple of 4.
+// whose length is not a multiple of 4.  Row data is touched once per launch:
+// non-temporal loads and stores (on blocked matrices the gossip step runs at
+// 83.6 % of the HBM peak with both, 76-77 % with either one as an ordinary
+// cached access; all-reduce 85 against 77 %, the local step 84 against 77 %).
 template <bool FULL = false>
 __device__ __forceinline__ f32x4 load_quad(const float* p, int valid)
 {
