@@ -45,7 +45,8 @@ constexpr unsigned DEFAULT_WORKGROUPS_PER_CU[GSGD_KERNEL_COUNT] = {1u, 1u, 1u, 0
 
 // Elastic averaging with few replicas is not limited by the memory system but by what one workgroup per compute
 // unit keeps in flight over its short tiles (almost no DRAM-credit stalls at k = 16): two per compute unit gain
-// 1.5-2 points at k = 16 and 32; from k = 48 on (two rows in flight) one is better by as much.
+// 1.5-2 points at k = 16 and 32; from k = 48 on (two rows in flight) one is better by as much.  On blocked matrices
+// (two rows in flight at every k) one workgroup per compute unit is best throughout.
 constexpr int EASGD_FEW_REPLICAS = 48;
 
 // From this many replicas on, short vectors split the rows of a tile over the wavefronts of a workgroup.
@@ -58,7 +59,7 @@ constexpr int SWEEP_WHOLE_UP_TO = 36;
 inline unsigned default_width(const gsgd_ctx* c, int kernel)
 {
     unsigned per_cu = DEFAULT_WORKGROUPS_PER_CU[kernel];
-    if (kernel == GSGD_KERNEL_EASGD && c->cfg.k < EASGD_FEW_REPLICAS) per_cu = 2u;
+    if (kernel == GSGD_KERNEL_EASGD && c->cfg.k < EASGD_FEW_REPLICAS && c->cfg.block_columns == 0) per_cu = 2u;
     return static_cast<unsigned>(c->cu_count) * per_cu;
 }
 

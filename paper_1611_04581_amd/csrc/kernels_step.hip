@@ -818,6 +818,7 @@ void local_walk_kernel(Geom geo, Hyper hp, SegTable seg,
 // ---------------------------------------------------------------------------
 #ifndef GSGD_NO_LAUNCHERS
 constexpr int RIF = GSGD_ROWS_IN_FLIGHT;
+constexpr int RIF_BLOCKED = 2;           // all-reduce on blocked matrices (see launch_step_allreduce)
 // Rows in flight for the kernels that walk a peer map.  Measured on MI355X at k = 32 and both ResNet sizes with
 // a fresh permutation per launch: 3 rows sustain 71.3-72.0 % of the HBM peak, 2 rows 70.6-71.4 %, 4-6 rows
 // 69.9-70.7 %; at k = 128 all sit within 0.3 % of each other.
@@ -872,6 +873,9 @@ constexpr int SWEEP_RIF = GSGD_SWEEP_ROWS_IN_FLIGHT;
 // behind the loads (k = 128: 76.7 % of the HBM peak with 8 rows against 73.7 % with 4; k = 32 and the kernels that
 // read g: 4 is best or tied, 3 / 5 / 6 / 8 rows 81.8 / 81.2 / 81.9 / 80.1 % against 83.0 % at the benchmark shape).
 constexpr int SWEEP_RIF_FUSED_SPLIT = 8;
+// Whole tiles with g read from memory: two rows in flight are half a point to a point ahead of four at k = 8, 16, 32
+// (84.0 against 83.4 % at the benchmark shape); with the generator fused two lose 7 points.
+constexpr int SWEEP_RIF_WHOLE = 2;
 // Parking space compiled in (rows): what fits the 160 KiB of LDS beside the segment table.
 constexpr int SWEEP_ROWS_WHOLE = 36, SWEEP_ROWS_WHOLE_STALE = 16;           // 1024-column tiles: 4 KiB per row
 constexpr int SWEEP_ROWS_SPLIT_FEW = 48, SWEEP_ROWS_SPLIT = 144, SWEEP_ROWS_SPLIT_STALE = 72;   // 256-column tiles: 1 KiB
@@ -893,7 +897,7 @@ hipError_t launch_step_gossip_sweep(const Geom& geo, const Hyper& hp, const SegT
                                  : grid_for(geo.d);
     const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
 #define GSGD_SWEEP(SPLIT, ROWS, FUSED, NOISE, EXT, STALE) \
-    hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, (SPLIT && FUSED) ? SWEEP_RIF_FUSED_SPLIT : SWEEP_RIF, FUSED, NOISE, \
+    hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, (SPLIT && FUSED) ? SWEEP_RIF_FUSED_SPLIT : ((!SPLIT && !FUSED) ? SWEEP_RIF_WHOLE : SWEEP_RIF), FUSED, NOISE, \
                                             EXT, STALE>), dim3(width), dim3(BLOCK), 0, \
                        stream, geo, hp, seg, -beta, peers, x, v, g, h, xstar, sigma, key, step, p, tiles)
     // the extended local step covers the plain one (no weight decay, heavy ball) wherever only one is compiled
@@ -1059,16 +1063,26 @@ hipError_t launch_step_allreduce(const Geom& geo, const Hyper& hp, const SegTabl
         }
         return hipGetLastError();
     }
-    if (hp.extended())
-        GSGD_LAUNCH((allreduce_step_kernel<RIF, true>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
-    else
-        GSGD_LAUNCH((allreduce_step_kernel<RIF>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
+    // Blocked matrices: shallower batches (pass 1 four rows, not eight).  Blocks of 16 Ki columns, ResNet-50 size,
+    // % of the HBM peak with RIF 4 / 2: k = 16 84.2 / 84.9, k = 32 81.7 / 83.0, k = 128 78.0 / 81.0 (k = 8 level; 3 is
+    // 4-8 points behind both).
+    const bool blocked = geo.block_log2 >= 0;
+    if (hp.extended()) {
+        if (blocked) GSGD_LAUNCH((allreduce_step_kernel<RIF_BLOCKED, true>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
+        else GSGD_LAUNCH((allreduce_step_kernel<RIF, true>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
+    } else {
+        if (blocked) GSGD_LAUNCH((allreduce_step_kernel<RIF_BLOCKED>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
+        else GSGD_LAUNCH((allreduce_step_kernel<RIF>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
+    }
     return hipGetLastError();
 }
 
 // Elastic averaging keeps an fp64 accumulator next to the rows in flight.  Measured at ResNet-50 size, alternating
-// on one allocation: with many replicas two rows in flight beat four (k = 64: 78.5 % against 75.5 % of the HBM peak,
-// k = 128: 79.6 % against 76.7 %), with few it is the other way round (k = 16: 65 % against 67 %).
+// on one allocation, row-major matrices: with many replicas two rows in flight beat four (k = 64: 78.5 % against
+// 75.5 % of the HBM peak, k = 128: 79.6 % against 76.7 %), with few it is the other way round (k = 16: 65 % against
+// 67 %).  On blocked matrices two rows in flight and one workgroup per compute unit are best at every k (blocks of
+// 16 Ki columns, RIF 4 with two workgroups per compute unit against RIF 2 with one: k = 8 85.4 / 88.7, k = 16
+// 81.3 / 86.8, k = 32 79.4 / 85.7 %; from k = 48 on the two coincide).
 constexpr int EASGD_RIF_MANY_REPLICAS = 2;
 constexpr int EASGD_MANY_REPLICAS = 48;
 
@@ -1091,7 +1105,7 @@ hipError_t launch_step_easgd(const Geom& geo, const Hyper& hp, const SegTable& s
         }
         return hipGetLastError();
     }
-    const bool many = geo.k >= EASGD_MANY_REPLICAS;
+    const bool many = geo.k >= EASGD_MANY_REPLICAS || geo.block_log2 >= 0;
     if (hp.extended()) {
         if (many)
             GSGD_LAUNCH((easgd_step_kernel<EASGD_RIF_MANY_REPLICAS, true>), geo, hp, seg, alpha_e, x, v, g, center, p,
