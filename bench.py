@@ -44,17 +44,17 @@ _OTHERS = "profiles/step_kernels_other_workloads.md"
 _GENERATOR = "profiles/generator_kernels_alu_vs_hbm.md"
 TRAFFIC_FROM_PROFILES = {
     # name: (bytes per launch, source)
-    "gossip_r50": (_kib(4792046.0, 6390790.8), _GOSSIP_R50),
-    "stale_gossip_r50": (_kib(4792118.6, 6395147.1), _GOSSIP_R50),
-    "pull_gossip_r50": (_kib(4792045.7, 6390877.3), _OTHERS),
-    "push_gossip_r50": (_kib(4792030.3, 6399408.0), _GOSSIP_R50),
-    "local_r50": (_kib(4792026.3, 6390055.0), _GOSSIP_R50),
-    "allreduce_r18": (_kib(548034.8, 731019.0), _OTHERS),
-    "gossip_r18": (_kib(2191860.2, 2923273.1), _OTHERS),
-    "easgd_r50": (_kib(2445976.6, 3295273.5), _OTHERS),
-    "seg_gossip_r50_k128": (_kib(19167923.2, 25563397.5), _OTHERS),
-    "gen_grad@gossip_r50": (_kib(1697280.3, 3195543.9), _GENERATOR),
-    "fused@gossip_r50": (_kib(3294615.4, 6391103.2), _GENERATOR),
+    "gossip_r50": (_kib(4792033.0, 6390759.6), _GOSSIP_R50),
+    "stale_gossip_r50": (_kib(4792067.2, 6394912.9), _GOSSIP_R50),
+    "pull_gossip_r50": (_kib(4792032.3, 6390840.2), _OTHERS),
+    "push_gossip_r50": (_kib(4792019.6, 6402735.9), _GOSSIP_R50),
+    "local_r50": (_kib(4792015.0, 6390055.8), _GOSSIP_R50),
+    "allreduce_r18": (_kib(548023.4, 730990.0), _OTHERS),
+    "gossip_r18": (_kib(2191853.6, 2923221.8), _OTHERS),
+    "easgd_r50": (_kib(2445956.2, 3295276.9), _OTHERS),
+    "seg_gossip_r50_k128": (_kib(19167946.3, 25562391.9), _OTHERS),
+    "gen_grad@gossip_r50": (_kib(1697255.1, 3195443.7), _GENERATOR),
+    "fused@gossip_r50": (_kib(3294604.3, 6391173.9), _GENERATOR),
 }
 TRAFFIC_NOTE = ("rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size; a separate "
                 "profile run, not this run")

@@ -876,6 +876,9 @@ constexpr int SWEEP_RIF_FUSED_SPLIT = 8;
 // Whole tiles with g read from memory: two rows in flight are half a point to a point ahead of four at k = 8, 16, 32
 // (84.0 against 83.4 % at the benchmark shape); with the generator fused two lose 7 points.
 constexpr int SWEEP_RIF_WHOLE = 2;
+// Push-gossip with g read from memory: two rows in flight a point ahead of four at k = 32, level at k = 16; the stale
+// rule and the local row walk: 2 / 4 / 8 within a point of each other.
+constexpr int SWEEP_RIF_PUSH = 2, SWEEP_RIF_STALE = 4, LOCAL_WALK_RIF = 4;
 // Parking space compiled in (rows): what fits the 160 KiB of LDS beside the segment table.
 constexpr int SWEEP_ROWS_WHOLE = 36, SWEEP_ROWS_WHOLE_STALE = 16;           // 1024-column tiles: 4 KiB per row
 constexpr int SWEEP_ROWS_SPLIT_FEW = 48, SWEEP_ROWS_SPLIT = 144, SWEEP_ROWS_SPLIT_STALE = 72;   // 256-column tiles: 1 KiB
@@ -897,7 +900,7 @@ hipError_t launch_step_gossip_sweep(const Geom& geo, const Hyper& hp, const SegT
                                  : grid_for(geo.d);
     const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
 #define GSGD_SWEEP(SPLIT, ROWS, FUSED, NOISE, EXT, STALE) \
-    hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, (SPLIT && FUSED) ? SWEEP_RIF_FUSED_SPLIT : ((!SPLIT && !FUSED) ? SWEEP_RIF_WHOLE : SWEEP_RIF), FUSED, NOISE, \
+    hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, (SPLIT && FUSED) ? SWEEP_RIF_FUSED_SPLIT : ((!SPLIT && !FUSED) ? SWEEP_RIF_WHOLE : ((STALE && !FUSED) ? SWEEP_RIF_STALE : SWEEP_RIF)), FUSED, NOISE, \
                                             EXT, STALE>), dim3(width), dim3(BLOCK), 0, \
                        stream, geo, hp, seg, -beta, peers, x, v, g, h, xstar, sigma, key, step, p, tiles)
     // the extended local step covers the plain one (no weight decay, heavy ball) wherever only one is compiled
@@ -934,7 +937,7 @@ hipError_t launch_step_gossip_push_sweep(const Geom& geo, const Hyper& hp, const
                                  : grid_for(geo.d);
     const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
 #define GSGD_PUSH_SWEEP(SPLIT, ROWS, FUSED, NOISE, EXT) \
-    hipLaunchKernelGGL((push_sweep_kernel<SPLIT, ROWS, SWEEP_RIF, FUSED, NOISE, EXT>), dim3(width), dim3(BLOCK), 0, stream, \
+    hipLaunchKernelGGL((push_sweep_kernel<SPLIT, ROWS, FUSED ? SWEEP_RIF : SWEEP_RIF_PUSH, FUSED, NOISE, EXT>), dim3(width), dim3(BLOCK), 0, stream, \
                        geo, hp, seg, index, senders, x, v, g, h, xstar, sigma, key, step, p, tiles)
 #define GSGD_PUSH_SWEEP_FLAGS(SPLIT, ROWS) \
     do { \
@@ -983,8 +986,8 @@ hipError_t launch_step_local(const Geom& geo, const Hyper& hp, const SegTable& s
                              float* x, float* v, const float* g, unsigned band_tiles, Persist p, hipStream_t stream)
 {
     if (p.tickets) {                                 // persistent workgroups walking the rows (blocked matrices)
-        if (hp.extended()) GSGD_LAUNCH((local_walk_kernel<RIF, true>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
-        else GSGD_LAUNCH((local_walk_kernel<RIF, false>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
+        if (hp.extended()) GSGD_LAUNCH((local_walk_kernel<LOCAL_WALK_RIF, true>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
+        else GSGD_LAUNCH((local_walk_kernel<LOCAL_WALK_RIF, false>), geo, hp, seg, x, v, g, p, grid_for(geo.d));
         return hipGetLastError();
     }
     const FlatGrid fg = flat_grid(geo, band_tiles);
