@@ -29,18 +29,6 @@ def _rowmajor(t, b):
     return W.from_blocked(t.cpu().numpy(), b)
 
 
-def test_layout_converters_are_inverse_and_match_the_documented_formula():
-    k, b, nb = 3, 8, 4
-    ld = b * nb
-    a = np.arange(k * ld, dtype=np.float32).reshape(k, ld)
-    blk = W.to_blocked(a, b)
-    flat = blk.reshape(-1)
-    for i in range(k):
-        for j in range(ld):
-            assert flat[(j // b) * k * b + i * b + j % b] == a[i, j]
-    assert np.array_equal(W.from_blocked(blk, b), a)
-
-
 @pytest.mark.parametrize("case", range(24))
 def test_random_case_blocked(oracle, case):
     """The chain of every step rule of the row-major random cases, on blocked matrices: several blocks, a last
