@@ -488,13 +488,15 @@ hipError_t launch_push(gsgd_ctx* ctx, const Walk& walk, const int32_t* target, b
             if (target[i] != i) ++count[target[i]];
         uint32_t at = 0;
         for (int32_t r = 0; r < k; ++r) {
-            index.seq[r] = at | (count[r] << 16);
+            index.seq[r] = (at << 10) | (count[r] << 20);   // bits 0-9, the group's first sender, are filled in below
             at += count[r];
             count[r] = 0;                                   // reused below as the fill position inside the group
         }
         for (int32_t i = 0; i < k; ++i) {                   // ascending i: every group ends up in ascending order
             const int32_t r = target[i];
-            if (r != i) senders.seq[(index.seq[r] & 0xFFFFu) + count[r]++] = static_cast<uint32_t>(i);
+            if (r == i) continue;
+            if (count[r] == 0) index.seq[r] |= static_cast<uint32_t>(i);
+            senders.seq[((index.seq[r] >> 10) & 0x3FFu) + count[r]++] = static_cast<uint32_t>(i);
         }
         return launch_step_gossip_push_sweep(geom_of(ctx), hyper_of(ctx), seg_of(ctx), index, senders,
                                              form == GSGD_GOSSIP_SWEEP_SPLIT, fused, x, v, g, h, xstar, ctx->cfg.sigma,

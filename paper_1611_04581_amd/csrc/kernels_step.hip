@@ -63,6 +63,14 @@ __device__ __forceinline__ f64x4 widen(f32x4 a)
 __device__ __forceinline__ f32x4 average(f64x4 sum, uint32_t count)
 {
     const double c = static_cast<double>(count);
+    if ((count & (count - 1u)) == 0u) {
+        // a power of two (uniform test: `count` is the same for the whole workgroup): scaling by its reciprocal is
+        // the same quotient exactly, without four fp64 divisions; with uniformly drawn targets half of the rows
+        // that received anything received from one sender
+        const double r = 1.0 / c;
+        return f32x4{static_cast<float>(sum.x * r), static_cast<float>(sum.y * r),
+                     static_cast<float>(sum.z * r), static_cast<float>(sum.w * r)};
+    }
     return f32x4{static_cast<float>(sum.x / c), static_cast<float>(sum.y / c),
                  static_cast<float>(sum.z / c), static_cast<float>(sum.w / c)};
 }
@@ -250,11 +258,14 @@ void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, co
             f32x4 out;
             if constexpr (PUSH) {
                 // Algorithm 4: the average of the row's own x' and of every x' sent to it, summed in fp64, own
-                // value first, then the senders in ascending index.  peers.seq[row] = first sender's place in
-                // `senders` (low half) and how many there are (high half).
-                const uint32_t start = peers.seq[row] & 0xFFFFu, count = peers.seq[row] >> 16;
+                // value first, then the senders in ascending index.  peers.seq[row] = the first sender (bits 0-9: most
+                // rows that receive anything have one, and need no second lookup), the place of the row's group
+                // in `senders` (bits 10-19) and how many senders there are (bits 20-29).
+                const uint32_t word = peers.seq[row];
+                const uint32_t first = word & 0x3FFu, start = (word >> 10) & 0x3FFu, count = word >> 20;
                 f64x4 sum = widen(mine);
-                for (uint32_t t = 0; t < count; ++t)
+                if (count > 0) sum = sum + widen(park_key[static_cast<int>(first) * SLOTS + slot]);
+                for (uint32_t t = 1; t < count; ++t)
                     sum = sum + widen(park_key[static_cast<int>(senders.seq[start + t]) * SLOTS + slot]);
                 out = count == 0 ? mine : average(sum, count + 1u);
             } else {
@@ -297,9 +308,10 @@ void gossip_sweep_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk 
     });
 }
 
-// Push-gossip (Algorithm 4) in the same two sweeps: sweep 2 averages what a row received.  `index.seq[r]` = place of
-// row r's first sender in `senders` (low 16 bits) and the number of its senders (high 16 bits); `senders.seq` lists
-// the senders of row 0, then of row 1, ..., each group in ascending order, self-sends left out.
+// Push-gossip (Algorithm 4) in the same two sweeps: sweep 2 averages what a row received.  `index.seq[r]` = row r's
+// first sender (bits 0-9), the place of its group in `senders` (bits 10-19) and the number of its senders (bits
+// 20-29); `senders.seq` lists the senders of row 0, then of row 1, ..., each group in ascending order, self-sends
+// left out.
 template <bool SPLIT, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT>
 __global__ __launch_bounds__(BLOCK)
 void push_sweep_kernel(Geom geo, Hyper hp, SegTable seg, Walk index, Walk senders,
