@@ -889,8 +889,9 @@ constexpr int SWEEP_RIF_FUSED_SPLIT = 8;
 // (84.0 against 83.4 % at the benchmark shape); with the generator fused two lose 7 points.
 constexpr int SWEEP_RIF_WHOLE = 2;
 // Push-gossip with g read from memory: two rows in flight a point ahead of four at k = 32, level at k = 16; the stale
-// rule and the local row walk: 2 / 4 / 8 within a point of each other.
-constexpr int SWEEP_RIF_PUSH = 2, SWEEP_RIF_STALE = 4, LOCAL_WALK_RIF = 4;
+// rule: 2 / 4 / 8 within a point of each other; the local row walk: two a point ahead of four at k = 32, level at
+// k = 16.  One row in flight loses 8-10 points in every kernel.
+constexpr int SWEEP_RIF_PUSH = 2, SWEEP_RIF_STALE = 4, LOCAL_WALK_RIF = 2;
 // Parking space compiled in (rows): what fits the 160 KiB of LDS beside the segment table.
 constexpr int SWEEP_ROWS_WHOLE = 36, SWEEP_ROWS_WHOLE_STALE = 16;           // 1024-column tiles: 4 KiB per row
 constexpr int SWEEP_ROWS_SPLIT_FEW = 48, SWEEP_ROWS_SPLIT = 144, SWEEP_ROWS_SPLIT_STALE = 72;   // 256-column tiles: 1 KiB
