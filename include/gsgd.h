@@ -79,7 +79,7 @@ enum { GSGD_FILL_XSTAR = 2, GSGD_FILL_H = 3, GSGD_FILL_X0 = 4 };
 enum { GSGD_ROW_SPLIT_AUTO = 0, GSGD_ROW_SPLIT_OFF = 1, GSGD_ROW_SPLIT_ON = 2 };
 enum { GSGD_GOSSIP_AUTO = 0, GSGD_GOSSIP_WALK = 1, GSGD_GOSSIP_SWEEP = 2, GSGD_GOSSIP_SWEEP_SPLIT = 3 };
 /* the streaming kernels, for gsgd_set_launch_width.  The local step and the gradient generator are plain grids on
- * row-major matrices (and the generator below 16 replicas): there the number is the 1024-column tiles per band of
+ * row-major matrices (and the generator below 12 replicas): there the number is the 1024-column tiles per band of
  * the grid; on blocked matrices they are persistent workgroups like the others and the number counts those. */
 enum { GSGD_KERNEL_GOSSIP = 0, GSGD_KERNEL_ALLREDUCE = 1, GSGD_KERNEL_EASGD = 2, GSGD_KERNEL_GEN_GRAD = 3,
        GSGD_KERNEL_GOSSIP_FUSED = 4, GSGD_KERNEL_LOCAL = 5, GSGD_KERNEL_COUNT = 6 };

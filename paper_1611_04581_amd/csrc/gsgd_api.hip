@@ -102,10 +102,11 @@ inline Persist persist_of(gsgd_ctx* c, int kernel, void* stream)
 // the rows of a tile in ascending order on blocked matrices, where that is the address order of a block, and as plain
 // banded grids (tickets == nullptr) on row-major ones.  Measured on MI355X, blocks of 16 Ki columns, ResNet-50 size
 // (% of the HBM peak, grid -> walk): local step k = 16 / 32 / 128: 70 / 76 / 73 -> 84 / 84 / 82 with one workgroup per
-// compute unit (79 / 79 / 78 with two); generator k = 32 / 128: 73 / 71 -> 82 / 79 with two per compute unit
-// (64 / 63 with one); at k = 8 the generator's grid stays ahead (77 against 68), hence the threshold.
+// compute unit (79 / 79 / 78 with two); generator k = 12 / 32 / 128: 76 / 73 / 71 -> 85 / 85 / 81 with two per compute
+// unit (64 / 63 with one); with few replicas the generator's tiles are too short for a walk and its grid stays
+// ahead (k = 8: 77 against 68, k = 4: 80 against 41), hence the threshold.
 constexpr unsigned LOCAL_WALK_WGS_PER_CU = 1, GEN_WALK_WGS_PER_CU = 2;
-constexpr int GEN_WALK_FROM_K = 16;
+constexpr int GEN_WALK_FROM_K = 12;
 // `set_width`: what gsgd_set_launch_width left for the kernel (0 = default); as a walk it counts workgroups.
 inline Persist row_walk_of(gsgd_ctx* c, int kernel, void* stream)
 {

@@ -277,7 +277,7 @@ def test_blocked_and_row_major_contexts_agree_bitwise():
 
 @pytest.mark.parametrize("k", [5, 20])
 def test_launch_widths_do_not_change_results_blocked(oracle, k):
-    """On blocked matrices the local step and (from 16 replicas on) the generator run as persistent workgroups whose
+    """On blocked matrices the local step and (from 12 replicas on) the generator run as persistent workgroups whose
     number gsgd_set_launch_width sets; below, the generator is a banded grid and the number is its band."""
     from paper_1611_04581_amd import gsgd as G
     b, d = 2048, 9 * 1024 + 5
