@@ -31,21 +31,27 @@ def host(t):
     return np.ascontiguousarray(t.cpu().numpy())
 
 
-def test_two_streams_on_one_context_bit_exact(G, oracle):
+@pytest.mark.parametrize("k,b", [(8, 0), (20, 4096)])
+def test_two_streams_on_one_context_bit_exact(G, oracle, k, b):
     """Two independent replica sets advanced through ONE context from two
     streams with their launches interleaved and overlapping in time; both must
-    come out as the oracle computes them one after the other."""
+    come out as the oracle computes them one after the other.  Row-major
+    matrices (walk kernels, generator as a grid) and blocked ones (sweeps, and
+    the generator as a row walk that pulls tiles through the stream's counters too)."""
     import torch
-    k, d, steps = 8, 300 * 1024 + 37, 12          # 301 tiles: many more than one per workgroup when width is small
-    ld = W.round_up(d, 1024)
+    d, steps = 300 * 1024 + 37, 12                # 301 tiles: many more than one per workgroup when width is small
+    ld = W.round_up(d, b or 1024)
     sets = [W.make_inputs(k, d, ld, seed=21), W.make_inputs(k, d, ld, seed=22)]
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
-    with G.Context(k, d, ld, lr=0.05, momentum=0.9, sigma=0.1, seed=SEED, noise_kind=G.NOISE_UNIFORM) as ctx:
+    mat = (lambda a: dev(W.to_blocked(a, b))) if b else dev
+    rows = (lambda t: W.from_blocked(host(t), b)) if b else host
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, sigma=0.1, seed=SEED, noise_kind=G.NOISE_UNIFORM,
+                   block_columns=b) as ctx:
         ctx.set_launch_width(G.KERNEL_GOSSIP, 64)  # long-lived workgroups, so that the two streams really overlap
         ctx.set_launch_width(G.KERNEL_GEN_GRAD, 64)
         state = []
         for inp in sets:
-            state.append(dict(x=dev(inp.x), v=dev(inp.v), g=dev(inp.g), h=dev(inp.h), xs=dev(inp.xstar)))
+            state.append(dict(x=mat(inp.x), v=mat(inp.v), g=mat(inp.g), h=dev(inp.h), xs=dev(inp.xstar)))
         torch.cuda.synchronize()
         for t in range(steps):
             for s, st in zip(streams, state):
@@ -67,8 +73,8 @@ def test_two_streams_on_one_context_bit_exact(G, oracle):
                     oracle.step_allreduce(xo, vo, go, 0.05, 0.9, n=d)
                 else:
                     oracle.step_gossip(xo, vo, go, 0.05, 0.9, 0.5, G.make_perm(SEED, t, k), n=d)
-            assert_bitwise(host(st["x"]), xo, "x")
-            assert_bitwise(host(st["v"]), vo, "v")
+            assert_bitwise(rows(st["x"]), xo, "x")
+            assert_bitwise(rows(st["v"]), vo, "v")
 
 
 def test_overlapping_buffers_are_refused_by_range(G):
