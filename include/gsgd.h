@@ -70,7 +70,7 @@ enum {
     GSGD_ERR_UNSUPPORTED  = -5,    /* the context has launched on 32 distinct streams already */
     GSGD_ERR_NO_MEMORY    = -6,
     GSGD_ERR_BAD_STATE    = -7,    /* a tile counter was found non-zero on a drained stream; see gsgd_stats */
-    GSGD_ERR_TOO_LARGE    = -8     /* input beyond the fixed scratch of gsgd_stats_static */
+    GSGD_ERR_TOO_LARGE    = -8     /* input beyond the stated maximum of gsgd_stats_static */
 };
 
 enum { GSGD_NOISE_GAUSSIAN = 0, GSGD_NOISE_UNIFORM = 1 };
@@ -397,10 +397,11 @@ int gsgd_stats(gsgd_ctx* ctx, const float* x, const float* xstar, double out[4],
  * kernels in the same order (bit-identical to gsgd_stats), writes them to
  * out_device (device memory, 4 doubles, 8-byte aligned, caller-owned) and
  * returns without waiting for the stream.  It calls no hipMalloc / hipFree and
- * nothing else that allocates: the per-tile partial sums go to a fixed array
- * in device memory that the library holds on every GPU it runs on until the
- * process ends, sized for
- *   d <= GSGD_STATS_STATIC_MAX_D columns  (2 MiB of partial sums);
+ * nothing else that allocates: the partial sums of the pass (one set per
+ * workgroup, at most 2048 sets = 64 KiB) go to a fixed array in device memory
+ * that the library holds on every GPU it runs on until the process ends.  The
+ * entry point is specified for
+ *   d <= GSGD_STATS_STATIC_MAX_D columns;
  * a larger d is refused with GSGD_ERR_TOO_LARGE.  All calls on one GPU share
  * that array: calls that overlap in time on one GPU (different streams, or a
  * graph replaying beside eager calls) race on it and give garbage; calls that

@@ -20,7 +20,7 @@ struct gsgd_ctx {
     int         device;
     int64_t*    d_offsets;    // device copy of the segment table
     float*      d_scales;
-    double*     d_partials;   // stats scratch: stats_num_blocks(d) * 4 doubles
+    double*     d_partials;   // stats scratch: STATS_MAX_WORKGROUPS * 4 doubles
     double*     d_result;     // max(4, k) doubles
     double*     h_result;     // pinned host, max(4, k) doubles, then one more that receives a ticket pair
     double*     d_norm_partials;   // row-norm scratch: k * NORM_CHUNKS doubles
@@ -195,11 +195,10 @@ void release(gsgd_ctx* c)
 }  // namespace
 
 // ---- the statistics for callers that cannot allocate --------------------------------------------------------
-// Per-block partial sums of the two statistics kernels live in a fixed array in device memory instead of a
-// hipMalloc'ed buffer.  Every GPU the library runs on holds its own copy until the process ends.  The array's
+// The partial sums of the two statistics kernels (one set per workgroup of the pass, 64 KiB at most) live in a
+// fixed array in device memory instead of a hipMalloc'ed buffer.  Every GPU the library runs on holds its own copy until the process ends.  The array's
 // name is only a handle on the host: its device address is looked up once per device and kept.
-constexpr int64_t STATS_STATIC_MAX_TILES = GSGD_STATS_STATIC_MAX_D / (BLOCK_COLUMNS);
-static __device__ __align__(256) double scratch[STATS_STATIC_MAX_TILES * 4];
+static __device__ __align__(256) double scratch[STATS_MAX_WORKGROUPS * 4];
 
 namespace {
 constexpr int MAX_DEVICES = 64;
@@ -261,7 +260,7 @@ extern "C" int gsgd_create(const gsgd_config* cfg, gsgd_ctx** out)
         if (e == hipSuccess) e = hipMemcpy(c->d_scales, cfg->seg_lr_scale, nb_sc, hipMemcpyHostToDevice);
     }
     if (e == hipSuccess)
-        e = hipMalloc(reinterpret_cast<void**>(&c->d_partials), sizeof(double) * 4 * static_cast<size_t>(stats_num_blocks(cfg->d)));
+        e = hipMalloc(reinterpret_cast<void**>(&c->d_partials), sizeof(double) * 4 * STATS_MAX_WORKGROUPS);
     const size_t n_result = static_cast<size_t>(cfg->k > 4 ? cfg->k : 4);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_result), sizeof(double) * n_result);
     if (e == hipSuccess)
@@ -869,7 +868,7 @@ extern "C" const char* gsgd_strerror(int code)
         case GSGD_ERR_HIP: return "HIP runtime error";
         case GSGD_ERR_UNSUPPORTED: return "unsupported (a context serves at most 32 streams)";
         case GSGD_ERR_NO_MEMORY: return "out of memory";
-        case GSGD_ERR_TOO_LARGE: return "d is larger than GSGD_STATS_STATIC_MAX_D, the most gsgd_stats_static has scratch for";
+        case GSGD_ERR_TOO_LARGE: return "d is larger than GSGD_STATS_STATIC_MAX_D, the most gsgd_stats_static takes";
         case GSGD_ERR_BAD_STATE: return "a tile counter of the context was not zero on a drained stream (cleared now)";
         default: return "unknown error";
     }

@@ -161,8 +161,8 @@ hipError_t launch_philox_raw(RngKey key, uint32_t c1, uint32_t c2, uint32_t c3, 
 #define GSGD_BLOCK 256
 #endif
 constexpr int64_t BLOCK_COLUMNS = static_cast<int64_t>(GSGD_BLOCK) * 4;
-// stats: partials holds stats_num_blocks(d) * 4 doubles; result 4 doubles (device)
-int64_t    stats_num_blocks(int64_t d);
+// stats: partials holds STATS_MAX_WORKGROUPS * 4 doubles (one set per workgroup of the pass); result 4 doubles (device)
+constexpr unsigned STATS_MAX_WORKGROUPS = 2048;
 hipError_t launch_stats(const Geom&, const float* x, const float* xstar, double* partials, double* result,
                         hipStream_t);
 

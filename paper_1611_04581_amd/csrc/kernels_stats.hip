@@ -51,12 +51,14 @@ __device__ __forceinline__ void block_sum4(double val[4], double (*lds)[4])
     }
 }
 
-// Rows of x in flight per thread in the statistics pass.
-constexpr int STATS_ROWS_IN_FLIGHT = 4;
-// Most workgroups of the statistics pass: one per tile measured best for this read-only kernel (256 / 512 / 2048
-// striding workgroups: 44 / 69 / 71 % of the HBM peak at k = 32 against 70-78 % with one per tile), so the cap only
-// bounds the grid for very long vectors.
-constexpr unsigned STATS_WORKGROUPS = 1u << 20;
+// Launch shape of the statistics pass.  A thread keeps up to 32 rows of its quad in flight (its whole column for
+// k <= 32), and the grid is sized so that the workgroups together hold STATS_TILE_ROWS_IN_FLIGHT rows of a tile
+// (4 KB each) in flight: 512 workgroups from 32 replicas on, 1024 at 16, 2048 at 8 and below.  On matrices in
+// blocks of columns this read-only pass wants few workgroups that each read a tile's whole column of rows at once
+// (adjacent workgroups then cover whole blocks): at k = 32 and ResNet-50 length, 512 workgroups x 32 rows reach
+// 82 % of the HBM peak where one workgroup per tile with 4 rows in flight reached 69 %, and 84 % at k = 128;
+// row-major matrices reach 85 % (75 % before).  Grids that are no multiple of the 256 compute units lose 10 points.
+constexpr unsigned STATS_TILE_ROWS_IN_FLIGHT = 16384;
 
 // One pass over the rows.  Per column the deviations are taken from the first
 // row's value r instead of from the mean, which is not known yet:
@@ -64,65 +66,78 @@ constexpr unsigned STATS_WORKGROUPS = 1u << 20;
 // x_i - r is exact in fp64 for fp32 inputs, and since r is one of the k values, (xbar - r)^2 <= the left side, so
 // the subtraction loses at most a factor k + 1 of fp64's precision; k equal values give exactly zero.
 // Lanes past the vector's end load zeros for x and xstar and so add nothing.
+// Every workgroup strides over the tiles and leaves one set of partial sums, so the last bits of the result
+// depend on the grid, which depends on k and d only.
+template <int STATS_ROWS_IN_FLIGHT>
 __global__ __launch_bounds__(BLOCK)
 void stats_partial_kernel(Geom geo, int64_t n_tiles, const float* __restrict__ x, const float* __restrict__ xstar,
                           double* __restrict__ partials)
 {
     __shared__ double lds[BLOCK / 64][4];
-    // every tile leaves its own partial sums, so the result does not depend on the grid
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-    const Quad qd = quad_of_tile(tile, geo);
     double acc[4] = {0.0, 0.0, 0.0, 0.0};     // consensus, distance, mean distance, mean norm
-    if (qd.valid > 0) {
-        const int valid = qd.valid;
-        const float* xq = x + qd.mat + qd.lane_col;
-        const f32x4 xs4 = load_quad_cached(xstar + qd.col, valid);
-        const f32x4 r4 = load_quad(xq, valid);
-        const double xs[4] = {static_cast<double>(xs4.x), static_cast<double>(xs4.y),
-                              static_cast<double>(xs4.z), static_cast<double>(xs4.w)};
-        const double ref[4] = {static_cast<double>(r4.x), static_cast<double>(r4.y),
-                               static_cast<double>(r4.z), static_cast<double>(r4.w)};
-        double s1[4] = {0.0, 0.0, 0.0, 0.0}, s2[4] = {0.0, 0.0, 0.0, 0.0};
-        auto visit = [&](f32x4 xi) {
-            const double xv[4] = {static_cast<double>(xi.x), static_cast<double>(xi.y),
-                                  static_cast<double>(xi.z), static_cast<double>(xi.w)};
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const Quad qd = quad_of_tile(tile, geo);
+        if (qd.valid > 0) {
+            const int valid = qd.valid;
+            const float* xq = x + qd.mat + qd.lane_col;
+            const f32x4 xs4 = load_quad_cached(xstar + qd.col, valid);
+            const double xs[4] = {static_cast<double>(xs4.x), static_cast<double>(xs4.y),
+                                  static_cast<double>(xs4.z), static_cast<double>(xs4.w)};
+            double ref[4] = {0.0, 0.0, 0.0, 0.0};
+            double s1[4] = {0.0, 0.0, 0.0, 0.0}, s2[4] = {0.0, 0.0, 0.0, 0.0};
+            auto visit = [&](const f32x4& xi) {
+                const double xv[4] = {static_cast<double>(xi.x), static_cast<double>(xi.y),
+                                      static_cast<double>(xi.z), static_cast<double>(xi.w)};
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const double a = xv[m] - ref[m];
+                    const double b = xv[m] - xs[m];
+                    s1[m] += a;
+                    s2[m] += a * a;
+                    acc[1] += b * b;
+                }
+            };
+            // row 0 is the reference (its own deviation is zero); it rides in the first batch
+            auto take_ref = [&](const f32x4& r) {
+                ref[0] = static_cast<double>(r.x); ref[1] = static_cast<double>(r.y);
+                ref[2] = static_cast<double>(r.z); ref[3] = static_cast<double>(r.w);
+            };
+            int i = 0;
+            for (; i + STATS_ROWS_IN_FLIGHT <= geo.k; i += STATS_ROWS_IN_FLIGHT) {
+                f32x4 xi[STATS_ROWS_IN_FLIGHT];
+#pragma unroll
+                for (int u = 0; u < STATS_ROWS_IN_FLIGHT; ++u)
+                    xi[u] = load_quad(xq + static_cast<int64_t>(i + u) * geo.rs, valid);
+                if (i == 0) take_ref(xi[0]);
+#pragma unroll
+                for (int u = 0; u < STATS_ROWS_IN_FLIGHT; ++u) visit(xi[u]);
+            }
+            if (i < geo.k) {                                      // the rows left over, together
+                f32x4 xi[STATS_ROWS_IN_FLIGHT];
+#pragma unroll
+                for (int u = 0; u < STATS_ROWS_IN_FLIGHT - 1; ++u)
+                    if (i + u < geo.k) xi[u] = load_quad(xq + static_cast<int64_t>(i + u) * geo.rs, valid);
+                if (i == 0) take_ref(xi[0]);
+#pragma unroll
+                for (int u = 0; u < STATS_ROWS_IN_FLIGHT - 1; ++u)
+                    if (i + u < geo.k) visit(xi[u]);
+            }
+            const double kd = static_cast<double>(geo.k);
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                const double a = xv[m] - ref[m];
-                const double b = xv[m] - xs[m];
-                s1[m] += a;
-                s2[m] += a * a;
-                acc[1] += b * b;
+                const double shift = s1[m] / kd;                  // xbar - ref
+                const double dev = s2[m] - s1[m] * shift;
+                const double xbar = ref[m] + shift;
+                const double c = xbar - xs[m];
+                acc[0] += dev > 0.0 ? dev : 0.0;
+                acc[2] += c * c;
+                acc[3] += xbar * xbar;
             }
-        };
-        visit(r4);                                            // row 0: deviation zero, distance counted
-        int i = 1;
-        for (; i + STATS_ROWS_IN_FLIGHT <= geo.k; i += STATS_ROWS_IN_FLIGHT) {
-            f32x4 xi[STATS_ROWS_IN_FLIGHT];
-#pragma unroll
-            for (int u = 0; u < STATS_ROWS_IN_FLIGHT; ++u)
-                xi[u] = load_quad(xq + static_cast<int64_t>(i + u) * geo.rs, valid);
-#pragma unroll
-            for (int u = 0; u < STATS_ROWS_IN_FLIGHT; ++u) visit(xi[u]);
-        }
-        for (; i < geo.k; ++i) visit(load_quad(xq + static_cast<int64_t>(i) * geo.rs, valid));
-        const double kd = static_cast<double>(geo.k);
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const double shift = s1[m] / kd;                  // xbar - ref
-            const double dev = s2[m] - s1[m] * shift;
-            const double xbar = ref[m] + shift;
-            const double c = xbar - xs[m];
-            acc[0] += dev > 0.0 ? dev : 0.0;
-            acc[2] += c * c;
-            acc[3] += xbar * xbar;
         }
     }
     block_sum4(acc, lds);
     if (threadIdx.x == 0)
-        for (int m = 0; m < 4; ++m) partials[tile * 4 + m] = acc[m];
-    __syncthreads();                          // thread 0 has read the wave sums before the next tile overwrites them
-    }
+        for (int m = 0; m < 4; ++m) partials[static_cast<int64_t>(blockIdx.x) * 4 + m] = acc[m];
 }
 
 __global__ __launch_bounds__(BLOCK)
@@ -184,18 +199,40 @@ hipError_t launch_row_sqnorms(const Geom& geo, const float* x, double* partials,
     return hipGetLastError();
 }
 
-int64_t stats_num_blocks(int64_t d) { return static_cast<int64_t>(grid_for(d)); }
+// Workgroups of the statistics pass = sets of partial sums it leaves.
+static unsigned stats_rows_in_flight(int k)
+{
+    return k >= 32 ? 32u : k >= 16 ? 16u : 8u;
+}
+
+static unsigned stats_workgroups(int k, int64_t d)
+{
+    const unsigned rif = stats_rows_in_flight(k);
+    const unsigned per_wg = static_cast<unsigned>(k) < rif ? static_cast<unsigned>(k) : rif;
+    unsigned wgs = STATS_TILE_ROWS_IN_FLIGHT / per_wg;
+    if (wgs > STATS_MAX_WORKGROUPS) wgs = STATS_MAX_WORKGROUPS;
+    const unsigned tiles = grid_for(d);
+    return wgs < tiles ? wgs : tiles;
+}
 
 hipError_t launch_stats(const Geom& geo, const float* x, const float* xstar, double* partials, double* result,
                         hipStream_t stream)
 {
-    const unsigned nb = grid_for(geo.d);
-    const unsigned wgs = nb < STATS_WORKGROUPS ? nb : STATS_WORKGROUPS;
-    hipLaunchKernelGGL(stats_partial_kernel, dim3(wgs), dim3(BLOCK), 0, stream, geo, static_cast<int64_t>(nb), x, xstar,
-                       partials);
+    const int64_t tiles = static_cast<int64_t>(grid_for(geo.d));
+    const unsigned wgs = stats_workgroups(geo.k, geo.d);
+    switch (stats_rows_in_flight(geo.k)) {
+    case 32u:
+        hipLaunchKernelGGL(stats_partial_kernel<32>, dim3(wgs), dim3(BLOCK), 0, stream, geo, tiles, x, xstar, partials);
+        break;
+    case 16u:
+        hipLaunchKernelGGL(stats_partial_kernel<16>, dim3(wgs), dim3(BLOCK), 0, stream, geo, tiles, x, xstar, partials);
+        break;
+    default:
+        hipLaunchKernelGGL(stats_partial_kernel<8>, dim3(wgs), dim3(BLOCK), 0, stream, geo, tiles, x, xstar, partials);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(stats_final_kernel, dim3(1), dim3(BLOCK), 0, stream, static_cast<int64_t>(nb), partials, result);
+    hipLaunchKernelGGL(stats_final_kernel, dim3(1), dim3(BLOCK), 0, stream, static_cast<int64_t>(wgs), partials, result);
     return hipGetLastError();
 }
 

@@ -329,6 +329,28 @@ def test_stats_where_one_pass_could_cancel(G, oracle, name, x):
         assert got[0] == 0.0
 
 
+@pytest.mark.parametrize("k,tiles,b", [(3, 2100, 0), (3, 2100, 4096), (20, 1100, 0), (20, 1100, 2048),
+                                       (32, 700, 0), (32, 700, 16384), (45, 600, 1024), (128, 520, 0)])
+def test_stats_when_workgroups_take_several_tiles(G, oracle, k, tiles, b):
+    """Vectors longer than the statistics pass has workgroups (2048 up to 8 replicas, 1024 up to 16, 512 beyond), so
+    that workgroups stride over several tiles, some over one more than others; replica counts that fill the
+    batches of rows exactly, leave rows over, or fit no batch at all; both layouts."""
+    d = tiles * 1024 + 13
+    ld = W.round_up(d, b or 1024)
+    rng = np.random.default_rng(77 + k)
+    x = np.zeros((k, ld), np.float32)
+    x[:, :d] = 2.0 + 0.1 * rng.standard_normal((k, d)).astype(np.float32)
+    xs = np.zeros(ld, np.float32)
+    xs[:d] = rng.standard_normal(d).astype(np.float32)
+    want = oracle.stats(x, xs, n=d)
+    with G.Context(k, d, ld, block_columns=b) as ctx:
+        xd = dev(W.to_blocked(x, b) if b else x)
+        got = ctx.stats(xd, dev(xs))
+        again = ctx.stats(xd, dev(xs))
+    assert np.allclose(got, want, rtol=1e-11, atol=0), (got, want)
+    assert np.array_equal(got, again)
+
+
 def test_bad_arguments_leave_state_untouched(G):
     import torch
     k, d = 4, 1024

@@ -15,8 +15,9 @@ def test_stats_static_matches_stats_twice_in_a_row_second_smaller():
     from paper_1611_04581_amd import gsgd as G
     assert torch.cuda.is_available()
     out = torch.zeros(4, dtype=torch.float64, device="cuda")
-    # 701 tiles of partial sums, then 10; then the same pair on blocked matrices (blocks of 2048 columns)
-    for (k, d, b) in [(8, 700 * 1024 + 13, 0), (5, 9 * 1024 + 2, 0), (8, 700 * 1024 + 13, 2048), (5, 9 * 1024 + 2, 2048)]:
+    # 701 tiles over 512 workgroups' partial sums, then 10 tiles; then the same pair on blocked matrices (blocks of
+    # 2048 columns)
+    for (k, d, b) in [(32, 700 * 1024 + 13, 0), (5, 9 * 1024 + 2, 0), (32, 700 * 1024 + 13, 2048), (5, 9 * 1024 + 2, 2048)]:
         ld = W.round_up(d, b or 1024)
         inp = W.make_inputs(k, d, ld, seed=31 + k)
         x = torch.from_numpy(W.to_blocked(inp.x, b) if b else inp.x).cuda()
@@ -36,14 +37,14 @@ def test_stats_static_matches_stats_twice_in_a_row_second_smaller():
         assert np.allclose(got, ref, rtol=1e-11, atol=0)
 
 
-def test_stats_static_rejects_what_it_has_no_scratch_for():
+def test_stats_static_rejects_what_it_is_not_specified_for():
     import torch
     from paper_1611_04581_amd import gsgd as G
     x = torch.zeros(4096, dtype=torch.float32, device="cuda")
     out = torch.zeros(4, dtype=torch.float64, device="cuda")
     L = G.lib()
     too_big = G.STATS_STATIC_MAX_D + 4
-    # sizes beyond the fixed scratch are refused before anything is launched (the pointers are never followed)
+    # sizes beyond the stated maximum are refused before anything is launched (the pointers are never followed)
     assert L.gsgd_stats_static(1, too_big, too_big, 0, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == G.ERR_TOO_LARGE
     assert "GSGD_STATS_STATIC_MAX_D" in G.strerror(G.ERR_TOO_LARGE)
     assert L.gsgd_stats_static(0, 16, 16, 0, x.data_ptr(), x.data_ptr(), out.data_ptr(), None) == G.ERR_INVALID_ARG
