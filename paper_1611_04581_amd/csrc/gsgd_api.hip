@@ -29,6 +29,7 @@ struct gsgd_ctx {
     int         n_pairs;
     int         cu_count;     // compute units of the device
     unsigned    width[GSGD_KERNEL_COUNT];   // persistent workgroups per streaming kernel
+    bool        width_set[GSGD_KERNEL_COUNT];   // the width came from gsgd_set_launch_width, not from the defaults
     float       weight_decay;               // extras of the local step (Section 4.2); 0 / 0 = the boxed algorithms
     int         nesterov;
     int         row_split;                  // GSGD_ROW_SPLIT_*: how the k-way sums of short vectors are laid out
@@ -279,7 +280,7 @@ extern "C" int gsgd_create(const gsgd_config* cfg, gsgd_ctx** out)
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->cu_count, hipDeviceAttributeMultiprocessorCount, c->device);
     if (e == hipSuccess) {
         if (c->cu_count < 1) c->cu_count = 1;
-        for (int kn = 0; kn < GSGD_KERNEL_COUNT; ++kn) c->width[kn] = default_width(c, kn);
+        for (int kn = 0; kn < GSGD_KERNEL_COUNT; ++kn) { c->width[kn] = default_width(c, kn); c->width_set[kn] = false; }
     }
     if (e != hipSuccess) {
         release(c);
@@ -337,6 +338,7 @@ extern "C" int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups)
     if (!ctx || kernel < 0 || kernel >= GSGD_KERNEL_COUNT || workgroups < 0 || workgroups > (1 << 20))
         return GSGD_ERR_INVALID_ARG;
     ctx->width[kernel] = workgroups > 0 ? static_cast<unsigned>(workgroups) : default_width(ctx, kernel);
+    ctx->width_set[kernel] = workgroups > 0;
     return GSGD_OK;
 }
 
@@ -432,14 +434,21 @@ namespace {
 // layout: four times the workgroups and a quarter of the rows per wavefront (microseconds per step, walk -> split,
 // row-major: d = 16,384: k = 32 17.1 -> 10.6, k = 128 58 -> 20; d = 65,536: 19.9 -> 14.3, 66 -> 37; at d = 262,144 the
 // walk is level or ahead).  A form that cannot park k rows falls back to the next one.
-int gossip_form_of(const gsgd_ctx* c, bool stale)
+//
+// Push-gossip does more arithmetic per row in the second sweep (fp64 sums and a division), which one workgroup per
+// compute unit does not hide: from 20 replicas on it takes the split sweeps with two workgroups per compute unit
+// while two fit the LDS (blocks of 16 Ki columns, ResNet-50 length, % of the HBM peak, whole tiles -> split at two
+// per compute unit: k = 16 80 -> 74, k = 24 79 -> 82, k = 32 80 -> 82, k = 48 72 (split at one) -> 81).
+constexpr int PUSH_SPLIT_FROM_K = 20;
+int gossip_form_of(const gsgd_ctx* c, bool stale, bool push = false)
 {
     int form = c->gossip_form;
     if (form == GSGD_GOSSIP_AUTO) {
         const int64_t tiles = (c->cfg.d + BLOCK_COLUMNS - 1) / BLOCK_COLUMNS;
+        const int whole_up_to = push ? PUSH_SPLIT_FROM_K - 1 : SWEEP_WHOLE_UP_TO;
         if (tiles < c->cu_count && c->cfg.k >= ROW_SPLIT_MIN_K) form = GSGD_GOSSIP_SWEEP_SPLIT;
         else if (c->cfg.block_columns == 0) form = GSGD_GOSSIP_WALK;
-        else form = c->cfg.k <= SWEEP_WHOLE_UP_TO ? GSGD_GOSSIP_SWEEP : GSGD_GOSSIP_SWEEP_SPLIT;
+        else form = c->cfg.k <= whole_up_to ? GSGD_GOSSIP_SWEEP : GSGD_GOSSIP_SWEEP_SPLIT;
     }
     if (form == GSGD_GOSSIP_SWEEP && c->cfg.k > sweep_capacity(false, stale)) form = GSGD_GOSSIP_SWEEP_SPLIT;
     if (form == GSGD_GOSSIP_SWEEP_SPLIT && c->cfg.k > sweep_capacity(true, stale)) form = GSGD_GOSSIP_WALK;
@@ -478,10 +487,16 @@ hipError_t launch_push(gsgd_ctx* ctx, const Walk& walk, const int32_t* target, b
                        const float* g, const float* h, const float* xstar, uint64_t step, const Persist& ps, void* stream)
 {
     const hipStream_t st = static_cast<hipStream_t>(stream);
-    const int form = gossip_form_of(ctx, false);
+    const int form = gossip_form_of(ctx, false, true);
     if (form != GSGD_GOSSIP_WALK) {
         const int32_t k = ctx->cfg.k;
+        Persist wide = ps;
+        // two split workgroups per compute unit where they fit, unless the caller has chosen the width
+        if (form == GSGD_GOSSIP_SWEEP_SPLIT && k <= sweep_rows_two_per_cu() &&
+            !ctx->width_set[fused ? GSGD_KERNEL_GOSSIP_FUSED : GSGD_KERNEL_GOSSIP])
+            wide.workgroups = 2u * static_cast<unsigned>(ctx->cu_count);
         Walk index{}, senders{};
+        static_assert(GSGD_MAX_K <= 0x3FF, "the index word holds ten bits per field");
         uint32_t count[GSGD_MAX_K];
         for (int32_t r = 0; r < k; ++r) count[r] = 0;
         for (int32_t i = 0; i < k; ++i)
@@ -500,7 +515,7 @@ hipError_t launch_push(gsgd_ctx* ctx, const Walk& walk, const int32_t* target, b
         }
         return launch_step_gossip_push_sweep(geom_of(ctx), hyper_of(ctx), seg_of(ctx), index, senders,
                                              form == GSGD_GOSSIP_SWEEP_SPLIT, fused, x, v, g, h, xstar, ctx->cfg.sigma,
-                                             key_of(ctx), static_cast<uint32_t>(step), ctx->cfg.noise_kind, ps, st);
+                                             key_of(ctx), static_cast<uint32_t>(step), ctx->cfg.noise_kind, wide, st);
     }
     if (fused)
         return launch_step_gossip_push_fused(geom_of(ctx), hyper_of(ctx), seg_of(ctx), walk, x, v, h, xstar, ctx->cfg.sigma,

@@ -249,7 +249,10 @@ void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, co
             i0 += N;
         };
         while (i0 + U <= r1) batch(Count<U>{});
-        while (i0 < r1) batch(Count<1>{});
+        // the rows left over go out in batches of 4, 2 and 1 rather than one at a time
+        if constexpr (U > 4) { if (i0 + 4 <= r1) batch(Count<4>{}); }
+        if constexpr (U > 2) { if (i0 + 2 <= r1) batch(Count<2>{}); }
+        if (i0 < r1) batch(Count<1>{});
     }
     if constexpr (SPLIT) __syncthreads();             // a row's peer may be parked by another wavefront
     if (FULL || valid > 0) {
@@ -895,6 +898,11 @@ constexpr int SWEEP_RIF_PUSH = 2, SWEEP_RIF_STALE = 4, LOCAL_WALK_RIF = 2;
 // Parking space compiled in (rows): what fits the 160 KiB of LDS beside the segment table.
 constexpr int SWEEP_ROWS_WHOLE = 36, SWEEP_ROWS_WHOLE_STALE = 16;           // 1024-column tiles: 4 KiB per row
 constexpr int SWEEP_ROWS_SPLIT_FEW = 48, SWEEP_ROWS_SPLIT = 144, SWEEP_ROWS_SPLIT_STALE = 72;   // 256-column tiles: 1 KiB
+// Push-gossip also has a split form that leaves room for two workgroups per compute unit (see sweep_rows_two_per_cu).
+constexpr int SWEEP_ROWS_SPLIT_PUSH_MID = 64;     // 64 KiB + the 12 KiB segment table, twice, in 160 KiB
+
+// Most rows for which two workgroups of the split push kernel fit one compute unit's LDS.
+int sweep_rows_two_per_cu() { return SWEEP_ROWS_SPLIT_PUSH_MID; }
 
 int sweep_capacity(bool split, bool stale)
 {
@@ -961,6 +969,7 @@ hipError_t launch_step_gossip_push_sweep(const Geom& geo, const Hyper& hp, const
     } while (0)
     if (!split) GSGD_PUSH_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE);
     else if (geo.k <= SWEEP_ROWS_SPLIT_FEW) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW);
+    else if (geo.k <= SWEEP_ROWS_SPLIT_PUSH_MID) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_PUSH_MID);
     else GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT);
 #undef GSGD_PUSH_SWEEP_FLAGS
 #undef GSGD_PUSH_SWEEP
