@@ -44,11 +44,11 @@ _OTHERS = "profiles/step_kernels_other_workloads.md"
 _GENERATOR = "profiles/generator_kernels_alu_vs_hbm.md"
 TRAFFIC_FROM_PROFILES = {
     # name: (bytes per launch, source)
-    "gossip_r50": (_kib(4792027.4, 6390789.8), _GOSSIP_R50),
-    "stale_gossip_r50": (_kib(4792083.7, 6394069.4), _GOSSIP_R50),
+    "gossip_r50": (_kib(4792041.7, 6390782.9), _GOSSIP_R50),
+    "stale_gossip_r50": (_kib(4792026.1, 6390058.6), _GOSSIP_R50),
     "pull_gossip_r50": (_kib(4792032.3, 6390840.2), _OTHERS),
-    "push_gossip_r50": (_kib(4792081.9, 6392483.1), _GOSSIP_R50),
-    "local_r50": (_kib(4792017.6, 6390125.0), _GOSSIP_R50),
+    "push_gossip_r50": (_kib(4792102.9, 6392507.2), _GOSSIP_R50),
+    "local_r50": (_kib(4792016.7, 6390055.1), _GOSSIP_R50),
     "allreduce_r18": (_kib(548023.4, 730990.0), _OTHERS),
     "gossip_r18": (_kib(2191853.6, 2923221.8), _OTHERS),
     "easgd_r50": (_kib(2445956.2, 3295276.9), _OTHERS),

@@ -135,9 +135,9 @@ int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups);
  *   GSGD_GOSSIP_WALK         rows visited along the cycles (and trees) of the peer map, values handed from row to
  *                            row in registers;
  *   GSGD_GOSSIP_SWEEP        rows visited in ascending order twice, the values a row's mix needs parked in LDS in
- *                            between; a workgroup owns 1024 columns (at most 36 replicas, 16 for the stale rule);
+ *                            between; a workgroup owns 1024 columns (at most 36 replicas);
  *   GSGD_GOSSIP_SWEEP_SPLIT  the same with 256 columns per workgroup and the rows split over its four wavefronts
- *                            (at most 144 replicas, 72 for the stale rule);
+ *                            (at most 144 replicas);
  *   GSGD_GOSSIP_AUTO         (default) the walk on row-major matrices, the sweeps on blocked ones: the memory system
  *                            serves the row pieces of a block fastest in address order; in either layout the
  *                            split sweeps for vectors too short to fill the chip with 1024-column tiles.

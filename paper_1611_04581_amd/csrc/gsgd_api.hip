@@ -440,7 +440,7 @@ namespace {
 // while two fit the LDS (blocks of 16 Ki columns, ResNet-50 length, % of the HBM peak, whole tiles -> split at two
 // per compute unit: k = 16 80 -> 74, k = 24 79 -> 82, k = 32 80 -> 82, k = 48 72 (split at one) -> 81).
 constexpr int PUSH_SPLIT_FROM_K = 20;
-int gossip_form_of(const gsgd_ctx* c, bool stale, bool push = false)
+int gossip_form_of(const gsgd_ctx* c, bool push = false)
 {
     int form = c->gossip_form;
     if (form == GSGD_GOSSIP_AUTO) {
@@ -450,8 +450,8 @@ int gossip_form_of(const gsgd_ctx* c, bool stale, bool push = false)
         else if (c->cfg.block_columns == 0) form = GSGD_GOSSIP_WALK;
         else form = c->cfg.k <= whole_up_to ? GSGD_GOSSIP_SWEEP : GSGD_GOSSIP_SWEEP_SPLIT;
     }
-    if (form == GSGD_GOSSIP_SWEEP && c->cfg.k > sweep_capacity(false, stale)) form = GSGD_GOSSIP_SWEEP_SPLIT;
-    if (form == GSGD_GOSSIP_SWEEP_SPLIT && c->cfg.k > sweep_capacity(true, stale)) form = GSGD_GOSSIP_WALK;
+    if (form == GSGD_GOSSIP_SWEEP && c->cfg.k > sweep_capacity(false)) form = GSGD_GOSSIP_SWEEP_SPLIT;
+    if (form == GSGD_GOSSIP_SWEEP_SPLIT && c->cfg.k > sweep_capacity(true)) form = GSGD_GOSSIP_WALK;
     return form;
 }
 
@@ -469,7 +469,7 @@ hipError_t launch_gossip(gsgd_ctx* ctx, const Walk& walk, const int32_t* peer, b
                          uint64_t step, const Persist& ps, void* stream)
 {
     const hipStream_t st = static_cast<hipStream_t>(stream);
-    const int form = gossip_form_of(ctx, stale);
+    const int form = gossip_form_of(ctx);
     if (form != GSGD_GOSSIP_WALK)
         return launch_step_gossip_sweep(geom_of(ctx), hyper_of(ctx), seg_of(ctx), beta, peers_of(peer, ctx->cfg.k), stale,
                                         form == GSGD_GOSSIP_SWEEP_SPLIT, fused, x, v, g, h, xstar, ctx->cfg.sigma,
@@ -487,7 +487,7 @@ hipError_t launch_push(gsgd_ctx* ctx, const Walk& walk, const int32_t* target, b
                        const float* g, const float* h, const float* xstar, uint64_t step, const Persist& ps, void* stream)
 {
     const hipStream_t st = static_cast<hipStream_t>(stream);
-    const int form = gossip_form_of(ctx, false, true);
+    const int form = gossip_form_of(ctx, true);
     if (form != GSGD_GOSSIP_WALK) {
         const int32_t k = ctx->cfg.k;
         Persist wide = ps;

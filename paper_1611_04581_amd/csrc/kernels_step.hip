@@ -173,9 +173,13 @@ void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk w
 // order (one sequential stream per block instead of jumps inside it).  So the
 // rows are visited in ascending order twice:
 //   sweep 1: load x, v, g of a row, take the local step, store v, park the
-//            row's key (and, for the stale rule, its x' as well) in LDS;
+//            row's x' in LDS;
 //   sweep 2: finish every row from its own and its peer's parked values and
 //            store x.
+// The stale-parameter rule mixes the x from before the local step, so there
+// sweep 1 only loads and parks x, and sweep 2 loads v and g, takes the local
+// step from the parked x, mixes with the peer's parked x and stores v and x:
+// one parked value per row in either rule.
 // Each of x, v, g is still read once and x, v written once (20 bytes per
 // replica-element); the parked values cost 16 bytes of LDS per thread and row.
 // Any peer map works (no cycles or trees to follow).
@@ -191,7 +195,7 @@ template <bool SPLIT, bool FULL, int ROWS, int U, bool FUSED_GEN, int NOISE, boo
 __device__ __forceinline__
 void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds,
                        int64_t tile_col, int64_t mat, float neg_beta, const Walk& peers, const Walk& senders,
-                       f32x4* __restrict__ park_key, f32x4* __restrict__ park_post,
+                       f32x4* __restrict__ park_key,
                        float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
                        const float* __restrict__ h, const float* __restrict__ xstar,
                        float sigma, RngKey key, uint32_t step)
@@ -219,6 +223,7 @@ void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, co
         }
         const uint32_t quad_index = static_cast<uint32_t>(col >> 2);
         int i0 = r0;
+        // rows i0 .. i0 + N - 1: X (and V, G unless STALE) in, local step, v out, x' parked; STALE: X in and parked
         auto batch = [&](auto n) {
             constexpr int N = decltype(n)::value;
             f32x4 X[N], V[N], G[N];
@@ -226,35 +231,87 @@ void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, co
             for (int u = 0; u < N; ++u) {
                 const int64_t off = static_cast<int64_t>(i0 + u) * geo.rs + mat;
                 X[u] = load_quad<FULL>(x + off + lane_col, valid);
-                V[u] = load_quad<FULL>(v + off + lane_col, valid);
-                if constexpr (!FUSED_GEN) G[u] = load_quad<FULL>(g + off + lane_col, valid);
+                if constexpr (!STALE) V[u] = load_quad<FULL>(v + off + lane_col, valid);
+                if constexpr (!STALE && !FUSED_GEN) G[u] = load_quad<FULL>(g + off + lane_col, valid);
             }
 #pragma unroll
             for (int u = 0; u < N; ++u) {
                 const int row = i0 + u;
-                const int64_t off = static_cast<int64_t>(row) * geo.rs + mat;
-                if constexpr (FUSED_GEN) {
-                    const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, static_cast<uint32_t>(row), step, STREAM_GRAD,
-                                                                 key.k0, key.k1));
-                    const f32x4 t1 = X[u] - xs4;
-                    const f32x4 t2 = sigma * xi;
-                    G[u] = fma4(h4, t1, t2);
+                if constexpr (STALE) {
+                    park_key[row * SLOTS + slot] = X[u];
+                } else {
+                    const int64_t off = static_cast<int64_t>(row) * geo.rs + mat;
+                    if constexpr (FUSED_GEN) {
+                        const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, static_cast<uint32_t>(row), step,
+                                                                     STREAM_GRAD, key.k0, key.k1));
+                        const f32x4 t1 = X[u] - xs4;
+                        const f32x4 t2 = sigma * xi;
+                        G[u] = fma4(h4, t1, t2);
+                    }
+                    f32x4 vn, post;
+                    local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, post);
+                    store_quad<FULL>(v + off + lane_col, vn, valid);
+                    park_key[row * SLOTS + slot] = post;
                 }
-                f32x4 vn, post;
-                local_step<EXT>(X[u], V[u], G[u], neg_lr, hp, vn, post);
-                store_quad<FULL>(v + off + lane_col, vn, valid);
-                park_key[row * SLOTS + slot] = STALE ? X[u] : post;
-                if constexpr (STALE) park_post[row * SLOTS + slot] = post;
             }
             i0 += N;
         };
-        while (i0 + U <= r1) batch(Count<U>{});
-        // the rows left over go out in batches of 4, 2 and 1 rather than one at a time
-        if constexpr (U > 4) { if (i0 + 4 <= r1) batch(Count<4>{}); }
-        if constexpr (U > 2) { if (i0 + 2 <= r1) batch(Count<2>{}); }
+        constexpr int U1 = STALE ? 2 * U : U;         // the stale rule's first sweep loads x alone: twice the rows
+        while (i0 + U1 <= r1) batch(Count<U1>{});
+        // the rows left over go out in batches of 8, 4, 2 and 1 rather than one at a time
+        if constexpr (U1 > 8) { if (i0 + 8 <= r1) batch(Count<8>{}); }
+        if constexpr (U1 > 4) { if (i0 + 4 <= r1) batch(Count<4>{}); }
+        if constexpr (U1 > 2) { if (i0 + 2 <= r1) batch(Count<2>{}); }
         if (i0 < r1) batch(Count<1>{});
     }
     if constexpr (SPLIT) __syncthreads();             // a row's peer may be parked by another wavefront
+    if constexpr (STALE) {
+        if (FULL || valid > 0) {
+            const f32x4 neg_lr = -quad_lr(seg, lds, col, valid, hp.lr);
+            f32x4 h4 = {0.f, 0.f, 0.f, 0.f}, xs4 = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (FUSED_GEN) {
+                h4 = load_quad_cached<FULL>(h + col, valid);
+                xs4 = load_quad_cached<FULL>(xstar + col, valid);
+            }
+            const uint32_t quad_index = static_cast<uint32_t>(col >> 2);
+            int i0 = r0;
+            // second sweep of the stale rule: V (and G) in, local step from the parked x, mix with the peer's parked x, v and x out
+            auto stale_batch = [&](auto n) {
+                constexpr int N = decltype(n)::value;
+                f32x4 V[N], G[N];
+#pragma unroll
+                for (int u = 0; u < N; ++u) {
+                    const int64_t off = static_cast<int64_t>(i0 + u) * geo.rs + mat;
+                    V[u] = load_quad<FULL>(v + off + lane_col, valid);
+                    if constexpr (!FUSED_GEN) G[u] = load_quad<FULL>(g + off + lane_col, valid);
+                }
+#pragma unroll
+                for (int u = 0; u < N; ++u) {
+                    const int row = i0 + u;
+                    const int64_t off = static_cast<int64_t>(row) * geo.rs + mat;
+                    const f32x4 mine = park_key[row * SLOTS + slot];
+                    const f32x4 theirs = park_key[static_cast<int>(peers.seq[row]) * SLOTS + slot];
+                    if constexpr (FUSED_GEN) {
+                        const f32x4 xi = noise4<NOISE>(philox4x32_10(quad_index, static_cast<uint32_t>(row), step, STREAM_GRAD,
+                                                                     key.k0, key.k1));
+                        const f32x4 t1 = mine - xs4;
+                        const f32x4 t2 = sigma * xi;
+                        G[u] = fma4(h4, t1, t2);
+                    }
+                    f32x4 vn, post;
+                    local_step<EXT>(mine, V[u], G[u], neg_lr, hp, vn, post);
+                    store_quad<FULL>(v + off + lane_col, vn, valid);
+                    store_quad<FULL>(x + off + lane_col, mix_keys(post, mine, theirs, neg_beta), valid);
+                }
+                i0 += N;
+            };
+            while (i0 + U <= r1) stale_batch(Count<U>{});
+            if constexpr (U > 4) { if (i0 + 4 <= r1) stale_batch(Count<4>{}); }
+            if constexpr (U > 2) { if (i0 + 2 <= r1) stale_batch(Count<2>{}); }
+            if (i0 < r1) stale_batch(Count<1>{});
+        }
+        return;
+    }
     if (FULL || valid > 0) {
         for (int row = r0; row < r1; ++row) {
             const f32x4 mine = park_key[row * SLOTS + slot];
@@ -273,8 +330,7 @@ void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, co
                 out = count == 0 ? mine : average(sum, count + 1u);
             } else {
                 const f32x4 theirs = park_key[static_cast<int>(peers.seq[row]) * SLOTS + slot];
-                const f32x4 post = STALE ? park_post[row * SLOTS + slot] : mine;
-                out = mix_keys(post, mine, theirs, neg_beta);
+                out = mix_keys(mine, mine, theirs, neg_beta);
             }
             store_quad<FULL>(x + static_cast<int64_t>(row) * geo.rs + mat + lane_col, out, valid);
         }
@@ -294,7 +350,6 @@ void gossip_sweep_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk 
     constexpr int TILE_COLUMNS = SPLIT ? SWEEP_SPLIT_COLUMNS : BLOCK * 4;
     __shared__ SegLds lds;
     __shared__ f32x4 park_key[ROWS * SLOTS];
-    __shared__ f32x4 park_post[STALE ? ROWS * SLOTS : 1];
     stage_segments(seg, lds);
     for_each_tile(pst, n_tiles, [&](uint32_t tile) {
         const int64_t tile_col = static_cast<int64_t>(tile) * TILE_COLUMNS;
@@ -302,11 +357,11 @@ void gossip_sweep_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk 
         // every thread takes the same branch (the barrier inside the body is reached by all or by none)
         if (tile_col + TILE_COLUMNS <= geo.d)
             gossip_sweep_body<SPLIT, true, ROWS, U, FUSED_GEN, NOISE, EXT, STALE>(
-                geo, hp, seg, lds, tile_col, mat, neg_beta, peers, peers, park_key, park_post, x, v, g, h, xstar, sigma, key,
+                geo, hp, seg, lds, tile_col, mat, neg_beta, peers, peers, park_key, x, v, g, h, xstar, sigma, key,
                 step);
         else
             gossip_sweep_body<SPLIT, false, ROWS, U, FUSED_GEN, NOISE, EXT, STALE>(
-                geo, hp, seg, lds, tile_col, mat, neg_beta, peers, peers, park_key, park_post, x, v, g, h, xstar, sigma, key,
+                geo, hp, seg, lds, tile_col, mat, neg_beta, peers, peers, park_key, x, v, g, h, xstar, sigma, key,
                 step);
     });
 }
@@ -332,11 +387,11 @@ void push_sweep_kernel(Geom geo, Hyper hp, SegTable seg, Walk index, Walk sender
         const int64_t mat = column_origin(geo, tile_col);
         if (tile_col + TILE_COLUMNS <= geo.d)
             gossip_sweep_body<SPLIT, true, ROWS, U, FUSED_GEN, NOISE, EXT, false, true>(
-                geo, hp, seg, lds, tile_col, mat, 0.0f, index, senders, park_key, park_key, x, v, g, h, xstar, sigma, key,
+                geo, hp, seg, lds, tile_col, mat, 0.0f, index, senders, park_key, x, v, g, h, xstar, sigma, key,
                 step);
         else
             gossip_sweep_body<SPLIT, false, ROWS, U, FUSED_GEN, NOISE, EXT, false, true>(
-                geo, hp, seg, lds, tile_col, mat, 0.0f, index, senders, park_key, park_key, x, v, g, h, xstar, sigma, key,
+                geo, hp, seg, lds, tile_col, mat, 0.0f, index, senders, park_key, x, v, g, h, xstar, sigma, key,
                 step);
     });
 }
@@ -891,27 +946,33 @@ constexpr int SWEEP_RIF_FUSED_SPLIT = 8;
 // Whole tiles with g read from memory: two rows in flight are half a point to a point ahead of four at k = 8, 16, 32
 // (84.0 against 83.4 % at the benchmark shape); with the generator fused two lose 7 points.
 constexpr int SWEEP_RIF_WHOLE = 2;
-// Push-gossip with g read from memory: two rows in flight a point ahead of four at k = 32, level at k = 16; the stale
-// rule: 2 / 4 / 8 within a point of each other; the local row walk: two a point ahead of four at k = 32, level at
-// k = 16.  One row in flight loses 8-10 points in every kernel.
-constexpr int SWEEP_RIF_PUSH = 2, SWEEP_RIF_STALE = 4, LOCAL_WALK_RIF = 2;
+// Push-gossip with g read from memory: two rows in flight a point ahead of four at k = 32, level at k = 16; the local
+// row walk: two a point ahead of four at k = 32, level at k = 16.  One row in flight loses 8-10 points in every kernel.
+constexpr int SWEEP_RIF_PUSH = 2, LOCAL_WALK_RIF = 2;
+// The stale rule: rows of v and g in flight in its second sweep; its first sweep, which loads x alone, takes twice
+// as many.  Whole tiles: 2 and 4 level, 1 loses 13 points; split tiles: 8 a point ahead of 4 at k = 40 and 64, level
+// at k = 128, 2 loses 4-6 points.
+constexpr int SWEEP_RIF_STALE_WHOLE = 2, SWEEP_RIF_STALE_SPLIT = 8;
+constexpr int sweep_rif(bool split, bool fused, bool stale)
+{
+    if (stale && !fused) return split ? SWEEP_RIF_STALE_SPLIT : SWEEP_RIF_STALE_WHOLE;
+    if (split && fused) return SWEEP_RIF_FUSED_SPLIT;
+    if (!split && !fused) return SWEEP_RIF_WHOLE;
+    return SWEEP_RIF;
+}
 // Parking space compiled in (rows): what fits the 160 KiB of LDS beside the segment table.
-constexpr int SWEEP_ROWS_WHOLE = 36, SWEEP_ROWS_WHOLE_STALE = 16;           // 1024-column tiles: 4 KiB per row
-constexpr int SWEEP_ROWS_SPLIT_FEW = 48, SWEEP_ROWS_SPLIT = 144, SWEEP_ROWS_SPLIT_STALE = 72;   // 256-column tiles: 1 KiB
+constexpr int SWEEP_ROWS_WHOLE = 36;                                        // 1024-column tiles: 4 KiB per row
+constexpr int SWEEP_ROWS_SPLIT_FEW = 48, SWEEP_ROWS_SPLIT = 144;            // 256-column tiles: 1 KiB
 // Push-gossip also has a split form that leaves room for two workgroups per compute unit (see sweep_rows_two_per_cu).
 constexpr int SWEEP_ROWS_SPLIT_PUSH_MID = 64;     // 64 KiB + the 12 KiB segment table, twice, in 160 KiB
 
 // Most rows for which two workgroups of the split push kernel fit one compute unit's LDS.
 int sweep_rows_two_per_cu() { return SWEEP_ROWS_SPLIT_PUSH_MID; }
 
-int sweep_capacity(bool split, bool stale)
-{
-    if (split) return stale ? SWEEP_ROWS_SPLIT_STALE : SWEEP_ROWS_SPLIT;
-    return stale ? SWEEP_ROWS_WHOLE_STALE : SWEEP_ROWS_WHOLE;
-}
+int sweep_capacity(bool split) { return split ? SWEEP_ROWS_SPLIT : SWEEP_ROWS_WHOLE; }
 
 // The gossip step in its two-sweep form; `fused` takes g from the generator (h, xstar, sigma, key, step) instead
-// of reading it.  The caller has checked geo.k <= sweep_capacity(split, stale).
+// of reading it.  The caller has checked geo.k <= sweep_capacity(split).
 hipError_t launch_step_gossip_sweep(const Geom& geo, const Hyper& hp, const SegTable& seg, float beta, const Walk& peers,
                                     bool stale, bool split, bool fused, float* x, float* v, const float* g,
                                     const float* h, const float* xstar, float sigma, RngKey key, uint32_t step,
@@ -921,34 +982,34 @@ hipError_t launch_step_gossip_sweep(const Geom& geo, const Hyper& hp, const SegT
                                  : grid_for(geo.d);
     const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
 #define GSGD_SWEEP(SPLIT, ROWS, FUSED, NOISE, EXT, STALE) \
-    hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, (SPLIT && FUSED) ? SWEEP_RIF_FUSED_SPLIT : ((!SPLIT && !FUSED) ? SWEEP_RIF_WHOLE : ((STALE && !FUSED) ? SWEEP_RIF_STALE : SWEEP_RIF)), FUSED, NOISE, \
-                                            EXT, STALE>), dim3(width), dim3(BLOCK), 0, \
+    hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, sweep_rif(SPLIT, FUSED, STALE), FUSED, NOISE, EXT, STALE>), \
+                       dim3(width), dim3(BLOCK), 0, \
                        stream, geo, hp, seg, -beta, peers, x, v, g, h, xstar, sigma, key, step, p, tiles)
     // the extended local step covers the plain one (no weight decay, heavy ball) wherever only one is compiled
-#define GSGD_SWEEP_FLAGS(SPLIT, ROWS, ROWS_STALE) \
+#define GSGD_SWEEP_FLAGS(SPLIT, ROWS) \
     do { \
         if (fused) { \
             if (noise_kind == GSGD_NOISE_UNIFORM) { \
-                if (stale) GSGD_SWEEP(SPLIT, ROWS_STALE, true, GSGD_NOISE_UNIFORM, true, true); \
+                if (stale) GSGD_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_UNIFORM, true, true); \
                 else GSGD_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_UNIFORM, true, false); \
             } else { \
-                if (stale) GSGD_SWEEP(SPLIT, ROWS_STALE, true, GSGD_NOISE_GAUSSIAN, true, true); \
+                if (stale) GSGD_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_GAUSSIAN, true, true); \
                 else GSGD_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_GAUSSIAN, true, false); \
             } \
-        } else if (stale) GSGD_SWEEP(SPLIT, ROWS_STALE, false, 0, true, true); \
+        } else if (stale) GSGD_SWEEP(SPLIT, ROWS, false, 0, true, true); \
         else if (hp.extended()) GSGD_SWEEP(SPLIT, ROWS, false, 0, true, false); \
         else GSGD_SWEEP(SPLIT, ROWS, false, 0, false, false); \
     } while (0)
-    if (!split) GSGD_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE, SWEEP_ROWS_WHOLE_STALE);
-    else if (geo.k <= SWEEP_ROWS_SPLIT_FEW && !stale) GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW, SWEEP_ROWS_SPLIT_STALE);
-    else GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT, SWEEP_ROWS_SPLIT_STALE);
+    if (!split) GSGD_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE);
+    else if (geo.k <= SWEEP_ROWS_SPLIT_FEW) GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW);
+    else GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT);
 #undef GSGD_SWEEP_FLAGS
 #undef GSGD_SWEEP
     return hipGetLastError();
 }
 
 // Push-gossip in the two-sweep form; `index` / `senders` as push_sweep_kernel takes them.  The caller has checked
-// geo.k <= sweep_capacity(split, false).
+// geo.k <= sweep_capacity(split).
 hipError_t launch_step_gossip_push_sweep(const Geom& geo, const Hyper& hp, const SegTable& seg, const Walk& index,
                                          const Walk& senders, bool split, bool fused, float* x, float* v, const float* g,
                                          const float* h, const float* xstar, float sigma, RngKey key, uint32_t step,
