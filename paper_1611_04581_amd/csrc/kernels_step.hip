@@ -942,6 +942,8 @@ constexpr int SWEEP_RIF = GSGD_SWEEP_ROWS_IN_FLIGHT;
 // With the generator fused and the rows split over the wavefronts a deeper batch hides the generator's arithmetic
 // behind the loads (k = 128: 76.7 % of the HBM peak with 8 rows against 73.7 % with 4; k = 32 and the kernels that
 // read g: 4 is best or tied, 3 / 5 / 6 / 8 rows 81.8 / 81.2 / 81.9 / 80.1 % against 83.0 % at the benchmark shape).
+// Issuing the next batch's loads before the generator works on the current one (two register sets in turn) does not
+// help: level at k = 16 and 32, 5-10 points worse at k = 64 and 128.
 constexpr int SWEEP_RIF_FUSED_SPLIT = 8;
 // Whole tiles with g read from memory: two rows in flight are half a point to a point ahead of four at k = 8, 16, 32
 // (84.0 against 83.4 % at the benchmark shape); with the generator fused two lose 7 points.
@@ -963,11 +965,12 @@ constexpr int sweep_rif(bool split, bool fused, bool stale)
 // Parking space compiled in (rows): what fits the 160 KiB of LDS beside the segment table.
 constexpr int SWEEP_ROWS_WHOLE = 36;                                        // 1024-column tiles: 4 KiB per row
 constexpr int SWEEP_ROWS_SPLIT_FEW = 48, SWEEP_ROWS_SPLIT = 144;            // 256-column tiles: 1 KiB
-// Push-gossip also has a split form that leaves room for two workgroups per compute unit (see sweep_rows_two_per_cu).
-constexpr int SWEEP_ROWS_SPLIT_PUSH_MID = 64;     // 64 KiB + the 12 KiB segment table, twice, in 160 KiB
+// The largest split form that leaves room for two workgroups per compute unit (64 KiB + the 12 KiB segment table,
+// twice, in 160 KiB), which the kernels with arithmetic to hide want: push-gossip's averaging, the fused generator.
+constexpr int SWEEP_ROWS_SPLIT_MID = 64;
 
 // Most rows for which two workgroups of the split push kernel fit one compute unit's LDS.
-int sweep_rows_two_per_cu() { return SWEEP_ROWS_SPLIT_PUSH_MID; }
+int sweep_rows_two_per_cu() { return SWEEP_ROWS_SPLIT_MID; }
 
 int sweep_capacity(bool split) { return split ? SWEEP_ROWS_SPLIT : SWEEP_ROWS_WHOLE; }
 
@@ -1002,6 +1005,7 @@ hipError_t launch_step_gossip_sweep(const Geom& geo, const Hyper& hp, const SegT
     } while (0)
     if (!split) GSGD_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE);
     else if (geo.k <= SWEEP_ROWS_SPLIT_FEW) GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW);
+    else if (geo.k <= SWEEP_ROWS_SPLIT_MID) GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_MID);
     else GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT);
 #undef GSGD_SWEEP_FLAGS
 #undef GSGD_SWEEP
@@ -1030,7 +1034,7 @@ hipError_t launch_step_gossip_push_sweep(const Geom& geo, const Hyper& hp, const
     } while (0)
     if (!split) GSGD_PUSH_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE);
     else if (geo.k <= SWEEP_ROWS_SPLIT_FEW) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW);
-    else if (geo.k <= SWEEP_ROWS_SPLIT_PUSH_MID) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_PUSH_MID);
+    else if (geo.k <= SWEEP_ROWS_SPLIT_MID) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_MID);
     else GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT);
 #undef GSGD_PUSH_SWEEP_FLAGS
 #undef GSGD_PUSH_SWEEP
