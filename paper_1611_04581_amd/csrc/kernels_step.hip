@@ -20,9 +20,10 @@
 //
 // Rows are fetched in batches of U: all loads of a batch are issued before the
 // first dependent instruction, the batch loop has no conditionals around the
-// loads (the k % U leftover rows run through a batch of one), and the row
-// order comes from scalar registers, so nothing waits on the vector-memory
-// counter except the uses of the loaded rows themselves.
+// loads (the k % U leftover rows run through a batch of one; in the sweeps
+// through batches of 4, 2 and 1), and the row order comes from scalar
+// registers, so nothing waits on the vector-memory counter except the uses
+// of the loaded rows themselves.
 #include "device_common.hpp"
 
 namespace gsgd {
