@@ -53,7 +53,8 @@ __device__ __forceinline__ void block_sum4(double val[4], double (*lds)[4])
 
 // Launch shape of the statistics pass.  A thread keeps up to 32 rows of its quad in flight (its whole column for
 // k <= 32), and the grid is sized so that the workgroups together hold STATS_TILE_ROWS_IN_FLIGHT rows of a tile
-// (4 KB each) in flight: 512 workgroups from 32 replicas on, 1024 at 16, 2048 at 8 and below.  On matrices in
+// (4 KB each) in flight: 512 workgroups from 32 replicas on (one per compute unit resident at a time: 32 rows in
+// flight take 255 registers), 1024 at 16, 2048 at 8 and below.  On matrices in
 // blocks of columns this read-only pass wants few workgroups that each read a tile's whole column of rows at once
 // (adjacent workgroups then cover whole blocks): at k = 32 and ResNet-50 length, 512 workgroups x 32 rows reach
 // 82 % of the HBM peak where one workgroup per tile with 4 rows in flight reached 69 %, and 84 % at k = 128;
