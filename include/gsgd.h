@@ -136,8 +136,8 @@ int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups);
  *                            row in registers;
  *   GSGD_GOSSIP_SWEEP        rows visited in ascending order twice, the values a row's mix needs parked in LDS in
  *                            between; a workgroup owns 1024 columns (at most 36 replicas);
- *   GSGD_GOSSIP_SWEEP_SPLIT  the same with 256 columns per workgroup and the rows split over its four wavefronts
- *                            (at most 144 replicas);
+ *   GSGD_GOSSIP_SWEEP_SPLIT  the same with 256 columns per workgroup and the rows split over its wavefronts (four;
+ *                            eight or twelve beyond 64 replicas) (at most 144 replicas);
  *   GSGD_GOSSIP_AUTO         (default) the walk on row-major matrices, the sweeps on blocked ones: the memory system
  *                            serves the row pieces of a block fastest in address order; in either layout the
  *                            split sweeps for vectors too short to fill the chip with 1024-column tiles.

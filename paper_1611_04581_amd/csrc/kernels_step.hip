@@ -187,10 +187,21 @@ void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk w
 //
 // SPLIT = false: a workgroup owns a 1024-column tile, a thread parks its own
 // quads of all k rows (rows <= ROWS, ROWS * 4 KiB of LDS, no barrier at all).
-// SPLIT = true: a workgroup owns a 256-column tile and its four wavefronts
-// take a quarter of the rows each (ROWS KiB of LDS, one barrier between the
-// sweeps): the form for many replicas.
+// SPLIT = true: a workgroup owns a 256-column tile and its wavefronts (four,
+// or more: see sweep_block) take an equal share of the rows each (ROWS KiB of
+// LDS, one barrier between the sweeps): the form for many replicas.
 constexpr int SWEEP_SPLIT_COLUMNS = 256;
+// Threads per workgroup.  Of the split form for the most rows only one workgroup fits a compute unit's LDS, and four
+// wavefronts (one per SIMD) leave the arithmetic of a sweep uncovered; the rows are split over however many
+// wavefronts there are, so these kernels run with 8 (12 with the generator fused, where 8 and 4 are level).  Blocks
+// of 16 Ki columns, ResNet-50 length, % of the HBM peak with 4 -> 8 wavefronts: push-gossip k = 80 73 -> 81.5,
+// k = 128 73 -> 80; stale rule k = 128 80.5 -> 83; plain gossip k = 128 80.5 -> 81.5 (k = 80 level); 4 -> 12 with the
+// generator fused: k = 80 74 -> 79, k = 128 76 -> 78.5 (12 lose 2-3 points in the others; 16 spill registers).
+constexpr int SWEEP_ROWS_ONE_PER_CU = 65;          // parking space from which only one workgroup fits
+constexpr int sweep_block(bool split, int rows, bool fused_gossip)
+{
+    return split && rows >= SWEEP_ROWS_ONE_PER_CU ? (fused_gossip ? 12 : 8) * 64 : BLOCK;
+}
 
 template <bool SPLIT, bool FULL, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE, bool PUSH = false>
 __device__ __forceinline__
@@ -207,11 +218,12 @@ void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, co
     const int64_t col = tile_col + lane_col;
     const int64_t left = geo.d - col;
     const int valid = FULL ? 4 : (left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0));
-    // rows of this thread: all of them, or its wavefront's quarter
+    // rows of this thread: all of them, or its wavefront's share
     int r0 = 0, r1 = geo.k;
     if constexpr (SPLIT) {
         const int wave = static_cast<int>(threadIdx.x >> 6);
-        const int per = (geo.k + BLOCK / 64 - 1) / (BLOCK / 64);
+        const int waves = static_cast<int>(blockDim.x >> 6);
+        const int per = (geo.k + waves - 1) / waves;
         r0 = wave * per < geo.k ? wave * per : geo.k;
         r1 = r0 + per < geo.k ? r0 + per : geo.k;
     }
@@ -341,7 +353,7 @@ void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, co
 // `peers.seq[i]` is the plain index of the row that row i mixes with.  n_tiles counts tiles of the kernel's own
 // width (1024 columns, or 256 when SPLIT).  Needs k <= ROWS (checked by the launcher).
 template <bool SPLIT, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE>
-__global__ __launch_bounds__(BLOCK)
+__global__ __launch_bounds__(sweep_block(SPLIT, ROWS, FUSED_GEN))
 void gossip_sweep_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk peers,
                          float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
                          const float* __restrict__ h, const float* __restrict__ xstar,
@@ -372,7 +384,7 @@ void gossip_sweep_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk 
 // 20-29); `senders.seq` lists the senders of row 0, then of row 1, ..., each group in ascending order, self-sends
 // left out.
 template <bool SPLIT, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT>
-__global__ __launch_bounds__(BLOCK)
+__global__ __launch_bounds__(sweep_block(SPLIT, ROWS, false))
 void push_sweep_kernel(Geom geo, Hyper hp, SegTable seg, Walk index, Walk senders,
                        float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
                        const float* __restrict__ h, const float* __restrict__ xstar,
@@ -987,7 +999,7 @@ hipError_t launch_step_gossip_sweep(const Geom& geo, const Hyper& hp, const SegT
     const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
 #define GSGD_SWEEP(SPLIT, ROWS, FUSED, NOISE, EXT, STALE) \
     hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, sweep_rif(SPLIT, FUSED, STALE), FUSED, NOISE, EXT, STALE>), \
-                       dim3(width), dim3(BLOCK), 0, \
+                       dim3(width), dim3(sweep_block(SPLIT, ROWS, FUSED)), 0, \
                        stream, geo, hp, seg, -beta, peers, x, v, g, h, xstar, sigma, key, step, p, tiles)
     // the extended local step covers the plain one (no weight decay, heavy ball) wherever only one is compiled
 #define GSGD_SWEEP_FLAGS(SPLIT, ROWS) \
@@ -1024,7 +1036,7 @@ hipError_t launch_step_gossip_push_sweep(const Geom& geo, const Hyper& hp, const
                                  : grid_for(geo.d);
     const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
 #define GSGD_PUSH_SWEEP(SPLIT, ROWS, FUSED, NOISE, EXT) \
-    hipLaunchKernelGGL((push_sweep_kernel<SPLIT, ROWS, FUSED ? SWEEP_RIF : SWEEP_RIF_PUSH, FUSED, NOISE, EXT>), dim3(width), dim3(BLOCK), 0, stream, \
+    hipLaunchKernelGGL((push_sweep_kernel<SPLIT, ROWS, FUSED ? SWEEP_RIF : SWEEP_RIF_PUSH, FUSED, NOISE, EXT>), dim3(width), dim3(sweep_block(SPLIT, ROWS, false)), 0, stream, \
                        geo, hp, seg, index, senders, x, v, g, h, xstar, sigma, key, step, p, tiles)
 #define GSGD_PUSH_SWEEP_FLAGS(SPLIT, ROWS) \
     do { \
