@@ -142,7 +142,8 @@ int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups);
  *                            serves the row pieces of a block fastest in address order; in either layout the
  *                            split sweeps for vectors too short to fill the chip with 1024-column tiles.
  *                            On blocked matrices push-gossip takes the split sweeps from 20 replicas on, and up to
- *                            64 replicas with twice the workgroups unless gsgd_set_launch_width has set their number.
+ *                            64 replicas (up to 16 in whole tiles) with twice the workgroups unless
+ *                            gsgd_set_launch_width has set their number.
  * Push-gossip's fp64 sums are taken own value first, then the senders in ascending index by the sweep forms, and in
  * visiting order by the walk (the two can differ in the last place of the rounded average).
  * A sweep form asked for with more replicas than it can park falls back (SWEEP -> SWEEP_SPLIT -> WALK).  Host only. */

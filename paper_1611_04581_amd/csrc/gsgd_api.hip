@@ -491,8 +491,8 @@ hipError_t launch_push(gsgd_ctx* ctx, const Walk& walk, const int32_t* target, b
     if (form != GSGD_GOSSIP_WALK) {
         const int32_t k = ctx->cfg.k;
         Persist wide = ps;
-        // two split workgroups per compute unit where they fit, unless the caller has chosen the width
-        if (form == GSGD_GOSSIP_SWEEP_SPLIT && k <= sweep_rows_two_per_cu() &&
+        // two workgroups per compute unit where they fit, unless the caller has chosen the width
+        if (k <= sweep_rows_two_per_cu(form == GSGD_GOSSIP_SWEEP_SPLIT) &&
             !ctx->width_set[fused ? GSGD_KERNEL_GOSSIP_FUSED : GSGD_KERNEL_GOSSIP])
             wide.workgroups = 2u * static_cast<unsigned>(ctx->cu_count);
         Walk index{}, senders{};

@@ -126,7 +126,7 @@ hipError_t launch_easgd_tick(const Geom&, const Hyper&, const SegTable&, float a
 hipError_t launch_step_local(const Geom&, const Hyper&, const SegTable&, float* x, float* v, const float* g,
                              unsigned band_tiles, Persist, hipStream_t);
 int        sweep_capacity(bool split);                   // most replicas the two-sweep gossip kernels can park
-int        sweep_rows_two_per_cu();      // most replicas for which two split workgroups fit a compute unit's LDS
+int        sweep_rows_two_per_cu(bool split);   // most replicas for which two workgroups fit a compute unit's LDS
 hipError_t launch_step_gossip_push_sweep(const Geom&, const Hyper&, const SegTable&, const Walk& index,
                                          const Walk& senders, bool split, bool fused, float* x, float* v, const float* g,
                                          const float* h, const float* xstar, float sigma, RngKey key, uint32_t step,

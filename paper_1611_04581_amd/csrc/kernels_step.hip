@@ -976,14 +976,15 @@ constexpr int sweep_rif(bool split, bool fused, bool stale)
     return SWEEP_RIF;
 }
 // Parking space compiled in (rows): what fits the 160 KiB of LDS beside the segment table.
-constexpr int SWEEP_ROWS_WHOLE = 36;                                        // 1024-column tiles: 4 KiB per row
+constexpr int SWEEP_ROWS_WHOLE = 36, SWEEP_ROWS_WHOLE_FEW = 16;             // 1024-column tiles: 4 KiB per row
 constexpr int SWEEP_ROWS_SPLIT_FEW = 48, SWEEP_ROWS_SPLIT = 144;            // 256-column tiles: 1 KiB
-// The largest split form that leaves room for two workgroups per compute unit (64 KiB + the 12 KiB segment table,
-// twice, in 160 KiB), which the kernels with arithmetic to hide want: push-gossip's averaging, the fused generator.
+// The largest forms that leave room for two workgroups per compute unit (64 KiB + the 12 KiB segment table, twice,
+// in 160 KiB), which the kernels with arithmetic to hide want: push-gossip's averaging, the fused generator.
+// SWEEP_ROWS_WHOLE_FEW is the same for whole tiles.
 constexpr int SWEEP_ROWS_SPLIT_MID = 64;
 
 // Most rows for which two workgroups of the split push kernel fit one compute unit's LDS.
-int sweep_rows_two_per_cu() { return SWEEP_ROWS_SPLIT_MID; }
+int sweep_rows_two_per_cu(bool split) { return split ? SWEEP_ROWS_SPLIT_MID : SWEEP_ROWS_WHOLE_FEW; }
 
 int sweep_capacity(bool split) { return split ? SWEEP_ROWS_SPLIT : SWEEP_ROWS_WHOLE; }
 
@@ -1016,7 +1017,8 @@ hipError_t launch_step_gossip_sweep(const Geom& geo, const Hyper& hp, const SegT
         else if (hp.extended()) GSGD_SWEEP(SPLIT, ROWS, false, 0, true, false); \
         else GSGD_SWEEP(SPLIT, ROWS, false, 0, false, false); \
     } while (0)
-    if (!split) GSGD_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE);
+    if (!split && geo.k <= SWEEP_ROWS_WHOLE_FEW) GSGD_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE_FEW);
+    else if (!split) GSGD_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE);
     else if (geo.k <= SWEEP_ROWS_SPLIT_FEW) GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW);
     else if (geo.k <= SWEEP_ROWS_SPLIT_MID) GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_MID);
     else GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT);
@@ -1045,7 +1047,8 @@ hipError_t launch_step_gossip_push_sweep(const Geom& geo, const Hyper& hp, const
         else if (hp.extended()) GSGD_PUSH_SWEEP(SPLIT, ROWS, false, 0, true); \
         else GSGD_PUSH_SWEEP(SPLIT, ROWS, false, 0, false); \
     } while (0)
-    if (!split) GSGD_PUSH_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE);
+    if (!split && geo.k <= SWEEP_ROWS_WHOLE_FEW) GSGD_PUSH_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE_FEW);
+    else if (!split) GSGD_PUSH_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE);
     else if (geo.k <= SWEEP_ROWS_SPLIT_FEW) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW);
     else if (geo.k <= SWEEP_ROWS_SPLIT_MID) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_MID);
     else GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT);
