@@ -187,9 +187,12 @@ void gossip_step_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk w
 //
 // SPLIT = false: a workgroup owns a 1024-column tile, a thread parks its own
 // quads of all k rows (rows <= ROWS, ROWS * 4 KiB of LDS, no barrier at all).
-// SPLIT = true: a workgroup owns a 256-column tile and its wavefronts (four,
-// or more: see sweep_block) take an equal share of the rows each (ROWS KiB of
-// LDS, one barrier between the sweeps): the form for many replicas.
+// SPLIT = true: a workgroup owns a tile of CG x 256 columns; CG wavefronts
+// side by side cover its columns, and the rows are shared out equally among
+// the rows of wavefronts (ROWS x CG KiB of LDS, one barrier between the
+// sweeps).  CG = 1, four wavefronts or more (see sweep_block): the form for
+// many replicas.  CG = 4, eight wavefronts: a whole 1024-column tile for the
+// kernels whose arithmetic one wavefront per SIMD does not hide.
 constexpr int SWEEP_SPLIT_COLUMNS = 256;
 // Threads per workgroup.  Of the split form for the most rows only one workgroup fits a compute unit's LDS, and four
 // wavefronts (one per SIMD) leave the arithmetic of a sweep uncovered; the rows are split over however many
@@ -198,12 +201,21 @@ constexpr int SWEEP_SPLIT_COLUMNS = 256;
 // k = 128 73 -> 80; stale rule k = 128 80.5 -> 83; plain gossip k = 128 80.5 -> 81.5 (k = 80 level); 4 -> 12 with the
 // generator fused: k = 80 74 -> 79, k = 128 76 -> 78.5 (12 lose 2-3 points in the others; 16 spill registers).
 constexpr int SWEEP_ROWS_ONE_PER_CU = 65;          // parking space from which only one workgroup fits
-constexpr int sweep_block(bool split, int rows, bool fused_gossip)
+// Whole 1024-column tiles for the kernels with arithmetic to hide, beyond the 16 rows of which two workgroups fit:
+// SWEEP_WIDE_GROUPS wavefronts side by side cover the tile's columns, and two such rows of wavefronts take half of
+// the tile's rows each (eight wavefronts, one barrier between the sweeps, the same LDS as a thread per quad).
+// % of the HBM peak, a thread per quad -> this form: generator-fused gossip k = 24 82 -> 84.6, k = 32 83.5 -> 84.4;
+// push-gossip k = 18 78.8 -> 81.4.  The kernels that read g and do little else lose 1.5-2.5 points and keep a
+// thread per quad.
+constexpr int SWEEP_WIDE_GROUPS = 4;
+constexpr int sweep_block(bool split, int rows, bool fused_gossip, int column_groups)
 {
+    if (column_groups > 1) return 2 * column_groups * 64;
     return split && rows >= SWEEP_ROWS_ONE_PER_CU ? (fused_gossip ? 12 : 8) * 64 : BLOCK;
 }
 
-template <bool SPLIT, bool FULL, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE, bool PUSH = false>
+template <bool SPLIT, bool FULL, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE, bool PUSH = false,
+          int CG = 1>
 __device__ __forceinline__
 void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, const SegLds& lds,
                        int64_t tile_col, int64_t mat, float neg_beta, const Walk& peers, const Walk& senders,
@@ -212,8 +224,9 @@ void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, co
                        const float* __restrict__ h, const float* __restrict__ xstar,
                        float sigma, RngKey key, uint32_t step)
 {
-    constexpr int SLOTS = SPLIT ? 64 : BLOCK;                   // parked quads per row
-    const int slot = SPLIT ? static_cast<int>(threadIdx.x & 63u) : static_cast<int>(threadIdx.x);
+    constexpr int SLOTS = SPLIT ? 64 * CG : BLOCK;              // parked quads per row
+    const int slot = SPLIT ? static_cast<int>(((threadIdx.x >> 6) % CG) * 64u + (threadIdx.x & 63u))
+                           : static_cast<int>(threadIdx.x);
     const uint32_t lane_col = static_cast<uint32_t>(slot) * 4u;
     const int64_t col = tile_col + lane_col;
     const int64_t left = geo.d - col;
@@ -221,8 +234,8 @@ void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, co
     // rows of this thread: all of them, or its wavefront's share
     int r0 = 0, r1 = geo.k;
     if constexpr (SPLIT) {
-        const int wave = static_cast<int>(threadIdx.x >> 6);
-        const int waves = static_cast<int>(blockDim.x >> 6);
+        const int wave = static_cast<int>(threadIdx.x >> 6) / CG;          // CG wavefronts side by side share rows
+        const int waves = static_cast<int>(blockDim.x >> 6) / CG;
         const int per = (geo.k + waves - 1) / waves;
         r0 = wave * per < geo.k ? wave * per : geo.k;
         r1 = r0 + per < geo.k ? r0 + per : geo.k;
@@ -352,15 +365,15 @@ void gossip_sweep_body(const Geom& geo, const Hyper& hp, const SegTable& seg, co
 
 // `peers.seq[i]` is the plain index of the row that row i mixes with.  n_tiles counts tiles of the kernel's own
 // width (1024 columns, or 256 when SPLIT).  Needs k <= ROWS (checked by the launcher).
-template <bool SPLIT, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE>
-__global__ __launch_bounds__(sweep_block(SPLIT, ROWS, FUSED_GEN))
+template <bool SPLIT, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT, bool STALE, int CG = 1>
+__global__ __launch_bounds__(sweep_block(SPLIT, ROWS, FUSED_GEN, CG))
 void gossip_sweep_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk peers,
                          float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
                          const float* __restrict__ h, const float* __restrict__ xstar,
                          float sigma, RngKey key, uint32_t step, Persist pst, uint32_t n_tiles)
 {
-    constexpr int SLOTS = SPLIT ? 64 : BLOCK;
-    constexpr int TILE_COLUMNS = SPLIT ? SWEEP_SPLIT_COLUMNS : BLOCK * 4;
+    constexpr int SLOTS = SPLIT ? 64 * CG : BLOCK;
+    constexpr int TILE_COLUMNS = SPLIT ? SWEEP_SPLIT_COLUMNS * CG : BLOCK * 4;
     __shared__ SegLds lds;
     __shared__ f32x4 park_key[ROWS * SLOTS];
     stage_segments(seg, lds);
@@ -369,11 +382,11 @@ void gossip_sweep_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk 
         const int64_t mat = column_origin(geo, tile_col);
         // every thread takes the same branch (the barrier inside the body is reached by all or by none)
         if (tile_col + TILE_COLUMNS <= geo.d)
-            gossip_sweep_body<SPLIT, true, ROWS, U, FUSED_GEN, NOISE, EXT, STALE>(
+            gossip_sweep_body<SPLIT, true, ROWS, U, FUSED_GEN, NOISE, EXT, STALE, false, CG>(
                 geo, hp, seg, lds, tile_col, mat, neg_beta, peers, peers, park_key, x, v, g, h, xstar, sigma, key,
                 step);
         else
-            gossip_sweep_body<SPLIT, false, ROWS, U, FUSED_GEN, NOISE, EXT, STALE>(
+            gossip_sweep_body<SPLIT, false, ROWS, U, FUSED_GEN, NOISE, EXT, STALE, false, CG>(
                 geo, hp, seg, lds, tile_col, mat, neg_beta, peers, peers, park_key, x, v, g, h, xstar, sigma, key,
                 step);
     });
@@ -383,15 +396,15 @@ void gossip_sweep_kernel(Geom geo, Hyper hp, SegTable seg, float neg_beta, Walk 
 // first sender (bits 0-9), the place of its group in `senders` (bits 10-19) and the number of its senders (bits
 // 20-29); `senders.seq` lists the senders of row 0, then of row 1, ..., each group in ascending order, self-sends
 // left out.
-template <bool SPLIT, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT>
-__global__ __launch_bounds__(sweep_block(SPLIT, ROWS, false))
+template <bool SPLIT, int ROWS, int U, bool FUSED_GEN, int NOISE, bool EXT, int CG = 1>
+__global__ __launch_bounds__(sweep_block(SPLIT, ROWS, false, CG))
 void push_sweep_kernel(Geom geo, Hyper hp, SegTable seg, Walk index, Walk senders,
                        float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
                        const float* __restrict__ h, const float* __restrict__ xstar,
                        float sigma, RngKey key, uint32_t step, Persist pst, uint32_t n_tiles)
 {
-    constexpr int SLOTS = SPLIT ? 64 : BLOCK;
-    constexpr int TILE_COLUMNS = SPLIT ? SWEEP_SPLIT_COLUMNS : BLOCK * 4;
+    constexpr int SLOTS = SPLIT ? 64 * CG : BLOCK;
+    constexpr int TILE_COLUMNS = SPLIT ? SWEEP_SPLIT_COLUMNS * CG : BLOCK * 4;
     __shared__ SegLds lds;
     __shared__ f32x4 park_key[ROWS * SLOTS];
     stage_segments(seg, lds);
@@ -399,11 +412,11 @@ void push_sweep_kernel(Geom geo, Hyper hp, SegTable seg, Walk index, Walk sender
         const int64_t tile_col = static_cast<int64_t>(tile) * TILE_COLUMNS;
         const int64_t mat = column_origin(geo, tile_col);
         if (tile_col + TILE_COLUMNS <= geo.d)
-            gossip_sweep_body<SPLIT, true, ROWS, U, FUSED_GEN, NOISE, EXT, false, true>(
+            gossip_sweep_body<SPLIT, true, ROWS, U, FUSED_GEN, NOISE, EXT, false, true, CG>(
                 geo, hp, seg, lds, tile_col, mat, 0.0f, index, senders, park_key, x, v, g, h, xstar, sigma, key,
                 step);
         else
-            gossip_sweep_body<SPLIT, false, ROWS, U, FUSED_GEN, NOISE, EXT, false, true>(
+            gossip_sweep_body<SPLIT, false, ROWS, U, FUSED_GEN, NOISE, EXT, false, true, CG>(
                 geo, hp, seg, lds, tile_col, mat, 0.0f, index, senders, park_key, x, v, g, h, xstar, sigma, key,
                 step);
     });
@@ -968,8 +981,10 @@ constexpr int SWEEP_RIF_PUSH = 2, LOCAL_WALK_RIF = 2;
 // as many.  Whole tiles: 2 and 4 level, 1 loses 13 points; split tiles: 8 a point ahead of 4 at k = 40 and 64, level
 // at k = 128, 2 loses 4-6 points.
 constexpr int SWEEP_RIF_STALE_WHOLE = 2, SWEEP_RIF_STALE_SPLIT = 8;
-constexpr int sweep_rif(bool split, bool fused, bool stale)
+constexpr int SWEEP_RIF_WIDE = 2;                 // whole tiles under eight wavefronts: 2 a point ahead of 4
+constexpr int sweep_rif(bool split, bool fused, bool stale, int column_groups)
 {
+    if (column_groups > 1) return SWEEP_RIF_WIDE;
     if (stale && !fused) return split ? SWEEP_RIF_STALE_SPLIT : SWEEP_RIF_STALE_WHOLE;
     if (split && fused) return SWEEP_RIF_FUSED_SPLIT;
     if (!split && !fused) return SWEEP_RIF_WHOLE;
@@ -998,31 +1013,38 @@ hipError_t launch_step_gossip_sweep(const Geom& geo, const Hyper& hp, const SegT
     const uint32_t tiles = split ? static_cast<uint32_t>((geo.d + SWEEP_SPLIT_COLUMNS - 1) / SWEEP_SPLIT_COLUMNS)
                                  : grid_for(geo.d);
     const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
-#define GSGD_SWEEP(SPLIT, ROWS, FUSED, NOISE, EXT, STALE) \
-    hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, sweep_rif(SPLIT, FUSED, STALE), FUSED, NOISE, EXT, STALE>), \
-                       dim3(width), dim3(sweep_block(SPLIT, ROWS, FUSED)), 0, \
+#define GSGD_SWEEP(SPLIT, ROWS, CG, FUSED, NOISE, EXT, STALE) \
+    hipLaunchKernelGGL((gossip_sweep_kernel<SPLIT, ROWS, sweep_rif(SPLIT, FUSED, STALE, CG), FUSED, NOISE, EXT, STALE, CG>), \
+                       dim3(width), dim3(sweep_block(SPLIT, ROWS, FUSED, CG)), 0, \
                        stream, geo, hp, seg, -beta, peers, x, v, g, h, xstar, sigma, key, step, p, tiles)
     // the extended local step covers the plain one (no weight decay, heavy ball) wherever only one is compiled
-#define GSGD_SWEEP_FLAGS(SPLIT, ROWS) \
+#define GSGD_SWEEP_GIVEN_G(SPLIT, ROWS) \
     do { \
-        if (fused) { \
-            if (noise_kind == GSGD_NOISE_UNIFORM) { \
-                if (stale) GSGD_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_UNIFORM, true, true); \
-                else GSGD_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_UNIFORM, true, false); \
-            } else { \
-                if (stale) GSGD_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_GAUSSIAN, true, true); \
-                else GSGD_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_GAUSSIAN, true, false); \
-            } \
-        } else if (stale) GSGD_SWEEP(SPLIT, ROWS, false, 0, true, true); \
-        else if (hp.extended()) GSGD_SWEEP(SPLIT, ROWS, false, 0, true, false); \
-        else GSGD_SWEEP(SPLIT, ROWS, false, 0, false, false); \
+        if (stale) GSGD_SWEEP(SPLIT, ROWS, 1, false, 0, true, true); \
+        else if (hp.extended()) GSGD_SWEEP(SPLIT, ROWS, 1, false, 0, true, false); \
+        else GSGD_SWEEP(SPLIT, ROWS, 1, false, 0, false, false); \
     } while (0)
-    if (!split && geo.k <= SWEEP_ROWS_WHOLE_FEW) GSGD_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE_FEW);
-    else if (!split) GSGD_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE);
-    else if (geo.k <= SWEEP_ROWS_SPLIT_FEW) GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW);
-    else if (geo.k <= SWEEP_ROWS_SPLIT_MID) GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_MID);
-    else GSGD_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT);
-#undef GSGD_SWEEP_FLAGS
+#define GSGD_SWEEP_FUSED(SPLIT, ROWS, CG) \
+    do { \
+        if (noise_kind == GSGD_NOISE_UNIFORM) { \
+            if (stale) GSGD_SWEEP(SPLIT, ROWS, CG, true, GSGD_NOISE_UNIFORM, true, true); \
+            else GSGD_SWEEP(SPLIT, ROWS, CG, true, GSGD_NOISE_UNIFORM, true, false); \
+        } else { \
+            if (stale) GSGD_SWEEP(SPLIT, ROWS, CG, true, GSGD_NOISE_GAUSSIAN, true, true); \
+            else GSGD_SWEEP(SPLIT, ROWS, CG, true, GSGD_NOISE_GAUSSIAN, true, false); \
+        } \
+    } while (0)
+#define GSGD_SWEEP_EITHER(SPLIT, ROWS) \
+    do { if (fused) GSGD_SWEEP_FUSED(SPLIT, ROWS, 1); else GSGD_SWEEP_GIVEN_G(SPLIT, ROWS); } while (0)
+    if (!split && geo.k <= SWEEP_ROWS_WHOLE_FEW) GSGD_SWEEP_EITHER(false, SWEEP_ROWS_WHOLE_FEW);
+    else if (!split && fused) GSGD_SWEEP_FUSED(true, SWEEP_ROWS_WHOLE, SWEEP_WIDE_GROUPS);     // whole tiles, eight wavefronts
+    else if (!split) GSGD_SWEEP_GIVEN_G(false, SWEEP_ROWS_WHOLE);
+    else if (geo.k <= SWEEP_ROWS_SPLIT_FEW) GSGD_SWEEP_EITHER(true, SWEEP_ROWS_SPLIT_FEW);
+    else if (geo.k <= SWEEP_ROWS_SPLIT_MID) GSGD_SWEEP_EITHER(true, SWEEP_ROWS_SPLIT_MID);
+    else GSGD_SWEEP_EITHER(true, SWEEP_ROWS_SPLIT);
+#undef GSGD_SWEEP_EITHER
+#undef GSGD_SWEEP_FUSED
+#undef GSGD_SWEEP_GIVEN_G
 #undef GSGD_SWEEP
     return hipGetLastError();
 }
@@ -1037,21 +1059,22 @@ hipError_t launch_step_gossip_push_sweep(const Geom& geo, const Hyper& hp, const
     const uint32_t tiles = split ? static_cast<uint32_t>((geo.d + SWEEP_SPLIT_COLUMNS - 1) / SWEEP_SPLIT_COLUMNS)
                                  : grid_for(geo.d);
     const unsigned width = p.workgroups < tiles ? (p.workgroups ? p.workgroups : 1u) : tiles;
-#define GSGD_PUSH_SWEEP(SPLIT, ROWS, FUSED, NOISE, EXT) \
-    hipLaunchKernelGGL((push_sweep_kernel<SPLIT, ROWS, FUSED ? SWEEP_RIF : SWEEP_RIF_PUSH, FUSED, NOISE, EXT>), dim3(width), dim3(sweep_block(SPLIT, ROWS, false)), 0, stream, \
+#define GSGD_PUSH_SWEEP(SPLIT, ROWS, CG, FUSED, NOISE, EXT) \
+    hipLaunchKernelGGL((push_sweep_kernel<SPLIT, ROWS, (FUSED && CG == 1) ? SWEEP_RIF : SWEEP_RIF_PUSH, FUSED, NOISE, EXT, CG>), \
+                       dim3(width), dim3(sweep_block(SPLIT, ROWS, false, CG)), 0, stream, \
                        geo, hp, seg, index, senders, x, v, g, h, xstar, sigma, key, step, p, tiles)
-#define GSGD_PUSH_SWEEP_FLAGS(SPLIT, ROWS) \
+#define GSGD_PUSH_SWEEP_FLAGS(SPLIT, ROWS, CG) \
     do { \
-        if (fused && noise_kind == GSGD_NOISE_UNIFORM) GSGD_PUSH_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_UNIFORM, true); \
-        else if (fused) GSGD_PUSH_SWEEP(SPLIT, ROWS, true, GSGD_NOISE_GAUSSIAN, true); \
-        else if (hp.extended()) GSGD_PUSH_SWEEP(SPLIT, ROWS, false, 0, true); \
-        else GSGD_PUSH_SWEEP(SPLIT, ROWS, false, 0, false); \
+        if (fused && noise_kind == GSGD_NOISE_UNIFORM) GSGD_PUSH_SWEEP(SPLIT, ROWS, CG, true, GSGD_NOISE_UNIFORM, true); \
+        else if (fused) GSGD_PUSH_SWEEP(SPLIT, ROWS, CG, true, GSGD_NOISE_GAUSSIAN, true); \
+        else if (hp.extended()) GSGD_PUSH_SWEEP(SPLIT, ROWS, CG, false, 0, true); \
+        else GSGD_PUSH_SWEEP(SPLIT, ROWS, CG, false, 0, false); \
     } while (0)
-    if (!split && geo.k <= SWEEP_ROWS_WHOLE_FEW) GSGD_PUSH_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE_FEW);
-    else if (!split) GSGD_PUSH_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE);
-    else if (geo.k <= SWEEP_ROWS_SPLIT_FEW) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW);
-    else if (geo.k <= SWEEP_ROWS_SPLIT_MID) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_MID);
-    else GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT);
+    if (!split && geo.k <= SWEEP_ROWS_WHOLE_FEW) GSGD_PUSH_SWEEP_FLAGS(false, SWEEP_ROWS_WHOLE_FEW, 1);
+    else if (!split) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_WHOLE, SWEEP_WIDE_GROUPS);          // whole tiles, eight wavefronts
+    else if (geo.k <= SWEEP_ROWS_SPLIT_FEW) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_FEW, 1);
+    else if (geo.k <= SWEEP_ROWS_SPLIT_MID) GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT_MID, 1);
+    else GSGD_PUSH_SWEEP_FLAGS(true, SWEEP_ROWS_SPLIT, 1);
 #undef GSGD_PUSH_SWEEP_FLAGS
 #undef GSGD_PUSH_SWEEP
     return hipGetLastError();
