@@ -44,17 +44,17 @@ _OTHERS = "profiles/step_kernels_other_workloads.md"
 _GENERATOR = "profiles/generator_kernels_alu_vs_hbm.md"
 TRAFFIC_FROM_PROFILES = {
     # name: (bytes per launch, source)
-    "gossip_r50": (_kib(4792031.5, 6390747.3), _GOSSIP_R50),
-    "stale_gossip_r50": (_kib(4792026.1, 6390059.0), _GOSSIP_R50),
+    "gossip_r50": (_kib(4792037.3, 6390778.6), _GOSSIP_R50),
+    "stale_gossip_r50": (_kib(4792028.2, 6390059.6), _GOSSIP_R50),
     "pull_gossip_r50": (_kib(4792032.3, 6390840.2), _OTHERS),
-    "push_gossip_r50": (_kib(4792076.2, 6392459.3), _GOSSIP_R50),
-    "local_r50": (_kib(4792014.6, 6390054.8), _GOSSIP_R50),
-    "allreduce_r18": (_kib(548019.2, 730980.3), _OTHERS),
-    "gossip_r18": (_kib(2191848.6, 2923234.7), _OTHERS),
-    "easgd_r50": (_kib(2445965.8, 3295277.5), _OTHERS),
+    "push_gossip_r50": (_kib(4792100.4, 6392455.2), _GOSSIP_R50),
+    "local_r50": (_kib(4792016.9, 6390055.1), _GOSSIP_R50),
+    "allreduce_r18": (_kib(548018.5, 730983.1), _OTHERS),
+    "gossip_r18": (_kib(2191852.5, 2923219.8), _OTHERS),
+    "easgd_r50": (_kib(2445969.7, 3295277.8), _OTHERS),
     "seg_gossip_r50_k128": (_kib(19167946.7, 25562415.2), _OTHERS),
-    "gen_grad@gossip_r50": (_kib(1697255.1, 3195443.7), _GENERATOR),
-    "fused@gossip_r50": (_kib(3294604.3, 6391173.9), _GENERATOR),
+    "gen_grad@gossip_r50": (_kib(1697262.5, 3195443.6), _GENERATOR),
+    "fused@gossip_r50": (_kib(3294575.8, 6390697.4), _GENERATOR),
 }
 TRAFFIC_NOTE = ("rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size; a separate "
                 "profile run, not this run")
