@@ -141,9 +141,9 @@ int gsgd_set_launch_width(gsgd_ctx* ctx, int kernel, int workgroups);
  *   GSGD_GOSSIP_AUTO         (default) the walk on row-major matrices, the sweeps on blocked ones: the memory system
  *                            serves the row pieces of a block fastest in address order; in either layout the
  *                            split sweeps for vectors too short to fill the chip with 1024-column tiles.
- *                            On blocked matrices push-gossip takes the split sweeps from 20 replicas on, and up to
- *                            64 replicas (up to 16 in whole tiles) with twice the workgroups unless
- *                            gsgd_set_launch_width has set their number.
+ *                            Push-gossip runs with twice the workgroups where two fit a compute unit (up to 16
+ *                            replicas in whole tiles, 37 to 64 in split ones) unless gsgd_set_launch_width has set
+ *                            their number.
  * Push-gossip's fp64 sums are taken own value first, then the senders in ascending index by the sweep forms, and in
  * visiting order by the walk (the two can differ in the last place of the rounded average).
  * A sweep form asked for with more replicas than it can park falls back (SWEEP -> SWEEP_SPLIT -> WALK).  Host only. */

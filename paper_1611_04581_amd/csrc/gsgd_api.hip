@@ -434,21 +434,14 @@ namespace {
 // layout: four times the workgroups and a quarter of the rows per wavefront (microseconds per step, walk -> split,
 // row-major: d = 16,384: k = 32 17.1 -> 10.6, k = 128 58 -> 20; d = 65,536: 19.9 -> 14.3, 66 -> 37; at d = 262,144 the
 // walk is level or ahead).  A form that cannot park k rows falls back to the next one.
-//
-// Push-gossip does more arithmetic per row in the second sweep (fp64 sums and a division), which one workgroup per
-// compute unit does not hide: from 20 replicas on it takes the split sweeps with two workgroups per compute unit
-// while two fit the LDS (blocks of 16 Ki columns, ResNet-50 length, % of the HBM peak, whole tiles -> split at two
-// per compute unit: k = 16 80 -> 74, k = 24 79 -> 82, k = 32 80 -> 82, k = 48 72 (split at one) -> 81).
-constexpr int PUSH_SPLIT_FROM_K = 20;
-int gossip_form_of(const gsgd_ctx* c, bool push = false)
+int gossip_form_of(const gsgd_ctx* c)
 {
     int form = c->gossip_form;
     if (form == GSGD_GOSSIP_AUTO) {
         const int64_t tiles = (c->cfg.d + BLOCK_COLUMNS - 1) / BLOCK_COLUMNS;
-        const int whole_up_to = push ? PUSH_SPLIT_FROM_K - 1 : SWEEP_WHOLE_UP_TO;
         if (tiles < c->cu_count && c->cfg.k >= ROW_SPLIT_MIN_K) form = GSGD_GOSSIP_SWEEP_SPLIT;
         else if (c->cfg.block_columns == 0) form = GSGD_GOSSIP_WALK;
-        else form = c->cfg.k <= whole_up_to ? GSGD_GOSSIP_SWEEP : GSGD_GOSSIP_SWEEP_SPLIT;
+        else form = c->cfg.k <= SWEEP_WHOLE_UP_TO ? GSGD_GOSSIP_SWEEP : GSGD_GOSSIP_SWEEP_SPLIT;
     }
     if (form == GSGD_GOSSIP_SWEEP && c->cfg.k > sweep_capacity(false)) form = GSGD_GOSSIP_SWEEP_SPLIT;
     if (form == GSGD_GOSSIP_SWEEP_SPLIT && c->cfg.k > sweep_capacity(true)) form = GSGD_GOSSIP_WALK;
@@ -487,11 +480,12 @@ hipError_t launch_push(gsgd_ctx* ctx, const Walk& walk, const int32_t* target, b
                        const float* g, const float* h, const float* xstar, uint64_t step, const Persist& ps, void* stream)
 {
     const hipStream_t st = static_cast<hipStream_t>(stream);
-    const int form = gossip_form_of(ctx, true);
+    const int form = gossip_form_of(ctx);
     if (form != GSGD_GOSSIP_WALK) {
         const int32_t k = ctx->cfg.k;
         Persist wide = ps;
-        // two workgroups per compute unit where they fit, unless the caller has chosen the width
+        // Push-gossip does more arithmetic per row in the second sweep (fp64 sums and a division) than one workgroup
+        // per compute unit hides: two where they fit, unless the caller has chosen the width
         if (k <= sweep_rows_two_per_cu(form == GSGD_GOSSIP_SWEEP_SPLIT) &&
             !ctx->width_set[fused ? GSGD_KERNEL_GOSSIP_FUSED : GSGD_KERNEL_GOSSIP])
             wide.workgroups = 2u * static_cast<unsigned>(ctx->cu_count);

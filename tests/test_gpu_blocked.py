@@ -188,8 +188,8 @@ def test_gossip_forms_at_their_capacity_edges(oracle, k, b):
     """The walk and the two sweep forms of the pull-gossip step (fresh and stale parameters, gradient given or drawn
     by the fused generator), forced one after the other in one context, in both layouts: all bit-equal to the
     oracle.  The replica counts sit on either side of what each sweep form can park (36 / 144 rows); beyond it the call
-    falls back to the next form.  16 / 17 and 72 / 73 sit on either side of full batches of rows.  19 / 20 is where push-gossip goes from whole to split
-    tiles by itself, 48 / 49 and 64 / 65 are the sizes the split kernels are compiled for."""
+    falls back to the next form.  16 / 17, 48 / 49 and 64 / 65 are the sizes the kernels are compiled
+    for; 19, 20, 72 and 73 leave rows over after the full batches."""
     from paper_1611_04581_amd import gsgd as G
     d = 2 * 1024 + 256 + 7                      # two whole 1024-column tiles, one whole 256-column tile, a ragged rest
     ld = W.round_up(d, b or 4)
