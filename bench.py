@@ -47,7 +47,7 @@ TRAFFIC_FROM_PROFILES = {
     "gossip_r50": (_kib(4792037.3, 6390778.6), _GOSSIP_R50),
     "stale_gossip_r50": (_kib(4792028.2, 6390059.6), _GOSSIP_R50),
     "pull_gossip_r50": (_kib(4792032.3, 6390840.2), _OTHERS),
-    "push_gossip_r50": (_kib(4792100.4, 6392455.2), _GOSSIP_R50),
+    "push_gossip_r50": (_kib(4792027.0, 6390304.0), _GOSSIP_R50),
     "local_r50": (_kib(4792016.9, 6390055.1), _GOSSIP_R50),
     "allreduce_r18": (_kib(548018.5, 730983.1), _OTHERS),
     "gossip_r18": (_kib(2191852.5, 2923219.8), _OTHERS),
