@@ -182,6 +182,53 @@ def test_generator_and_fused_steps_blocked(oracle, k, d, b, kind):
             assert_bitwise(_rowmajor(v, b), vo, "ticks v")
 
 
+@pytest.mark.parametrize("k,b", [(8, 4096), (16, 16384), (17, 4096), (24, 16384), (36, 4096), (40, 16384), (48, 4096),
+                                 (56, 16384), (64, 4096), (65, 16384), (100, 4096), (144, 16384)])
+def test_the_form_the_library_picks_on_vectors_that_fill_the_chip(oracle, k, b):
+    """More 1024-column tiles than compute units, so that the library's own choice of kernel is the one for long
+    vectors (whole tiles with a thread per quad or under eight wavefronts, split tiles with one or two workgroups per
+    compute unit and four, eight or twelve wavefronts), with a row length that ends inside a 256-column tile and inside
+    a quad: every gossip rule, gradient given or drawn by the fused generator, bit-equal to the oracle."""
+    from paper_1611_04581_amd import gsgd as G
+    d = 263 * 1024 + 300 + 3
+    ld = W.round_up(d, b)
+    inp = W.make_inputs(k, d, ld, seed=700 + k)
+    rng = np.random.default_rng(900 + k)
+    sigma = 0.2
+    with G.Context(k, d, ld, lr=0.05, momentum=0.9, sigma=sigma, seed=SEED, noise_kind=G.NOISE_UNIFORM,
+                   block_columns=b) as ctx:
+        h, xs = _dev(inp.h), _dev(inp.xstar)
+        x, v, g = _blocked(inp.x, b), _blocked(inp.v, b), _blocked(inp.g, b)
+        xo, vo, go = inp.x.copy(), inp.v.copy(), inp.g.copy()
+        perm = [int(t) for t in rng.permutation(k)]
+        peer = [int(t) for t in rng.integers(0, k, size=k)]
+        target = [int(t) for t in rng.integers(0, k, size=k)]
+        ctx.step_gossip(x, v, g, perm, 0.5)
+        oracle.step_gossip(xo, vo, go, 0.05, 0.9, 0.5, perm, n=d)
+        ctx.step_gossip_stale(x, v, g, perm, 0.3)
+        oracle.step_gossip_ext(xo, vo, go, 0.05, 0.9, 0.3, perm, stale=True, n=d)
+        ctx.step_gossip_pull(x, v, g, peer, 0.5)
+        oracle.step_gossip(xo, vo, go, 0.05, 0.9, 0.5, peer, n=d)
+        ctx.step_gossip_push(x, v, g, target)
+        oracle.step_gossip_push(xo, vo, inp.g, 0.05, 0.9, target, n=d)
+        ctx.step_gossip_fused(x, v, h, xs, perm, 21, 0.5)
+        oracle.gen_grad(xo, inp.h, inp.xstar, go, sigma, SEED, 21, 1, n=d)
+        oracle.step_gossip(xo, vo, go, 0.05, 0.9, 0.5, perm, n=d)
+        ctx.step_gossip_pull_fused(x, v, h, xs, peer, 22, 0.5, True)
+        oracle.gen_grad(xo, inp.h, inp.xstar, go, sigma, SEED, 22, 1, n=d)
+        oracle.step_gossip_ext(xo, vo, go, 0.05, 0.9, 0.5, peer, stale=True, n=d)
+        ctx.step_gossip_push_fused(x, v, h, xs, target, 23)
+        oracle.gen_grad(xo, inp.h, inp.xstar, go, sigma, SEED, 23, 1, n=d)
+        oracle.step_gossip_push(xo, vo, go, 0.05, 0.9, target, n=d)
+        ctx.set_local_step(1e-3, True)
+        ctx.step_gossip_push(x, v, g, target)
+        oracle.step_gossip_push(xo, vo, inp.g, 0.05, 0.9, target, wd=1e-3, nesterov=True, n=d)
+        assert_bitwise(_rowmajor(x, b), xo, "x (k=%d block=%d)" % (k, b))
+        assert_bitwise(_rowmajor(v, b), vo, "v (k=%d block=%d)" % (k, b))
+        assert_bitwise(_rowmajor(g, b), inp.g, "g is read-only")
+        ctx.stats(x, xs)                # the tile counters of every launch above drained to zero
+
+
 @pytest.mark.parametrize("b", [0, 1024, 4096])
 @pytest.mark.parametrize("k", [1, 2, 16, 17, 19, 20, 36, 37, 48, 49, 64, 65, 72, 73, 144, 145, 200])
 def test_gossip_forms_at_their_capacity_edges(oracle, k, b):
