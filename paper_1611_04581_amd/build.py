@@ -2,12 +2,15 @@
 import os
 import shutil
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgsgd.so")
-SOURCES = ["gsgd_api.hip", "host_perm.hip", "kernels_step.hip", "kernels_async.hip", "kernels_gen.hip", "kernels_stats.hip"]
+SOURCES = ["gsgd_api.hip", "host_perm.hip", "kernels_step.hip", "kernels_sweep.hip", "kernels_async.hip", "kernels_gen.hip",
+           "kernels_stats.hip"]
 
 # FP contraction is off: every fused multiply-add in the kernels is written out,
 # so results do not depend on what the optimiser decides to fuse.  Packed fp32
@@ -29,11 +32,22 @@ DEMO = os.path.join(HERE, "abi_demo")
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [hipcc(), *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-shared", *srcs, "-o", LIB]
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.run(cmd, check=True)
+    """Every source to an object of its own, side by side, then one link; the objects live in a temporary folder."""
+    common = [hipcc(), *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    with tempfile.TemporaryDirectory(prefix="gsgd_build_") as tmp:
+        def compile_one(name):
+            obj = os.path.join(tmp, os.path.splitext(name)[0] + ".o")
+            cmd = [*common, "-c", os.path.join(CSRC, name), "-o", obj]
+            if verbose:
+                print(" ".join(cmd))
+            subprocess.run(cmd, check=True)
+            return obj
+        with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
+            objects = list(pool.map(compile_one, SOURCES))
+        cmd = [*common, "-shared", *objects, "-o", LIB]
+        if verbose:
+            print(" ".join(cmd))
+        subprocess.run(cmd, check=True)
     build_demo(verbose)
     return LIB
 

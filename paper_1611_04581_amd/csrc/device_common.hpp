@@ -118,6 +118,28 @@ __device__ __forceinline__ f32x4 mix_keys(f32x4 post, f32x4 mine, f32x4 theirs, 
     return fma4(neg_beta, diff, post);
 }
 
+// Push-gossip (Algorithm 4) sums what a node received in fp64.
+__device__ __forceinline__ f64x4 widen(f32x4 a)
+{
+    return f64x4{static_cast<double>(a.x), static_cast<double>(a.y), static_cast<double>(a.z), static_cast<double>(a.w)};
+}
+
+// average of `count` received values whose fp64 sum is `sum`, rounded once
+__device__ __forceinline__ f32x4 average(f64x4 sum, uint32_t count)
+{
+    const double c = static_cast<double>(count);
+    if ((count & (count - 1u)) == 0u) {
+        // a power of two (uniform test: `count` is the same for the whole workgroup): scaling by its reciprocal is
+        // the same quotient exactly, without four fp64 divisions; with uniformly drawn targets half of the rows
+        // that received anything received from one sender
+        const double r = 1.0 / c;
+        return f32x4{static_cast<float>(sum.x * r), static_cast<float>(sum.y * r),
+                     static_cast<float>(sum.z * r), static_cast<float>(sum.w * r)};
+    }
+    return f32x4{static_cast<float>(sum.x / c), static_cast<float>(sum.y / c),
+                 static_cast<float>(sum.z / c), static_cast<float>(sum.w / c)};
+}
+
 // ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).  Stream ids select what
 // the numbers are used for; they are the fourth counter word.
